@@ -1,0 +1,166 @@
+/*
+ * isa.h -- C ABI of the In-Context Sparse Attention (ISA) library for AMD MI355X (gfx950).
+ *
+ * ISA (the paper's Sec. 3 and Algorithms 1 and 2) replaces the softmax attention of an
+ * in-context video-editing transformer, whose token sequence is a source segment followed
+ * by one or more context references, by four stages:
+ *   1. pre-selection: score context key/value blocks by pooled attention and keep a top-k;
+ *   2. query grouping: split query blocks by the sharpness of their pooled attention row;
+ *   3. exact attention of the sharp query blocks over the source + kept context keys;
+ *   4. block-wise 0-th order Taylor attention of the remaining query blocks, in which a
+ *      key/value block enters through its mean key, mean value and token count;
+ * and writes every result at its token's original position.
+ *
+ * Conventions shared by all entry points
+ *   - Every function returns ISA_OK (0) or a negative isa_status.  Nothing throws, aborts or
+ *     prints.  isa_strerror() names a status.
+ *   - `q`, `k`, `v`, `out`, `workspace` and every array argument described as "device" are
+ *     device pointers owned by the caller.  `isa_problem` and the arrays it points to
+ *     (`seg_ptr`, `seg_len`) are host memory, read during the call only.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and the call returns without synchronising.  The library allocates no memory and keeps
+ *     no state between calls (isa_attention_simple excepted, see there).
+ *   - Tensors q, k, v, out are [B, H, S_max, D] with element strides stride_b, stride_h,
+ *     stride_t and a contiguous last dimension.  Batch item b holds S_b = sum of its segment
+ *     lengths tokens, source segment first; rows S_b .. S_max-1 are neither read nor written.
+ *   - Blocks: every segment is cut into blocks of `block` tokens starting at the segment's
+ *     first token, so the last block of a segment may be short.  Block indices run over the
+ *     source blocks first (0 .. T_src-1), then the context blocks.  T_max is the largest
+ *     per-batch block count; per-(batch, head) block arrays are laid out [B, H, T_max].
+ *   - Supported shapes: D in {64, 128}; block in {64, 128}; 1 <= B <= ISA_MAX_BATCH; at most
+ *     ISA_MAX_SEGMENTS segments over all batch items; at most ISA_MAX_BLOCKS blocks per batch
+ *     item; strides multiples of 8 elements.  gamma must be 0.
+ */
+#ifndef ISA_H
+#define ISA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ISA_MAX_BATCH 8
+#define ISA_MAX_SEGMENTS 32
+#define ISA_MAX_BLOCKS 4096
+
+typedef enum {
+  ISA_OK = 0,
+  ISA_ERR_NULL = -1,        /* a required pointer is NULL */
+  ISA_ERR_SHAPE = -2,       /* B, H, D, block, segments or strides outside the supported set */
+  ISA_ERR_RATIO = -3,       /* a ratio outside [0, 1] or not finite */
+  ISA_ERR_DTYPE = -4,       /* dtype is neither ISA_BF16 nor ISA_F32 */
+  ISA_ERR_UNSUPPORTED = -5, /* gamma != 0, or a feature this build does not carry */
+  ISA_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than required */
+  ISA_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed */
+} isa_status;
+
+typedef enum { ISA_BF16 = 0, ISA_F32 = 1 } isa_dtype;
+
+/* The problem statement of Algorithm 1: shapes, segments and the three ratios. */
+typedef struct isa_problem {
+  int32_t B, H, D;
+  int32_t dtype;          /* isa_dtype of q, k, v and out.  bf16 is the production path; fp32 is the checking mode */
+  int32_t block;          /* tokens per query block and per key/value block (the paper's b = L_Q = L_K) */
+  const int32_t* seg_ptr; /* host [B+1]: batch item b owns seg_len[seg_ptr[b] .. seg_ptr[b+1]) */
+  const int32_t* seg_len; /* host: first segment of a batch item = source, the others = context references */
+  int64_t stride_b, stride_h, stride_t; /* element strides of q, k, v and out */
+  double keep_ratio;      /* Select Ratio alpha_s: fraction of context blocks kept (Sec. 3, Eq. 1-2) */
+  double full_frac;       /* fraction of query blocks given exact attention (Alg. 1 Stage 3) */
+  double exact_frac;      /* No-Sparsity Ratio alpha_ns: fraction of kept blocks a Taylor query block still
+                             evaluates exactly (Alg. 2 Stage 2) */
+  double gamma;           /* coarse stacking factor of Alg. 1; must be 0 */
+} isa_problem;
+
+/* Block and list counts of one batch item, all derived on the host in double precision. */
+typedef struct isa_counts {
+  int32_t S;       /* tokens */
+  int32_t T;       /* blocks */
+  int32_t T_src;   /* source blocks */
+  int32_t T_ctx;   /* context blocks */
+  int32_t k_keep;  /* floor(keep_ratio * T_ctx) kept context blocks */
+  int32_t T_new;   /* T_src + k_keep: length of kv_list */
+  int32_t n_flat;  /* floor((1 - full_frac) * T): query blocks of the Taylor branch */
+  int32_t n_full;  /* T - n_flat: query blocks of the exact branch */
+  int32_t k_exact; /* floor(exact_frac * T_new): exact blocks per Taylor query block */
+  int32_t T_max;   /* largest T over the batch (stride of block arrays) */
+} isa_counts;
+
+/* Host only.  Validates `p` and reports the counts of batch item `b`.  Needs no GPU. */
+int isa_get_counts(const isa_problem* p, int b, isa_counts* out);
+
+/* Host only.  Bytes of device workspace any entry point below needs for `p` (0 if `p` is invalid).
+ * The workspace must be 256-byte aligned.  Its contents are scratch: undefined before and after. */
+size_t isa_workspace_bytes(const isa_problem* p);
+
+/* Algorithm 1 (gamma = 0), all stages, for every (batch, head): out = ISA(q, k, v).
+ * `out` is written for every real token.  Errors: see isa_status. */
+int isa_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Standard attention softmax(q k^T / sqrt(D)) v (Sec. 2 "Standard Attention") over all S_b keys of
+ * each batch item; the ratios in `p` are ignored.  This is the kernel ISA is timed against. */
+int isa_dense_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Convenience form: B = 1, bf16, contiguous [H, n_src + n_ctx, D] tensors, one context segment,
+ * exact_frac = 0.  Unlike every other entry point it obtains its workspace with hipMallocAsync on
+ * `hip_stream` and releases it with hipFreeAsync, so it is not for callers that must not allocate. */
+int isa_attention_simple(const void* q, const void* k, const void* v, int H, int D, int n_src, int n_ctx,
+                         double keep_ratio, double full_frac, int block, void* out, void* hip_stream);
+
+/* ---- staged entry points: one per stage, so each can be checked on its own ---------------- */
+
+/* Alg. 1 Stage 1 / Alg. 2 Stage 1: block means over each block's real tokens.
+ * qc, kc, vc: device fp32 [B, H, T_max, D]; rows past a batch item's T are not written. */
+int isa_block_means(const isa_problem* p, const void* q, const void* k, const void* v,
+                    float* qc, float* kc, float* vc, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Pooling attention (Sec. 2) + Eq. 1 + the sharpness of Alg. 1 Stage 3.
+ * S_coarse = row softmax over all T key blocks of qc kc^T / sqrt(D).
+ * s_ctx: device fp32 [B, H, T_max]; entry j < T_ctx = mean over source query blocks of S_coarse[i, T_src + j].
+ * sharp: device fp32 [B, H, T_max]; entry i < T = population variance of S_coarse[i, 0..T_src).
+ * z: device fp32 [B, H, T_max, T_max] or NULL; if given, receives the scaled logits qc kc^T / sqrt(D). */
+int isa_coarse_scores(const isa_problem* p, const float* qc, const float* kc, float* s_ctx, float* sharp, float* z,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Eq. 2 selection and the Alg. 1 Stage 3 split, as integer work on given fp32 scores.
+ * Rankings are by descending score, ties to the lower index; all lists are stored ascending.
+ * kv_list:   device int32 [B, H, T_max]; first T_new entries = source blocks 0..T_src-1, then kept context blocks.
+ * full_list: device int32 [B, H, T_max]; first n_full entries = query blocks of the exact branch.
+ * flat_list: device int32 [B, H, T_max]; first n_flat entries = query blocks of the Taylor branch.
+ * Entries past those counts are set to -1.
+ * z / exact_mask: only read / written when exact_frac > 0 (both may be NULL otherwise).
+ * exact_mask: device uint32 [B, H, T_max, ceil(T_max/32)]; in the row of the Taylor query block stored at position r
+ * of flat_list, bit (t mod 32) of word t/32 is set iff kv_list[t] is one of its k_exact exact blocks (largest z,
+ * ties to the lower position in kv_list; Alg. 2 Stage 2). */
+int isa_select(const isa_problem* p, const float* s_ctx, const float* sharp, const float* z,
+               int32_t* kv_list, int32_t* full_list, int32_t* flat_list, uint32_t* exact_mask,
+               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Alg. 1 Stages 4-5 on given lists: exact attention (online softmax, Alg. 2 Part A) for the blocks of
+ * full_list, block-wise 0-th order Taylor attention (Eq. 3-4, Alg. 2 Parts A+B, with a block's real token
+ * count in place of L_K) for the blocks of flat_list, both over the blocks of kv_list, each result stored at its
+ * token's position in `out`.  kc, vc: block means as written by isa_block_means.  exact_mask may be NULL when
+ * exact_frac == 0.  The lists must be valid (in range, no duplicates); they are not checked. */
+int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v, const float* kc, const float* vc,
+               const int32_t* kv_list, const int32_t* full_list, const int32_t* flat_list, const uint32_t* exact_mask,
+               void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Name of a status code; never NULL. */
+const char* isa_strerror(int status);
+
+/* hipError_t (as int) of the most recent failing HIP call made by this library on the calling thread,
+ * 0 if none.  Only meaningful right after a call returned ISA_ERR_HIP. */
+int isa_last_hip_error(void);
+
+/* Selects the attention kernels used for bf16 problems with D = 128 and block = 128:
+ * 1 (default) = MFMA kernels, 0 = the portable scalar kernels that also serve fp32 and the other shapes.
+ * Returns the previous setting.  Process-wide; meant for tests and comparisons. */
+int isa_set_mfma(int enabled);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ISA_H */

@@ -1,0 +1,318 @@
+// Host side of libisa_hip: argument validation, count derivation, workspace carve-up and the
+// sequence of kernel launches behind each C-ABI entry point declared in include/isa.h.
+#include <math.h>
+#include <string.h>
+
+#include <atomic>
+
+#include "isa_internal.h"
+
+namespace isa {
+
+static thread_local int g_last_hip = 0;
+static std::atomic<int> g_use_mfma{0};   // flipped to 1 once the MFMA kernels are in
+
+static inline bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }   // false for NaN
+
+int validate(const isa_problem* p, Problem* out) {
+  if (!p || !out) return ISA_ERR_NULL;
+  if (!p->seg_ptr || !p->seg_len) return ISA_ERR_NULL;
+  if (p->dtype != ISA_BF16 && p->dtype != ISA_F32) return ISA_ERR_DTYPE;
+  if (p->B < 1 || p->B > ISA_MAX_BATCH || p->H < 1 || p->H > 65535) return ISA_ERR_SHAPE;
+  if (p->D != 64 && p->D != 128) return ISA_ERR_SHAPE;
+  if (p->block != 64 && p->block != 128) return ISA_ERR_SHAPE;
+  if (!ratio_ok(p->keep_ratio) || !ratio_ok(p->full_frac) || !ratio_ok(p->exact_frac)) return ISA_ERR_RATIO;
+  if (!(p->gamma == 0.0)) return ISA_ERR_UNSUPPORTED;
+  if (p->stride_t < p->D || p->stride_t % 8 || p->stride_h % 8 || p->stride_b % 8) return ISA_ERR_SHAPE;
+  if (p->stride_h < 0 || p->stride_b < 0) return ISA_ERR_SHAPE;
+
+  Problem& pr = *out;
+  memset(&pr, 0, sizeof(pr));
+  pr.p = *p;
+  pr.seg.B = p->B;
+  if (p->seg_ptr[0] != 0) return ISA_ERR_SHAPE;
+  int T_max = 0, Tsrc_max = 0, Tctx_max = 0, Tnew_max = 0;
+  for (int b = 0; b < p->B; ++b) {
+    const int s0 = p->seg_ptr[b], s1 = p->seg_ptr[b + 1];
+    if (s1 <= s0 || s1 > ISA_MAX_SEGMENTS) return ISA_ERR_SHAPE;      // at least the source segment
+    pr.seg.seg_ptr[b] = s0;
+    pr.seg.seg_ptr[b + 1] = s1;
+    long long S = 0, T = 0;
+    for (int s = s0; s < s1; ++s) {
+      const int len = p->seg_len[s];
+      if (len < 0 || (s == s0 && len < 1)) return ISA_ERR_SHAPE;     // empty source segment
+      pr.seg.seg_len[s] = len;
+      S += len;
+      T += (len + p->block - 1) / p->block;
+      if (S > 0x7fffffffLL / 2) return ISA_ERR_SHAPE;
+    }
+    if (T > ISA_MAX_BLOCKS) return ISA_ERR_SHAPE;
+    BatchCounts& c = pr.cnt.b[b];
+    c.S = (int)S;
+    c.T = (int)T;
+    c.T_src = (p->seg_len[s0] + p->block - 1) / p->block;
+    c.T_ctx = c.T - c.T_src;
+    c.k_keep = (int)floor(p->keep_ratio * (double)c.T_ctx);
+    c.T_new = c.T_src + c.k_keep;
+    c.n_flat = (int)floor((1.0 - p->full_frac) * (double)c.T);
+    c.n_full = c.T - c.n_flat;
+    c.k_exact = (int)floor(p->exact_frac * (double)c.T_new);
+    T_max = c.T > T_max ? c.T : T_max;
+    Tsrc_max = c.T_src > Tsrc_max ? c.T_src : Tsrc_max;
+    Tctx_max = c.T_ctx > Tctx_max ? c.T_ctx : Tctx_max;
+    Tnew_max = c.T_new > Tnew_max ? c.T_new : Tnew_max;
+  }
+  pr.cnt.T_max = T_max;
+  pr.cnt.mask_words = (T_max + 31) / 32;
+  pr.Tsrc_max = Tsrc_max;
+  pr.Tctx_max = Tctx_max > 0 ? Tctx_max : 1;
+  pr.Tn_pad = (Tnew_max + 127) / 128 * 128;
+  pr.geo = Geometry{p->B, p->H, p->D, p->block, T_max, p->stride_b, p->stride_h, p->stride_t};
+  pr.mfma_shape = (p->dtype == ISA_BF16 && p->D == 128 && p->block == 128);
+  return ISA_OK;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+void carve(const Problem& pr, void* base, Workspace* ws) {
+  const size_t B = pr.p.B, H = pr.p.H, D = pr.p.D, T = pr.cnt.T_max;
+  size_t off = 0;
+  char* b0 = (char*)base;
+  auto take = [&](size_t bytes) { char* r = b0 + off; off += align256(bytes); return (void*)r; };
+  ws->blk_start = (int*)take(B * T * 4);
+  ws->blk_n = (int*)take(B * T * 4);
+  ws->qc = (float*)take(B * H * T * D * 4);
+  ws->kc = (float*)take(B * H * T * D * 4);
+  ws->vc = (float*)take(B * H * T * D * 4);
+  ws->s_ctx = (float*)take(B * H * T * 4);
+  ws->sharp = (float*)take(B * H * T * 4);
+  ws->pctx = (float*)take(B * H * (size_t)pr.Tsrc_max * (size_t)pr.Tctx_max * 4);
+  ws->kv_list = (int*)take(B * H * T * 4);
+  ws->full_list = (int*)take(B * H * T * 4);
+  ws->flat_list = (int*)take(B * H * T * 4);
+  if (pr.p.exact_frac > 0.0) {
+    ws->z = (float*)take(B * H * T * T * 4);
+    ws->exact_mask = (uint32_t*)take(B * H * T * (size_t)pr.cnt.mask_words * 4);
+  } else {
+    ws->z = nullptr;
+    ws->exact_mask = nullptr;
+  }
+  if (pr.mfma_shape) {
+    ws->vt = (uint16_t*)take(B * H * T * D * 128 * 2);
+    ws->kcn = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
+    ws->vcnt = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
+    ws->biasn = (float*)take(B * H * (size_t)pr.Tn_pad * 4);
+  } else {
+    ws->vt = ws->kcn = ws->vcnt = nullptr;
+    ws->biasn = nullptr;
+  }
+  ws->bytes = off;
+}
+
+static int check_ws(const Problem& pr, void* workspace, size_t bytes, Workspace* ws) {
+  if (!workspace || ((uintptr_t)workspace & 255)) return ISA_ERR_WORKSPACE;
+  carve(pr, workspace, ws);
+  if (bytes < ws->bytes) return ISA_ERR_WORKSPACE;
+  return ISA_OK;
+}
+
+static int hip_fail(hipError_t e) {
+  g_last_hip = (int)e;
+  return ISA_ERR_HIP;
+}
+
+#define ISA_TRY(expr)                         \
+  do {                                        \
+    hipError_t e__ = (expr);                  \
+    if (e__ != hipSuccess) return hip_fail(e__); \
+  } while (0)
+
+static AttnArgs attn_args(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v, void* out,
+                          const float* kc, const float* vc, const int* kv, const int* full, const int* flat,
+                          const uint32_t* mask, int dense) {
+  AttnArgs a;
+  a.q = q; a.k = k; a.v = v; a.out = out;
+  a.kc = kc; a.vc = vc;
+  a.blk_start = ws.blk_start; a.blk_n = ws.blk_n;
+  a.kv_list = kv; a.full_list = full; a.flat_list = flat;
+  a.exact_mask = mask;
+  a.geo = pr.geo;
+  a.cnt = pr.cnt;
+  a.dense = dense;
+  return a;
+}
+
+static int run_attend(const Problem& pr, const Workspace& ws, const AttnArgs& a, const void* v, bool vt_ready,
+                      hipStream_t st) {
+  const bool mfma = pr.mfma_shape && g_use_mfma.load();
+  if (!mfma) {
+    ISA_TRY(launch_attn_simt(pr, a, st));
+    return ISA_OK;
+  }
+  if (!vt_ready) ISA_TRY(launch_pack_vt(pr, ws, v, st));
+  if (!a.dense) ISA_TRY(launch_gather_means(pr, ws, a.kc, a.vc, a.kv_list, st));
+  ISA_TRY(launch_attn_mfma(pr, ws, a, st));
+  return ISA_OK;
+}
+
+}  // namespace isa
+
+using namespace isa;
+
+extern "C" {
+
+int isa_get_counts(const isa_problem* p, int b, isa_counts* out) {
+  if (!out) return ISA_ERR_NULL;
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (b < 0 || b >= p->B) return ISA_ERR_SHAPE;
+  const BatchCounts& c = pr.cnt.b[b];
+  *out = isa_counts{c.S, c.T, c.T_src, c.T_ctx, c.k_keep, c.T_new, c.n_flat, c.n_full, c.k_exact, pr.cnt.T_max};
+  return ISA_OK;
+}
+
+size_t isa_workspace_bytes(const isa_problem* p) {
+  Problem pr;
+  if (validate(p, &pr) != ISA_OK) return 0;
+  Workspace ws;
+  carve(pr, nullptr, &ws);
+  return ws.bytes;
+}
+
+int isa_block_means(const isa_problem* p, const void* q, const void* k, const void* v, float* qc, float* kc, float* vc,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !qc || !kc || !vc) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_TRY(launch_layout(pr, ws, st));
+  ISA_TRY(launch_block_means(pr, ws, q, k, v, qc, kc, vc, st));
+  return ISA_OK;
+}
+
+int isa_coarse_scores(const isa_problem* p, const float* qc, const float* kc, float* s_ctx, float* sharp, float* z,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!qc || !kc || !s_ctx || !sharp) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_TRY(launch_coarse(pr, ws, qc, kc, s_ctx, sharp, z, st));
+  return ISA_OK;
+}
+
+int isa_select(const isa_problem* p, const float* s_ctx, const float* sharp, const float* z, int32_t* kv_list,
+               int32_t* full_list, int32_t* flat_list, uint32_t* exact_mask, void* workspace, size_t workspace_bytes,
+               void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!s_ctx || !sharp || !kv_list || !full_list || !flat_list) return ISA_ERR_NULL;
+  if (p->exact_frac > 0.0 && (!z || !exact_mask)) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_TRY(launch_select(pr, ws, s_ctx, sharp, z, kv_list, full_list, flat_list, exact_mask, st));
+  return ISA_OK;
+}
+
+int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v, const float* kc, const float* vc,
+               const int32_t* kv_list, const int32_t* full_list, const int32_t* flat_list, const uint32_t* exact_mask,
+               void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !kc || !vc || !kv_list || !full_list || !flat_list || !out) return ISA_ERR_NULL;
+  if (p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_TRY(launch_layout(pr, ws, st));
+  AttnArgs a = attn_args(pr, ws, q, k, v, out, kc, vc, kv_list, full_list, flat_list,
+                         p->exact_frac > 0.0 ? exact_mask : nullptr, 0);
+  return run_attend(pr, ws, a, v, false, st);
+}
+
+int isa_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_TRY(launch_layout(pr, ws, st));
+  ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
+  ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, ws.z, st));
+  ISA_TRY(launch_select(pr, ws, ws.s_ctx, ws.sharp, ws.z, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, st));
+  AttnArgs a = attn_args(pr, ws, q, k, v, out, ws.kc, ws.vc, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, 0);
+  return run_attend(pr, ws, a, v, false, st);
+}
+
+int isa_dense_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_TRY(launch_layout(pr, ws, st));
+  AttnArgs a = attn_args(pr, ws, q, k, v, out, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1);
+  return run_attend(pr, ws, a, v, false, st);
+}
+
+int isa_attention_simple(const void* q, const void* k, const void* v, int H, int D, int n_src, int n_ctx,
+                         double keep_ratio, double full_frac, int block, void* out, void* hip_stream) {
+  int32_t seg_ptr[2] = {0, n_ctx > 0 ? 2 : 1};
+  int32_t seg_len[2] = {n_src, n_ctx};
+  if (n_src < 1 || n_ctx < 0) return ISA_ERR_SHAPE;
+  isa_problem p;
+  memset(&p, 0, sizeof(p));
+  p.B = 1; p.H = H; p.D = D; p.dtype = ISA_BF16; p.block = block;
+  p.seg_ptr = seg_ptr; p.seg_len = seg_len;
+  p.stride_t = D;
+  p.stride_h = (int64_t)D * ((int64_t)n_src + n_ctx);
+  p.stride_b = p.stride_h * H;
+  p.keep_ratio = keep_ratio; p.full_frac = full_frac; p.exact_frac = 0.0; p.gamma = 0.0;
+  Problem pr;
+  int rc = validate(&p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  const size_t bytes = isa_workspace_bytes(&p);
+  hipStream_t st = (hipStream_t)hip_stream;
+  void* ws = nullptr;
+  ISA_TRY(hipMallocAsync(&ws, bytes, st));
+  rc = isa_attention(&p, q, k, v, out, ws, bytes, hip_stream);
+  hipError_t e = hipFreeAsync(ws, st);
+  if (rc == ISA_OK && e != hipSuccess) return hip_fail(e);
+  return rc;
+}
+
+const char* isa_strerror(int status) {
+  switch (status) {
+    case ISA_OK: return "ISA_OK";
+    case ISA_ERR_NULL: return "ISA_ERR_NULL: a required pointer is NULL";
+    case ISA_ERR_SHAPE: return "ISA_ERR_SHAPE: unsupported shape, segments or strides";
+    case ISA_ERR_RATIO: return "ISA_ERR_RATIO: ratio outside [0, 1]";
+    case ISA_ERR_DTYPE: return "ISA_ERR_DTYPE: unknown dtype";
+    case ISA_ERR_UNSUPPORTED: return "ISA_ERR_UNSUPPORTED: feature not available (gamma must be 0)";
+    case ISA_ERR_WORKSPACE: return "ISA_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case ISA_ERR_HIP: return "ISA_ERR_HIP: a HIP call failed (see isa_last_hip_error)";
+    default: return "unknown isa_status";
+  }
+}
+
+int isa_last_hip_error(void) { return g_last_hip; }
+
+int isa_set_mfma(int enabled) { return g_use_mfma.exchange(enabled ? 1 : 0); }
+
+}  // extern "C"

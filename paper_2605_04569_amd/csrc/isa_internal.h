@@ -1,0 +1,97 @@
+// Internal declarations shared by the host API and the kernel files of libisa_hip.
+// Nothing here is exported; the C ABI lives in include/isa.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "isa.h"
+
+namespace isa {
+
+// Segment lengths of every batch item, passed to kernels by value.
+struct SegDesc {
+  int B;
+  int seg_ptr[ISA_MAX_BATCH + 1];
+  int seg_len[ISA_MAX_SEGMENTS];
+};
+
+// Per-batch counts derived on the host (see isa_counts), passed to kernels by value.
+struct BatchCounts {
+  int S, T, T_src, T_ctx, k_keep, T_new, n_flat, n_full, k_exact;
+};
+struct Counts {
+  BatchCounts b[ISA_MAX_BATCH];
+  int T_max;
+  int mask_words;   // uint32 words per exact_mask row = ceil(T_max / 32)
+};
+
+// Shapes and strides common to all kernels.
+struct Geometry {
+  int B, H, D, block, T_max;
+  long long stride_b, stride_h, stride_t;   // element strides of q, k, v, out
+};
+
+// Workspace carve-up (device pointers into the caller's workspace).
+struct Workspace {
+  int* blk_start;        // [B][T_max] token offset of each block inside its batch item
+  int* blk_n;            // [B][T_max] real tokens of each block
+  float* qc;             // [B,H,T_max,D]
+  float* kc;
+  float* vc;
+  float* s_ctx;          // [B,H,T_max]
+  float* sharp;          // [B,H,T_max]
+  float* pctx;           // [B,H,Tsrc_max,Tctx_max] context part of the source rows of S_coarse
+  int* kv_list;          // [B,H,T_max]
+  int* full_list;
+  int* flat_list;
+  float* z;              // [B,H,T_max,T_max], only when exact_frac > 0
+  uint32_t* exact_mask;  // [B,H,T_max,mask_words], only when exact_frac > 0
+  // operand copies of the MFMA path (bf16, D = 128, block = 128)
+  uint16_t* vt;          // [B,H,T_max][D][128]: V of each block, transposed and key-permuted
+  uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order
+  uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
+  float* biasn;          // [B,H,Tn_pad]: log2(n_j) per gathered mean key, -inf for padding
+  size_t bytes;          // total size
+};
+
+struct Problem {          // validated problem + everything derived from it
+  isa_problem p;
+  SegDesc seg;
+  Counts cnt;
+  Geometry geo;
+  int Tsrc_max, Tctx_max, Tn_pad;
+  bool mfma_shape;        // bf16, D = 128, block = 128
+};
+
+int validate(const isa_problem* p, Problem* out);
+void carve(const Problem& pr, void* base, Workspace* ws);
+
+// ---- kernel launchers (each returns hipError_t of the launch) -------------------------------
+struct AttnArgs {
+  const void* q; const void* k; const void* v; void* out;
+  const float* kc; const float* vc;             // block means, fp32 [B,H,T_max,D]
+  const int* blk_start; const int* blk_n;       // [B][T_max]
+  const int* kv_list; const int* full_list; const int* flat_list;   // [B,H,T_max]; null in dense mode
+  const uint32_t* exact_mask;                   // may be null
+  Geometry geo;
+  Counts cnt;
+  int dense;                                    // 1: every query block attends to every block
+};
+
+hipError_t launch_layout(const Problem& pr, const Workspace& ws, hipStream_t st);
+hipError_t launch_block_means(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v,
+                              float* qc, float* kc, float* vc, hipStream_t st);
+hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc, const float* kc,
+                         float* s_ctx, float* sharp, float* z, hipStream_t st);
+hipError_t launch_select(const Problem& pr, const Workspace& ws, const float* s_ctx, const float* sharp, const float* z,
+                         int* kv_list, int* full_list, int* flat_list, uint32_t* exact_mask, hipStream_t st);
+hipError_t launch_attn_simt(const Problem& pr, const AttnArgs& a, hipStream_t st);
+
+// MFMA path (bf16, D = 128, block = 128)
+hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, hipStream_t st);
+hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
+                               const int* kv_list, hipStream_t st);
+hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st);
+
+}  // namespace isa

@@ -1,0 +1,367 @@
+"""Parity of the HIP path with the fp64 oracle, stage by stage and end to end, on seeded inputs small
+enough for the oracle to evaluate every element, yet spanning several tiles and ragged tails.
+All calls go through the C ABI (via the ctypes binding)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import isa_oracle as O
+from util import err_stats, f64, oracle_plan, problem_of, selection_is_valid
+
+pytestmark = pytest.mark.gpu
+
+# tolerances (north-star): bf16 outputs max-abs 2e-2 / mean-abs 2e-3, fp32 outputs 1e-4
+TOL = {"bf16": (2e-2, 2e-3), "f32": (1e-4, 1e-4)}
+
+CFG0 = W.CONFIGS["cfg0"]
+# bf16, D=128, block=128: 5 full source blocks + a 20-token tail; two context references with tails
+SMALL_BF16 = W.CONFIGS["cfg1"].with_(name="small_bf16", H=3, src_grid=(2, 10, 33), ctx_grids=(((1, 10, 33), (1, 9, 20)),),
+                                     keep_ratio=0.5, full_frac=0.3, seed=77)
+# ragged batch of two items with different context layouts, D=64 / block=64 in bf16
+RAGGED_B2 = W.CONFIGS["cfg3"].with_(name="ragged_b2", H=2, D=64, block=64, src_grid=(2, 9, 17),
+                                    ctx_grids=(((1, 3, 5), (2, 9, 17)), ((1, 9, 17),)), keep_ratio=0.4, full_frac=0.35,
+                                    seed=78)
+# fp32 with D=128 / block=128
+SMALL_F32 = W.CONFIGS["cfg0"].with_(name="small_f32", H=2, D=128, block=128, src_grid=(2, 10, 23), ctx_grids=(((2, 10, 23),),),
+                                    seed=79)
+CASES = [CFG0, SMALL_BF16, RAGGED_B2, SMALL_F32]
+IDS = [c.name for c in CASES]
+
+
+@pytest.fixture(scope="module")
+def I():
+    import paper_2605_04569_amd as isa
+    isa.lib()                                     # fail loudly if the HIP library is not built
+    return isa
+
+
+def gen(wl):
+    Q, K, V = W.make_inputs(wl, "cpu")
+    return Q, K, V, Q.cuda(), K.cuda(), V.cuda()
+
+
+def alloc_stage_buffers(wl, pr, I):
+    T_max = I.isa_get_counts(pr, 0)["T_max"]
+    f = dict(device="cuda", dtype=torch.float32)
+    i = dict(device="cuda", dtype=torch.int32)
+    return dict(T_max=T_max,
+                qc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f), kc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f),
+                vc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f),
+                s_ctx=torch.zeros((wl.B, wl.H, T_max), **f), sharp=torch.zeros((wl.B, wl.H, T_max), **f),
+                z=torch.zeros((wl.B, wl.H, T_max, T_max), **f),
+                kv=torch.full((wl.B, wl.H, T_max), -7, **i), full=torch.full((wl.B, wl.H, T_max), -7, **i),
+                flat=torch.full((wl.B, wl.H, T_max), -7, **i),
+                mask=torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), **i))
+
+
+# ------------------------------------------------------------------------------------------------
+# (i) block means and pooled scores
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("wl", CASES, ids=IDS)
+def test_block_means_and_scores(I, wl):
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    buf = alloc_stage_buffers(wl, pr, I)
+    I.isa_block_means(pr, q, k, v, buf["qc"], buf["kc"], buf["vc"], ws)
+    I.isa_coarse_scores(pr, buf["qc"], buf["kc"], buf["s_ctx"], buf["sharp"], buf["z"], ws)
+    torch.cuda.synchronize()
+    for b in range(wl.B):
+        for h in range(wl.H):
+            plan = oracle_plan(wl, Q, K, V, b, h)
+            T, T_src = plan["T"], plan["T_src"]
+            # means: fp32 sums of <= 128 values -> relative error a few ulp of fp32
+            for name, key in (("qc", "Qc"), ("kc", "Kc"), ("vc", "Vc")):
+                np.testing.assert_allclose(f64(buf[name][b, h, :T]), plan[key], rtol=2e-6, atol=2e-6)
+            np.testing.assert_allclose(f64(buf["z"][b, h, :T, :T]), plan["Z"], rtol=1e-5, atol=1e-5)
+            # probabilities carry fp32 exp error (~1e-7 relative); the variance amplifies it by p/|p - mean|
+            np.testing.assert_allclose(f64(buf["s_ctx"][b, h, :T - T_src]), plan["s_ctx"], rtol=1e-5, atol=1e-12)
+            np.testing.assert_allclose(f64(buf["sharp"][b, h, :T]), plan["sharp"], rtol=2e-4, atol=1e-14)
+
+
+# ------------------------------------------------------------------------------------------------
+# (ii) selection: bit-identical lists when both sides rank the same fp32 scores
+# ------------------------------------------------------------------------------------------------
+def _select_case(I, wl, s_ctx32, sharp32, z32, buf, pr, ws):
+    buf["s_ctx"].copy_(torch.from_numpy(s_ctx32))
+    buf["sharp"].copy_(torch.from_numpy(sharp32))
+    buf["z"].copy_(torch.from_numpy(z32))
+    I.isa_select(pr, buf["s_ctx"], buf["sharp"], buf["z"], buf["kv"], buf["full"], buf["flat"], buf["mask"], ws)
+    torch.cuda.synchronize()
+    kv, full, flat, mask = (buf[n].cpu().numpy() for n in ("kv", "full", "flat", "mask"))
+    for b in range(wl.B):
+        c = I.isa_get_counts(pr, b)
+        for h in range(wl.H):
+            want_kv = O.preselect(s_ctx32[b, h, :c["T_ctx"]], c["k_keep"], c["T_src"])
+            want_full, want_flat = O.group_queries(sharp32[b, h, :c["T"]], c["n_full"])
+            assert kv[b, h, :c["T_new"]].tolist() == want_kv.tolist()
+            assert full[b, h, :c["n_full"]].tolist() == want_full.tolist()
+            assert flat[b, h, :c["n_flat"]].tolist() == want_flat.tolist()
+            assert (kv[b, h, c["T_new"]:] == -1).all() and (full[b, h, c["n_full"]:] == -1).all()
+            assert (flat[b, h, c["n_flat"]:] == -1).all()
+            if pr.exact_frac > 0:
+                for r, i in enumerate(want_flat):
+                    ex = O.exact_set(z32[b, h, i], want_kv, c["k_exact"])
+                    bits = mask[b, h, r].view(np.uint32)
+                    got = [int(want_kv[t]) for t in range(c["T_new"]) if (bits[t >> 5] >> (t & 31)) & 1]
+                    assert got == ex.tolist(), (b, h, r)
+
+
+@pytest.mark.parametrize("wl", [CFG0, RAGGED_B2, SMALL_BF16], ids=["cfg0", "ragged_b2", "small_bf16"])
+@pytest.mark.parametrize("ratios", [(0.5, 0.25, 0.0), (0.0, 0.0, 0.25), (1.0, 1.0, 0.0), (0.33, 0.6, 1.0), (0.9, 0.1, 0.0625)])
+def test_select_bit_exact_on_shared_scores(I, wl, ratios):
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl, keep_ratio=ratios[0], full_frac=ratios[1], exact_frac=ratios[2])
+    ws = I.new_workspace(pr)
+    buf = alloc_stage_buffers(wl, pr, I)
+    T_max = buf["T_max"]
+    s_ctx32 = np.zeros((wl.B, wl.H, T_max), np.float32)
+    sharp32 = np.zeros((wl.B, wl.H, T_max), np.float32)
+    z32 = np.zeros((wl.B, wl.H, T_max, T_max), np.float32)
+    for b in range(wl.B):
+        for h in range(wl.H):
+            plan = oracle_plan(wl, Q, K, V, b, h)
+            T, T_src = plan["T"], plan["T_src"]
+            s_ctx32[b, h, :T - T_src] = plan["s_ctx"].astype(np.float32)
+            sharp32[b, h, :T] = plan["sharp"].astype(np.float32)
+            z32[b, h, :T, :T] = plan["Z"].astype(np.float32)
+    _select_case(I, wl, s_ctx32, sharp32, z32, buf, pr, ws)
+    # heavy ties: scores quantised to a few levels must still give the oracle's lower-index-first lists
+    rng = np.random.default_rng(5)
+    s_q = rng.integers(0, 3, s_ctx32.shape).astype(np.float32)
+    m_q = rng.integers(0, 3, sharp32.shape).astype(np.float32)
+    z_q = rng.integers(0, 4, z32.shape).astype(np.float32)
+    _select_case(I, wl, s_q, m_q, z_q, buf, pr, ws)
+
+
+def test_select_many_blocks(I):
+    """A long sequence of small blocks: 1200 blocks per head exercises the multi-chunk scan."""
+    wl = W.CONFIGS["cfg0"].with_(name="many", H=2, src_grid=(1, 1, 64 * 500), ctx_grids=(((1, 1, 64 * 700 - 3),),))
+    pr = problem_of(wl, keep_ratio=0.37, full_frac=0.21, exact_frac=0.05)
+    ws = I.new_workspace(pr)
+    buf = alloc_stage_buffers(wl, pr, I)
+    rng = np.random.default_rng(6)
+    T_max = buf["T_max"]
+    assert T_max == 1200
+    s = rng.standard_normal((1, 2, T_max)).astype(np.float32)
+    m = np.round(rng.standard_normal((1, 2, T_max)), 1).astype(np.float32)      # some ties
+    z = rng.standard_normal((1, 2, T_max, T_max)).astype(np.float32)
+    _select_case(I, wl, s, m, z, buf, pr, ws)
+
+
+# ------------------------------------------------------------------------------------------------
+# (iii) attention on the oracle's lists
+# ------------------------------------------------------------------------------------------------
+def _attend_with_oracle_lists(I, wl, exact_frac=0.0, mfma=True):
+    Q, K, V, q, k, v = gen(wl)
+    wl = wl.with_(exact_frac=exact_frac)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    buf = alloc_stage_buffers(wl, pr, I)
+    plans = {}
+    for b in range(wl.B):
+        c = I.isa_get_counts(pr, b)
+        for h in range(wl.H):
+            plan = plans[b, h] = oracle_plan(wl, Q, K, V, b, h)
+            T = plan["T"]
+            buf["kc"][b, h, :T] = torch.from_numpy(plan["Kc"]).float()
+            buf["vc"][b, h, :T] = torch.from_numpy(plan["Vc"]).float()
+            buf["kv"][b, h, :c["T_new"]] = torch.from_numpy(plan["kv_list"]).int()
+            buf["full"][b, h, :c["n_full"]] = torch.from_numpy(plan["full_list"]).int()
+            buf["flat"][b, h, :c["n_flat"]] = torch.from_numpy(plan["flat_list"]).int()
+            if exact_frac > 0:
+                words = np.zeros((buf["T_max"], (buf["T_max"] + 31) // 32), np.uint32)
+                for r, i in enumerate(plan["flat_list"]):
+                    ex = set(O.exact_set(plan["Z"][i], plan["kv_list"], plan["k_exact"]).tolist())
+                    for t, j in enumerate(plan["kv_list"]):
+                        if int(j) in ex:
+                            words[r, t >> 5] |= np.uint32(1 << (t & 31))
+                buf["mask"][b, h] = torch.from_numpy(words.view(np.int32))
+    out = torch.full_like(q, float("nan"))
+    prev = I.isa_set_mfma(mfma)
+    try:
+        I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"],
+                     buf["mask"] if exact_frac > 0 else None, out, ws)
+        torch.cuda.synchronize()
+    finally:
+        I.isa_set_mfma(prev)
+    tol_max, tol_mean = TOL[wl.dtype]
+    for b in range(wl.B):
+        n = wl.tokens(b)
+        for h in range(wl.H):
+            want, _ = O.isa_attention(f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n]), wl.seg_len(b), wl.block,
+                                      wl.keep_ratio, wl.full_frac, wl.exact_frac)
+            got = f64(out[b, h, :n])
+            assert np.isfinite(got).all(), (b, h)
+            emax, emean = err_stats(got, want)
+            assert emax <= tol_max and emean <= tol_mean, (wl.name, b, h, emax, emean)
+        if n < out.shape[2]:
+            assert torch.isnan(out[b, :, n:]).all()                  # rows past the batch item's end are untouched
+
+
+@pytest.mark.parametrize("wl", CASES, ids=IDS)
+@pytest.mark.parametrize("exact_frac", [0.0, 0.25])
+def test_attend_on_oracle_lists(I, wl, exact_frac):
+    _attend_with_oracle_lists(I, wl, exact_frac)
+
+
+@pytest.mark.parametrize("exact_frac", [0.0, 0.25])
+def test_attend_on_oracle_lists_portable_kernels(I, exact_frac):
+    _attend_with_oracle_lists(I, SMALL_BF16, exact_frac, mfma=False)
+
+
+# ------------------------------------------------------------------------------------------------
+# dense attention
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("wl", CASES, ids=IDS)
+def test_dense_attention(I, wl):
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    out = torch.full_like(q, float("nan"))
+    I.isa_dense_attention(pr, q, k, v, out, ws)
+    torch.cuda.synchronize()
+    tol_max, tol_mean = TOL[wl.dtype]
+    for b in range(wl.B):
+        n = wl.tokens(b)
+        for h in range(wl.H):
+            want = O.dense_attention(f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n]))
+            emax, emean = err_stats(f64(out[b, h, :n]), want)
+            assert emax <= tol_max and emean <= tol_mean, (wl.name, b, h, emax, emean)
+
+
+# ------------------------------------------------------------------------------------------------
+# (iv) the whole operator
+# ------------------------------------------------------------------------------------------------
+def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, seed=0):
+    """Runs isa_attention, reads back the lists it chose, checks that they are valid selections of the oracle's
+    scores, and checks outputs against the oracle evaluated on those lists.  Returns the index agreement rates."""
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    out = torch.full_like(q, float("nan"))
+    I.isa_attention(pr, q, k, v, out, ws)
+    torch.cuda.synchronize()
+    # re-run the staged entry points to read the lists (same kernels, same inputs -> same lists)
+    buf = alloc_stage_buffers(wl, pr, I)
+    I.isa_block_means(pr, q, k, v, buf["qc"], buf["kc"], buf["vc"], ws)
+    I.isa_coarse_scores(pr, buf["qc"], buf["kc"], buf["s_ctx"], buf["sharp"], buf["z"] if wl.exact_frac > 0 else None, ws)
+    I.isa_select(pr, buf["s_ctx"], buf["sharp"], buf["z"], buf["kv"], buf["full"], buf["flat"],
+                 buf["mask"] if wl.exact_frac > 0 else None, ws)
+    torch.cuda.synchronize()
+    kv_g, full_g = buf["kv"].cpu().numpy(), buf["full"].cpu().numpy()
+    mask_g = buf["mask"].cpu().numpy()
+    rng = np.random.default_rng(seed)
+    tol_max, tol_mean = TOL[wl.dtype]
+    agree_kv = agree_grp = total = 0
+    for b in range(wl.B):
+        c = I.isa_get_counts(pr, b)
+        n = wl.tokens(b)
+        for h in (range(wl.H) if heads is None else heads):
+            Qh, Kh, Vh = f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n])
+            plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(b), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac)
+            kv = kv_g[b, h, :c["T_new"]]
+            full = full_g[b, h, :c["n_full"]]
+            # validity: the GPU's choices are top-k sets of the oracle's scores up to fp32 score noise
+            assert kv[:c["T_src"]].tolist() == list(range(c["T_src"]))
+            assert selection_is_valid(plan["s_ctx"], kv[c["T_src"]:] - c["T_src"], c["k_keep"], 1e-4), (b, h)
+            assert selection_is_valid(plan["sharp"], full, c["n_full"], 1e-3), (b, h)
+            assert (np.diff(kv) > 0).all() and (np.diff(full) > 0).all()
+            total += 1
+            agree_kv += kv.tolist() == plan["kv_list"].tolist()
+            agree_grp += full.tolist() == plan["full_list"].tolist()
+            flat = np.setdiff1d(np.arange(c["T"]), full)
+            blocks = range(c["T"]) if blocks_per_head is None else \
+                sorted(set(rng.choice(full, min(len(full), blocks_per_head), replace=False).tolist() if len(full) else []) |
+                       set(rng.choice(flat, min(len(flat), blocks_per_head), replace=False).tolist() if len(flat) else []))
+            for i in blocks:
+                in_full = bool((full == i).any())
+                ex = None
+                if not in_full and wl.exact_frac > 0:
+                    r = int(np.searchsorted(flat, i))
+                    bits = mask_g[b, h, r].view(np.uint32)
+                    ex = [int(kv[t]) for t in range(c["T_new"]) if (bits[t >> 5] >> (t & 31)) & 1]
+                    assert selection_is_valid(plan["Z"][i][kv], [t for t in range(c["T_new"]) if int(kv[t]) in set(ex)],
+                                              c["k_exact"], 1e-4)
+                want = O.attend_block(int(i), plan, Qh, Kh, Vh, kv_list=kv, in_full=in_full, exact_blocks=ex)
+                s0, cnt = plan["starts"][i], plan["counts"][i]
+                got = f64(out[b, h, s0:s0 + cnt])
+                assert np.isfinite(got).all()
+                emax, emean = err_stats(got, want)
+                assert emax <= tol_max and emean <= tol_mean, (wl.name, b, h, int(i), in_full, emax, emean)
+    return agree_kv / total, agree_grp / total
+
+
+@pytest.mark.parametrize("wl", CASES, ids=IDS)
+@pytest.mark.parametrize("exact_frac", [0.0, 0.2])
+def test_isa_attention_end_to_end(I, wl, exact_frac):
+    wl = wl.with_(exact_frac=exact_frac)
+    Q, K, V, q, k, v = gen(wl)
+    a_kv, a_grp = check_end_to_end(I, wl, Q, K, V, q, k, v)
+    assert a_kv >= 0.5 and a_grp >= 0.5
+
+
+def test_all_exact_equals_dense(I):
+    """full_frac = 1 and keep_ratio = 1: ISA must reproduce dense attention (GPU vs GPU, and vs the oracle)."""
+    wl = SMALL_BF16.with_(keep_ratio=1.0, full_frac=1.0)
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    a, d = torch.empty_like(q), torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, a, ws)
+    I.isa_dense_attention(pr, q, k, v, d, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, d)
+
+
+def test_runs_are_bitwise_reproducible(I):
+    wl = SMALL_BF16
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    a, b2 = torch.empty_like(q), torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, a, ws)
+    I.isa_attention(pr, q, k, v, b2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b2)
+
+
+def test_strided_layout(I):
+    """[B, S, H, D] storage viewed as [B, H, S, D]: strides are honoured."""
+    wl = SMALL_BF16
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    ref = torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, ref, ws)
+    qs, ks, vs = (t.transpose(1, 2).contiguous().transpose(1, 2) for t in (q, k, v))
+    outs = torch.empty_like(qs)
+    assert qs.stride() != q.stride() and outs.stride() == qs.stride()
+    I.isa_attention(pr, qs, ks, vs, outs, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(outs, ref)
+
+
+def test_simple_entry_point(I):
+    wl = SMALL_BF16.with_(ctx_grids=(((1, 10, 33),),))
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    ref, out = torch.empty_like(q), torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, ref, ws)
+    seg = wl.seg_len(0)
+    I.isa_attention_simple(q[0], k[0], v[0], seg[0], seg[1], wl.keep_ratio, wl.full_frac, wl.block, out[0])
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+
+
+def test_degenerate_shapes(I):
+    """No context at all; a source shorter than one block; keep_ratio = 0 (source-only keys)."""
+    for seg_grids, keep, full in ((((1, 1, 130), ()), 0.5, 0.5), (((1, 1, 7), ((1, 1, 3),)), 1.0, 0.0),
+                                  (((1, 2, 100), ((1, 2, 100),)), 0.0, 0.5)):
+        wl = W.CONFIGS["cfg1"].with_(name="degenerate", H=2, src_grid=seg_grids[0], ctx_grids=(tuple(seg_grids[1]),),
+                                     keep_ratio=keep, full_frac=full, seed=80)
+        Q, K, V, q, k, v = gen(wl)
+        check_end_to_end(I, wl, Q, K, V, q, k, v)

@@ -1,0 +1,91 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, validates its
+arguments and derives the same counts as the oracle.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2605_04569_amd as I
+from oracle import isa_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "isa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(isa_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = I.lib()
+    names = declared_symbols()
+    assert "isa_attention" in names and "isa_dense_attention" in names and len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def base_problem(**kw):
+    d = dict(H=2, D=64, dtype="f32", block=64, seg_len=[[512, 512]], keep_ratio=0.5, full_frac=0.25)
+    d.update(kw)
+    return I.Problem(**d)
+
+
+def status(pr, **kw):
+    cp, keep = pr.c_struct(**kw)
+    out = I.binding._CCounts()
+    return I.lib().isa_get_counts(C.byref(cp), 0, C.byref(out))
+
+
+def test_validation_errors():
+    assert status(base_problem()) == 0
+    assert status(base_problem(D=96)) == -2
+    assert status(base_problem(block=32)) == -2
+    assert status(base_problem(seg_len=[[0, 512]])) == -2                  # empty source segment
+    assert status(base_problem(seg_len=[[64] * 40])) == -2                 # too many segments
+    assert status(base_problem(seg_len=[[64]] * 9)) == -2                  # too many batch items
+    assert status(base_problem(keep_ratio=1.5)) == -3
+    assert status(base_problem(full_frac=-0.1)) == -3
+    assert status(base_problem(exact_frac=float("nan"))) == -3
+    assert status(base_problem(dtype="f16")) == -4
+    assert status(base_problem(gamma=0.1)) == -5
+    assert status(base_problem(), strides=(0, 0, 60)) == -2                # stride_t < D
+    assert status(base_problem(), strides=(8 * 1024 * 64, 1024 * 64 + 4, 64)) == -2
+    assert I.lib().isa_get_counts(None, 0, None) == -1
+    assert I.isa_workspace_bytes(base_problem(D=96)) == 0
+    assert "RATIO" in I.isa_strerror(-3) and I.isa_strerror(0) == "ISA_OK" and "unknown" in I.isa_strerror(-99)
+
+
+def test_null_and_workspace_errors_need_no_gpu():
+    pr = base_problem()
+    cp, keep = pr.c_struct()
+    L = I.lib()
+    one = C.c_void_p(256)   # non-null, 256-aligned dummy; never dereferenced because validation fails first
+    assert L.isa_attention(C.byref(cp), None, one, one, one, one, 1 << 40, None) == -1
+    assert L.isa_attention(C.byref(cp), one, one, one, one, None, 1 << 40, None) == -6
+    assert L.isa_attention(C.byref(cp), one, one, one, one, C.c_void_p(264), 1 << 40, None) == -6
+    assert L.isa_attention(C.byref(cp), one, one, one, one, one, 16, None) == -6
+    assert L.isa_dense_attention(C.byref(cp), one, one, one, None, one, 1 << 40, None) == -1
+    assert L.isa_attention_simple(one, one, one, 2, 64, 0, 10, 0.5, 0.5, 64, one, None) == -2
+
+
+@pytest.mark.parametrize("seg,block,keep,full,exact", [
+    ([[512, 512]], 64, 0.5, 0.25, 0.0),
+    ([[7800, 7800]], 128, 0.5, 0.25, 0.0625),
+    ([[32760, 1560, 32760], [32760, 17160]], 128, 0.75, 0.4, 0.0625),
+    ([[75600, 75600]], 128, 0.5, 0.2, 0.0),
+    ([[130]], 128, 0.3, 0.9, 0.5),
+    ([[1000, 77, 1, 129]], 64, 0.1, 0.1, 0.1),
+])
+def test_counts_agree_with_oracle(seg, block, keep, full, exact):
+    pr = base_problem(seg_len=seg, block=block, keep_ratio=keep, full_frac=full, exact_frac=exact)
+    for b, s in enumerate(seg):
+        c = I.isa_get_counts(pr, b)
+        starts, counts, T_src = O.block_layout(s, block)
+        T = len(starts)
+        assert (c["S"], c["T"], c["T_src"], c["T_ctx"]) == (sum(s), T, T_src, T - T_src)
+        assert c["k_keep"] == O.keep_count(keep, T - T_src) and c["T_new"] == T_src + c["k_keep"]
+        assert (c["n_full"], c["n_flat"]) == O.group_counts(full, T)
+        assert c["k_exact"] == O.exact_count(exact, c["T_new"])
+    assert I.isa_workspace_bytes(pr) > 0
