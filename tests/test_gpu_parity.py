@@ -155,7 +155,7 @@ def test_select_many_blocks(I):
 # ------------------------------------------------------------------------------------------------
 # (iii) attention on the oracle's lists
 # ------------------------------------------------------------------------------------------------
-def _attend_with_oracle_lists(I, wl, exact_frac=0.0, mfma=True):
+def _attend_with_oracle_lists(I, wl, exact_frac=0.0, mfma=None):
     Q, K, V, q, k, v = gen(wl)
     wl = wl.with_(exact_frac=exact_frac)
     pr = problem_of(wl)
@@ -181,7 +181,8 @@ def _attend_with_oracle_lists(I, wl, exact_frac=0.0, mfma=True):
                             words[r, t >> 5] |= np.uint32(1 << (t & 31))
                 buf["mask"][b, h] = torch.from_numpy(words.view(np.int32))
     out = torch.full_like(q, float("nan"))
-    prev = I.isa_set_mfma(mfma)
+    prev = I.isa_set_mfma(True)
+    I.isa_set_mfma(prev if mfma is None else mfma)
     try:
         I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"],
                      buf["mask"] if exact_frac > 0 else None, out, ws)

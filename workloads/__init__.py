@@ -10,8 +10,8 @@ Recipe (one per configuration, all seeded):
     source segment comes first, then every context reference;
   * K and V: per (batch, head, channel, segment) an independent N(0,1) field
     on the segment's grid, smoothed with a separable Gaussian (sigma = 2
-    tokens, radius 6, renormalised at the borders), rescaled to unit standard
-    deviation, plus 0.3 * N(0,1) white noise;
+    tokens, radius 6, renormalised at the borders), centred and rescaled to
+    unit standard deviation, plus 0.3 * N(0,1) white noise;
   * context keys are multiplied by 0.5 (context is less salient than source);
   * Q: N(0,1) times a per-(batch, head, token) factor drawn log-uniformly
     from [0.5, 4];
@@ -103,7 +103,8 @@ def smooth_field(n_fields: int, grid: Grid, gen: torch.Generator, device, sigma=
     for axis in (1, 2, 3):
         f = _smooth_axis(f, axis, wts)
     f = f.reshape(n_fields, -1)
-    f = f / f.std(dim=1, unbiased=False, keepdim=True).clamp_min(1e-12)
+    f = f - f.mean(dim=1, keepdim=True)            # small grids: keep the field centred before rescaling
+    f = f / f.std(dim=1, unbiased=False, keepdim=True).clamp_min(1e-6)
     f = f + noise * torch.randn(f.shape, generator=gen, device=device, dtype=torch.float32)
     return f
 
