@@ -1,10 +1,413 @@
-// MFMA attention kernels (bf16, D = 128, block = 128): placeholder until the kernels land.
+// MFMA attention kernels for bf16, D = 128, block = 128 on gfx950 (wave64, v_mfma_f32_32x32x16_bf16).
+//
+// One workgroup (4 waves) owns one query block of 128 rows; wave w owns rows 32w .. 32w+31.  Two
+// workgroups fit a compute unit (<= 256 VGPRs, 70 KB LDS each) so that one wave's softmax VALU work
+// overlaps another wave's MFMA work on the same SIMD.
+//
+// Scores are computed transposed, S^T = K Q^T (M = keys, N = queries), so that the accumulator layout of
+// the MFMA (a lane holds one query column and 16 key rows per 32-key group) is already the B-operand
+// layout of the second product O^T = V^T P^T: P never leaves registers, and the row maximum / row sum of
+// the online softmax (Alg. 2 Part A) need one cross-lane exchange only.  The A operand of the second
+// product wants, per lane, 8 consecutive keys of one channel; V is therefore read from a copy that the
+// pack kernel stores transposed per 64-key half block, with key positions permuted to the accumulator's
+// key order (bits 2 and 3 of the key index swapped).
+//
+// The Taylor branch (Sec. 3, Eq. 4; Alg. 2 Part B) runs through the same tile code: its "keys" are the
+// block means gathered in kv_list order, its "values" the gathered mean values, and the token count n_j
+// enters as an additive log2(n_j) on the scaled logit, which is the same as weighting exp() by n_j.
 #include "isa_internal.h"
 
 namespace isa {
-hipError_t launch_pack_vt(const Problem&, const Workspace&, const void*, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_gather_means(const Problem&, const Workspace&, const float*, const float*, const int*, hipStream_t) {
-  return hipErrorNotSupported;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int MD = 128;           // head dim
+constexpr int KT = 64;            // keys per LDS tile
+constexpr int KS = 136;           // LDS row stride of the K tile in bf16 elements (272 B: conflict-free b128 reads)
+constexpr int VS = 72;            // LDS row stride of the V^T tile in bf16 elements (144 B)
+constexpr int K_TILE = KT * KS;   // elements
+constexpr int V_TILE = MD * VS;
+constexpr size_t MFMA_LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;
+constexpr float RESCALE_TAU = 8.0f;    // the running max is only raised when a tile exceeds it by 2^tau
+constexpr float M_INIT = -1.0e30f;
+
+__device__ inline uint16_t f2bf(float f) {     // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
-hipError_t launch_attn_mfma(const Problem&, const Workspace&, const AttnArgs&, hipStream_t) { return hipErrorNotSupported; }
+__device__ inline int swap23(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
+
+// ------------------------------------------------------------------------------------------
+// Pack kernels
+// ------------------------------------------------------------------------------------------
+// V^T copy: vt[((bh*T_max + j)*2 + half)][d][pos], pos = swap23(key % 64); keys past n_j are zero.
+__global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
+                                                 const int* __restrict__ blk_start, const int* __restrict__ blk_n,
+                                                 Geometry g) {
+  __shared__ uint16_t tile[128][MD + 2];
+  const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int n = blk_n[b * g.T_max + j];
+  if (n == 0) return;
+  const int start = blk_start[b * g.T_max + j];
+  const long long base = (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)start * g.stride_t;
+  for (int x = threadIdx.x; x < 128 * 16; x += 256) {          // 16-byte chunks
+    const int r = x >> 4, c = x & 15;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < n) val = *reinterpret_cast<const uint4*>(v + base + (long long)r * g.stride_t + c * 8);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[r][c * 8]);
+    dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
+  }
+  __syncthreads();
+  uint16_t* out = vt + (((long long)b * g.H + h) * g.T_max + j) * (2 * MD * KT);
+  for (int x = threadIdx.x; x < 2 * MD * 8; x += 256) {         // one 16-byte chunk = 8 key positions of one channel
+    const int half = x / (MD * 8), rem = x % (MD * 8);
+    const int d = rem >> 3, pc = rem & 7;
+    uint16_t e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = tile[half * 64 + swap23(pc * 8 + i)][d];    // swap23 is an involution
+    uint4 o;
+    o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
+    o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
+    *reinterpret_cast<uint4*>(out + (half * MD + d) * KT + pc * 8) = o;
+  }
+}
+
+hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, hipStream_t st) {
+  hipLaunchKernelGGL(k_pack_vt, dim3(pr.cnt.T_max, pr.p.H, pr.p.B), dim3(256), 0, st, (const uint16_t*)v, ws.vt,
+                     ws.blk_start, ws.blk_n, pr.geo);
+  return hipGetLastError();
+}
+
+// Mean keys / values gathered in kv_list order, rounded to bf16, in the layouts the attention kernel reads:
+// kcn[bh][t][d]; vcnt[bh][t/64][d][swap23(t%64)]; biasn[bh][t] = log2(n_j), -inf past T_new.
+__global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
+                                                      const int* __restrict__ kv_list, const int* __restrict__ blk_n,
+                                                      uint16_t* __restrict__ kcn, uint16_t* __restrict__ vcnt,
+                                                      float* __restrict__ biasn, Counts cnt, int H, int Tn_pad) {
+  __shared__ uint16_t vtile[KT][MD + 2];
+  __shared__ int ids[KT];
+  const int tile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int T_new = cnt.b[b].T_new, T_max = cnt.T_max;
+  const long long bh = (long long)b * H + h;
+  const int t0 = tile * KT;
+  if (threadIdx.x < KT) {
+    const int t = t0 + threadIdx.x;
+    const int j = t < T_new ? kv_list[bh * T_max + t] : -1;
+    ids[threadIdx.x] = j;
+    biasn[bh * Tn_pad + t] = j >= 0 ? log2f((float)blk_n[b * T_max + j]) : -INFINITY;
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < KT * MD; x += 256) {
+    const int r = x / MD, d = x % MD;
+    const int j = ids[r];
+    float kval = 0.f, vval = 0.f;
+    if (j >= 0) {
+      kval = kc[(bh * T_max + j) * MD + d];
+      vval = vc[(bh * T_max + j) * MD + d];
+    }
+    kcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kval);
+    vtile[r][d] = f2bf(vval);
+  }
+  __syncthreads();
+  uint16_t* out = vcnt + (bh * (Tn_pad / KT) + tile) * (MD * KT);
+  for (int x = threadIdx.x; x < MD * KT; x += 256) {
+    const int d = x / KT, pos = x % KT;
+    out[d * KT + pos] = vtile[swap23(pos)][d];
+  }
+}
+
+hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
+                               const int* kv_list, hipStream_t st) {
+  hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
+                     ws.kcn, ws.vcnt, ws.biasn, pr.cnt, pr.p.H, pr.Tn_pad);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention kernel
+// ------------------------------------------------------------------------------------------
+struct MfmaArgs {
+  const uint16_t* q; const uint16_t* k; uint16_t* out;
+  const uint16_t* vt;                       // packed V^T
+  const uint16_t* kcn; const uint16_t* vcnt; const float* biasn;
+  const int* blk_start; const int* blk_n;
+  const int* kv_list; const int* full_list; const int* flat_list;
+  const uint32_t* exact_mask;
+  Geometry geo;
+  Counts cnt;
+  int dense;
+  int Tn_pad;
+  int slots;                                // work slots per (batch, head) = T_max
+  int total;                                // B * H * slots
+};
+
+struct Tile {                               // wave-uniform description of one 64-key tile
+  const uint16_t* krows;                    // first key row
+  long long kstride;                        // elements between key rows
+  const uint16_t* vt;                       // 128 x 64 packed V^T
+  const float* bias;                        // per-key additive term in the log2 domain, or null
+  int nk;                                   // valid keys (1..64)
+  int tpos;                                 // position of key 0 in kv_list (mean tiles), for the exact mask
+};
+
+__global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  uint16_t* ldsK = lds;                     // [2][K_TILE]
+  uint16_t* ldsV = lds + 2 * K_TILE;        // [2][V_TILE]
+
+  // ---- which work item: consecutive logical ids go to the same XCD, so that the workgroups that run
+  // together on one XCD (and share its L2) read the same head's keys and values
+  const int nwg = gridDim.x;
+  const int per_xcd = nwg >> 3;             // grid is a multiple of 8
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.total) return;
+  const int slot = logical % a.slots;
+  const int bhid = logical / a.slots;
+  const int h = bhid % a.geo.H, b = bhid / a.geo.H;
+  const BatchCounts c = a.cnt.b[b];
+  if (slot >= c.T) return;
+  const int T_max = a.geo.T_max;
+  const long long bh = bhid;
+
+  int qi, n_list;
+  bool taylor = false;
+  const int* kvl = nullptr;
+  if (a.dense) {
+    qi = slot;
+    n_list = c.T;
+  } else {
+    kvl = a.kv_list + bh * T_max;
+    n_list = c.T_new;
+    if (slot < c.n_full) qi = a.full_list[bh * T_max + slot];
+    else { qi = a.flat_list[bh * T_max + slot - c.n_full]; taylor = true; }
+  }
+  const uint32_t* mrow = (taylor && a.exact_mask && c.k_exact > 0)
+                             ? a.exact_mask + (bh * T_max + (slot - c.n_full)) * a.cnt.mask_words : nullptr;
+  const int n_q = a.blk_n[b * T_max + qi];
+  const int q_start = a.blk_start[b * T_max + qi];
+  const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, g = lane >> 5;
+
+  // ---- Q fragments: B operand of S^T = K Q^T; lane holds channels 16s + 8g .. +7 of its query row
+  const int row = wave * 32 + col;
+  const bool row_ok = row < n_q;
+  const uint16_t* qp = a.q + tbase + (long long)(q_start + (row_ok ? row : 0)) * a.geo.stride_t + 8 * g;
+  bf16x8 qf[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
+  float m_run = M_INIT, l_run = 0.f;
+  const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
+
+  // ---- tile sequence: phase A = token tiles of list entries, phase B = mean tiles (Taylor only)
+  int it_t = 0, it_sub = 0, it_mean = 0;
+  const int n_mean_tiles = taylor ? (n_list + KT - 1) / KT : 0;
+  auto next_tile = [&](Tile& t) -> bool {
+    while (it_t < n_list) {
+      if (taylor && !(mrow && ((mrow[it_t >> 5] >> (it_t & 31)) & 1u))) { ++it_t; continue; }
+      const int j = a.dense ? it_t : kvl[it_t];
+      const int n_j = a.blk_n[b * T_max + j];
+      const int k0 = it_sub * KT;
+      if (k0 >= n_j) { ++it_t; it_sub = 0; continue; }
+      t.krows = a.k + tbase + (long long)(a.blk_start[b * T_max + j] + k0) * a.geo.stride_t;
+      t.kstride = a.geo.stride_t;
+      t.vt = a.vt + ((bh * T_max + j) * 2 + it_sub) * (long long)(MD * KT);
+      t.bias = nullptr;
+      t.nk = min(KT, n_j - k0);
+      t.tpos = 0;
+      if (++it_sub == 2) { it_sub = 0; ++it_t; }
+      return true;
+    }
+    if (it_mean < n_mean_tiles) {
+      const long long row0 = bh * a.Tn_pad + (long long)it_mean * KT;
+      t.krows = a.kcn + row0 * MD;
+      t.kstride = MD;
+      t.vt = a.vcnt + (bh * (a.Tn_pad / KT) + it_mean) * (long long)(MD * KT);
+      t.bias = a.biasn + row0;
+      t.nk = min(KT, n_list - it_mean * KT);
+      t.tpos = it_mean * KT;
+      ++it_mean;
+      return true;
+    }
+    return false;
+  };
+
+  // ---- global -> register staging of one tile (K: 64 rows x 16 chunks; V^T: 128 rows x 8 chunks)
+  uint4 stK[4], stV[4];
+  auto load_tile = [&](const Tile& t) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ch = tid + 256 * i;
+      const int r = min(ch >> 4, t.nk - 1), cc = ch & 15;           // rows past nk re-read the last valid row
+      stK[i] = *reinterpret_cast<const uint4*>(t.krows + (long long)r * t.kstride + cc * 8);
+      stV[i] = *reinterpret_cast<const uint4*>(t.vt + ch * 8);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ch = tid + 256 * i;
+      *reinterpret_cast<uint4*>(ldsK + buf * K_TILE + (ch >> 4) * KS + (ch & 15) * 8) = stK[i];
+      *reinterpret_cast<uint4*>(ldsV + buf * V_TILE + (ch >> 3) * VS + (ch & 7) * 8) = stV[i];
+    }
+  };
+
+  Tile cur, nxt;
+  bool have = next_tile(cur);
+  if (have) {
+    load_tile(cur);
+    store_tile(0);
+  }
+  __syncthreads();
+  int buf = 0;
+  while (have) {
+    const bool have_next = next_tile(nxt);
+    if (have_next) load_tile(nxt);
+
+    // ---- S^T = K Q^T for 64 keys x 32 queries
+    f32x16 sacc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
+    const uint16_t* kbase = ldsK + buf * K_TILE + col * KS + 8 * g;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 af = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * KS + 16 * s);
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[s], sacc[kb], 0, 0, 0);
+      }
+    }
+
+    // ---- online softmax in the log2 domain; accumulator element e of group kb is key 32kb + 8(e/4) + 4g + e%4
+    const bool general = (cur.bias != nullptr) || (cur.nk < KT);
+    float tmax;
+    if (general) {
+      uint32_t mw0 = 0, mw1 = 0;
+      if (mrow && cur.bias) { mw0 = mrow[cur.tpos >> 5]; mw1 = mrow[(cur.tpos >> 5) + 1 < a.cnt.mask_words ? (cur.tpos >> 5) + 1 : (cur.tpos >> 5)]; }
+      tmax = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int key = 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3);
+          float add = 0.f;
+          if (cur.bias) add = cur.bias[key < cur.nk ? key : 0];
+          if (key >= cur.nk) add = -INFINITY;
+          if (mrow && cur.bias && (((kb ? mw1 : mw0) >> (key & 31)) & 1u)) add = -INFINITY;
+          const float t = fmaf(sacc[kb][e], cscale, add);
+          sacc[kb][e] = t;
+          tmax = fmaxf(tmax, t);
+        }
+    } else {
+      float mx = sacc[0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][e]);
+      tmax = mx * cscale;
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const bool raise = tmax > m_run + RESCALE_TAU;
+    if (__ballot(raise) != 0ull) {                     // rare after the first tiles: rescale the accumulators
+      const float m_new = raise ? tmax : m_run;
+      const float alpha = exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+    }
+    bf16x8 pf[4];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        float p0, p1;
+        if (general) {
+          p0 = __builtin_amdgcn_exp2f(sacc[kb][e] - m_run);
+          p1 = __builtin_amdgcn_exp2f(sacc[kb][e + 1] - m_run);
+        } else {
+          p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], cscale, -m_run));
+          p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e + 1], cscale, -m_run));
+        }
+        bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
+        pf[kb * 2 + (e >> 3)][e & 7] = pp[0];
+        pf[kb * 2 + (e >> 3)][(e & 7) + 1] = pp[1];
+      }
+
+    // ---- O^T += V^T P^T
+    const uint16_t* vbase = ldsV + buf * V_TILE + col * VS + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x8 af = *reinterpret_cast<const bf16x8*>(vbase + db * 32 * VS + 16 * ks);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pf[ks], oacc[db], 0, 0, 0);
+      }
+    }
+
+    if (have_next) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+    cur = nxt;
+    have = have_next;
+  }
+
+  // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (row_ok) {
+    const float inv = 1.0f / l_tot;
+    uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        bf16x2 lo = {(__bf16)(oacc[db][4 * e4] * inv), (__bf16)(oacc[db][4 * e4 + 1] * inv)};
+        bf16x2 hi = {(__bf16)(oacc[db][4 * e4 + 2] * inv), (__bf16)(oacc[db][4 * e4 + 3] * inv)};
+        uint2 o;
+        o.x = *reinterpret_cast<uint32_t*>(&lo);
+        o.y = *reinterpret_cast<uint32_t*>(&hi);
+        *reinterpret_cast<uint2*>(op + 32 * db + 8 * e4) = o;
+      }
+  }
+}
+
+hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_attn_mfma, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)MFMA_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  MfmaArgs m;
+  m.q = (const uint16_t*)a.q; m.k = (const uint16_t*)a.k; m.out = (uint16_t*)a.out;
+  m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn;
+  m.blk_start = a.blk_start; m.blk_n = a.blk_n;
+  m.kv_list = a.kv_list; m.full_list = a.full_list; m.flat_list = a.flat_list;
+  m.exact_mask = a.exact_mask;
+  m.geo = a.geo; m.cnt = a.cnt; m.dense = a.dense;
+  m.Tn_pad = pr.Tn_pad;
+  m.slots = pr.cnt.T_max;
+  m.total = pr.p.B * pr.p.H * pr.cnt.T_max;
+  const int grid = (m.total + 7) / 8 * 8;
+  hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(256), MFMA_LDS_BYTES, st, m);
+  return hipGetLastError();
+}
+
 }  // namespace isa

@@ -10,7 +10,7 @@
 namespace isa {
 
 static thread_local int g_last_hip = 0;
-static std::atomic<int> g_use_mfma{0};   // flipped to 1 once the MFMA kernels are in
+static std::atomic<int> g_use_mfma{1};
 
 static inline bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }   // false for NaN
 
