@@ -160,6 +160,14 @@ int isa_last_hip_error(void);
  * Returns the previous setting.  Process-wide; meant for tests and comparisons. */
 int isa_set_mfma(int enabled);
 
+/* Measurement hook.  isa_time_attention_kernel(1) makes every later launch of the MFMA attention kernel record a
+ * pair of HIP events (created by the library on first use) just before and just after the kernel on the launch
+ * stream; isa_time_attention_kernel(0) switches that off.  isa_last_attention_kernel_ms() waits for the most
+ * recently recorded pair and returns the kernel's duration in milliseconds (ISA_ERR_UNSUPPORTED if none was
+ * recorded).  Process-wide; not for concurrent callers. */
+int isa_time_attention_kernel(int enabled);
+int isa_last_attention_kernel_ms(float* ms);
+
 #ifdef __cplusplus
 }
 #endif

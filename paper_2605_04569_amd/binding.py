@@ -64,6 +64,8 @@ def lib():
         L.isa_strerror.restype = C.c_char_p
         L.isa_last_hip_error.argtypes = []
         L.isa_set_mfma.argtypes = [C.c_int]
+        L.isa_time_attention_kernel.argtypes = [C.c_int]
+        L.isa_last_attention_kernel_ms.argtypes = [C.POINTER(C.c_float)]
         _LIB = L
     return _LIB
 
@@ -129,6 +131,16 @@ def isa_strerror(code: int) -> str:
 
 def isa_set_mfma(enabled: bool) -> int:
     return lib().isa_set_mfma(1 if enabled else 0)
+
+
+def isa_time_attention_kernel(enabled: bool):
+    _check(lib().isa_time_attention_kernel(1 if enabled else 0), "isa_time_attention_kernel")
+
+
+def isa_last_attention_kernel_ms() -> float:
+    ms = C.c_float()
+    _check(lib().isa_last_attention_kernel_ms(C.byref(ms)), "isa_last_attention_kernel_ms")
+    return ms.value
 
 
 def isa_get_counts(pr: Problem, b: int = 0) -> dict:

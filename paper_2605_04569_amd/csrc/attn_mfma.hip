@@ -406,8 +406,15 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   m.slots = pr.cnt.T_max;
   m.total = pr.p.B * pr.p.H * pr.cnt.T_max;
   const int grid = (m.total + 7) / 8 * 8;
+  const bool prof = g_prof_on && g_prof_start && g_prof_stop;
+  if (prof) (void)hipEventRecord(g_prof_start, st);
   hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(256), MFMA_LDS_BYTES, st, m);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (prof) {
+    (void)hipEventRecord(g_prof_stop, st);
+    g_prof_recorded = 1;
+  }
+  return e;
 }
 
 }  // namespace isa

@@ -10,6 +10,8 @@
 namespace isa {
 
 static thread_local int g_last_hip = 0;
+hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+int g_prof_on = 0, g_prof_recorded = 0;
 static std::atomic<int> g_use_mfma{1};
 
 static inline bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }   // false for NaN
@@ -314,5 +316,22 @@ const char* isa_strerror(int status) {
 int isa_last_hip_error(void) { return g_last_hip; }
 
 int isa_set_mfma(int enabled) { return g_use_mfma.exchange(enabled ? 1 : 0); }
+
+int isa_time_attention_kernel(int enabled) {
+  if (enabled && !isa::g_prof_start) {
+    ISA_TRY(hipEventCreate(&isa::g_prof_start));
+    ISA_TRY(hipEventCreate(&isa::g_prof_stop));
+  }
+  isa::g_prof_on = enabled ? 1 : 0;
+  return ISA_OK;
+}
+
+int isa_last_attention_kernel_ms(float* ms) {
+  if (!ms) return ISA_ERR_NULL;
+  if (!isa::g_prof_recorded) return ISA_ERR_UNSUPPORTED;
+  ISA_TRY(hipEventSynchronize(isa::g_prof_stop));
+  ISA_TRY(hipEventElapsedTime(ms, isa::g_prof_start, isa::g_prof_stop));
+  return ISA_OK;
+}
 
 }  // extern "C"

@@ -64,6 +64,9 @@ struct Problem {          // validated problem + everything derived from it
   bool mfma_shape;        // bf16, D = 128, block = 128
 };
 
+extern hipEvent_t g_prof_start, g_prof_stop;   // events recorded around the MFMA attention kernel when g_prof_on
+extern int g_prof_on, g_prof_recorded;
+
 int validate(const isa_problem* p, Problem* out);
 void carve(const Problem& pr, void* base, Workspace* ws);
 

@@ -83,16 +83,21 @@ def _gauss_weights(sigma: float, radius: int, device) -> torch.Tensor:
 
 
 def _smooth_axis(x: torch.Tensor, axis: int, w: torch.Tensor) -> torch.Tensor:
-    """Filter along one grid axis with zero padding, renormalised at the borders."""
+    """Filter along one grid axis with zero padding, renormalised at the borders.
+    Written as a sum of shifted slices (plain elementwise kernels on any device)."""
     radius = (w.numel() - 1) // 2
-    x = x.movedim(axis, -1)
-    shp = x.shape
-    n = shp[-1]
-    flat = x.reshape(-1, 1, n)
-    y = torch.nn.functional.conv1d(flat, w.view(1, 1, -1), padding=radius)
-    norm = torch.nn.functional.conv1d(torch.ones(1, 1, n, device=x.device), w.view(1, 1, -1), padding=radius)
-    y = (y / norm).reshape(shp)
-    return y.movedim(-1, axis)
+    n = x.shape[axis]
+    pad = [0, 0] * (x.dim() - 1 - axis) + [radius, radius]
+    xp = torch.nn.functional.pad(x, pad)
+    ones = torch.nn.functional.pad(torch.ones(n, device=x.device, dtype=x.dtype), [radius, radius])
+    y = torch.zeros_like(x)
+    norm = torch.zeros(n, device=x.device, dtype=x.dtype)
+    for k in range(w.numel()):
+        y = y + float(w[k]) * xp.narrow(axis, k, n)
+        norm = norm + float(w[k]) * ones[k:k + n]
+    shape = [1] * x.dim()
+    shape[axis] = n
+    return y / norm.view(shape)
 
 
 def smooth_field(n_fields: int, grid: Grid, gen: torch.Generator, device, sigma=2.0, radius=6, noise=0.3):
