@@ -1,7 +1,7 @@
 // MFMA attention kernels for bf16, D = 128, block = 128 on gfx950 (wave64, v_mfma_f32_32x32x16_bf16).
 //
 // One workgroup (4 waves) owns one query block of 128 rows; wave w owns rows 32w .. 32w+31.  Two
-// workgroups fit a compute unit (<= 256 VGPRs, 70 KB LDS each) so that one wave's softmax VALU work
+// workgroups fit a compute unit (<= 256 VGPRs, 64 KB LDS each) so that one wave's softmax VALU work
 // overlaps another wave's MFMA work on the same SIMD.
 //
 // Scores are computed transposed, S^T = K Q^T (M = keys, N = queries), so that the accumulator layout of
@@ -25,11 +25,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int MD = 128;           // head dim
 constexpr int KT = 64;            // keys per LDS tile
-constexpr int KS = 136;           // LDS row stride of the K tile in bf16 elements (272 B: conflict-free b128 reads)
-constexpr int VS = 72;            // LDS row stride of the V^T tile in bf16 elements (144 B)
-constexpr int K_TILE = KT * KS;   // elements
-constexpr int V_TILE = MD * VS;
-constexpr size_t MFMA_LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;
+constexpr int K_TILE = KT * MD;   // bf16 elements of one K tile in LDS: 64 rows x 256 B, 16-byte chunks XOR-swizzled
+constexpr int V_TILE = MD * KT;   // bf16 elements of one V^T tile in LDS: 128 rows x 128 B, 16-byte chunks XOR-swizzled
+constexpr size_t MFMA_LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;   // 64 KB: two workgroups per compute unit
 constexpr float RESCALE_TAU = 8.0f;    // the running max is only raised when a tile exceeds it by 2^tau
 constexpr float M_INIT = -1.0e30f;
 
@@ -145,16 +143,105 @@ struct MfmaArgs {
 };
 
 struct Tile {                               // wave-uniform description of one 64-key tile
-  const uint16_t* krows;                    // first key row
-  long long kstride;                        // elements between key rows
+  const uint16_t* krows;                    // row 0 of the block (token tiles) or of the tile (mean tiles)
+  int row0;                                 // first row of the tile relative to krows
+  int kstride;                              // elements between key rows
   const uint16_t* vt;                       // 128 x 64 packed V^T
   const float* bias;                        // per-key additive term in the log2 domain, or null
-  int nk;                                   // valid keys (1..64)
+  int nk;                                   // valid keys (0..64); rows past it are masked
+  int last_row;                             // last row relative to krows that may be read (>= 0)
   int tpos;                                 // position of key 0 in kv_list (mean tiles), for the exact mask
 };
 
+// One 64-key tile for the 32 query columns of a wave: S^T = K Q^T, online softmax in the log2 domain
+// (Alg. 2 Part A / Part B), O^T += V^T P^T.  GENERAL adds the per-key bias and the masks.
+template <bool GENERAL>
+__device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, const uint16_t* __restrict__ vbase,
+                                          const bf16x8 (&qf)[8], f32x16 (&oacc)[4], float& m_run, float& l_run,
+                                          const int (&koff)[8], const int (&voff)[4], float cscale, int g, int nk,
+                                          const float* __restrict__ bias, uint32_t mw0, uint32_t mw1) {
+  f32x16 sacc[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const bf16x8 af = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * MD + koff[s]);
+      sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[s], sacc[kb], 0, 0, 0);
+    }
+  }
+  // accumulator element e of group kb is key 32kb + 8(e/4) + 4g + e%4
+  float tmax;
+  if (GENERAL) {
+    tmax = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const uint32_t mw = kb ? mw1 : mw0;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3);
+        float add = bias ? bias[key] : 0.f;                       // bias arrays are padded to whole tiles
+        add = (key >= nk || ((mw >> (key & 31)) & 1u)) ? -INFINITY : add;
+        const float t = fmaf(sacc[kb][e], cscale, add);
+        sacc[kb][e] = t;
+        tmax = fmaxf(tmax, t);
+      }
+    }
+  } else {
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][e]);
+    tmax = mx * cscale;
+  }
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  const bool raise = tmax > m_run + RESCALE_TAU;
+  if (__ballot(raise) != 0ull) {                     // rare after the first tiles: rescale the accumulators
+    const float m_new = raise ? tmax : m_run;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+  }
+  bf16x8 pf[4];
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  const float neg_m = -m_run;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+      float p0, p1;
+      if (GENERAL) {
+        p0 = __builtin_amdgcn_exp2f(sacc[kb][e] + neg_m);
+        p1 = __builtin_amdgcn_exp2f(sacc[kb][e + 1] + neg_m);
+      } else {
+        p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], cscale, neg_m));
+        p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e + 1], cscale, neg_m));
+      }
+      const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
+      pf[kb * 2 + (e >> 3)][e & 7] = pp[0];
+      pf[kb * 2 + (e >> 3)][(e & 7) + 1] = pp[1];
+    }
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const bf16x8 af = *reinterpret_cast<const bf16x8*>(vbase + db * 32 * KT + voff[ks]);
+      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pf[ks], oacc[db], 0, 0, 0);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE];
   uint16_t* ldsK = lds;                     // [2][K_TILE]
   uint16_t* ldsV = lds + 2 * K_TILE;        // [2][V_TILE]
 
@@ -186,11 +273,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   }
   const uint32_t* mrow = (taylor && a.exact_mask && c.k_exact > 0)
                              ? a.exact_mask + (bh * T_max + (slot - c.n_full)) * a.cnt.mask_words : nullptr;
-  const int n_q = a.blk_n[b * T_max + qi];
-  const int q_start = a.blk_start[b * T_max + qi];
+  const int* bn = a.blk_n + b * T_max;
+  const int* bs = a.blk_start + b * T_max;
+  const int n_q = bn[qi];
+  const int q_start = bs[qi];
   const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, kept in a scalar register
   const int col = lane & 31, g = lane >> 5;
 
   // ---- Q fragments: B operand of S^T = K Q^T; lane holds channels 16s + 8g .. +7 of its query row
@@ -209,32 +299,41 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   float m_run = M_INIT, l_run = 0.f;
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
-  // ---- tile sequence: phase A = token tiles of list entries, phase B = mean tiles (Taylor only)
+  // ---- tile sequence.  Phase A: the token tiles (two 64-key halves) of the list entries that are evaluated
+  // exactly -- all of them for the exact branch and for dense attention, the marked ones for a Taylor block.
+  // Phase B (Taylor only): tiles of 64 gathered block means.
   int it_t = 0, it_sub = 0, it_mean = 0;
+  if (taylor && !mrow) it_t = n_list;
   const int n_mean_tiles = taylor ? (n_list + KT - 1) / KT : 0;
   auto next_tile = [&](Tile& t) -> bool {
-    while (it_t < n_list) {
-      if (taylor && !(mrow && ((mrow[it_t >> 5] >> (it_t & 31)) & 1u))) { ++it_t; continue; }
+    if (mrow) {
+      while (it_t < n_list && !((mrow[it_t >> 5] >> (it_t & 31)) & 1u)) ++it_t;
+    }
+    if (it_t < n_list) {
       const int j = a.dense ? it_t : kvl[it_t];
-      const int n_j = a.blk_n[b * T_max + j];
+      const int n_j = bn[j];
       const int k0 = it_sub * KT;
-      if (k0 >= n_j) { ++it_t; it_sub = 0; continue; }
-      t.krows = a.k + tbase + (long long)(a.blk_start[b * T_max + j] + k0) * a.geo.stride_t;
-      t.kstride = a.geo.stride_t;
+      t.krows = a.k + tbase + (long long)bs[j] * a.geo.stride_t;
+      t.row0 = k0;
+      t.kstride = (int)a.geo.stride_t;
       t.vt = a.vt + ((bh * T_max + j) * 2 + it_sub) * (long long)(MD * KT);
       t.bias = nullptr;
-      t.nk = min(KT, n_j - k0);
+      t.nk = max(0, min(KT, n_j - k0));
+      t.last_row = max(n_j - 1, 0);
       t.tpos = 0;
-      if (++it_sub == 2) { it_sub = 0; ++it_t; }
+      it_t += it_sub;
+      it_sub ^= 1;
       return true;
     }
     if (it_mean < n_mean_tiles) {
       const long long row0 = bh * a.Tn_pad + (long long)it_mean * KT;
       t.krows = a.kcn + row0 * MD;
+      t.row0 = 0;
       t.kstride = MD;
       t.vt = a.vcnt + (bh * (a.Tn_pad / KT) + it_mean) * (long long)(MD * KT);
       t.bias = a.biasn + row0;
       t.nk = min(KT, n_list - it_mean * KT);
+      t.last_row = KT - 1;                                          // the gathered arrays are padded to whole tiles
       t.tpos = it_mean * KT;
       ++it_mean;
       return true;
@@ -242,126 +341,69 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
     return false;
   };
 
-  // ---- global -> register staging of one tile (K: 64 rows x 16 chunks; V^T: 128 rows x 8 chunks)
-  uint4 stK[4], stV[4];
-  auto load_tile = [&](const Tile& t) {
+  // ---- global -> LDS, 16 bytes per lane, no staging registers.  One wave instruction fills 1024 contiguous
+  // LDS bytes (lane i -> bytes 16i..16i+15), so rows cannot be padded; instead the 16-byte chunk c of a row is
+  // stored at chunk position c ^ f(row), applied here on the source side: the lane that fills position pc of
+  // row r fetches chunk pc ^ f(r).  K rows are 256 B (f = r & 15), V^T rows are 128 B (f = (r >> 1) & 7); with
+  // these the 16-lane groups of a b128 fragment read hit 16 different bank groups.
+  // Per-lane constants of the four wave instructions a wave issues per tile and tensor: K row / swizzled chunk
+  // offset, and the V^T source offset (bytes).
+  int krow[4];
+  uint32_t kchunk_b[4], vsrc_b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ch = (wave * 4 + i) * 64 + lane;
+    krow[i] = ch >> 4;
+    kchunk_b[i] = (uint32_t)((((ch & 15) ^ ((ch >> 4) & 15)) * 8) * 2);
+    const int r = ch >> 3;
+    vsrc_b[i] = (uint32_t)((r * KT + (((ch & 7) ^ ((r >> 1) & 7)) * 8)) * 2);
+  }
+  auto load_tile = [&](const Tile& t, int buf) {
+    const char* kb = reinterpret_cast<const char*>(t.krows);
+    const char* vb = reinterpret_cast<const char*>(t.vt);
+    const uint32_t kstride_b = (uint32_t)t.kstride * 2u;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int ch = tid + 256 * i;
-      const int r = min(ch >> 4, t.nk - 1), cc = ch & 15;           // rows past nk re-read the last valid row
-      stK[i] = *reinterpret_cast<const uint4*>(t.krows + (long long)r * t.kstride + cc * 8);
-      stV[i] = *reinterpret_cast<const uint4*>(t.vt + ch * 8);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ch = tid + 256 * i;
-      *reinterpret_cast<uint4*>(ldsK + buf * K_TILE + (ch >> 4) * KS + (ch & 15) * 8) = stK[i];
-      *reinterpret_cast<uint4*>(ldsV + buf * V_TILE + (ch >> 3) * VS + (ch & 7) * 8) = stV[i];
+      const int wchunk = (wave * 4 + i) * 64;                       // first chunk this wave instruction fills
+      // rows past the block's end re-read its last row; the row index is never negative
+      const uint32_t koff_b = (uint32_t)max(min(t.row0 + krow[i], t.last_row), 0) * kstride_b + kchunk_b[i];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + koff_b),
+                                       (__attribute__((address_space(3))) void*)(ldsK + buf * K_TILE + wchunk * 8), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + vsrc_b[i]),
+                                       (__attribute__((address_space(3))) void*)(ldsV + buf * V_TILE + wchunk * 8), 16, 0, 0);
     }
   };
 
+  // per-lane fragment offsets (bf16 elements): K row = col, chunk (2s+g) ^ (col & 15); V^T row = col, chunk (2ks+g) ^ ((col>>1)&7)
+  int koff[8], voff[4];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) koff[s] = col * MD + (((2 * s + g) ^ (col & 15)) * 8);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) voff[ks] = col * KT + (((2 * ks + g) ^ ((col >> 1) & 7)) * 8);
+
   Tile cur, nxt;
   bool have = next_tile(cur);
-  if (have) {
-    load_tile(cur);
-    store_tile(0);
-  }
+  if (have) load_tile(cur, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int buf = 0;
   while (have) {
     const bool have_next = next_tile(nxt);
-    if (have_next) load_tile(nxt);
-
-    // ---- S^T = K Q^T for 64 keys x 32 queries
-    f32x16 sacc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
-    const uint16_t* kbase = ldsK + buf * K_TILE + col * KS + 8 * g;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 af = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * KS + 16 * s);
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[s], sacc[kb], 0, 0, 0);
-      }
-    }
-
-    // ---- online softmax in the log2 domain; accumulator element e of group kb is key 32kb + 8(e/4) + 4g + e%4
-    const bool general = (cur.bias != nullptr) || (cur.nk < KT);
-    float tmax;
-    if (general) {
+    if (have_next) load_tile(nxt, buf ^ 1);
+    const uint16_t* kbase = ldsK + buf * K_TILE;
+    const uint16_t* vbase = ldsV + buf * V_TILE;
+    if (cur.bias != nullptr || cur.nk < KT) {
       uint32_t mw0 = 0, mw1 = 0;
-      if (mrow && cur.bias) { mw0 = mrow[cur.tpos >> 5]; mw1 = mrow[(cur.tpos >> 5) + 1 < a.cnt.mask_words ? (cur.tpos >> 5) + 1 : (cur.tpos >> 5)]; }
-      tmax = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3);
-          float add = 0.f;
-          if (cur.bias) add = cur.bias[key < cur.nk ? key : 0];
-          if (key >= cur.nk) add = -INFINITY;
-          if (mrow && cur.bias && (((kb ? mw1 : mw0) >> (key & 31)) & 1u)) add = -INFINITY;
-          const float t = fmaf(sacc[kb][e], cscale, add);
-          sacc[kb][e] = t;
-          tmax = fmaxf(tmax, t);
-        }
+      if (mrow && cur.bias) {
+        const int w = cur.tpos >> 5;
+        mw0 = mrow[w];
+        mw1 = (w + 1 < a.cnt.mask_words) ? mrow[w + 1] : 0u;
+      }
+      tile_body<true>(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, cur.nk, cur.bias, mw0, mw1);
     } else {
-      float mx = sacc[0][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][e]);
-      tmax = mx * cscale;
+      tile_body<false>(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, KT, nullptr, 0u, 0u);
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const bool raise = tmax > m_run + RESCALE_TAU;
-    if (__ballot(raise) != 0ull) {                     // rare after the first tiles: rescale the accumulators
-      const float m_new = raise ? tmax : m_run;
-      const float alpha = exp2f(m_run - m_new);
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
-    }
-    bf16x8 pf[4];
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; e += 2) {
-        float p0, p1;
-        if (general) {
-          p0 = __builtin_amdgcn_exp2f(sacc[kb][e] - m_run);
-          p1 = __builtin_amdgcn_exp2f(sacc[kb][e + 1] - m_run);
-        } else {
-          p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], cscale, -m_run));
-          p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e + 1], cscale, -m_run));
-        }
-        bf16x2 pp = {(__bf16)p0, (__bf16)p1};
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
-        pf[kb * 2 + (e >> 3)][e & 7] = pp[0];
-        pf[kb * 2 + (e >> 3)][(e & 7) + 1] = pp[1];
-      }
-
-    // ---- O^T += V^T P^T
-    const uint16_t* vbase = ldsV + buf * V_TILE + col * VS + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x8 af = *reinterpret_cast<const bf16x8*>(vbase + db * 32 * VS + 16 * ks);
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pf[ks], oacc[db], 0, 0, 0);
-      }
-    }
-
-    if (have_next) store_tile(buf ^ 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     buf ^= 1;
     cur = nxt;
@@ -388,13 +430,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
 }
 
 hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_attn_mfma, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)MFMA_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   MfmaArgs m;
   m.q = (const uint16_t*)a.q; m.k = (const uint16_t*)a.k; m.out = (uint16_t*)a.out;
   m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn;
@@ -408,7 +443,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   const int grid = (m.total + 7) / 8 * 8;
   const bool prof = g_prof_on && g_prof_start && g_prof_stop;
   if (prof) (void)hipEventRecord(g_prof_start, st);
-  hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(256), MFMA_LDS_BYTES, st, m);
+  hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(256), 0, st, m);
   hipError_t e = hipGetLastError();
   if (prof) {
     (void)hipEventRecord(g_prof_stop, st);
