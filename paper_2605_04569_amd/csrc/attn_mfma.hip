@@ -14,7 +14,7 @@
 //
 // The Taylor branch (Sec. 3, Eq. 4; Alg. 2 Part B) runs through the same tile code: its "keys" are the
 // block means gathered in kv_list order, its "values" the gathered mean values, and the token count n_j
-// enters as an additive log2(n_j) on the scaled logit, which is the same as weighting exp() by n_j.
+// enters as an additive ln(n_j) on the scaled logit, which is the same as weighting exp() by n_j.
 #include "isa_internal.h"
 
 namespace isa {
@@ -80,7 +80,7 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
 }
 
 // Mean keys / values gathered in kv_list order, rounded to bf16, in the layouts the attention kernel reads:
-// kcn[bh][t][d]; vcnt[bh][t/64][d][swap23(t%64)]; biasn[bh][t] = log2(n_j), -inf past T_new.
+// kcn[bh][t][d]; vcnt[bh][t/64][d][swap23(t%64)]; biasn[bh][t] = ln(n_j) sqrt(D), -inf past T_new.
 __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
                                                       const int* __restrict__ kv_list, const int* __restrict__ blk_n,
                                                       uint16_t* __restrict__ kcn, uint16_t* __restrict__ vcnt,
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     const int t = t0 + threadIdx.x;
     const int j = t < T_new ? kv_list[bh * T_max + t] : -1;
     ids[threadIdx.x] = j;
-    biasn[bh * Tn_pad + t] = j >= 0 ? log2f((float)blk_n[b * T_max + j]) : -INFINITY;
+    // ln(n_j) * sqrt(D): added to the raw score q.k, it becomes ln(n_j) after the 1/sqrt(D) scaling
+    biasn[bh * Tn_pad + t] = j >= 0 ? logf((float)blk_n[b * T_max + j]) * sqrtf((float)MD) : -INFINITY;
   }
   __syncthreads();
   for (int x = threadIdx.x; x < KT * MD; x += 256) {
@@ -147,57 +148,69 @@ struct Tile {                               // wave-uniform description of one 6
   int row0;                                 // first row of the tile relative to krows
   int kstride;                              // elements between key rows
   const uint16_t* vt;                       // 128 x 64 packed V^T
-  const float* bias;                        // per-key additive term in the log2 domain, or null
+  const float* bias;                        // per-key additive term on the raw score, or null
   int nk;                                   // valid keys (0..64); rows past it are masked
   int last_row;                             // last row relative to krows that may be read (>= 0)
   int tpos;                                 // position of key 0 in kv_list (mean tiles), for the exact mask
 };
 
 // One 64-key tile for the 32 query columns of a wave: S^T = K Q^T, online softmax in the log2 domain
-// (Alg. 2 Part A / Part B), O^T += V^T P^T.  GENERAL adds the per-key bias and the masks.
-template <bool GENERAL>
+// (Alg. 2 Part A / Part B), O^T += V^T P^T.  When `general` (wave-uniform) the per-key bias and the masks are
+// added to the raw scores first; the bias arrives pre-divided by the softmax scale so that both cases share
+// the rest of the code.
 __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[8], f32x16 (&oacc)[4], float& m_run, float& l_run,
-                                          const int (&koff)[8], const int (&voff)[4], float cscale, int g, int nk,
-                                          const float* __restrict__ bias, uint32_t mw0, uint32_t mw1) {
+                                          const int (&koff)[8], const int (&voff)[4], float cscale, int g, bool general,
+                                          int nk, const float* __restrict__ bias, uint32_t mw0, uint32_t mw1) {
   f32x16 sacc[2];
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
+  // K fragments are fetched from LDS two k-steps ahead of the MFMAs that consume them
+  bf16x8 kf[3][2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) kf[s][kb] = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * MD + koff[s]);
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
+    if (s + 2 < 8) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const bf16x8 af = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * MD + koff[s]);
-      sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[s], sacc[kb], 0, 0, 0);
+      for (int kb = 0; kb < 2; ++kb)
+        kf[(s + 2) % 3][kb] = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * MD + koff[s + 2]);
     }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+      sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s % 3][kb], qf[s], sacc[kb], 0, 0, 0);
   }
   // accumulator element e of group kb is key 32kb + 8(e/4) + 4g + e%4
-  float tmax;
-  if (GENERAL) {
-    tmax = -INFINITY;
+  if (general) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       const uint32_t mw = kb ? mw1 : mw0;
+      float addv[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) addv[e] = 0.f;
+      if (bias) {
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {                                  // keys 8*e4 + 4g + 0..3: one 16-byte load
+          const float4 bv = *reinterpret_cast<const float4*>(bias + 32 * kb + 8 * e4 + 4 * g);
+          addv[4 * e4] = bv.x; addv[4 * e4 + 1] = bv.y; addv[4 * e4 + 2] = bv.z; addv[4 * e4 + 3] = bv.w;
+        }
+      }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int key = 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3);
-        float add = bias ? bias[key] : 0.f;                       // bias arrays are padded to whole tiles
-        add = (key >= nk || ((mw >> (key & 31)) & 1u)) ? -INFINITY : add;
-        const float t = fmaf(sacc[kb][e], cscale, add);
-        sacc[kb][e] = t;
-        tmax = fmaxf(tmax, t);
+        const bool off = (key >= nk) || ((mw >> (key & 31)) & 1u);
+        sacc[kb][e] = off ? -INFINITY : sacc[kb][e] + addv[e];
       }
     }
-  } else {
-    float mx = sacc[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][e]);
-    tmax = mx * cscale;
   }
+  float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+  for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(sacc[0][e], sacc[1][e]));
+  float tmax = mx * cscale;
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
   const bool raise = tmax > m_run + RESCALE_TAU;
   if (__ballot(raise) != 0ull) {                     // rare after the first tiles: rescale the accumulators
@@ -217,14 +230,8 @@ __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, co
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int e = 0; e < 16; e += 2) {
-      float p0, p1;
-      if (GENERAL) {
-        p0 = __builtin_amdgcn_exp2f(sacc[kb][e] + neg_m);
-        p1 = __builtin_amdgcn_exp2f(sacc[kb][e + 1] + neg_m);
-      } else {
-        p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], cscale, neg_m));
-        p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e + 1], cscale, neg_m));
-      }
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], cscale, neg_m));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e + 1], cscale, neg_m));
       const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
       l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
       pf[kb * 2 + (e >> 3)][e & 7] = pp[0];
@@ -392,17 +399,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
     if (have_next) load_tile(nxt, buf ^ 1);
     const uint16_t* kbase = ldsK + buf * K_TILE;
     const uint16_t* vbase = ldsV + buf * V_TILE;
-    if (cur.bias != nullptr || cur.nk < KT) {
-      uint32_t mw0 = 0, mw1 = 0;
-      if (mrow && cur.bias) {
-        const int w = cur.tpos >> 5;
-        mw0 = mrow[w];
-        mw1 = (w + 1 < a.cnt.mask_words) ? mrow[w + 1] : 0u;
-      }
-      tile_body<true>(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, cur.nk, cur.bias, mw0, mw1);
-    } else {
-      tile_body<false>(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, KT, nullptr, 0u, 0u);
+    const bool general = cur.bias != nullptr || cur.nk < KT;
+    uint32_t mw0 = 0, mw1 = 0;
+    if (mrow && cur.bias) {
+      const int w = cur.tpos >> 5;
+      mw0 = mrow[w];
+      mw1 = (w + 1 < a.cnt.mask_words) ? mrow[w + 1] : 0u;
     }
+    tile_body(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, general, cur.nk, cur.bias, mw0, mw1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     buf ^= 1;

@@ -51,7 +51,7 @@ struct Workspace {
   uint16_t* vt;          // [B,H,T_max][D][128]: V of each block, transposed and key-permuted
   uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order
   uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
-  float* biasn;          // [B,H,Tn_pad]: log2(n_j) per gathered mean key, -inf for padding
+  float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key, -inf for padding
   size_t bytes;          // total size
 };
 
