@@ -167,23 +167,25 @@ __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, co
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
-  // K fragments are fetched from LDS two k-steps ahead of the MFMAs that consume them
-  bf16x8 kf[3][2];
+  // All 16 K fragments of the tile are requested from LDS up front (64 VGPRs that are free in this phase); the
+  // MFMAs then start as the fragments arrive.  The sched_group_barrier sequence pins that order.
+  bf16x8 kf[8][2];
 #pragma unroll
-  for (int s = 0; s < 2; ++s)
+  for (int s = 0; s < 8; ++s)
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) kf[s][kb] = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * MD + koff[s]);
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    if (s + 2 < 8) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        kf[(s + 2) % 3][kb] = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * MD + koff[s + 2]);
-    }
+  for (int s = 0; s < 8; ++s)
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
-      sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s % 3][kb], qf[s], sacc[kb], 0, 0, 0);
+      sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s][kb], qf[s], sacc[kb], 0, 0, 0);
+  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);     // 8 DS reads
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
   }
+  __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);     // the remaining MFMAs
   // accumulator element e of group kb is key 32kb + 8(e/4) + 4g + e%4
   if (general) {
 #pragma unroll
