@@ -1,0 +1,46 @@
+// Declarations shared by the MFMA attention kernels (bf16, D = 128, block = 128).
+#pragma once
+
+#include "isa_internal.h"
+
+namespace isa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int MD = 128;           // head dim
+constexpr int KT = 64;            // keys per LDS tile
+constexpr int K_TILE = KT * MD;   // bf16 elements of one K tile in LDS: 64 rows x 256 B, 16-byte chunks XOR-swizzled
+constexpr int V_TILE = MD * KT;   // bf16 elements of one V^T tile in LDS: 128 rows x 128 B, 16-byte chunks XOR-swizzled
+constexpr size_t MFMA_LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;   // 64 KB: two workgroups per compute unit
+constexpr float RESCALE_TAU = 8.0f;    // the running max is only raised when a tile exceeds it by 2^tau
+constexpr float M_INIT = -1.0e30f;
+
+__device__ inline uint16_t f2bf(float f) {     // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ inline int swap23(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
+
+struct MfmaArgs {
+  const uint16_t* q; const uint16_t* k; uint16_t* out;
+  const uint16_t* vt;                       // packed V^T
+  const uint16_t* kcn; const uint16_t* vcnt; const float* biasn;
+  const int* blk_start; const int* blk_n;
+  const int* kv_list; const int* full_list; const int* flat_list;
+  const uint32_t* exact_mask;
+  Geometry geo;
+  Counts cnt;
+  int dense;
+  int Tn_pad;
+  int slots;                                // work slots per (batch, head) = T_max
+  int total;                                // B * H * slots
+  int taylor_only;                          // k_attn_mfma: process only the Taylor slots (the exact branch ran elsewhere)
+  int taylor_here;                          // k_attn_pp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only
+};
+
+hipError_t launch_attn_mfma4(const Problem& pr, MfmaArgs m, hipStream_t st);
+
+}  // namespace isa

@@ -15,28 +15,9 @@
 // The Taylor branch (Sec. 3, Eq. 4; Alg. 2 Part B) runs through the same tile code: its "keys" are the
 // block means gathered in kv_list order, its "values" the gathered mean values, and the token count n_j
 // enters as an additive ln(n_j) on the scaled logit, which is the same as weighting exp() by n_j.
-#include "isa_internal.h"
+#include "attn_mfma.h"
 
 namespace isa {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int MD = 128;           // head dim
-constexpr int KT = 64;            // keys per LDS tile
-constexpr int K_TILE = KT * MD;   // bf16 elements of one K tile in LDS: 64 rows x 256 B, 16-byte chunks XOR-swizzled
-constexpr int V_TILE = MD * KT;   // bf16 elements of one V^T tile in LDS: 128 rows x 128 B, 16-byte chunks XOR-swizzled
-constexpr size_t MFMA_LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;   // 64 KB: two workgroups per compute unit
-constexpr float RESCALE_TAU = 8.0f;    // the running max is only raised when a tile exceeds it by 2^tau
-constexpr float M_INIT = -1.0e30f;
-
-__device__ inline uint16_t f2bf(float f) {     // round to nearest even
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-__device__ inline int swap23(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
 
 // ------------------------------------------------------------------------------------------
 // Pack kernels
@@ -128,21 +109,6 @@ hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const flo
 // ------------------------------------------------------------------------------------------
 // Attention kernel
 // ------------------------------------------------------------------------------------------
-struct MfmaArgs {
-  const uint16_t* q; const uint16_t* k; uint16_t* out;
-  const uint16_t* vt;                       // packed V^T
-  const uint16_t* kcn; const uint16_t* vcnt; const float* biasn;
-  const int* blk_start; const int* blk_n;
-  const int* kv_list; const int* full_list; const int* flat_list;
-  const uint32_t* exact_mask;
-  Geometry geo;
-  Counts cnt;
-  int dense;
-  int Tn_pad;
-  int slots;                                // work slots per (batch, head) = T_max
-  int total;                                // B * H * slots
-};
-
 struct Tile {                               // wave-uniform description of one 64-key tile
   const uint16_t* krows;                    // row 0 of the block (token tiles) or of the tile (mean tiles)
   int row0;                                 // first row of the tile relative to krows
@@ -277,8 +243,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   } else {
     kvl = a.kv_list + bh * T_max;
     n_list = c.T_new;
-    if (slot < c.n_full) qi = a.full_list[bh * T_max + slot];
-    else { qi = a.flat_list[bh * T_max + slot - c.n_full]; taylor = true; }
+    if (slot < c.n_full) {
+      if (a.taylor_only) return;
+      qi = a.full_list[bh * T_max + slot];
+    } else {
+      qi = a.flat_list[bh * T_max + slot - c.n_full];
+      taylor = true;
+    }
   }
   const uint32_t* mrow = (taylor && a.exact_mask && c.k_exact > 0)
                              ? a.exact_mask + (bh * T_max + (slot - c.n_full)) * a.cnt.mask_words : nullptr;
@@ -435,27 +406,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   }
 }
 
-hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st) {
-  MfmaArgs m;
-  m.q = (const uint16_t*)a.q; m.k = (const uint16_t*)a.k; m.out = (uint16_t*)a.out;
-  m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn;
-  m.blk_start = a.blk_start; m.blk_n = a.blk_n;
-  m.kv_list = a.kv_list; m.full_list = a.full_list; m.flat_list = a.flat_list;
-  m.exact_mask = a.exact_mask;
-  m.geo = a.geo; m.cnt = a.cnt; m.dense = a.dense;
-  m.Tn_pad = pr.Tn_pad;
+// The 4-wave kernel on the Taylor slots only (used when Taylor blocks carry exact sets).
+hipError_t launch_attn_mfma4(const Problem& pr, MfmaArgs m, hipStream_t st) {
   m.slots = pr.cnt.T_max;
   m.total = pr.p.B * pr.p.H * pr.cnt.T_max;
   const int grid = (m.total + 7) / 8 * 8;
-  const bool prof = g_prof_on && g_prof_start && g_prof_stop;
-  if (prof) (void)hipEventRecord(g_prof_start, st);
   hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(256), 0, st, m);
-  hipError_t e = hipGetLastError();
-  if (prof) {
-    (void)hipEventRecord(g_prof_stop, st);
-    g_prof_recorded = 1;
-  }
-  return e;
+  return hipGetLastError();
 }
 
 }  // namespace isa
