@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libisa_hip.so")
-SOURCES = ["isa_api.hip", "kernels_small.hip", "attn_simt.hip", "attn_mfma.hip", "attn_pp.hip"]
+SOURCES = ["isa_api.hip", "kernels_small.hip", "attn_simt.hip", "attn_mfma.hip", "attn_sp.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
@@ -20,10 +20,10 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose=False, extra_flags=()):
+def build(verbose=False, extra_flags=(), out=None, objdir=None):
     """Compile every HIP source and link the shared library.  Always recompiles."""
     hipcc = _hipcc()
-    objdir = os.path.join(HERE, "_build")
+    objdir = objdir or os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):
@@ -38,11 +38,11 @@ def build(verbose=False, extra_flags=()):
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out or LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s" % r.stderr[-8000:])
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":

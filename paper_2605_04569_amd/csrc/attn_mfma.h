@@ -28,7 +28,9 @@ struct MfmaArgs {
   const uint16_t* q; const uint16_t* k; uint16_t* out;
   const uint16_t* vt;                       // packed V^T
   const uint16_t* kcn; const uint16_t* vcnt; const float* biasn;
+  const uint16_t* zero_tile;                // 16 KB of zeros (a V^T tile that contributes nothing)
   const int* blk_start; const int* blk_n;
+  const int4* btab; const int4* ktab;        // {token offset, real tokens, block index} per block / per kv_list entry
   const int* kv_list; const int* full_list; const int* flat_list;
   const uint32_t* exact_mask;
   Geometry geo;
@@ -38,7 +40,7 @@ struct MfmaArgs {
   int slots;                                // work slots per (batch, head) = T_max
   int total;                                // B * H * slots
   int taylor_only;                          // k_attn_mfma: process only the Taylor slots (the exact branch ran elsewhere)
-  int taylor_here;                          // k_attn_pp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only
+  int taylor_here;                          // k_attn_sp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only
 };
 
 hipError_t launch_attn_mfma4(const Problem& pr, MfmaArgs m, hipStream_t st);

@@ -25,9 +25,11 @@ namespace isa {
 // V^T copy: vt[((bh*T_max + j)*2 + half)][d][pos], pos = swap23(key % 64); keys past n_j are zero.
 __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
                                                  const int* __restrict__ blk_start, const int* __restrict__ blk_n,
-                                                 Geometry g) {
+                                                 uint16_t* __restrict__ zero_tile, Geometry g) {
   __shared__ uint16_t tile[128][MD + 2];
   const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (j == 0 && h == 0 && b == 0)                                 // the all-zero V^T tile the attention kernel pads with
+    for (int x = threadIdx.x; x < MD * KT / 8; x += 256) reinterpret_cast<uint4*>(zero_tile)[x] = make_uint4(0, 0, 0, 0);
   const int n = blk_n[b * g.T_max + j];
   if (n == 0) return;
   const int start = blk_start[b * g.T_max + j];
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v,
 
 hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, hipStream_t st) {
   hipLaunchKernelGGL(k_pack_vt, dim3(pr.cnt.T_max, pr.p.H, pr.p.B), dim3(256), 0, st, (const uint16_t*)v, ws.vt,
-                     ws.blk_start, ws.blk_n, pr.geo);
+                     ws.blk_start, ws.blk_n, ws.zero_tile, pr.geo);
   return hipGetLastError();
 }
 
@@ -64,8 +66,9 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
 // kcn[bh][t][d]; vcnt[bh][t/64][d][swap23(t%64)]; biasn[bh][t] = ln(n_j) sqrt(D), -inf past T_new.
 __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
                                                       const int* __restrict__ kv_list, const int* __restrict__ blk_n,
-                                                      uint16_t* __restrict__ kcn, uint16_t* __restrict__ vcnt,
-                                                      float* __restrict__ biasn, Counts cnt, int H, int Tn_pad) {
+                                                      const int4* __restrict__ btab, uint16_t* __restrict__ kcn,
+                                                      uint16_t* __restrict__ vcnt, float* __restrict__ biasn,
+                                                      int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad) {
   __shared__ uint16_t vtile[KT][MD + 2];
   __shared__ int ids[KT];
   const int tile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -76,6 +79,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     const int t = t0 + threadIdx.x;
     const int j = t < T_new ? kv_list[bh * T_max + t] : -1;
     ids[threadIdx.x] = j;
+    if (j >= 0) ktab[bh * T_max + t] = btab[b * T_max + j];
     // ln(n_j) * sqrt(D): added to the raw score q.k, it becomes ln(n_j) after the 1/sqrt(D) scaling
     biasn[bh * Tn_pad + t] = j >= 0 ? logf((float)blk_n[b * T_max + j]) * sqrtf((float)MD) : -INFINITY;
   }
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st) {
   hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
-                     ws.kcn, ws.vcnt, ws.biasn, pr.cnt, pr.p.H, pr.Tn_pad);
+                     ws.btab, ws.kcn, ws.vcnt, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
   return hipGetLastError();
 }
 

@@ -1,0 +1,431 @@
+// Software-pipelined MFMA attention kernel for bf16, D = 128, block = 128 on gfx950: dense attention, the
+// exact branch of ISA (Alg. 1 Stage 4 / Alg. 2 Part A) and the Taylor branch without exact sets (Eq. 4,
+// Alg. 2 Part B).
+//
+// Why it is shaped this way.  On this chip a wave whose next instruction is an MFMA that has to wait for the
+// matrix pipe blocks the vector-ALU issue of its SIMD for every wave, so "one wave multiplies while another
+// wave does softmax" does not happen by itself: measured, a wave of back-to-back MFMAs and a wave of pure
+// VALU work on one SIMD take the sum of their times.  What does overlap is VALU work issued in the shadow of
+// an MFMA by the same instruction stream.  So each wave here runs one stream in which every MFMA is followed
+// by the few VALU instructions and the one LDS read that fit under it:
+//
+//   keys are handled in halves of 32 (one MFMA row group).  While the 8 MFMAs that compute the raw scores of
+//   half h+1 are in flight, the wave exponentiates the scores of half h (computed one step earlier); while
+//   the 8 MFMAs that add V_h^T P_h^T to the output are in flight, it takes the maximum of the new scores.
+//
+// The score product of a 64-key K tile is therefore half a tile ahead of the value product, and the V^T tile
+// that is staged in LDS per loop iteration is shifted by 32 keys against the K tile (second half of tile T-1,
+// first half of tile T), which keeps one barrier and one load group per iteration.
+//
+// One workgroup (4 waves) owns one query block of 128 rows; two workgroups share a compute unit.  Scores are
+// computed transposed (S^T = K Q^T) and V is read from the packed, key-permuted V^T copy, as in the 4-wave
+// kernel: P stays in registers in the layout the second product needs.
+#include "attn_mfma.h"
+
+namespace isa {
+
+struct STile {                              // wave-uniform description of one 64-key tile
+  const uint16_t* krows;                    // row 0 of the block (token tiles) or of the tile (mean tiles)
+  const uint16_t* vt;                       // 128 x 64 packed V^T of the tile
+  const float* bias;                        // per-key additive term on the raw score, or null
+  int row0, kstride, nk, last_row;
+};
+
+#ifdef ISA_DBG_NO_FENCE
+#define ISA_FENCE()
+#else
+#define ISA_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+
+// 16 bytes per lane from global memory straight into LDS: lane i of the wave writes LDS bytes lds_addr + 16 i.
+// Written as inline assembly on purpose.  Issued through the compiler's builtin, every later LDS read is
+// preceded by a wait for all such loads in flight (the compiler cannot tell that they fill the *other*
+// buffer), which puts the whole memory latency in front of the first MFMA of each iteration.  Here the only
+// wait is the explicit one at the top of the loop.  M0 is not used by anything else in this kernel.
+__device__ __forceinline__ void lds_dma16(const void* sbase, uint32_t voff_bytes, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(voff_bytes), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// One half step.  Scores of the half that is softmaxed come in `sin` (raw, bias and masks already applied,
+// running maximum already raised); the raw scores of the next half are produced in `sout` from the 8 K
+// fragments in `kf` (rows KB*32 .. +31 of the K tile, fetched from LDS one phase earlier), and their raw
+// maximum in `mx_out`.  The value product uses V^T unit VU of the staged V^T tile.
+// LDS fragments are requested a whole phase (8 MFMAs) before the MFMA that consumes them: the V^T fragments
+// during the score MFMAs, and (NEXT_K) the K fragments of rows (KB+1)*32 .. for the following half step during
+// the value MFMAs.
+template <int KB, int VU, bool NEXT_K>
+__device__ __forceinline__ void half_step(const uint16_t* __restrict__ kbase, const uint16_t* __restrict__ vbase,
+                                          const bf16x8 (&qf)[8], bf16x8 (&kf)[8], const f32x16& sin, f32x16& sout,
+                                          f32x16 (&oacc)[4], float m_run, float& l_run, float& mx_out,
+                                          const int (&koff)[8], const int (&voff)[2], float cscale) {
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  const float neg_m = -m_run;
+  bf16x8 pf[2], vf[8];
+  f32x16 zero;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+  // 8 score MFMAs, each followed by one pair of weights (2 fma, 2 exp2, 1 convert, 1 dot) and one LDS read
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    ISA_FENCE();
+    vf[s] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + (s & 3) * 32 * 32 + voff[s >> 2]);   // ks = s/4, db = s%4
+    sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], s == 0 ? zero : sout, 0, 0, 0);
+#ifdef ISA_DBG_NO_PAIR
+    if (s == 0) { pf[0] = kf[0]; pf[1] = kf[1]; }
+#else
+    {
+#ifdef ISA_DBG_NO_SOFTMAX
+      const float p0 = sin[2 * s], p1 = sin[2 * s + 1];
+#else
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s], cscale, neg_m));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s + 1], cscale, neg_m));
+#endif
+      const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
+      pf[s >> 2][2 * (s & 3)] = pp[0];
+      pf[s >> 2][2 * (s & 3) + 1] = pp[1];
+    }
+#endif
+  }
+  // 8 value MFMAs (2 key steps x 4 channel groups); the raw maximum of the new scores fills the VALU slots
+  float mx = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int ks = c >> 2, db = c & 3;
+    ISA_FENCE();
+    if (NEXT_K) kf[c] = *reinterpret_cast<const bf16x8*>(kbase + (KB + 1) * 32 * MD + koff[c]);
+    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[ks], oacc[db], 0, 0, 0);
+    if (c >= 2 && c < 6) {
+#pragma unroll
+      for (int e = 4 * (c - 2); e < 4 * (c - 2) + 4; ++e) mx = fmaxf(mx, sout[e]);
+    }
+  }
+  ISA_FENCE();
+  mx_out = mx;
+}
+
+// Bias / masks of a special half (block means, ragged tails), then the running maximum of the online softmax
+// (Alg. 2 Part A) with the rare rescale of the accumulators.  Element e of a half is key 8(e/4) + 4g + e%4.
+__device__ __forceinline__ void prepare_half(f32x16& sc, float& mx, bool general, int nk_half, const float* __restrict__ bias,
+                                             int g, float cscale, float& m_run, float& l_run, f32x16 (&oacc)[4]) {
+  if (general) {
+    float addv[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) addv[e] = 0.f;
+    if (bias) {
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {                                    // keys 8*e4 + 4g + 0..3: one 16-byte load
+        const float4 bv = *reinterpret_cast<const float4*>(bias + 8 * e4 + 4 * g);
+        addv[4 * e4] = bv.x; addv[4 * e4 + 1] = bv.y; addv[4 * e4 + 2] = bv.z; addv[4 * e4 + 3] = bv.w;
+      }
+    }
+    float m2 = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int key = 8 * (e >> 2) + 4 * g + (e & 3);
+      sc[e] = key >= nk_half ? -INFINITY : sc[e] + addv[e];
+      m2 = fmaxf(m2, sc[e]);
+    }
+    mx = m2;
+  }
+  float tmax = mx * cscale;
+  {
+    // lanes l and l ^ 32 hold the two key halves of one query: exchange through v_permlane32_swap, which (unlike
+    // a shuffle through the LDS crossbar) does not queue behind the LDS fragment reads in flight
+    const uint32_t u = __float_as_uint(tmax);
+    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+  }
+  const bool raise = tmax > m_run + RESCALE_TAU;
+  if (__ballot(raise) != 0ull) {                       // rare after the first tiles
+    const float m_new = raise ? tmax : m_run;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE];
+  uint16_t* ldsK = lds;                     // K tile T lives in buffer T & 1
+  uint16_t* ldsV = lds + 2 * K_TILE;        // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T & 1
+
+  // ---- which work item: consecutive logical ids go to the same XCD, so that the workgroups that run
+  // together on one XCD (and share its L2) read the same head's keys and values
+  const int per_xcd = gridDim.x >> 3;       // grid is a multiple of 8
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.total) return;
+  const int slot = logical % a.slots;
+  const int bhid = logical / a.slots;
+  const int h = bhid % a.geo.H, b = bhid / a.geo.H;
+  const BatchCounts c = a.cnt.b[b];
+  const int T_max = a.geo.T_max;
+  const long long bh = bhid;
+
+  // slots of a (batch, head): exact-branch blocks first (the long ones), then Taylor blocks
+  const int n_first = a.dense ? c.T : c.n_full;
+  const int n_second = (a.dense || !a.taylor_here) ? 0 : c.n_flat;
+  if (slot >= n_first + n_second) return;
+  const bool taylor = slot >= n_first;
+  const int n_list = a.dense ? c.T : c.T_new;
+  const int qi = a.dense ? slot : (taylor ? a.flat_list[bh * T_max + slot - n_first] : a.full_list[bh * T_max + slot]);
+  const int* bn = a.blk_n + b * T_max;
+  const int* bs = a.blk_start + b * T_max;
+  const int n_q = bn[qi];
+  const int q_start = bs[qi];
+  const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
+  const int n_tiles = taylor ? (n_list + KT - 1) / KT : 2 * n_list;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar
+  const int col = lane & 31, g = lane >> 5;
+
+  // Tile idx of the sequence, built from the table row `ent` = {token offset, real tokens, block index} of its list
+  // entry (token tiles); idx == n_tiles (one past the end) gives a fully masked tile over valid memory.
+  const int4* tab = a.dense ? a.btab + (long long)b * T_max : a.ktab + bh * T_max;
+  // The workgroups that run together on an XCD would all walk the tile sequence in step, so that only the one in
+  // front ever misses the L2.  Each workgroup therefore starts at one of eight evenly spaced points of the
+  // (cyclic) sequence.  The online softmax does not care about the order of the tiles.
+  const int rot = (slot & 7) * ((n_tiles >> 3) & ~1);
+  auto rotated = [&](int idx) { const int r = idx + rot; return r >= n_tiles ? r - n_tiles : r; };
+  // Table rows are fetched 64 at a time with one vector load (lane L holds the row of list position pbase + L)
+  // and handed out with readlane, so that no load other than the tile loads is in flight inside the loop.
+  int4 ecache = make_int4(0, 0, 0, 0);
+  int pbase = 0;
+  auto refill = [&](int p0) {
+    if (!taylor) {
+      int e = min(p0 + lane, n_list - 1) + (rot >> 1);
+      if (e >= n_list) e -= n_list;
+      ecache = tab[e];
+      // consume the rows here, so that the wait for this (rare) load sits inside this branch and not at the
+      // loop-wide join, where it would also wait for the tile loads that were just issued
+      asm volatile("" : "+v"(ecache.x), "+v"(ecache.y), "+v"(ecache.z));
+    }
+    pbase = p0;
+  };
+  auto entry_of = [&](int idx) -> int4 {
+    const int l = (min(idx, n_tiles - 1) >> 1) - pbase;          // 0..63 by construction of the refills
+    return make_int4(__builtin_amdgcn_readlane(ecache.x, l), __builtin_amdgcn_readlane(ecache.y, l),
+                     __builtin_amdgcn_readlane(ecache.z, l), 0);
+  };
+  auto make_tile = [&](int idx, int4 ent, STile& t) {
+    const bool past = idx >= n_tiles;
+    if (past) idx = n_tiles - 1;
+    idx = rotated(idx);
+    if (!taylor) {
+      const int sub = idx & 1;
+      const int n_j = ent.y;
+      t.krows = a.k + tbase + (long long)ent.x * a.geo.stride_t;
+      t.row0 = sub * KT;
+      t.kstride = (int)a.geo.stride_t;
+      t.vt = a.vt + ((bh * T_max + ent.z) * 2 + sub) * (long long)(MD * KT);
+      t.bias = nullptr;
+      t.nk = max(0, min(KT, n_j - sub * KT));
+      t.last_row = max(n_j - 1, 0);
+    } else {
+      const long long row0 = bh * a.Tn_pad + (long long)idx * KT;
+      t.krows = a.kcn + row0 * MD;
+      t.row0 = 0;
+      t.kstride = MD;
+      t.vt = a.vcnt + (bh * (a.Tn_pad / KT) + idx) * (long long)(MD * KT);
+      t.bias = a.biasn + row0;
+      t.nk = min(KT, n_list - idx * KT);
+      t.last_row = KT - 1;                                          // the gathered arrays are padded to whole tiles
+    }
+    if (past) { t.nk = 0; t.vt = a.zero_tile; }
+  };
+
+  // ---- Q fragments: B operand of S^T = K Q^T; lane holds channels 16s + 8g .. +7 of its query row
+  const int row = wave * 32 + col;
+  const bool row_ok = row < n_q;
+  const uint16_t* qp = a.q + tbase + (long long)(q_start + (row_ok ? row : 0)) * a.geo.stride_t + 8 * g;
+  bf16x8 qf[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+  // consume the fragments here: the compiler's own wait for these loads must not land inside the loop, where
+  // it would also wait for the tile loads in flight (which it does not know about)
+#pragma unroll
+  for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
+
+  // ---- global -> LDS, 16 bytes per lane, no staging registers.  One wave instruction fills 1024 contiguous
+  // LDS bytes (lane i -> bytes 16i..16i+15), so rows cannot be padded; instead the 16-byte chunk c of a row is
+  // stored at chunk position c ^ f(row), applied on the source side: the lane that fills position pc of row r
+  // fetches chunk pc ^ f(r).  K rows are 256 B (f = r & 15), V^T rows are 128 B (f = (r >> 1) & 7); with these
+  // the 16-lane groups of a b128 fragment read hit 16 different bank groups.  A wave issues four such
+  // instructions per tile and tensor; instruction i of wave w fills chunks (4w+i)*64 .. +63, i.e. K rows
+  // 16w+4i .. +3 and V^T rows 32w+8i .. +7.
+  const int l16 = lane >> 4;
+  const uint32_t kstride_b = (uint32_t)(taylor ? MD : (int)a.geo.stride_t) * 2u;
+  uint32_t kchunk_b[4], klane_b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    kchunk_b[i] = (uint32_t)((((lane & 15) ^ ((4 * i + l16) & 15)) * 8) * 2);
+    klane_b[i] = (uint32_t)l16 * kstride_b + kchunk_b[i];
+  }
+  auto load_k = [&](const STile& t, int buf) {
+    const char* kb = reinterpret_cast<const char*>(t.krows);
+    if (t.row0 + KT - 1 <= t.last_row) {                            // whole tile inside the block: lane-constant offsets
+      const char* kw = kb + (size_t)(t.row0 + wave * 16) * kstride_b;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        lds_dma16(kw + (size_t)(4 * i) * kstride_b, klane_b[i], lds_addr_of(ldsK + buf * K_TILE + (wave * 4 + i) * 512));
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // rows past the block's end re-read its last row; the row index is never negative
+        const int r = max(min(t.row0 + wave * 16 + 4 * i + l16, t.last_row), 0);
+        const uint32_t koff_b = (uint32_t)r * kstride_b + kchunk_b[i];
+        lds_dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + (wave * 4 + i) * 512));
+      }
+    }
+  };
+  // Shifted V^T tile in LDS, unit-major: unit 0 = key positions 32..63 of tile `ta`, unit 1 = positions 0..31 of
+  // `tb`; a unit is 128 rows (channels) of 64 B, 16-byte chunk c of row r stored at chunk c ^ ((r >> 2) & 3).
+  // Waves 0,1 fill unit 0 and waves 2,3 unit 1, so the source tile of an instruction is wave-uniform and the
+  // per-lane part of the address is one constant: rows 16(4w+i mod 8) + lane/4, chunk (lane & 3) ^ (lane >> 4).
+  const uint32_t vlane_b = (uint32_t)(((lane >> 2) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
+  auto load_v = [&](const uint16_t* ta, const uint16_t* tb, int buf) {
+    const uint16_t* srcu = wave < 2 ? ta + 32 : tb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 4 + i) & 7) * 16) * KT);
+      lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 4 + i) * 512));
+    }
+  };
+
+  // per-lane fragment offsets (bf16 elements): K row = col, chunk (2s+g) ^ (col & 15); V^T unit row = col, chunk (2ks+g) ^ ((col>>2)&3)
+  int koff[8], voff[2];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) koff[s] = col * MD + (((2 * s + g) ^ (col & 15)) * 8);
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) voff[ks] = col * 32 + (((2 * ks + g) ^ ((col >> 2) & 3)) * 8);
+
+  f32x16 oacc[4], s0, s1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { s0[e] = -INFINITY; s1[e] = -INFINITY; }
+  float m_run = M_INIT, l_run = 0.f, mx0 = -INFINITY, mx1 = -INFINITY;
+  const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
+
+  // ---- loop over T = 0 .. n_tiles (one extra, fully masked iteration drains the pipeline).  Iteration T:
+  //   barrier; request K tile T+1 and shifted V^T tile T+1 for the next iteration;
+  //   softmax of half (T-1,1) under the score MFMAs of half (T,0); value MFMAs of half (T-1,1);
+  //   softmax of half (T,0)   under the score MFMAs of half (T,1); value MFMAs of half (T,0).
+  // The table row of tile T+2 is requested (scalar load) in iteration T and first used in iteration T+1, so its
+  // latency is never waited for.
+  STile tprev, tcur, tnext;
+  refill(0);
+  make_tile(0, entry_of(0), tcur);
+  tprev = tcur; tprev.nk = 0; tprev.bias = nullptr; tprev.vt = a.zero_tile;
+  load_k(tcur, 0);
+  load_v(a.zero_tile, tcur.vt, 0);
+  int4 ent_next = entry_of(1);
+  for (int T = 0; T <= n_tiles; ++T) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#ifndef ISA_DBG_NO_BARRIER
+    __syncthreads();
+#endif
+    make_tile(T + 1, ent_next, tnext);
+#ifndef ISA_DBG_NO_LOADS
+    if (T < n_tiles) {
+#ifndef ISA_DBG_NO_KLOAD
+      load_k(tnext, (T + 1) & 1);
+#endif
+#ifndef ISA_DBG_NO_VLOAD
+      load_v(tcur.vt, tnext.vt, (T + 1) & 1);
+#endif
+    }
+#endif
+    if ((min(T + 2, n_tiles - 1) >> 1) >= pbase + 64) refill(pbase + 64);
+    ent_next = entry_of(T + 2);
+    const uint16_t* kbase = ldsK + (T & 1) * K_TILE;
+    const uint16_t* vbase = ldsV + (T & 1) * V_TILE;
+    bf16x8 kf[8];                         // K fragments of rows 0..31 of the new tile; they arrive under prepare_half
+#pragma unroll
+    for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(kbase + koff[s8]);
+    {   // half (T-1, 1): scores in s1
+      const int nkh = min(32, max(0, tprev.nk - 32));
+      const bool general = tprev.bias != nullptr || nkh < 32;
+#ifndef ISA_DBG_NO_PREPARE
+      prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, g, cscale, m_run, l_run, oacc);
+#endif
+#ifndef ISA_DBG_NO_COMPUTE
+      half_step<0, 0, true>(kbase, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale);
+#endif
+    }
+    {   // half (T, 0): scores in s0
+      const int nkh = min(32, tcur.nk);
+      const bool general = tcur.bias != nullptr || nkh < 32;
+#ifndef ISA_DBG_NO_PREPARE
+      prepare_half(s0, mx0, general, nkh, tcur.bias, g, cscale, m_run, l_run, oacc);
+#endif
+#ifndef ISA_DBG_NO_COMPUTE
+      half_step<1, 1, false>(kbase, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale);
+#endif
+    }
+    tprev = tcur;
+    tcur = tnext;
+  }
+
+  // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (row_ok) {
+    const float inv = 1.0f / l_tot;
+    uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        bf16x2 lo = {(__bf16)(oacc[db][4 * e4] * inv), (__bf16)(oacc[db][4 * e4 + 1] * inv)};
+        bf16x2 hi = {(__bf16)(oacc[db][4 * e4 + 2] * inv), (__bf16)(oacc[db][4 * e4 + 3] * inv)};
+        uint2 o;
+        o.x = *reinterpret_cast<uint32_t*>(&lo);
+        o.y = *reinterpret_cast<uint32_t*>(&hi);
+        *reinterpret_cast<uint2*>(op + 32 * db + 8 * e4) = o;
+      }
+  }
+}
+
+// Launches the attention kernels of the MFMA path: the software-pipelined kernel for dense attention, the
+// exact branch and the Taylor branch without exact sets; the 4-wave kernel for Taylor blocks with exact sets.
+hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st) {
+  MfmaArgs m;
+  m.q = (const uint16_t*)a.q; m.k = (const uint16_t*)a.k; m.out = (uint16_t*)a.out;
+  m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn;
+  m.zero_tile = ws.zero_tile;
+  m.blk_start = a.blk_start; m.blk_n = a.blk_n;
+  m.btab = ws.btab; m.ktab = ws.ktab;
+  m.kv_list = a.kv_list; m.full_list = a.full_list; m.flat_list = a.flat_list;
+  m.exact_mask = a.exact_mask;
+  m.geo = a.geo; m.cnt = a.cnt; m.dense = a.dense;
+  m.Tn_pad = pr.Tn_pad;
+  const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
+  m.taylor_here = exact_sets ? 0 : 1;
+  m.taylor_only = 1;
+  m.slots = pr.cnt.T_max;
+  m.total = pr.p.B * pr.p.H * pr.cnt.T_max;
+  const int grid = (m.total + 7) / 8 * 8;
+  const bool prof = g_prof_on && g_prof_start && g_prof_stop;
+  if (prof) (void)hipEventRecord(g_prof_start, st);
+  hipLaunchKernelGGL(k_attn_sp, dim3(grid), dim3(256), 0, st, m);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && exact_sets) e = launch_attn_mfma4(pr, m, st);
+  if (prof) {
+    (void)hipEventRecord(g_prof_stop, st);
+    g_prof_recorded = 1;
+  }
+  return e;
+}
+
+}  // namespace isa

@@ -83,6 +83,7 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
   auto take = [&](size_t bytes) { char* r = b0 + off; off += align256(bytes); return (void*)r; };
   ws->blk_start = (int*)take(B * T * 4);
   ws->blk_n = (int*)take(B * T * 4);
+  ws->btab = (int4*)take(B * T * 16);
   ws->qc = (float*)take(B * H * T * D * 4);
   ws->kc = (float*)take(B * H * T * D * 4);
   ws->vc = (float*)take(B * H * T * D * 4);
@@ -104,9 +105,13 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->kcn = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
     ws->vcnt = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
     ws->biasn = (float*)take(B * H * (size_t)pr.Tn_pad * 4);
+    ws->zero_tile = (uint16_t*)take(128 * 64 * 2);
+    ws->ktab = (int4*)take(B * H * T * 16);
   } else {
     ws->vt = ws->kcn = ws->vcnt = nullptr;
     ws->biasn = nullptr;
+    ws->zero_tile = nullptr;
+    ws->ktab = nullptr;
   }
   ws->bytes = off;
 }

@@ -36,6 +36,7 @@ struct Geometry {
 struct Workspace {
   int* blk_start;        // [B][T_max] token offset of each block inside its batch item
   int* blk_n;            // [B][T_max] real tokens of each block
+  int4* btab;            // [B][T_max] {token offset, real tokens, block index, 0} of each block
   float* qc;             // [B,H,T_max,D]
   float* kc;
   float* vc;
@@ -52,6 +53,8 @@ struct Workspace {
   uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order
   uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
   float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key, -inf for padding
+  uint16_t* zero_tile;   // 16 KB of zeros, written by the V^T pack kernel
+  int4* ktab;            // [B,H,T_max] the btab rows of the blocks of kv_list, in list order
   size_t bytes;          // total size
 };
 

@@ -49,7 +49,7 @@ __device__ inline float bf16_bits_to_float(uint16_t b) { return __uint_as_float(
 // ------------------------------------------------------------------------------------------
 // Block table: token offset and real token count of every block of every batch item.
 // ------------------------------------------------------------------------------------------
-__global__ void k_layout(SegDesc seg, int block, int T_max, int* blk_start, int* blk_n) {
+__global__ void k_layout(SegDesc seg, int block, int T_max, int* blk_start, int* blk_n, int4* btab) {
   const int b = blockIdx.x;
   for (int j = threadIdx.x; j < T_max; j += blockDim.x) {
     int start = 0, n = 0, first = 0, off = 0;
@@ -66,11 +66,12 @@ __global__ void k_layout(SegDesc seg, int block, int T_max, int* blk_start, int*
     }
     blk_start[b * T_max + j] = start;   // blocks past the batch item's T get n = 0
     blk_n[b * T_max + j] = n;
+    btab[b * T_max + j] = make_int4(start, n, j, 0);
   }
 }
 
 hipError_t launch_layout(const Problem& pr, const Workspace& ws, hipStream_t st) {
-  hipLaunchKernelGGL(k_layout, dim3(pr.p.B), dim3(256), 0, st, pr.seg, pr.p.block, pr.cnt.T_max, ws.blk_start, ws.blk_n);
+  hipLaunchKernelGGL(k_layout, dim3(pr.p.B), dim3(256), 0, st, pr.seg, pr.p.block, pr.cnt.T_max, ws.blk_start, ws.blk_n, ws.btab);
   return hipGetLastError();
 }
 
