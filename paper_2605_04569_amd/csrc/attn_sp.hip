@@ -17,7 +17,8 @@
 // that is staged in LDS per loop iteration is shifted by 32 keys against the K tile (second half of tile T-1,
 // first half of tile T), which keeps one barrier and one load group per iteration.
 //
-// One workgroup (4 waves) owns one query block of 128 rows; two workgroups share a compute unit.  Scores are
+// One workgroup of 8 waves owns two query blocks (2 x 128 rows) that walk the same tile sequence, so every K /
+// V^T tile is fetched once per 256 query rows; a SIMD holds two waves.  Scores are
 // computed transposed (S^T = K Q^T) and V is read from the packed, key-permuted V^T copy, as in the 4-wave
 // kernel: P stays in registers in the layout the second product needs.
 #include "attn_mfma.h"
@@ -73,7 +74,11 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kbase, co
   for (int s = 0; s < 8; ++s) {
     ISA_FENCE();
     vf[s] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + (s & 3) * 32 * 32 + voff[s >> 2]);   // ks = s/4, db = s%4
+#ifndef ISA_DBG_NO_SMFMA
     sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], s == 0 ? zero : sout, 0, 0, 0);
+#else
+    if (s == 0) sout = zero; else sout[s] += (float)kf[s][0] * (float)qf[s][0];
+#endif
 #ifdef ISA_DBG_NO_PAIR
     if (s == 0) { pf[0] = kf[0]; pf[1] = kf[1]; }
 #else
@@ -98,7 +103,11 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kbase, co
     const int ks = c >> 2, db = c & 3;
     ISA_FENCE();
     if (NEXT_K) kf[c] = *reinterpret_cast<const bf16x8*>(kbase + (KB + 1) * 32 * MD + koff[c]);
+#ifndef ISA_DBG_NO_PVMFMA
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[ks], oacc[db], 0, 0, 0);
+#else
+    oacc[db][c] += (float)vf[c][0] * (float)pf[ks][0];
+#endif
     if (c >= 2 && c < 6) {
 #pragma unroll
       for (int e = 4 * (c - 2); e < 4 * (c - 2) + 4; ++e) mx = fmaxf(mx, sout[e]);
@@ -153,7 +162,7 @@ __device__ __forceinline__ void prepare_half(f32x16& sc, float& mx, bool general
   }
 }
 
-__global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
+__global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE];
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T & 1
   uint16_t* ldsV = lds + 2 * K_TILE;        // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T & 1
@@ -170,23 +179,30 @@ __global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
   const int T_max = a.geo.T_max;
   const long long bh = bhid;
 
-  // slots of a (batch, head): exact-branch blocks first (the long ones), then Taylor blocks
-  const int n_first = a.dense ? c.T : c.n_full;
-  const int n_second = (a.dense || !a.taylor_here) ? 0 : c.n_flat;
+  // slots of a (batch, head): pairs of exact-branch blocks first (the long ones), then pairs of Taylor blocks;
+  // waves 0-3 take the first block of the pair, waves 4-7 the second
+  const int n_first_blocks = a.dense ? c.T : c.n_full;
+  const int n_second_blocks = (a.dense || !a.taylor_here) ? 0 : c.n_flat;
+  const int n_first = (n_first_blocks + 1) >> 1, n_second = (n_second_blocks + 1) >> 1;
   if (slot >= n_first + n_second) return;
   const bool taylor = slot >= n_first;
   const int n_list = a.dense ? c.T : c.T_new;
-  const int qi = a.dense ? slot : (taylor ? a.flat_list[bh * T_max + slot - n_first] : a.full_list[bh * T_max + slot]);
   const int* bn = a.blk_n + b * T_max;
   const int* bs = a.blk_start + b * T_max;
-  const int n_q = bn[qi];
-  const int q_start = bs[qi];
   const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
   const int n_tiles = taylor ? (n_list + KT - 1) / KT : 2 * n_list;
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // 0..7, scalar
+  const int grp = wave >> 2, wq = wave & 3;
   const int col = lane & 31, g = lane >> 5;
+  // this wave's query block; the second group idles (computes on block 0, stores nothing) in the last pair of
+  // an odd list
+  const int entry = 2 * (taylor ? slot - n_first : slot) + grp;
+  const bool active = entry < (taylor ? n_second_blocks : n_first_blocks);
+  const int qi = !active ? 0 : a.dense ? entry : (taylor ? a.flat_list[bh * T_max + entry] : a.full_list[bh * T_max + entry]);
+  const int n_q = active ? bn[qi] : 0;
+  const int q_start = bs[qi];
 
   // Tile idx of the sequence, built from the table row `ent` = {token offset, real tokens, block index} of its list
   // entry (token tiles); idx == n_tiles (one past the end) gives a fully masked tile over valid memory.
@@ -244,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
   };
 
   // ---- Q fragments: B operand of S^T = K Q^T; lane holds channels 16s + 8g .. +7 of its query row
-  const int row = wave * 32 + col;
+  const int row = wq * 32 + col;
   const bool row_ok = row < n_q;
   const uint16_t* qp = a.q + tbase + (long long)(q_start + (row_ok ? row : 0)) * a.geo.stride_t + 8 * g;
   bf16x8 qf[8];
@@ -259,45 +275,45 @@ __global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
   // LDS bytes (lane i -> bytes 16i..16i+15), so rows cannot be padded; instead the 16-byte chunk c of a row is
   // stored at chunk position c ^ f(row), applied on the source side: the lane that fills position pc of row r
   // fetches chunk pc ^ f(r).  K rows are 256 B (f = r & 15), V^T rows are 128 B (f = (r >> 1) & 7); with these
-  // the 16-lane groups of a b128 fragment read hit 16 different bank groups.  A wave issues four such
-  // instructions per tile and tensor; instruction i of wave w fills chunks (4w+i)*64 .. +63, i.e. K rows
-  // 16w+4i .. +3 and V^T rows 32w+8i .. +7.
+  // the 16-lane groups of a b128 fragment read hit 16 different bank groups.  A wave issues two such
+  // instructions per tile and tensor; instruction i of wave w fills chunks (2w+i)*64 .. +63, i.e. K rows
+  // 8w+4i .. +3.
   const int l16 = lane >> 4;
   const uint32_t kstride_b = (uint32_t)(taylor ? MD : (int)a.geo.stride_t) * 2u;
-  uint32_t kchunk_b[4], klane_b[4];
+  uint32_t kchunk_b[2], klane_b[2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    kchunk_b[i] = (uint32_t)((((lane & 15) ^ ((4 * i + l16) & 15)) * 8) * 2);
+  for (int i = 0; i < 2; ++i) {
+    kchunk_b[i] = (uint32_t)((((lane & 15) ^ ((8 * wave + 4 * i + l16) & 15)) * 8) * 2);
     klane_b[i] = (uint32_t)l16 * kstride_b + kchunk_b[i];
   }
   auto load_k = [&](const STile& t, int buf) {
     const char* kb = reinterpret_cast<const char*>(t.krows);
     if (t.row0 + KT - 1 <= t.last_row) {                            // whole tile inside the block: lane-constant offsets
-      const char* kw = kb + (size_t)(t.row0 + wave * 16) * kstride_b;
+      const char* kw = kb + (size_t)(t.row0 + wave * 8) * kstride_b;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        lds_dma16(kw + (size_t)(4 * i) * kstride_b, klane_b[i], lds_addr_of(ldsK + buf * K_TILE + (wave * 4 + i) * 512));
+      for (int i = 0; i < 2; ++i)
+        lds_dma16(kw + (size_t)(4 * i) * kstride_b, klane_b[i], lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < 2; ++i) {
         // rows past the block's end re-read its last row; the row index is never negative
-        const int r = max(min(t.row0 + wave * 16 + 4 * i + l16, t.last_row), 0);
+        const int r = max(min(t.row0 + wave * 8 + 4 * i + l16, t.last_row), 0);
         const uint32_t koff_b = (uint32_t)r * kstride_b + kchunk_b[i];
-        lds_dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + (wave * 4 + i) * 512));
+        lds_dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
       }
     }
   };
   // Shifted V^T tile in LDS, unit-major: unit 0 = key positions 32..63 of tile `ta`, unit 1 = positions 0..31 of
   // `tb`; a unit is 128 rows (channels) of 64 B, 16-byte chunk c of row r stored at chunk c ^ ((r >> 2) & 3).
-  // Waves 0,1 fill unit 0 and waves 2,3 unit 1, so the source tile of an instruction is wave-uniform and the
-  // per-lane part of the address is one constant: rows 16(4w+i mod 8) + lane/4, chunk (lane & 3) ^ (lane >> 4).
+  // Waves 0-3 fill unit 0 and waves 4-7 unit 1, so the source tile of an instruction is wave-uniform and the
+  // per-lane part of the address is one constant: rows 16(2w+i mod 8) + lane/4, chunk (lane & 3) ^ (lane >> 4).
   const uint32_t vlane_b = (uint32_t)(((lane >> 2) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
   auto load_v = [&](const uint16_t* ta, const uint16_t* tb, int buf) {
-    const uint16_t* srcu = wave < 2 ? ta + 32 : tb;
+    const uint16_t* srcu = wave < 4 ? ta + 32 : tb;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 4 + i) & 7) * 16) * KT);
-      lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 4 + i) * 512));
+    for (int i = 0; i < 2; ++i) {
+      const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 2 + i) & 7) * 16) * KT);
+      lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 2 + i) * 512));
     }
   };
 
@@ -354,6 +370,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
     bf16x8 kf[8];                         // K fragments of rows 0..31 of the new tile; they arrive under prepare_half
 #pragma unroll
     for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(kbase + koff[s8]);
+#ifdef ISA_DBG_REPEAT
+    for (int rep = 0; rep < 2; ++rep) {
+#endif
     {   // half (T-1, 1): scores in s1
       const int nkh = min(32, max(0, tprev.nk - 32));
       const bool general = tprev.bias != nullptr || nkh < 32;
@@ -374,6 +393,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_sp(MfmaArgs a) {
       half_step<1, 1, false>(kbase, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale);
 #endif
     }
+#ifdef ISA_DBG_REPEAT
+    }
+#endif
     tprev = tcur;
     tcur = tnext;
   }
@@ -413,13 +435,23 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
   m.taylor_here = exact_sets ? 0 : 1;
   m.taylor_only = 1;
-  m.slots = pr.cnt.T_max;
-  m.total = pr.p.B * pr.p.H * pr.cnt.T_max;
-  const int grid = (m.total + 7) / 8 * 8;
+  // slots per (batch, head): the largest pair count over the batch
+  int slots = 0;
+  for (int b = 0; b < pr.p.B; ++b) {
+    const BatchCounts& c = pr.cnt.b[b];
+    const int sl = a.dense ? (c.T + 1) / 2 : (c.n_full + 1) / 2 + (m.taylor_here ? (c.n_flat + 1) / 2 : 0);
+    slots = sl > slots ? sl : slots;
+  }
   const bool prof = g_prof_on && g_prof_start && g_prof_stop;
   if (prof) (void)hipEventRecord(g_prof_start, st);
-  hipLaunchKernelGGL(k_attn_sp, dim3(grid), dim3(256), 0, st, m);
-  hipError_t e = hipGetLastError();
+  hipError_t e = hipSuccess;
+  if (slots > 0) {
+    m.slots = slots;
+    m.total = pr.p.B * pr.p.H * slots;
+    const int grid = (m.total + 7) / 8 * 8;
+    hipLaunchKernelGGL(k_attn_sp, dim3(grid), dim3(512), 0, st, m);
+    e = hipGetLastError();
+  }
   if (e == hipSuccess && exact_sets) e = launch_attn_mfma4(pr, m, st);
   if (prof) {
     (void)hipEventRecord(g_prof_stop, st);
