@@ -32,11 +32,7 @@ struct STile {                              // wave-uniform description of one 6
   int row0, kstride, nk, last_row;
 };
 
-#ifdef ISA_DBG_NO_FENCE
-#define ISA_FENCE()
-#else
 #define ISA_FENCE() __builtin_amdgcn_sched_barrier(0)
-#endif
 
 // 16 bytes per lane from global memory straight into LDS: lane i of the wave writes LDS bytes lds_addr + 16 i.
 // Written as inline assembly on purpose.  Issued through the compiler's builtin, every later LDS read is
@@ -74,27 +70,15 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kbase, co
   for (int s = 0; s < 8; ++s) {
     ISA_FENCE();
     vf[s] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + (s & 3) * 32 * 32 + voff[s >> 2]);   // ks = s/4, db = s%4
-#ifndef ISA_DBG_NO_SMFMA
     sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], s == 0 ? zero : sout, 0, 0, 0);
-#else
-    if (s == 0) sout = zero; else sout[s] += (float)kf[s][0] * (float)qf[s][0];
-#endif
-#ifdef ISA_DBG_NO_PAIR
-    if (s == 0) { pf[0] = kf[0]; pf[1] = kf[1]; }
-#else
     {
-#ifdef ISA_DBG_NO_SOFTMAX
-      const float p0 = sin[2 * s], p1 = sin[2 * s + 1];
-#else
       const float p0 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s], cscale, neg_m));
       const float p1 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s + 1], cscale, neg_m));
-#endif
       const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
       l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
       pf[s >> 2][2 * (s & 3)] = pp[0];
       pf[s >> 2][2 * (s & 3) + 1] = pp[1];
     }
-#endif
   }
   // 8 value MFMAs (2 key steps x 4 channel groups); the raw maximum of the new scores fills the VALU slots
   float mx = -INFINITY;
@@ -103,11 +87,7 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kbase, co
     const int ks = c >> 2, db = c & 3;
     ISA_FENCE();
     if (NEXT_K) kf[c] = *reinterpret_cast<const bf16x8*>(kbase + (KB + 1) * 32 * MD + koff[c]);
-#ifndef ISA_DBG_NO_PVMFMA
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[ks], oacc[db], 0, 0, 0);
-#else
-    oacc[db][c] += (float)vf[c][0] * (float)pf[ks][0];
-#endif
     if (c >= 2 && c < 6) {
 #pragma unroll
       for (int e = 4 * (c - 2); e < 4 * (c - 2) + 4; ++e) mx = fmaxf(mx, sout[e]);
@@ -349,20 +329,12 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   int4 ent_next = entry_of(1);
   for (int T = 0; T <= n_tiles; ++T) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#ifndef ISA_DBG_NO_BARRIER
     __syncthreads();
-#endif
     make_tile(T + 1, ent_next, tnext);
-#ifndef ISA_DBG_NO_LOADS
     if (T < n_tiles) {
-#ifndef ISA_DBG_NO_KLOAD
       load_k(tnext, (T + 1) & 1);
-#endif
-#ifndef ISA_DBG_NO_VLOAD
       load_v(tcur.vt, tnext.vt, (T + 1) & 1);
-#endif
     }
-#endif
     if ((min(T + 2, n_tiles - 1) >> 1) >= pbase + 64) refill(pbase + 64);
     ent_next = entry_of(T + 2);
     const uint16_t* kbase = ldsK + (T & 1) * K_TILE;
@@ -370,32 +342,18 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     bf16x8 kf[8];                         // K fragments of rows 0..31 of the new tile; they arrive under prepare_half
 #pragma unroll
     for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(kbase + koff[s8]);
-#ifdef ISA_DBG_REPEAT
-    for (int rep = 0; rep < 2; ++rep) {
-#endif
     {   // half (T-1, 1): scores in s1
       const int nkh = min(32, max(0, tprev.nk - 32));
       const bool general = tprev.bias != nullptr || nkh < 32;
-#ifndef ISA_DBG_NO_PREPARE
       prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, g, cscale, m_run, l_run, oacc);
-#endif
-#ifndef ISA_DBG_NO_COMPUTE
       half_step<0, 0, true>(kbase, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale);
-#endif
     }
     {   // half (T, 0): scores in s0
       const int nkh = min(32, tcur.nk);
       const bool general = tcur.bias != nullptr || nkh < 32;
-#ifndef ISA_DBG_NO_PREPARE
       prepare_half(s0, mx0, general, nkh, tcur.bias, g, cscale, m_run, l_run, oacc);
-#endif
-#ifndef ISA_DBG_NO_COMPUTE
       half_step<1, 1, false>(kbase, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale);
-#endif
     }
-#ifdef ISA_DBG_REPEAT
-    }
-#endif
     tprev = tcur;
     tcur = tnext;
   }

@@ -1,0 +1,73 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the whole isa_attention call
+on the 14B-shaped workloads, checked on sampled query blocks the oracle evaluates one by one (both branches), plus
+validity of every list it chose for the sampled heads; and dense attention on sampled query rows."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import isa_oracle as O
+from test_gpu_parity import TOL, check_end_to_end
+from util import err_stats, f64, problem_of
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def I():
+    import paper_2605_04569_amd as isa
+    isa.lib()
+    return isa
+
+
+def _gen_gpu(wl):
+    q, k, v = W.make_inputs(wl, "cuda")
+    torch.cuda.synchronize()
+    return q, k, v
+
+
+@pytest.mark.parametrize("name,heads,blocks", [("cfg1", (0, 17, 39), 4), ("cfg2", (3, 38), 3), ("cfg4", (21,), 2)])
+def test_isa_attention_full_size_sampled(I, name, heads, blocks):
+    wl = W.CONFIGS[name]
+    print("full-size parity:", name, flush=True)
+    q, k, v = _gen_gpu(wl)
+    a_kv, a_grp = check_end_to_end(I, wl, q, k, v, q, k, v, heads=heads, blocks_per_head=blocks, seed=1)
+    print("  list agreement with the oracle: kv %.2f, grouping %.2f" % (a_kv, a_grp), flush=True)
+
+
+def test_ragged_batch_full_size_sampled(I):
+    """cfg3: two batch items with different context layouts (one has two references)."""
+    wl = W.CONFIGS["cfg3"].with_(keep_ratio=0.25, full_frac=0.1)
+    print("full-size parity: cfg3", flush=True)
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(5,), blocks_per_head=2, seed=2)
+
+
+def test_paper_default_ratios_sampled(I):
+    """The paper's default operating point (Sec. 4.1): alpha_s = 0.125, alpha_f = 0.5, alpha_ns = 0.0625, at cfg1 size."""
+    wl = W.CONFIGS["cfg1"].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(2, 31), blocks_per_head=3, seed=3)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_dense_attention_full_size_sampled(I, name):
+    wl = W.CONFIGS[name]
+    q, k, v = _gen_gpu(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    out = torch.full_like(q, float("nan"))
+    I.isa_dense_attention(pr, q, k, v, out, ws)
+    torch.cuda.synchronize()
+    n = wl.tokens(0)
+    rng = np.random.default_rng(4)
+    tol_max, tol_mean = TOL[wl.dtype]
+    for h in (0, wl.H - 1):
+        Kh, Vh = f64(k[0, h, :n]), f64(v[0, h, :n])
+        rows = np.sort(np.concatenate([rng.choice(n, 96, replace=False), [0, 127, 128, n - 1]]))   # incl. block edges, ragged tail
+        want = O.dense_attention(f64(q[0, h][torch.from_numpy(rows).cuda()]), Kh, Vh)
+        got = f64(out[0, h][torch.from_numpy(rows).cuda()])
+        assert np.isfinite(got).all()
+        emax, emean = err_stats(got, want)
+        assert emax <= tol_max and emean <= tol_mean, (name, h, emax, emean)
+    assert torch.isfinite(out[0, :, :n].float()).all()
