@@ -48,49 +48,35 @@ def algorithmic_flops(wl, isa, pr, lists):
     return full_fl, taylor_fl, dense_fl
 
 
-def cpu_baseline(wl, Q, K, V, budget_s=14.0, max_blocks=48):
-    """The fp64 oracle (as it stands) on a bounded sample of the workload: every index of head 0 (block means,
-    pooled scores, selection, grouping) and the outputs of as many query blocks of each branch as fit in about
-    `budget_s` seconds; the value is extrapolated to the whole call by block counts."""
+def cpu_baseline(wl, Q, K, V, budget_s=12.0):
+    """The fp64 oracle (as it stands) on a bounded sample of the workload: whole heads of batch 0, one after another
+    (all indices and the outputs of every query block of both branches), until about `budget_s` seconds are spent;
+    the value is the mean cost of a head times the number of heads."""
     import numpy as np
     import torch
     from oracle import isa_oracle as O
     n = wl.tokens(0)
-    Qh, Kh, Vh = (t[0, 0, :n].to("cpu").to(torch.float64).numpy() for t in (Q, K, V))
-    t0 = time.perf_counter()
-    plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(0), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac)
-    t_plan = time.perf_counter() - t0
-    rng = np.random.default_rng(0)
-    fb = list(rng.permutation(plan["full_list"])[:max_blocks])
-    tb = list(rng.permutation(plan["flat_list"])[:max_blocks])
-    t_full, t_flat, n_f, n_t = 0.0, 0.0, 0, 0
-    start = time.perf_counter()
-    while (fb or tb) and time.perf_counter() - start < budget_s:
-        if fb:
-            t0 = time.perf_counter()
-            O.attend_block(int(fb.pop()), plan, Qh, Kh, Vh)
-            t_full += time.perf_counter() - t0
-            n_f += 1
-        if tb:
-            t0 = time.perf_counter()
-            O.attend_block(int(tb.pop()), plan, Qh, Kh, Vh)
-            t_flat += time.perf_counter() - t0
-            n_t += 1
-    per_full = t_full / max(1, n_f)
-    per_flat = t_flat / max(1, n_t)
-    per_head = t_plan + plan["n_full"] * per_full + plan["n_flat"] * per_flat
-    total_s = per_head * wl.H * wl.B
+    heads, spent = 0, 0.0
+    while heads < wl.H and spent < budget_s:
+        Qh, Kh, Vh = (t[0, heads, :n].to("cpu").to(torch.float64).numpy() for t in (Q, K, V))
+        t0 = time.perf_counter()
+        plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(0), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac)
+        for i in range(plan["T"]):
+            O.attend_block(i, plan, Qh, Kh, Vh)
+        spent += time.perf_counter() - t0
+        heads += 1
+        log("CPU oracle: head %d done, %.1f s so far" % (heads - 1, spent))
+    tokens_all = sum(wl.tokens(b) for b in range(wl.B))
+    total_s = spent / heads * wl.H * tokens_all / n
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": round(total_s * 1e3, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
-            "sample": "fp64 numpy oracle on head 0 of batch 0: all indices (%.2f s) + %d exact-branch blocks (%.3f s each) "
-                      "+ %d Taylor blocks (%.4f s each) = %.1f s measured; value = that cost extrapolated to %d heads x "
-                      "(%d exact + %d Taylor) blocks"
-                      % (t_plan, n_f, per_full, n_t, per_flat, t_plan + t_full + t_flat, wl.H * wl.B, plan["n_full"],
-                         plan["n_flat"])}
+            "sample": "fp64 numpy oracle, every stage and every query block of %d of the %d heads of batch element 0 "
+                      "(%.1f s measured); value = mean cost of a head x %d heads x batch %d (scaled by tokens)"
+                      % (heads, wl.H, spent, wl.H, wl.B)}
 
 
 def measured_traffic(workload):
@@ -106,38 +92,14 @@ def measured_traffic(workload):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 (480p, default) | cfg3 | cfg4 (720p)")
-    ap.add_argument("--dense-steps", type=int, default=3)
-    ap.add_argument("--exact-frac", type=float, default=None)
-    ap.add_argument("--keep-ratio", type=float, default=None)
-    ap.add_argument("--full-frac", type=float, default=None)
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--no-dense", action="store_true", help="skip the dense attention leg")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the operator shards by head with no exchange; "
-              "nothing here uses a second GPU). Re-run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
-
+def measure(wl, steps, warmup, dense_steps):
+    """Times isa_attention (whole call and the attention kernel alone) and dense attention on one workload."""
     import numpy as np
     import torch
 
     import paper_2605_04569_amd as isa
     import workloads as W
 
-    isa.lib()
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    wl = W.CONFIGS[args.workload]
-    over = {k: v for k, v in (("exact_frac", args.exact_frac), ("keep_ratio", args.keep_ratio),
-                              ("full_frac", args.full_frac)) if v is not None}
-    if over:
-        wl = wl.with_(**over)
     log("generating %s on the GPU" % wl.name)
     Q, K, V = W.make_inputs(wl, "cuda")
     torch.cuda.synchronize()
@@ -149,7 +111,7 @@ def main():
     torch.cuda.synchronize()
 
     # ---- whole call ----------------------------------------------------------------------------
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         isa.isa_attention(pr, Q, K, V, out, ws)
     torch.cuda.synchronize()
     log("warm-up done")
@@ -157,15 +119,15 @@ def main():
     kernel_ms = []
     torch.cuda.synchronize()
     e0.record()
-    for _ in range(args.steps):
+    for _ in range(steps):
         isa.isa_attention(pr, Q, K, V, out, ws)
     e1.record()
     torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step = e0.elapsed_time(e1) / steps
     # the dominant kernel alone: the hook re-records the same event pair at every launch, so time it launch by launch
     log("isa_attention: %.3f ms per call" % ms_per_step)
     isa.isa_time_attention_kernel(True)
-    for _ in range(args.steps):
+    for _ in range(steps):
         isa.isa_attention(pr, Q, K, V, out, ws)
         kernel_ms.append(isa.isa_last_attention_kernel_ms())
     isa.isa_time_attention_kernel(False)
@@ -193,21 +155,79 @@ def main():
 
     # ---- dense attention at the same shape --------------------------------------------------------
     dense_ms = None
-    if not args.no_dense:
+    if dense_steps > 0:
         dout = torch.empty_like(Q)
         isa.isa_dense_attention(pr, Q, K, V, dout, ws)
         torch.cuda.synchronize()
         e0.record()
-        for _ in range(args.dense_steps):
+        for _ in range(dense_steps):
             isa.isa_dense_attention(pr, Q, K, V, dout, ws)
         e1.record()
         torch.cuda.synchronize()
-        dense_ms = e0.elapsed_time(e1) / args.dense_steps
+        dense_ms = e0.elapsed_time(e1) / dense_steps
         del dout
         log("dense attention: %.3f ms per call" % dense_ms)
 
+    del out, ws
+    return {"ms_per_step": ms_per_step, "kern_ms": kern_ms, "dense_ms": dense_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
+            "inputs": (Q, K, V)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 (480p, default) | cfg3 | cfg4 (720p)")
+    ap.add_argument("--dense-steps", type=int, default=3)
+    ap.add_argument("--exact-frac", type=float, default=None)
+    ap.add_argument("--keep-ratio", type=float, default=None)
+    ap.add_argument("--full-frac", type=float, default=None)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense attention leg")
+    ap.add_argument("--also", default="cfg1,cfg4", help="other workloads to time briefly after the main one ('' = none)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the operator shards by head with no exchange; "
+              "nothing here uses a second GPU). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2605_04569_amd as isa
+    import workloads as W
+
+    isa.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = W.CONFIGS[args.workload]
+    over = {k: v for k, v in (("exact_frac", args.exact_frac), ("keep_ratio", args.keep_ratio),
+                              ("full_frac", args.full_frac)) if v is not None}
+    if over:
+        wl = wl.with_(**over)
+    r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps)
+    ms_per_step, kern_ms, dense_ms = r["ms_per_step"], r["kern_ms"], r["dense_ms"]
+    isa_fl, dense_fl = r["isa_fl"], r["dense_fl"]
+    Q, K, V = r["inputs"]
+
     log("CPU oracle sample ...")
     cpu = None if args.no_cpu else cpu_baseline(wl, Q, K, V)
+
+    del Q, K, V, r
+    torch.cuda.empty_cache()
+    others = []
+    for name in [n for n in args.also.split(",") if n and n != args.workload and not over]:
+        o_wl = W.CONFIGS[name]
+        o = measure(o_wl, 5, 2, 0 if args.no_dense else 2)
+        others.append({"workload": name, "tokens": [o_wl.tokens(b) for b in range(o_wl.B)],
+                       "isa_ms_per_call": round(o["ms_per_step"], 3), "kernel_ms": round(o["kern_ms"], 3),
+                       "kernel_tflops": round(o["isa_fl"] / (o["kern_ms"] * 1e-3) / 1e12, 1),
+                       "dense_ms_per_call": None if o["dense_ms"] is None else round(o["dense_ms"], 3),
+                       "dense_tflops": None if o["dense_ms"] is None else round(o["dense_fl"] / (o["dense_ms"] * 1e-3) / 1e12, 1),
+                       "speedup_vs_dense": None if o["dense_ms"] is None else round(o["dense_ms"] / o["ms_per_step"], 3),
+                       "steps": 5})
+        del o
+        torch.cuda.empty_cache()
 
     achieved = isa_fl / (kern_ms * 1e-3) / 1e12
     result = {
@@ -237,6 +257,7 @@ def main():
                      "algorithmic_tflop_per_launch": round(isa_fl / 1e12, 3),
                      "traffic": measured_traffic(wl.name) if not over else None},
         "cpu_baseline": cpu,
+        "other_workloads": others,
         "paper_context": "paper reports ~60% lower attention-module latency vs SDPA/FlashAttention (GPU not stated; Hopper implied)",
     }
     print(json.dumps(result))
