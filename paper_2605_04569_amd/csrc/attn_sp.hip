@@ -2,12 +2,10 @@
 // exact branch of ISA (Alg. 1 Stage 4 / Alg. 2 Part A) and the Taylor branch without exact sets (Eq. 4,
 // Alg. 2 Part B).
 //
-// Why it is shaped this way.  On this chip a wave whose next instruction is an MFMA that has to wait for the
-// matrix pipe blocks the vector-ALU issue of its SIMD for every wave, so "one wave multiplies while another
-// wave does softmax" does not happen by itself: measured, a wave of back-to-back MFMAs and a wave of pure
-// VALU work on one SIMD take the sum of their times.  What does overlap is VALU work issued in the shadow of
-// an MFMA by the same instruction stream.  So each wave here runs one stream in which every MFMA is followed
-// by the few VALU instructions and the one LDS read that fit under it:
+// Why it is shaped this way.  Vector-ALU work overlaps an MFMA best when the same wave issues it right behind
+// that MFMA (measured on a 2-wave SIMD: 8 MFMAs with 2 fma + 2 exp2 + 1 convert behind each run 5 % slower than
+// the MFMAs alone), so each wave runs one instruction stream in which every MFMA is followed by the few VALU
+// instructions and the one LDS read that fit under it, held in place with scheduling fences and value pins:
 //
 //   keys are handled in halves of 32 (one MFMA row group).  While the 8 MFMAs that compute the raw scores of
 //   half h+1 are in flight, the wave exponentiates the scores of half h (computed one step earlier); while
@@ -18,9 +16,16 @@
 // first half of tile T), which keeps one barrier and one load group per iteration.
 //
 // One workgroup of 8 waves owns two query blocks (2 x 128 rows) that walk the same tile sequence, so every K /
-// V^T tile is fetched once per 256 query rows; a SIMD holds two waves.  Scores are
-// computed transposed (S^T = K Q^T) and V is read from the packed, key-permuted V^T copy, as in the 4-wave
-// kernel: P stays in registers in the layout the second product needs.
+// V^T tile is fetched once per 256 query rows; a SIMD holds two waves.  Scores are computed transposed
+// (S^T = K Q^T) and V is read from the packed, key-permuted V^T copy, as in the 4-wave kernel: P stays in
+// registers in the layout the second product needs.
+//
+// What bounds it.  With real (non-constant) operands the matrix pipes of this chip are limited by power, not by
+// issue slots: a stream of nothing but 32x32x16 bf16 MFMAs runs at 2.4 PFLOP/s on constant operands and at
+// 1.8 PFLOP/s on random ones, and in this kernel taking stall cycles out of the loop (deeper prefetch, no
+// barrier, fewer vector instructions) lowers the clock the chip holds (1.9 - 2.2 GHz) and leaves the time
+// unchanged.  What does change the time is the energy per tile: bytes moved behind the L2, LDS traffic, and the
+// number of MFMAs themselves.
 #include "attn_mfma.h"
 
 namespace isa {
@@ -33,6 +38,7 @@ struct STile {                              // wave-uniform description of one 6
 };
 
 #define ISA_FENCE() __builtin_amdgcn_sched_barrier(0)
+constexpr int NBUF = 3;                     // LDS tile buffers: the loads of two tiles are in flight while one is consumed
 
 // 16 bytes per lane from global memory straight into LDS: lane i of the wave writes LDS bytes lds_addr + 16 i.
 // Written as inline assembly on purpose.  Issued through the compiler's builtin, every later LDS read is
@@ -47,59 +53,107 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
 }
 
+// Keeps a value (and everything it depends on) on this side of the next scheduling fence: without it the
+// compiler sinks work whose result is needed only later (row sums, maxima) out of the MFMA shadow it was placed in.
+__device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(bf16x2& x) {
+  uint32_t w = __builtin_bit_cast(uint32_t, x);
+  asm volatile("" : "+v"(w));
+  x = __builtin_bit_cast(bf16x2, w);
+}
+__device__ __forceinline__ float max_raw(float a, float b) {        // v_max_f32 without the NaN-quieting prologue
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 // One half step.  Scores of the half that is softmaxed come in `sin` (raw, bias and masks already applied,
 // running maximum already raised); the raw scores of the next half are produced in `sout` from the 8 K
-// fragments in `kf` (rows KB*32 .. +31 of the K tile, fetched from LDS one phase earlier), and their raw
-// maximum in `mx_out`.  The value product uses V^T unit VU of the staged V^T tile.
+// fragments in `kf` (32 rows of the K tile, fetched from LDS one phase earlier).  `tmax_out` is the scaled
+// maximum of `sout` over both key halves of the lane's query row (valid when `sout` needs no bias or mask).
+// The value product uses V^T unit VU of the staged V^T tile.
 // LDS fragments are requested a whole phase (8 MFMAs) before the MFMA that consumes them: the V^T fragments
-// during the score MFMAs, and (NEXT_K) the K fragments of rows (KB+1)*32 .. for the following half step during
-// the value MFMAs.
-template <int KB, int VU, bool NEXT_K>
-__device__ __forceinline__ void half_step(const uint16_t* __restrict__ kbase, const uint16_t* __restrict__ vbase,
+// during the score MFMAs, and the K fragments of the following half step (32 rows at `kpre`) during the value
+// MFMAs.  Every vector-ALU instruction of the softmax sits between two MFMAs of the same wave, and so does
+// whatever `hook(s)` adds after score MFMA s (tile set-up and tile loads of a later iteration).
+template <int VU, typename Hook>
+__device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[8], bf16x8 (&kf)[8], const f32x16& sin, f32x16& sout,
-                                          f32x16 (&oacc)[4], float m_run, float& l_run, float& mx_out,
-                                          const int (&koff)[8], const int (&voff)[2], float cscale) {
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+                                          f32x16 (&oacc)[4], float m_run, float& l_run, float& tmax_out,
+                                          const int (&koff)[8], const int (&voff)[2], float cscale, Hook hook
+                                          ) {
   const float neg_m = -m_run;
+  bf16x2 pw[8];
   bf16x8 pf[2], vf[8];
   f32x16 zero;
 #pragma unroll
   for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-  // 8 score MFMAs, each followed by one pair of weights (2 fma, 2 exp2, 1 convert, 1 dot) and one LDS read
+  // 8 score MFMAs, each followed by one pair of weights (2 fma, 2 exp2, 1 convert) and one LDS read
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
     ISA_FENCE();
     vf[s] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + (s & 3) * 32 * 32 + voff[s >> 2]);   // ks = s/4, db = s%4
     sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], s == 0 ? zero : sout, 0, 0, 0);
-    {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s], cscale, neg_m));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s + 1], cscale, neg_m));
-      const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
-      l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sum of the rounded weights
-      pf[s >> 2][2 * (s & 3)] = pp[0];
-      pf[s >> 2][2 * (s & 3) + 1] = pp[1];
-    }
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s], cscale, neg_m));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s + 1], cscale, neg_m));
+    pw[s] = bf16x2{(__bf16)p0, (__bf16)p1};
+    pin(pw[s]);
+    hook(s);
   }
-  // 8 value MFMAs (2 key steps x 4 channel groups); the raw maximum of the new scores fills the VALU slots
-  float mx = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    pf[s >> 2][2 * (s & 3)] = pw[s][0];
+    pf[s >> 2][2 * (s & 3) + 1] = pw[s][1];
+  }
+  // 8 value MFMAs (2 key steps x 4 channel groups).  Their shadows take the row sums of the weights
+  // (every c), the raw maximum of the new scores (c = 2..5; the last score MFMA has retired by then) and the
+  // exchange of that maximum between the two lanes that share a query row (c = 6, 7).
+  float mx = -INFINITY, other = 0.f;
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
     const int ks = c >> 2, db = c & 3;
     ISA_FENCE();
-    if (NEXT_K) kf[c] = *reinterpret_cast<const bf16x8*>(kbase + (KB + 1) * 32 * MD + koff[c]);
+    kf[c] = *reinterpret_cast<const bf16x8*>(kpre + koff[c]);
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[ks], oacc[db], 0, 0, 0);
+    {
+      // Row sum over the weights as rounded to bf16 (what the value product multiplies), so that the rounding of a
+      // dominant weight cancels between numerator and denominator.  Unpacked and added on the vector ALU: the
+      // packed bf16 dot instruction would do it in one go but executes in the matrix pipe and stalls the MFMAs.
+      const uint32_t w = __builtin_bit_cast(uint32_t, pw[c]);
+      l_run += __uint_as_float(w << 16);
+      l_run += __uint_as_float(w & 0xffff0000u);
+      pin(l_run);
+    }
     if (c >= 2 && c < 6) {
-#pragma unroll
-      for (int e = 4 * (c - 2); e < 4 * (c - 2) + 4; ++e) mx = fmaxf(mx, sout[e]);
+      const int e = 4 * (c - 2);
+      mx = fmaxf(fmaxf(mx, sout[e]), sout[e + 1]);
+      mx = fmaxf(fmaxf(mx, sout[e + 2]), sout[e + 3]);
+      pin(mx);
+    }
+    if (c == 6) {
+      // lanes l and l ^ 32 hold the two key halves of one query: exchange through v_permlane32_swap, which
+      // (unlike a shuffle through the LDS crossbar) does not queue behind the LDS fragment reads in flight
+      mx *= cscale;
+      const uint32_t u = __float_as_uint(mx);
+      const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+      mx = __uint_as_float(sw[0]);
+      other = __uint_as_float(sw[1]);
+      pin(mx);
+      pin(other);
+    }
+    if (c == 7) {
+      mx = max_raw(mx, other);
+      pin(mx);
     }
   }
   ISA_FENCE();
-  mx_out = mx;
+  tmax_out = mx;
 }
 
 // Bias / masks of a special half (block means, ragged tails), then the running maximum of the online softmax
 // (Alg. 2 Part A) with the rare rescale of the accumulators.  Element e of a half is key 8(e/4) + 4g + e%4.
-__device__ __forceinline__ void prepare_half(f32x16& sc, float& mx, bool general, int nk_half, const float* __restrict__ bias,
+// `tmax` comes in as the scaled row maximum of a plain half; a special half recomputes it here.
+__device__ __forceinline__ void prepare_half(f32x16& sc, float tmax, bool general, int nk_half, const float* __restrict__ bias,
                                              int g, float cscale, float& m_run, float& l_run, f32x16 (&oacc)[4]) {
   if (general) {
     float addv[16];
@@ -119,13 +173,8 @@ __device__ __forceinline__ void prepare_half(f32x16& sc, float& mx, bool general
       sc[e] = key >= nk_half ? -INFINITY : sc[e] + addv[e];
       m2 = fmaxf(m2, sc[e]);
     }
-    mx = m2;
-  }
-  float tmax = mx * cscale;
-  {
-    // lanes l and l ^ 32 hold the two key halves of one query: exchange through v_permlane32_swap, which (unlike
-    // a shuffle through the LDS crossbar) does not queue behind the LDS fragment reads in flight
-    const uint32_t u = __float_as_uint(tmax);
+    m2 *= cscale;
+    const uint32_t u = __float_as_uint(m2);
     const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
   }
@@ -143,9 +192,9 @@ __device__ __forceinline__ void prepare_half(f32x16& sc, float& mx, bool general
 }
 
 __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE];
-  uint16_t* ldsK = lds;                     // K tile T lives in buffer T & 1
-  uint16_t* ldsV = lds + 2 * K_TILE;        // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T & 1
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[NBUF * K_TILE + NBUF * V_TILE];
+  uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
+  uint16_t* ldsV = lds + NBUF * K_TILE;     // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T % NBUF
 
   // ---- which work item: consecutive logical ids go to the same XCD, so that the workgroups that run
   // together on one XCD (and share its L2) read the same head's keys and values
@@ -187,20 +236,16 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // Tile idx of the sequence, built from the table row `ent` = {token offset, real tokens, block index} of its list
   // entry (token tiles); idx == n_tiles (one past the end) gives a fully masked tile over valid memory.
   const int4* tab = a.dense ? a.btab + (long long)b * T_max : a.ktab + bh * T_max;
-  // The workgroups that run together on an XCD would all walk the tile sequence in step, so that only the one in
-  // front ever misses the L2.  Each workgroup therefore starts at one of eight evenly spaced points of the
-  // (cyclic) sequence.  The online softmax does not care about the order of the tiles.
-  const int rot = (slot & 7) * ((n_tiles >> 3) & ~1);
-  auto rotated = [&](int idx) { const int r = idx + rot; return r >= n_tiles ? r - n_tiles : r; };
+  // Every workgroup of a head walks the tile sequence from its start: the workgroups that run together on an XCD
+  // then stream the same tiles at about the same time and share them in that XCD's L2 (measured: starting them at
+  // spread-out points of the sequence multiplies the traffic behind the L2 and is slower).
   // Table rows are fetched 64 at a time with one vector load (lane L holds the row of list position pbase + L)
   // and handed out with readlane, so that no load other than the tile loads is in flight inside the loop.
   int4 ecache = make_int4(0, 0, 0, 0);
   int pbase = 0;
   auto refill = [&](int p0) {
     if (!taylor) {
-      int e = min(p0 + lane, n_list - 1) + (rot >> 1);
-      if (e >= n_list) e -= n_list;
-      ecache = tab[e];
+      ecache = tab[min(p0 + lane, n_list - 1)];
       // consume the rows here, so that the wait for this (rare) load sits inside this branch and not at the
       // loop-wide join, where it would also wait for the tile loads that were just issued
       asm volatile("" : "+v"(ecache.x), "+v"(ecache.y), "+v"(ecache.z));
@@ -215,7 +260,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   auto make_tile = [&](int idx, int4 ent, STile& t) {
     const bool past = idx >= n_tiles;
     if (past) idx = n_tiles - 1;
-    idx = rotated(idx);
     if (!taylor) {
       const int sub = idx & 1;
       const int n_j = ent.y;
@@ -266,36 +310,30 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     kchunk_b[i] = (uint32_t)((((lane & 15) ^ ((8 * wave + 4 * i + l16) & 15)) * 8) * 2);
     klane_b[i] = (uint32_t)l16 * kstride_b + kchunk_b[i];
   }
-  auto load_k = [&](const STile& t, int buf) {
+  auto load_k1 = [&](const STile& t, int buf, int i) {
     const char* kb = reinterpret_cast<const char*>(t.krows);
     if (t.row0 + KT - 1 <= t.last_row) {                            // whole tile inside the block: lane-constant offsets
       const char* kw = kb + (size_t)(t.row0 + wave * 8) * kstride_b;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-        lds_dma16(kw + (size_t)(4 * i) * kstride_b, klane_b[i], lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
+      lds_dma16(kw + (size_t)(4 * i) * kstride_b, klane_b[i], lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
     } else {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        // rows past the block's end re-read its last row; the row index is never negative
-        const int r = max(min(t.row0 + wave * 8 + 4 * i + l16, t.last_row), 0);
-        const uint32_t koff_b = (uint32_t)r * kstride_b + kchunk_b[i];
-        lds_dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
-      }
+      // rows past the block's end re-read its last row; the row index is never negative
+      const int r = max(min(t.row0 + wave * 8 + 4 * i + l16, t.last_row), 0);
+      const uint32_t koff_b = (uint32_t)r * kstride_b + kchunk_b[i];
+      lds_dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
     }
   };
+  auto load_k = [&](const STile& t, int buf) { load_k1(t, buf, 0); load_k1(t, buf, 1); };
   // Shifted V^T tile in LDS, unit-major: unit 0 = key positions 32..63 of tile `ta`, unit 1 = positions 0..31 of
   // `tb`; a unit is 128 rows (channels) of 64 B, 16-byte chunk c of row r stored at chunk c ^ ((r >> 2) & 3).
   // Waves 0-3 fill unit 0 and waves 4-7 unit 1, so the source tile of an instruction is wave-uniform and the
   // per-lane part of the address is one constant: rows 16(2w+i mod 8) + lane/4, chunk (lane & 3) ^ (lane >> 4).
   const uint32_t vlane_b = (uint32_t)(((lane >> 2) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
-  auto load_v = [&](const uint16_t* ta, const uint16_t* tb, int buf) {
+  auto load_v1 = [&](const uint16_t* ta, const uint16_t* tb, int buf, int i) {
     const uint16_t* srcu = wave < 4 ? ta + 32 : tb;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 2 + i) & 7) * 16) * KT);
-      lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 2 + i) * 512));
-    }
+    const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 2 + i) & 7) * 16) * KT);
+    lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 2 + i) * 512));
   };
+  auto load_v = [&](const uint16_t* ta, const uint16_t* tb, int buf) { load_v1(ta, tb, buf, 0); load_v1(ta, tb, buf, 1); };
 
   // per-lane fragment offsets (bf16 elements): K row = col, chunk (2s+g) ^ (col & 15); V^T unit row = col, chunk (2ks+g) ^ ((col>>2)&3)
   int koff[8], voff[2];
@@ -311,52 +349,69 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
 #pragma unroll
   for (int e = 0; e < 16; ++e) { s0[e] = -INFINITY; s1[e] = -INFINITY; }
-  float m_run = M_INIT, l_run = 0.f, mx0 = -INFINITY, mx1 = -INFINITY;
+  float m_run = M_INIT, l_run = 0.f, mx0 = -INFINITY, mx1 = -INFINITY;   // mx*: scaled row maxima of s0 / s1
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
   // ---- loop over T = 0 .. n_tiles (one extra, fully masked iteration drains the pipeline).  Iteration T:
-  //   barrier; request K tile T+1 and shifted V^T tile T+1 for the next iteration;
-  //   softmax of half (T-1,1) under the score MFMAs of half (T,0); value MFMAs of half (T-1,1);
-  //   softmax of half (T,0)   under the score MFMAs of half (T,1); value MFMAs of half (T,0).
-  // The table row of tile T+2 is requested (scalar load) in iteration T and first used in iteration T+1, so its
-  // latency is never waited for.
-  STile tprev, tcur, tnext;
+  //   wait for this wave's loads of tile T+1; barrier (tile T+1 is now complete for every wave);
+  //   softmax of half (T-1,1) under the score MFMAs of half (T,0), with the set-up and the loads of tile T+2 in the
+  //   same shadows; value MFMAs of half (T-1,1);
+  //   softmax of half (T,0) under the score MFMAs of half (T,1); value MFMAs of half (T,0), in whose shadows the K
+  //   fragments of half (T+1,0) are fetched, so that no LDS latency is exposed after the next barrier.
+  // Three buffers: tile T is consumed, tile T+1 is complete and read ahead, tile T+2 is in flight.  Buffer
+  // (T+2) % 3 was last read in iteration T-1, which every wave has left once it is past this iteration's barrier.
+  STile tprev, tcur, tnext, tnn;
   refill(0);
   make_tile(0, entry_of(0), tcur);
+  make_tile(1, entry_of(1), tnext);
   tprev = tcur; tprev.nk = 0; tprev.bias = nullptr; tprev.vt = a.zero_tile;
   load_k(tcur, 0);
   load_v(a.zero_tile, tcur.vt, 0);
-  int4 ent_next = entry_of(1);
+  load_k(tnext, 1);
+  load_v(tcur.vt, tnext.vt, 1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  bf16x8 kf[8];                           // K fragments of the next 32 rows to be multiplied
+#pragma unroll
+  for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(ldsK + koff[s8]);
+  int bcur = 0;                             // T % NBUF
   for (int T = 0; T <= n_tiles; ++T) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    make_tile(T + 1, ent_next, tnext);
-    if (T < n_tiles) {
-      load_k(tnext, (T + 1) & 1);
-      load_v(tcur.vt, tnext.vt, (T + 1) & 1);
-    }
-    if ((min(T + 2, n_tiles - 1) >> 1) >= pbase + 64) refill(pbase + 64);
-    ent_next = entry_of(T + 2);
-    const uint16_t* kbase = ldsK + (T & 1) * K_TILE;
-    const uint16_t* vbase = ldsV + (T & 1) * V_TILE;
-    bf16x8 kf[8];                         // K fragments of rows 0..31 of the new tile; they arrive under prepare_half
-#pragma unroll
-    for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(kbase + koff[s8]);
+    const int bnext = bcur == 2 ? 0 : bcur + 1;                     // (T + 1) % 3
+    const int bnn = bcur == 0 ? 2 : bcur - 1;                       // (T + 2) % 3
+    const uint16_t* kbase = ldsK + bcur * K_TILE;
+    const uint16_t* vbase = ldsV + bcur * V_TILE;
     {   // half (T-1, 1): scores in s1
       const int nkh = min(32, max(0, tprev.nk - 32));
       const bool general = tprev.bias != nullptr || nkh < 32;
       prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, g, cscale, m_run, l_run, oacc);
-      half_step<0, 0, true>(kbase, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale);
+      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale, [&](int s) {
+        if (s == 0) {
+          if ((min(T + 2, n_tiles - 1) >> 1) >= pbase + 64) refill(pbase + 64);
+          make_tile(T + 2, entry_of(T + 2), tnn);
+        }
+        if (s == 2) load_k1(tnn, bnn, 0);
+        if (s == 3) load_k1(tnn, bnn, 1);
+        if (s == 4) load_v1(tnext.vt, tnn.vt, bnn, 0);
+        if (s == 5) load_v1(tnext.vt, tnn.vt, bnn, 1);
+      }
+      );
     }
     {   // half (T, 0): scores in s0
       const int nkh = min(32, tcur.nk);
       const bool general = tcur.bias != nullptr || nkh < 32;
       prepare_half(s0, mx0, general, nkh, tcur.bias, g, cscale, m_run, l_run, oacc);
-      half_step<1, 1, false>(kbase, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale);
+      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale, [](int) {}
+      );
     }
     tprev = tcur;
     tcur = tnext;
+    tnext = tnn;
+    bcur = bnext;
   }
+  // the loads of the two tiles past the end still target this workgroup's LDS: let them land before the waves end
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
