@@ -196,25 +196,27 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
   uint16_t* ldsV = lds + NBUF * K_TILE;     // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T % NBUF
 
-  // ---- which work item: consecutive logical ids go to the same XCD, so that the workgroups that run
-  // together on one XCD (and share its L2) read the same head's keys and values
-  const int per_xcd = gridDim.x >> 3;       // grid is a multiple of 8
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= a.total) return;
-  const int slot = logical % a.slots;
-  const int bhid = logical / a.slots;
+  // ---- which work item.  Workgroup ids go round-robin over the 8 XCDs, so XCD x sees ids x, x + 8, ... in
+  // order.  Each XCD owns `hpx` consecutive (batch, head)s, so that the workgroups that run together on it (and
+  // share its L2) read the same head's keys and values; it is handed all their exact-branch pairs first (the long
+  // items) and then all their Taylor pairs (short items, which fill the compute units that the last, incomplete
+  // round of long items leaves idle).
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int n_long = a.n_long;
+  const bool taylor = j >= n_long;
+  const int hl = taylor ? (j - n_long) / a.slots_second : j / a.slots_first;
+  const int slot = taylor ? (j - n_long) % a.slots_second : j % a.slots_first;      // pair index inside its branch
+  const int bhid = xcd * a.hpx + hl;
+  if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const BatchCounts c = a.cnt.b[b];
   const int T_max = a.geo.T_max;
   const long long bh = bhid;
 
-  // slots of a (batch, head): pairs of exact-branch blocks first (the long ones), then pairs of Taylor blocks;
   // waves 0-3 take the first block of the pair, waves 4-7 the second
   const int n_first_blocks = a.dense ? c.T : c.n_full;
   const int n_second_blocks = (a.dense || !a.taylor_here) ? 0 : c.n_flat;
-  const int n_first = (n_first_blocks + 1) >> 1, n_second = (n_second_blocks + 1) >> 1;
-  if (slot >= n_first + n_second) return;
-  const bool taylor = slot >= n_first;
+  if (slot >= (((taylor ? n_second_blocks : n_first_blocks) + 1) >> 1)) return;
   const int n_list = a.dense ? c.T : c.T_new;
   const int* bn = a.blk_n + b * T_max;
   const int* bs = a.blk_start + b * T_max;
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   const int col = lane & 31, g = lane >> 5;
   // this wave's query block; the second group idles (computes on block 0, stores nothing) in the last pair of
   // an odd list
-  const int entry = 2 * (taylor ? slot - n_first : slot) + grp;
+  const int entry = 2 * slot + grp;
   const bool active = entry < (taylor ? n_second_blocks : n_first_blocks);
   const int qi = !active ? 0 : a.dense ? entry : (taylor ? a.flat_list[bh * T_max + entry] : a.full_list[bh * T_max + entry]);
   const int n_q = active ? bn[qi] : 0;
@@ -448,21 +450,26 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
   m.taylor_here = exact_sets ? 0 : 1;
   m.taylor_only = 1;
-  // slots per (batch, head): the largest pair count over the batch
-  int slots = 0;
+  // pair slots per (batch, head): the largest counts over the batch
+  int sf = 0, ss = 0;
   for (int b = 0; b < pr.p.B; ++b) {
     const BatchCounts& c = pr.cnt.b[b];
-    const int sl = a.dense ? (c.T + 1) / 2 : (c.n_full + 1) / 2 + (m.taylor_here ? (c.n_flat + 1) / 2 : 0);
-    slots = sl > slots ? sl : slots;
+    const int f = a.dense ? (c.T + 1) / 2 : (c.n_full + 1) / 2;
+    const int s2 = (a.dense || !m.taylor_here) ? 0 : (c.n_flat + 1) / 2;
+    sf = f > sf ? f : sf;
+    ss = s2 > ss ? s2 : ss;
   }
   const bool prof = g_prof_on && g_prof_start && g_prof_stop;
   if (prof) (void)hipEventRecord(g_prof_start, st);
   hipError_t e = hipSuccess;
-  if (slots > 0) {
-    m.slots = slots;
-    m.total = pr.p.B * pr.p.H * slots;
-    const int grid = (m.total + 7) / 8 * 8;
-    hipLaunchKernelGGL(k_attn_sp, dim3(grid), dim3(512), 0, st, m);
+  if (sf + ss > 0) {
+    m.slots_first = sf > 0 ? sf : 1;        // divisors in the kernel; a branch with no work gets no workgroups
+    m.slots_second = ss > 0 ? ss : 1;
+    m.hpx = (pr.p.B * pr.p.H + 7) / 8;
+    m.n_long = m.hpx * sf;
+    const long long per_xcd = (long long)m.hpx * (sf + ss);
+    m.slots = 0; m.total = 0;
+    hipLaunchKernelGGL(k_attn_sp, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, m);
     e = hipGetLastError();
   }
   if (e == hipSuccess && exact_sets) e = launch_attn_mfma4(pr, m, st);
