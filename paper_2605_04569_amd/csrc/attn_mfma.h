@@ -42,6 +42,8 @@ struct MfmaArgs {
   int taylor_only;                          // k_attn_mfma: process only the Taylor slots (the exact branch ran elsewhere)
   int slots_first, slots_second;            // k_attn_sp: exact / Taylor pair slots per (batch, head), each at least 1
   int hpx, n_long;                          // k_attn_sp: (batch, head)s per XCD; exact-branch items per XCD (0 if none)
+  int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges
+  float* split_o; float* split_ml;          // their partial results: unnormalised outputs [sub-item][2][128][128], {max, sum} [sub-item][2][128][2]
   int taylor_here;                          // k_attn_sp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only
 };
 

@@ -202,10 +202,16 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // items) and then all their Taylor pairs (short items, which fill the compute units that the last, incomplete
   // round of long items leaves idle).
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  const int n_long = a.n_long;
-  const bool taylor = j >= n_long;
-  const int hl = taylor ? (j - n_long) / a.slots_second : j / a.slots_first;
-  const int slot = taylor ? (j - n_long) % a.slots_second : j % a.slots_first;      // pair index inside its branch
+  // The last n_split long items of the XCD (those of its last, incomplete round) run as `parts` sub-items, each over
+  // 1/parts of the key sequence, so that the round fills all compute units; a merge kernel combines their partial
+  // results afterwards.
+  const int n_whole = a.n_long - a.n_split, n_sub = a.n_split * a.parts;
+  const bool taylor = j >= n_whole + n_sub;
+  const bool split = !taylor && j >= n_whole;
+  const int item = taylor ? j - n_whole - n_sub : split ? n_whole + (j - n_whole) / a.parts : j;
+  const int part = split ? (j - n_whole) % a.parts : 0;
+  const int hl = taylor ? item / a.slots_second : item / a.slots_first;
+  const int slot = taylor ? item % a.slots_second : item % a.slots_first;           // pair index inside its branch
   const int bhid = xcd * a.hpx + hl;
   if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
@@ -222,6 +228,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   const int* bs = a.blk_start + b * T_max;
   const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
   const int n_tiles = taylor ? (n_list + KT - 1) / KT : 2 * n_list;
+  // tiles [t_begin, t_end) of the sequence are this item's; sub-items cut the list at block boundaries
+  const int t_begin = split ? 2 * (int)(((long long)n_list * part) / a.parts) : 0;
+  const int t_end = split ? 2 * (int)(((long long)n_list * (part + 1)) / a.parts) : n_tiles;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // 0..7, scalar
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   const int q_start = bs[qi];
 
   // Tile idx of the sequence, built from the table row `ent` = {token offset, real tokens, block index} of its list
-  // entry (token tiles); idx == n_tiles (one past the end) gives a fully masked tile over valid memory.
+  // entry (token tiles); idx >= t_end (past the end) gives a fully masked tile over valid memory.
   const int4* tab = a.dense ? a.btab + (long long)b * T_max : a.ktab + bh * T_max;
   // Every workgroup of a head walks the tile sequence from its start: the workgroups that run together on an XCD
   // then stream the same tiles at about the same time and share them in that XCD's L2 (measured: starting them at
@@ -255,13 +264,13 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     pbase = p0;
   };
   auto entry_of = [&](int idx) -> int4 {
-    const int l = (min(idx, n_tiles - 1) >> 1) - pbase;          // 0..63 by construction of the refills
+    const int l = (min(idx, t_end - 1) >> 1) - pbase;            // 0..63 by construction of the refills
     return make_int4(__builtin_amdgcn_readlane(ecache.x, l), __builtin_amdgcn_readlane(ecache.y, l),
                      __builtin_amdgcn_readlane(ecache.z, l), 0);
   };
   auto make_tile = [&](int idx, int4 ent, STile& t) {
-    const bool past = idx >= n_tiles;
-    if (past) idx = n_tiles - 1;
+    const bool past = idx >= t_end;
+    if (past) idx = t_end - 1;
     if (!taylor) {
       const int sub = idx & 1;
       const int n_j = ent.y;
@@ -354,7 +363,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   float m_run = M_INIT, l_run = 0.f, mx0 = -INFINITY, mx1 = -INFINITY;   // mx*: scaled row maxima of s0 / s1
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
-  // ---- loop over T = 0 .. n_tiles (one extra, fully masked iteration drains the pipeline).  Iteration T:
+  // ---- loop over T = t_begin .. t_end (one extra, fully masked iteration drains the pipeline).  Iteration T:
   //   wait for this wave's loads of tile T+1; barrier (tile T+1 is now complete for every wave);
   //   softmax of half (T-1,1) under the score MFMAs of half (T,0), with the set-up and the loads of tile T+2 in the
   //   same shadows; value MFMAs of half (T-1,1);
@@ -363,9 +372,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // Three buffers: tile T is consumed, tile T+1 is complete and read ahead, tile T+2 is in flight.  Buffer
   // (T+2) % 3 was last read in iteration T-1, which every wave has left once it is past this iteration's barrier.
   STile tprev, tcur, tnext, tnn;
-  refill(0);
-  make_tile(0, entry_of(0), tcur);
-  make_tile(1, entry_of(1), tnext);
+  refill(t_begin >> 1);
+  make_tile(t_begin, entry_of(t_begin), tcur);
+  make_tile(t_begin + 1, entry_of(t_begin + 1), tnext);
   tprev = tcur; tprev.nk = 0; tprev.bias = nullptr; tprev.vt = a.zero_tile;
   load_k(tcur, 0);
   load_v(a.zero_tile, tcur.vt, 0);
@@ -377,7 +386,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
 #pragma unroll
   for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(ldsK + koff[s8]);
   int bcur = 0;                             // T % NBUF
-  for (int T = 0; T <= n_tiles; ++T) {
+  for (int T = t_begin; T <= t_end; ++T) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int bnext = bcur == 2 ? 0 : bcur + 1;                     // (T + 1) % 3
@@ -390,7 +399,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
       prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, g, cscale, m_run, l_run, oacc);
       half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale, [&](int s) {
         if (s == 0) {
-          if ((min(T + 2, n_tiles - 1) >> 1) >= pbase + 64) refill(pbase + 64);
+          if ((min(T + 2, t_end - 1) >> 1) >= pbase + 64) refill(pbase + 64);
           make_tile(T + 2, entry_of(T + 2), tnn);
         }
         if (s == 2) load_k1(tnn, bnn, 0);
@@ -417,7 +426,20 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
 
   // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (row_ok) {
+  if (split) {
+    // partial result of a sub-item: unnormalised fp32 outputs and the {maximum, sum} they refer to
+    const long long sid = (((long long)xcd * a.n_split + (item - n_whole)) * a.parts + part) * 2 + grp;
+    if (row_ok) {
+      float* op = a.split_o + (sid * 128 + row) * MD + 4 * g;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4)
+          *reinterpret_cast<float4*>(op + 32 * db + 8 * e4) =
+              make_float4(oacc[db][4 * e4], oacc[db][4 * e4 + 1], oacc[db][4 * e4 + 2], oacc[db][4 * e4 + 3]);
+      if (g == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(m_run, l_tot);
+    }
+  } else if (row_ok) {
     const float inv = 1.0f / l_tot;
     uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
 #pragma unroll
@@ -432,6 +454,48 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
         *reinterpret_cast<uint2*>(op + 32 * db + 8 * e4) = o;
       }
   }
+}
+
+// Combines the partial results of the split work items: out = sum_p O_p 2^(m_p - m) / sum_p l_p 2^(m_p - m) with
+// m = max_p m_p (the merge step of the online softmax, Alg. 2 Part A).  One workgroup per (XCD, split item, block of the
+// pair, 8 query rows); 32 threads per row, 4 channels each.
+__global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
+  const int rows8 = blockIdx.x & 15, grp = (blockIdx.x >> 4) & 1;
+  const int r = (blockIdx.x >> 5) % a.n_split, xcd = (blockIdx.x >> 5) / a.n_split;
+  const int item = a.n_long - a.n_split + r;
+  const int hl = item / a.slots_first, slot = item % a.slots_first;
+  const int bhid = xcd * a.hpx + hl;
+  if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
+  const int h = bhid % a.geo.H, b = bhid / a.geo.H;
+  const BatchCounts c = a.cnt.b[b];
+  const int T_max = a.geo.T_max;
+  const int n_blocks = a.dense ? c.T : c.n_full;
+  const int entry = 2 * slot + grp;
+  if (entry >= n_blocks) return;
+  const int qi = a.dense ? entry : a.full_list[(long long)bhid * T_max + entry];
+  const int n_q = a.blk_n[b * T_max + qi], q_start = a.blk_start[b * T_max + qi];
+  const int row = rows8 * 8 + (threadIdx.x >> 5), ch = (threadIdx.x & 31) * 4;
+  if (row >= n_q) return;
+  const long long sid0 = (((long long)xcd * a.n_split + r) * a.parts) * 2 + grp;       // part p is at sid0 + 2p
+  float m = M_INIT;
+  for (int p = 0; p < a.parts; ++p) m = fmaxf(m, a.split_ml[((sid0 + 2 * p) * 128 + row) * 2]);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float l = 0.f;
+  for (int p = 0; p < a.parts; ++p) {
+    const float2 ml = *reinterpret_cast<const float2*>(a.split_ml + ((sid0 + 2 * p) * 128 + row) * 2);
+    const float w = __builtin_amdgcn_exp2f(ml.x - m);
+    const float4 o = *reinterpret_cast<const float4*>(a.split_o + ((sid0 + 2 * p) * 128 + row) * MD + ch);
+    acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+    l += w * ml.y;
+  }
+  const float inv = 1.0f / l;
+  const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
+  bf16x2 lo = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv)};
+  bf16x2 hi = {(__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
+  uint2 o;
+  o.x = *reinterpret_cast<uint32_t*>(&lo);
+  o.y = *reinterpret_cast<uint32_t*>(&hi);
+  *reinterpret_cast<uint2*>(a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + ch) = o;
 }
 
 // Launches the attention kernels of the MFMA path: the software-pipelined kernel for dense attention, the
@@ -467,10 +531,29 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
     m.slots_second = ss > 0 ? ss : 1;
     m.hpx = (pr.p.B * pr.p.H + 7) / 8;
     m.n_long = m.hpx * sf;
-    const long long per_xcd = (long long)m.hpx * (sf + ss);
+    // An XCD runs one workgroup per compute unit, so its long items go in rounds of `cus`; when the last round is at
+    // most half full, its items are cut into as many key ranges as fill it (each at least 8 key blocks long).
+    m.n_split = 0; m.parts = 1;
+    m.split_o = ws.split_o; m.split_ml = ws.split_ml;
+    const int cus = 32, rem = m.n_long % cus;
+    if (rem > 0 && rem <= cus / 2 && rem <= sf && ws.split_o) {
+      int min_list = 1 << 30;
+      for (int b = 0; b < pr.p.B; ++b) {
+        const int nl = a.dense ? pr.cnt.b[b].T : pr.cnt.b[b].T_new;
+        min_list = nl < min_list ? nl : min_list;
+      }
+      int parts = cus / rem;
+      if (parts > min_list / 8) parts = min_list / 8;
+      if (parts >= 2 && 8 * rem * parts <= SPLIT_MAX_SUB) { m.n_split = rem; m.parts = parts; }
+    }
+    const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts + (long long)m.hpx * ss;
     m.slots = 0; m.total = 0;
     hipLaunchKernelGGL(k_attn_sp, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, m);
     e = hipGetLastError();
+    if (e == hipSuccess && m.n_split > 0) {
+      hipLaunchKernelGGL(k_split_merge, dim3((unsigned)(8 * m.n_split * 32)), dim3(256), 0, st, m);
+      e = hipGetLastError();
+    }
   }
   if (e == hipSuccess && exact_sets) e = launch_attn_mfma4(pr, m, st);
   if (prof) {

@@ -107,11 +107,14 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->biasn = (float*)take(B * H * (size_t)pr.Tn_pad * 4);
     ws->zero_tile = (uint16_t*)take(128 * 64 * 2);
     ws->ktab = (int4*)take(B * H * T * 16);
+    ws->split_o = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 128 * 4);
+    ws->split_ml = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 2 * 4);
   } else {
     ws->vt = ws->kcn = ws->vcnt = nullptr;
     ws->biasn = nullptr;
     ws->zero_tile = nullptr;
     ws->ktab = nullptr;
+    ws->split_o = ws->split_ml = nullptr;
   }
   ws->bytes = off;
 }

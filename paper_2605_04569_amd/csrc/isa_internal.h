@@ -33,6 +33,8 @@ struct Geometry {
 };
 
 // Workspace carve-up (device pointers into the caller's workspace).
+constexpr int SPLIT_MAX_SUB = 256;   // sub-items of split work items per launch: at most one per compute unit
+
 struct Workspace {
   int* blk_start;        // [B][T_max] token offset of each block inside its batch item
   int* blk_n;            // [B][T_max] real tokens of each block
@@ -55,6 +57,8 @@ struct Workspace {
   float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key, -inf for padding
   uint16_t* zero_tile;   // 16 KB of zeros, written by the V^T pack kernel
   int4* ktab;            // [B,H,T_max] the btab rows of the blocks of kv_list, in list order
+  float* split_o;        // partial outputs of work items split along the key sequence (at most 256 sub-items)
+  float* split_ml;       // their running maxima and sums
   size_t bytes;          // total size
 };
 

@@ -71,3 +71,46 @@ def test_dense_attention_full_size_sampled(I, name):
         emax, emean = err_stats(got, want)
         assert emax <= tol_max and emean <= tol_mean, (name, h, emax, emean)
     assert torch.isfinite(out[0, :, :n].float()).all()
+
+
+def test_split_work_items_isa_full_size(I):
+    """cfg2 gives every XCD 260 exact-branch work items for 32 compute units, so the launch cuts the last 4 items of the
+    XCD's last head (heads 4, 9, .. 39) into key ranges and merges them: check exactly those query blocks."""
+    wl = W.CONFIGS["cfg2"]
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(4, 39), blocks_per_head=1, seed=5, last_full=8)
+
+
+def _split_shape(**kw):
+    # 8 heads = one per XCD; 33 + 33 blocks, the last one 122 tokens long
+    return W.Workload(name="split", B=1, H=8, D=128, dtype="bf16", block=128, src_grid=(33, 8, 16),
+                      ctx_grids=(((3, 37, 38),),), keep_ratio=0.5, full_frac=0.122, seed=77, exact_frac=0.0).with_(**kw)
+
+
+def test_split_work_items_small_isa(I):
+    """One head per XCD and 5 exact-branch pairs per head: every exact-branch item is cut into 6 key ranges."""
+    wl = _split_shape()
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(0, 7))
+
+
+def test_split_work_items_small_dense(I):
+    """Dense attention with 33 pairs per XCD: the 33rd pair of every head is cut into 8 key ranges."""
+    wl = _split_shape()
+    q, k, v = _gen_gpu(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    out = torch.full_like(q, float("nan"))
+    I.isa_dense_attention(pr, q, k, v, out, ws)
+    torch.cuda.synchronize()
+    n = wl.tokens(0)
+    tol_max, tol_mean = TOL[wl.dtype]
+    for h in (0, 7):
+        Kh, Vh = f64(k[0, h, :n]), f64(v[0, h, :n])
+        for lo, hi in ((0, 256), (n - 256, n)):                     # first pair (whole item) and last pair (split item)
+            want = O.dense_attention(f64(q[0, h, lo:hi]), Kh, Vh)
+            got = f64(out[0, h, lo:hi])
+            assert np.isfinite(got).all()
+            emax, emean = err_stats(got, want)
+            assert emax <= tol_max and emean <= tol_mean, (h, lo, emax, emean)
+    assert torch.isfinite(out[0, :, :n].float()).all()

@@ -237,9 +237,11 @@ def test_dense_attention(I, wl):
 # ------------------------------------------------------------------------------------------------
 # (iv) the whole operator
 # ------------------------------------------------------------------------------------------------
-def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, seed=0):
+def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, seed=0, last_full=0):
     """Runs isa_attention, reads back the lists it chose, checks that they are valid selections of the oracle's
-    scores, and checks outputs against the oracle evaluated on those lists.  Returns the index agreement rates."""
+    scores, and checks outputs against the oracle evaluated on those lists.  Returns the index agreement rates.
+    `last_full` adds the last entries of each head's exact-branch list to the sampled blocks (the work items a launch
+    may cut into key ranges and merge)."""
     pr = problem_of(wl)
     ws = I.new_workspace(pr)
     out = torch.full_like(q, float("nan"))
@@ -276,7 +278,8 @@ def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, 
             flat = np.setdiff1d(np.arange(c["T"]), full)
             blocks = range(c["T"]) if blocks_per_head is None else \
                 sorted(set(rng.choice(full, min(len(full), blocks_per_head), replace=False).tolist() if len(full) else []) |
-                       set(rng.choice(flat, min(len(flat), blocks_per_head), replace=False).tolist() if len(flat) else []))
+                       set(rng.choice(flat, min(len(flat), blocks_per_head), replace=False).tolist() if len(flat) else []) |
+                       set(full[len(full) - min(len(full), last_full):].tolist()))
             for i in blocks:
                 in_full = bool((full == i).any())
                 ex = None
