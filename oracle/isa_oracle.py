@@ -27,7 +27,13 @@ its reason in the design notes of this repository):
 * full_frac is the fraction of query blocks that receive exact attention; the
   count of Taylor blocks is floor((1 - full_frac) * T) as in Alg. 1 Stage 3
   with the algorithm's alpha_f read as 1 - full_frac;
-* all rankings are by descending value with ties going to the lower index.
+* all rankings are by descending value with ties going to the lower index;
+* the optional coarse residual gamma * O_coarse (Alg. 1 Stage 1 and Stage 5)
+  adds block i's row of O_coarse = S_coarse V^c to every token of block i: the
+  algorithm adds a [T, D] array to an [S, D] one without saying how
+  [pinned as far as the mathematics goes: linear in gamma, rows of O_coarse
+  are convex combinations of the mean values, closed forms for uniform and
+  one-hot coarse maps; the broadcast itself is a reading].
 """
 import math
 
@@ -96,6 +102,12 @@ def coarse_map(Z):
     """S_coarse: row softmax of the coarse logits over all T key blocks."""
     E = np.exp(Z - Z.max(axis=1, keepdims=True))
     return E / E.sum(axis=1, keepdims=True)
+
+
+def coarse_output(S_coarse, Vc):
+    """O_coarse = S_coarse V^c: the pooled attention output, one row per query
+    block (Alg. 1 Stage 1).  -> [T, D]."""
+    return np.asarray(S_coarse, dtype=np.float64) @ np.asarray(Vc, dtype=np.float64)
 
 
 # --------------------------------------------------------------------------
@@ -217,10 +229,12 @@ def taylor_branch(q, K, V, Kc, Vc, starts, counts, kv_list, exact_blocks, return
 
 
 # --------------------------------------------------------------------------
-# Whole operator for one (batch, head) slice (Alg. 1, gamma = 0)
+# Whole operator for one (batch, head) slice (Alg. 1)
 # --------------------------------------------------------------------------
-def isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0):
-    """Stages 1-3 of Alg. 1: everything up to and including the index lists."""
+def isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0, gamma=0.0):
+    """Stages 1-3 of Alg. 1: everything up to and including the index lists,
+    plus the coarse output O_coarse and the stacking factor gamma that Stage 5
+    uses."""
     starts, counts, T_src = block_layout(seg_len, block)
     T = len(starts)
     Qc = block_means(Q, starts, counts)
@@ -235,30 +249,34 @@ def isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0):
     n_full, n_flat = group_counts(full_frac, T)
     full_list, flat_list = group_queries(M, n_full)
     return dict(starts=starts, counts=counts, T_src=T_src, T=T, Qc=Qc, Kc=Kc, Vc=Vc, Z=Z,
-                S_coarse=S, s_ctx=s_ctx, k_keep=k_keep, kv_list=kv_list, sharp=M,
+                S_coarse=S, O_coarse=coarse_output(S, Vc), gamma=float(gamma), s_ctx=s_ctx, k_keep=k_keep, kv_list=kv_list, sharp=M,
                 n_full=n_full, n_flat=n_flat, full_list=full_list, flat_list=flat_list,
                 exact_frac=float(exact_frac), k_exact=exact_count(exact_frac, len(kv_list)))
 
 
 def attend_block(i, plan, Q, K, V, kv_list=None, in_full=None, exact_blocks=None):
-    """Stage 4 for the tokens of query block i.  The index lists default to the
+    """Stage 4 for the tokens of query block i, plus the coarse residual of
+    Stage 5: gamma times block i's row of O_coarse is added to each of its
+    tokens (O_coarse has one row per block, the output one per token; reading:
+    a block's row is shared by its tokens).  The index lists default to the
     plan's own; a caller may substitute lists produced elsewhere."""
     starts, counts = plan["starts"], plan["counts"]
     kv_list = plan["kv_list"] if kv_list is None else np.asarray(kv_list, dtype=np.int64)
     if in_full is None:
         in_full = bool(np.any(plan["full_list"] == i))
     q = np.asarray(Q, dtype=np.float64)[starts[i]:starts[i] + counts[i]]
+    res = plan["gamma"] * plan["O_coarse"][i][None, :] if plan["gamma"] != 0.0 else 0.0
     if in_full:
-        return full_branch(q, K, V, starts, counts, kv_list)
+        return full_branch(q, K, V, starts, counts, kv_list) + res
     if exact_blocks is None:
         exact_blocks = exact_set(plan["Z"][i], kv_list, exact_count(plan["exact_frac"], len(kv_list)))
-    return taylor_branch(q, K, V, plan["Kc"], plan["Vc"], starts, counts, kv_list, exact_blocks)
+    return taylor_branch(q, K, V, plan["Kc"], plan["Vc"], starts, counts, kv_list, exact_blocks) + res
 
 
-def isa_attention(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0):
-    """Alg. 1 with gamma = 0 for one (batch, head) slice.  Q, K, V [S, D].
+def isa_attention(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0, gamma=0.0):
+    """Alg. 1 for one (batch, head) slice.  Q, K, V [S, D].
     Returns (out [S, D], plan)."""
-    plan = isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac)
+    plan = isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac, gamma)
     out = np.zeros((np.asarray(Q).shape[0], np.asarray(V).shape[1]), dtype=np.float64)
     for i in range(plan["T"]):
         s, n = plan["starts"][i], plan["counts"][i]

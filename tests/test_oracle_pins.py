@@ -448,3 +448,95 @@ def test_taylor_error_is_second_order_in_the_spread():
 
     e1, e2 = err(1e-2), err(5e-3)
     assert 3.6 < e1 / e2 < 4.4
+
+
+# --------------------------------------------------------------------------
+# Coarse residual gamma * O_coarse (Alg. 1 Stage 1 and Stage 5)
+# --------------------------------------------------------------------------
+def brute_coarse_output(Q, K, V, seg_len, b):
+    """O_coarse from the definitions with scalar long-double loops: block means, pooled logits / sqrt(D), row
+    softmax without max subtraction, weighted sum of the mean values."""
+    S_tot, D = Q.shape
+    blocks = []
+    for si, L in enumerate(seg_len):
+        base = sum(seg_len[:si])
+        for x in range((L + b - 1) // b):
+            blocks.append([base + t for t in range(x * b, min(L, (x + 1) * b))])
+    T = len(blocks)
+
+    def mean_of(X, toks):
+        return [sum(LD(X[t, d]) for t in toks) / LD(len(toks)) for d in range(X.shape[1])]
+    Qc = [mean_of(Q, tk) for tk in blocks]
+    Kc = [mean_of(K, tk) for tk in blocks]
+    Vc = [mean_of(V, tk) for tk in blocks]
+    out = np.zeros((T, V.shape[1]), dtype=LD)
+    for i in range(T):
+        w = [np.exp(sum(Qc[i][d] * Kc[j][d] for d in range(D)) / np.sqrt(LD(D))) for j in range(T)]
+        tot = sum(w)
+        for d in range(V.shape[1]):
+            out[i, d] = sum(w[j] * Vc[j][d] for j in range(T)) / tot
+    return out, blocks
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_coarse_residual_brute_force(seed):
+    rng = np.random.default_rng(500 + seed)
+    b = [2, 3, 4, 8][seed]
+    seg = [int(rng.integers(6, 15)), int(rng.integers(3, 12))]
+    Q, K, V = rand_case(rng, seg, int(rng.integers(2, 6)))
+    gamma = float(rng.uniform(-1, 1))
+    base, _ = O.isa_attention(Q, K, V, seg, b, 0.5, 0.5, 0.25)
+    got, plan = O.isa_attention(Q, K, V, seg, b, 0.5, 0.5, 0.25, gamma=gamma)
+    oc, blocks = brute_coarse_output(Q, K, V, seg, b)
+    np.testing.assert_allclose(plan["O_coarse"], oc.astype(np.float64), rtol=0, atol=1e-13)
+    want = base.copy()
+    for i, toks in enumerate(blocks):                           # a block's coarse row goes to each of its tokens
+        want[toks] += gamma * oc[i].astype(np.float64)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+
+
+def test_coarse_residual_zero_gamma_changes_nothing_and_is_linear():
+    rng = np.random.default_rng(7)
+    seg = [19, 14, 6]
+    Q, K, V = rand_case(rng, seg, 5)
+    o0, _ = O.isa_attention(Q, K, V, seg, 4, 0.4, 0.3, 0.2)
+    o0b, _ = O.isa_attention(Q, K, V, seg, 4, 0.4, 0.3, 0.2, gamma=0.0)
+    assert np.array_equal(o0, o0b)
+    o1, p1 = O.isa_attention(Q, K, V, seg, 4, 0.4, 0.3, 0.2, gamma=1.0)
+    o2, _ = O.isa_attention(Q, K, V, seg, 4, 0.4, 0.3, 0.2, gamma=-2.5)
+    np.testing.assert_allclose(o2 - o0, -2.5 * (o1 - o0), rtol=0, atol=1e-13)
+    # the selection does not depend on gamma
+    _, p2 = O.isa_attention(Q, K, V, seg, 4, 0.4, 0.3, 0.2, gamma=-2.5)
+    assert list(p1["kv_list"]) == list(p2["kv_list"]) and list(p1["full_list"]) == list(p2["full_list"])
+
+
+def test_coarse_output_rows_are_convex_combinations_of_mean_values():
+    rng = np.random.default_rng(8)
+    seg = [21, 10]
+    Q, K, V = rand_case(rng, seg, 6, qscale=3.0)
+    _, plan = O.isa_attention(Q, K, V, seg, 4, 0.5, 0.5, gamma=0.7)
+    oc, Vc = plan["O_coarse"], plan["Vc"]
+    assert (oc <= Vc.max(axis=0) + 1e-14).all() and (oc >= Vc.min(axis=0) - 1e-14).all()
+    # constant values: every convex combination is that constant, so the output is (1 + gamma) times it
+    out, _ = O.isa_attention(Q, K, np.full_like(V, 2.0), seg, 4, 0.5, 0.5, 0.3, gamma=0.7)
+    np.testing.assert_allclose(out, 2.0 * 1.7, rtol=0, atol=1e-13)
+
+
+def test_coarse_output_closed_forms():
+    rng = np.random.default_rng(9)
+    seg = [12, 9]
+    Q, K, V = rand_case(rng, seg, 4)
+    # zero queries: uniform coarse map -> every row of O_coarse is the plain average of the mean values
+    _, plan = O.isa_attention(Q * 0, K, V, seg, 4, 0.5, 0.5, gamma=1.0)
+    np.testing.assert_allclose(plan["O_coarse"], np.tile(plan["Vc"].mean(axis=0), (plan["T"], 1)), atol=1e-15)
+    # one-hot coarse map: row i of O_coarse is the mean value of the block it looks at
+    T, D = 6, 8
+    Kc = np.eye(T, D) * 50.0
+    target = [3, 0, 5, 1, 1, 4]
+    Qc = np.stack([Kc[c] for c in target])
+    Vc = rng.standard_normal((T, 3))
+    S = O.coarse_map(O.coarse_logits(Qc, Kc))
+    np.testing.assert_allclose(O.coarse_output(S, Vc), Vc[target], atol=1e-12)
+    # a transposed operand or a column softmax would fail this: asymmetric map, distinct values
+    S2 = np.array([[0.9, 0.1], [0.2, 0.8]])
+    np.testing.assert_allclose(O.coarse_output(S2, np.array([[1.0], [3.0]])), [[1.2], [2.6]], atol=1e-15)
