@@ -60,7 +60,7 @@ def cpu_baseline(wl, Q, K, V, budget_s=12.0):
     while heads < wl.H and spent < budget_s:
         Qh, Kh, Vh = (t[0, heads, :n].to("cpu").to(torch.float64).numpy() for t in (Q, K, V))
         t0 = time.perf_counter()
-        plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(0), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac)
+        plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(0), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac, wl.gamma)
         for i in range(plan["T"]):
             O.attend_block(i, plan, Qh, Kh, Vh)
         spent += time.perf_counter() - t0
@@ -105,7 +105,7 @@ def measure(wl, steps, warmup, dense_steps):
     torch.cuda.synchronize()
     log("inputs ready")
     pr = isa.Problem(H=wl.H, D=wl.D, dtype=wl.dtype, block=wl.block, seg_len=[wl.seg_len(b) for b in range(wl.B)],
-                     keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac)
+                     keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac, gamma=wl.gamma)
     ws = isa.new_workspace(pr)
     out = torch.empty_like(Q)
     torch.cuda.synchronize()
@@ -183,6 +183,7 @@ def main():
     ap.add_argument("--exact-frac", type=float, default=None)
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--full-frac", type=float, default=None)
+    ap.add_argument("--gamma", type=float, default=None, help="coarse stacking factor of Alg. 1 Stage 5 (default 0: no residual)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense attention leg")
     ap.add_argument("--also", default="cfg1,cfg4", help="other workloads to time briefly after the main one ('' = none)")
@@ -202,7 +203,7 @@ def main():
     torch.cuda.set_device(0)
     wl = W.CONFIGS[args.workload]
     over = {k: v for k, v in (("exact_frac", args.exact_frac), ("keep_ratio", args.keep_ratio),
-                              ("full_frac", args.full_frac)) if v is not None}
+                              ("full_frac", args.full_frac), ("gamma", args.gamma)) if v is not None}
     if over:
         wl = wl.with_(**over)
     r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps)
@@ -243,9 +244,9 @@ def main():
         "vs_baseline": None,
         "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": "%s: B=%d H=%d D=%d block=%d segments=%s keep_ratio=%g full_frac=%g exact_frac=%g"
+        "config": {"workload": "%s: B=%d H=%d D=%d block=%d segments=%s keep_ratio=%g full_frac=%g exact_frac=%g gamma=%g"
                                % (wl.name, wl.B, wl.H, wl.D, wl.block, [wl.seg_len(b) for b in range(wl.B)],
-                                  wl.keep_ratio, wl.full_frac, wl.exact_frac)},
+                                  wl.keep_ratio, wl.full_frac, wl.exact_frac, wl.gamma)},
         "isa_effective_tflops": round(isa_fl / (ms_per_step * 1e-3) / 1e12, 1),
         "isa_algorithmic_tflop": round(isa_fl / 1e12, 3),
         "dense_ms_per_call": None if dense_ms is None else round(dense_ms, 3),

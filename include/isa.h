@@ -29,7 +29,7 @@
  *     per-batch block count; per-(batch, head) block arrays are laid out [B, H, T_max].
  *   - Supported shapes: D in {64, 128}; block in {64, 128}; 1 <= B <= ISA_MAX_BATCH; at most
  *     ISA_MAX_SEGMENTS segments over all batch items; at most ISA_MAX_BLOCKS blocks per batch
- *     item; strides multiples of 8 elements.  gamma must be 0.
+ *     item; strides multiples of 8 elements; gamma finite.
  */
 #ifndef ISA_H
 #define ISA_H
@@ -51,7 +51,7 @@ typedef enum {
   ISA_ERR_SHAPE = -2,       /* B, H, D, block, segments or strides outside the supported set */
   ISA_ERR_RATIO = -3,       /* a ratio outside [0, 1] or not finite */
   ISA_ERR_DTYPE = -4,       /* dtype is neither ISA_BF16 nor ISA_F32 */
-  ISA_ERR_UNSUPPORTED = -5, /* gamma != 0, or a feature this build does not carry */
+  ISA_ERR_UNSUPPORTED = -5, /* a non-finite gamma, or a feature this build does not carry */
   ISA_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than required */
   ISA_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed */
 } isa_status;
@@ -70,7 +70,7 @@ typedef struct isa_problem {
   double full_frac;       /* fraction of query blocks given exact attention (Alg. 1 Stage 3) */
   double exact_frac;      /* No-Sparsity Ratio alpha_ns: fraction of kept blocks a Taylor query block still
                              evaluates exactly (Alg. 2 Stage 2) */
-  double gamma;           /* coarse stacking factor of Alg. 1; must be 0 */
+  double gamma;           /* coarse stacking factor of Alg. 1 (Stage 5): out += gamma * O_coarse; 0 = no residual */
 } isa_problem;
 
 /* Block and list counts of one batch item, all derived on the host in double precision. */
@@ -94,8 +94,10 @@ int isa_get_counts(const isa_problem* p, int b, isa_counts* out);
  * The workspace must be 256-byte aligned.  Its contents are scratch: undefined before and after. */
 size_t isa_workspace_bytes(const isa_problem* p);
 
-/* Algorithm 1 (gamma = 0), all stages, for every (batch, head): out = ISA(q, k, v).
- * `out` is written for every real token.  Errors: see isa_status. */
+/* Algorithm 1, all stages, for every (batch, head): out = ISA(q, k, v).
+ * With gamma != 0 the coarse residual of Stage 5 is added: every token of query block i receives
+ * gamma * O_coarse[i], where O_coarse = S_coarse vc (Stage 1; O_coarse has one row per block, so a block's row is
+ * shared by its tokens).  `out` is written for every real token.  Errors: see isa_status. */
 int isa_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -125,6 +127,11 @@ int isa_block_means(const isa_problem* p, const void* q, const void* k, const vo
 int isa_coarse_scores(const isa_problem* p, const float* qc, const float* kc, float* s_ctx, float* sharp, float* z,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The pooled attention output of Alg. 1 Stage 1: O_coarse = S_coarse vc, with S_coarse as in isa_coarse_scores.
+ * o_coarse: device fp32 [B, H, T_max, D]; rows past a batch item's T are not written. */
+int isa_coarse_output(const isa_problem* p, const float* qc, const float* kc, const float* vc, float* o_coarse,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Eq. 2 selection and the Alg. 1 Stage 3 split, as integer work on given fp32 scores.
  * Rankings are by descending score, ties to the lower index; all lists are stored ascending.
  * kv_list:   device int32 [B, H, T_max]; first T_new entries = source blocks 0..T_src-1, then kept context blocks.
@@ -143,10 +150,12 @@ int isa_select(const isa_problem* p, const float* s_ctx, const float* sharp, con
  * full_list, block-wise 0-th order Taylor attention (Eq. 3-4, Alg. 2 Parts A+B, with a block's real token
  * count in place of L_K) for the blocks of flat_list, both over the blocks of kv_list, each result stored at its
  * token's position in `out`.  kc, vc: block means as written by isa_block_means.  exact_mask may be NULL when
- * exact_frac == 0.  The lists must be valid (in range, no duplicates); they are not checked. */
+ * exact_frac == 0.  o_coarse: as written by isa_coarse_output; read only when gamma != 0 (then required), in which
+ * case gamma * o_coarse[block] is added to every token of the block (Stage 5).  The lists must be valid (in range,
+ * no duplicates); they are not checked. */
 int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v, const float* kc, const float* vc,
                const int32_t* kv_list, const int32_t* full_list, const int32_t* flat_list, const uint32_t* exact_mask,
-               void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+               const float* o_coarse, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Name of a status code; never NULL. */
 const char* isa_strerror(int status);

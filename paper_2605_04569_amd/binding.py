@@ -59,7 +59,8 @@ def lib():
         L.isa_block_means.argtypes = [P, V, V, V, V, V, V, V, SZ, ST]
         L.isa_coarse_scores.argtypes = [P, V, V, V, V, V, V, SZ, ST]
         L.isa_select.argtypes = [P, V, V, V, V, V, V, V, V, SZ, ST]
-        L.isa_attend.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
+        L.isa_coarse_output.argtypes = [P, V, V, V, V, V, SZ, ST]
+        L.isa_attend.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
         L.isa_strerror.argtypes = [C.c_int]
         L.isa_strerror.restype = C.c_char_p
         L.isa_last_hip_error.argtypes = []
@@ -203,6 +204,12 @@ def isa_coarse_scores(pr: Problem, qc, kc, s_ctx, sharp, z, workspace):
                                    workspace.numel(), _stream()), "isa_coarse_scores")
 
 
+def isa_coarse_output(pr: Problem, qc, kc, vc, o_coarse, workspace):
+    cp, keep = pr.c_struct()
+    _check(lib().isa_coarse_output(C.byref(cp), _ptr(qc), _ptr(kc), _ptr(vc), _ptr(o_coarse), _ptr(workspace),
+                                   workspace.numel(), _stream()), "isa_coarse_output")
+
+
 def isa_select(pr: Problem, s_ctx, sharp, z, kv_list, full_list, flat_list, exact_mask, workspace):
     cp, keep = pr.c_struct()
     _check(lib().isa_select(C.byref(cp), _ptr(s_ctx), _ptr(sharp), _ptr(z), _ptr(kv_list), _ptr(full_list),
@@ -210,10 +217,10 @@ def isa_select(pr: Problem, s_ctx, sharp, z, kv_list, full_list, flat_list, exac
            "isa_select")
 
 
-def isa_attend(pr: Problem, q, k, v, kc, vc, kv_list, full_list, flat_list, exact_mask, out, workspace):
+def isa_attend(pr: Problem, q, k, v, kc, vc, kv_list, full_list, flat_list, exact_mask, out, workspace, o_coarse=None):
     _same_layout(q, k, v, out)
     cp, keep = pr.c_struct(q)
     _check(lib().isa_attend(C.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(kc), _ptr(vc), _ptr(kv_list), _ptr(full_list),
-                            _ptr(flat_list), _ptr(exact_mask), _ptr(out), _ptr(workspace), workspace.numel(),
+                            _ptr(flat_list), _ptr(exact_mask), _ptr(o_coarse), _ptr(out), _ptr(workspace), workspace.numel(),
                             _stream()), "isa_attend")
     return out

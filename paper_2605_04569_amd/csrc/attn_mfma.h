@@ -33,6 +33,7 @@ struct MfmaArgs {
   const int4* btab; const int4* ktab;        // {token offset, real tokens, block index} per block / per kv_list entry
   const int* kv_list; const int* full_list; const int* flat_list;
   const uint32_t* exact_mask;
+  const float* ocoarse; float gamma;        // coarse residual: out += gamma * ocoarse[bh, block] (never in dense mode)
   Geometry geo;
   Counts cnt;
   int dense;

@@ -396,12 +396,21 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   if (row_ok) {
     const float inv = 1.0f / l_tot;
     uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
+    // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
+    const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * g : nullptr;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
-        bf16x2 lo = {(__bf16)(oacc[db][4 * e4] * inv), (__bf16)(oacc[db][4 * e4 + 1] * inv)};
-        bf16x2 hi = {(__bf16)(oacc[db][4 * e4 + 2] * inv), (__bf16)(oacc[db][4 * e4 + 3] * inv)};
+        float4 r = make_float4(oacc[db][4 * e4] * inv, oacc[db][4 * e4 + 1] * inv, oacc[db][4 * e4 + 2] * inv,
+                               oacc[db][4 * e4 + 3] * inv);
+        if (oc) {
+          const float4 c4 = *reinterpret_cast<const float4*>(oc + 32 * db + 8 * e4);
+          r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
+          r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
+        }
+        bf16x2 lo = {(__bf16)r.x, (__bf16)r.y};
+        bf16x2 hi = {(__bf16)r.z, (__bf16)r.w};
         uint2 o;
         o.x = *reinterpret_cast<uint32_t*>(&lo);
         o.y = *reinterpret_cast<uint32_t*>(&hi);

@@ -175,9 +175,18 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnArgs a) {
   if (row_ok) {
     const float inv = 1.0f / l;
     T* op = (T*)a.out + tbase + (long long)(q_start + row) * a.geo.stride_t;
+    // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
+    const float* oc = (a.ocoarse && !a.dense) ? a.ocoarse + (bh * T_max + qi) * D : nullptr;
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-      store4(op + (g * 4 + part) * 4, make_float4(o[g].x * inv, o[g].y * inv, o[g].z * inv, o[g].w * inv));
+    for (int g = 0; g < G; ++g) {
+      float4 r = make_float4(o[g].x * inv, o[g].y * inv, o[g].z * inv, o[g].w * inv);
+      if (oc) {
+        const float4 c4 = *reinterpret_cast<const float4*>(oc + (g * 4 + part) * 4);
+        r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
+        r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
+      }
+      store4(op + (g * 4 + part) * 4, r);
+    }
   }
 }
 

@@ -442,12 +442,21 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   } else if (row_ok) {
     const float inv = 1.0f / l_tot;
     uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
+    // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
+    const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * g : nullptr;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
-        bf16x2 lo = {(__bf16)(oacc[db][4 * e4] * inv), (__bf16)(oacc[db][4 * e4 + 1] * inv)};
-        bf16x2 hi = {(__bf16)(oacc[db][4 * e4 + 2] * inv), (__bf16)(oacc[db][4 * e4 + 3] * inv)};
+        float4 r = make_float4(oacc[db][4 * e4] * inv, oacc[db][4 * e4 + 1] * inv, oacc[db][4 * e4 + 2] * inv,
+                               oacc[db][4 * e4 + 3] * inv);
+        if (oc) {
+          const float4 c4 = *reinterpret_cast<const float4*>(oc + 32 * db + 8 * e4);
+          r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
+          r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
+        }
+        bf16x2 lo = {(__bf16)r.x, (__bf16)r.y};
+        bf16x2 hi = {(__bf16)r.z, (__bf16)r.w};
         uint2 o;
         o.x = *reinterpret_cast<uint32_t*>(&lo);
         o.y = *reinterpret_cast<uint32_t*>(&hi);
@@ -490,8 +499,14 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
   }
   const float inv = 1.0f / l;
   const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
-  bf16x2 lo = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv)};
-  bf16x2 hi = {(__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
+  acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+  if (a.ocoarse) {                                           // coarse residual, as in the attention kernel's own store
+    const float4 c4 = *reinterpret_cast<const float4*>(a.ocoarse + ((long long)bhid * T_max + qi) * MD + ch);
+    acc.x = fmaf(a.gamma, c4.x, acc.x); acc.y = fmaf(a.gamma, c4.y, acc.y);
+    acc.z = fmaf(a.gamma, c4.z, acc.z); acc.w = fmaf(a.gamma, c4.w, acc.w);
+  }
+  bf16x2 lo = {(__bf16)acc.x, (__bf16)acc.y};
+  bf16x2 hi = {(__bf16)acc.z, (__bf16)acc.w};
   uint2 o;
   o.x = *reinterpret_cast<uint32_t*>(&lo);
   o.y = *reinterpret_cast<uint32_t*>(&hi);
@@ -509,6 +524,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   m.btab = ws.btab; m.ktab = ws.ktab;
   m.kv_list = a.kv_list; m.full_list = a.full_list; m.flat_list = a.flat_list;
   m.exact_mask = a.exact_mask;
+  m.ocoarse = a.dense ? nullptr : a.ocoarse; m.gamma = a.gamma;
   m.geo = a.geo; m.cnt = a.cnt; m.dense = a.dense;
   m.Tn_pad = pr.Tn_pad;
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;

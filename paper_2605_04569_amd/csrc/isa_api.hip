@@ -24,7 +24,7 @@ int validate(const isa_problem* p, Problem* out) {
   if (p->D != 64 && p->D != 128) return ISA_ERR_SHAPE;
   if (p->block != 64 && p->block != 128) return ISA_ERR_SHAPE;
   if (!ratio_ok(p->keep_ratio) || !ratio_ok(p->full_frac) || !ratio_ok(p->exact_frac)) return ISA_ERR_RATIO;
-  if (!(p->gamma == 0.0)) return ISA_ERR_UNSUPPORTED;
+  if (!isfinite(p->gamma)) return ISA_ERR_UNSUPPORTED;
   if (p->stride_t < p->D || p->stride_t % 8 || p->stride_h % 8 || p->stride_b % 8) return ISA_ERR_SHAPE;
   if (p->stride_h < 0 || p->stride_b < 0) return ISA_ERR_SHAPE;
 
@@ -93,6 +93,7 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
   ws->kv_list = (int*)take(B * H * T * 4);
   ws->full_list = (int*)take(B * H * T * 4);
   ws->flat_list = (int*)take(B * H * T * 4);
+  ws->ocoarse = pr.p.gamma != 0.0 ? (float*)take(B * H * T * D * 4) : nullptr;
   if (pr.p.exact_frac > 0.0) {
     ws->z = (float*)take(B * H * T * T * 4);
     ws->exact_mask = (uint32_t*)take(B * H * T * (size_t)pr.cnt.mask_words * 4);
@@ -139,13 +140,15 @@ static int hip_fail(hipError_t e) {
 
 static AttnArgs attn_args(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v, void* out,
                           const float* kc, const float* vc, const int* kv, const int* full, const int* flat,
-                          const uint32_t* mask, int dense) {
+                          const uint32_t* mask, const float* ocoarse, int dense) {
   AttnArgs a;
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.kc = kc; a.vc = vc;
   a.blk_start = ws.blk_start; a.blk_n = ws.blk_n;
   a.kv_list = kv; a.full_list = full; a.flat_list = flat;
   a.exact_mask = mask;
+  a.ocoarse = (!dense && pr.p.gamma != 0.0) ? ocoarse : nullptr;
+  a.gamma = (float)pr.p.gamma;
   a.geo = pr.geo;
   a.cnt = pr.cnt;
   a.dense = dense;
@@ -213,7 +216,21 @@ int isa_coarse_scores(const isa_problem* p, const float* qc, const float* kc, fl
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  ISA_TRY(launch_coarse(pr, ws, qc, kc, s_ctx, sharp, z, st));
+  ISA_TRY(launch_coarse(pr, ws, qc, kc, s_ctx, sharp, z, nullptr, nullptr, st));
+  return ISA_OK;
+}
+
+int isa_coarse_output(const isa_problem* p, const float* qc, const float* kc, const float* vc, float* o_coarse,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!qc || !kc || !vc || !o_coarse) return ISA_ERR_NULL;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // the same kernel as isa_coarse_scores; its scores land in the workspace's own arrays
+  ISA_TRY(launch_coarse(pr, ws, qc, kc, ws.s_ctx, ws.sharp, nullptr, vc, o_coarse, st));
   return ISA_OK;
 }
 
@@ -234,18 +251,19 @@ int isa_select(const isa_problem* p, const float* s_ctx, const float* sharp, con
 
 int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v, const float* kc, const float* vc,
                const int32_t* kv_list, const int32_t* full_list, const int32_t* flat_list, const uint32_t* exact_mask,
-               void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+               const float* o_coarse, void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Problem pr;
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !kc || !vc || !kv_list || !full_list || !flat_list || !out) return ISA_ERR_NULL;
   if (p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
+  if (p->gamma != 0.0 && !o_coarse) return ISA_ERR_NULL;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   ISA_TRY(launch_layout(pr, ws, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, kc, vc, kv_list, full_list, flat_list,
-                         p->exact_frac > 0.0 ? exact_mask : nullptr, 0);
+                         p->exact_frac > 0.0 ? exact_mask : nullptr, o_coarse, 0);
   return run_attend(pr, ws, a, v, false, st);
 }
 
@@ -260,9 +278,9 @@ int isa_attention(const isa_problem* p, const void* q, const void* k, const void
   hipStream_t st = (hipStream_t)hip_stream;
   ISA_TRY(launch_layout(pr, ws, st));
   ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
-  ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, ws.z, st));
+  ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, ws.z, ws.vc, ws.ocoarse, st));
   ISA_TRY(launch_select(pr, ws, ws.s_ctx, ws.sharp, ws.z, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, st));
-  AttnArgs a = attn_args(pr, ws, q, k, v, out, ws.kc, ws.vc, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, 0);
+  AttnArgs a = attn_args(pr, ws, q, k, v, out, ws.kc, ws.vc, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, ws.ocoarse, 0);
   return run_attend(pr, ws, a, v, false, st);
 }
 
@@ -276,7 +294,7 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   ISA_TRY(launch_layout(pr, ws, st));
-  AttnArgs a = attn_args(pr, ws, q, k, v, out, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1);
+  AttnArgs a = attn_args(pr, ws, q, k, v, out, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1);
   return run_attend(pr, ws, a, v, false, st);
 }
 
@@ -314,7 +332,7 @@ const char* isa_strerror(int status) {
     case ISA_ERR_SHAPE: return "ISA_ERR_SHAPE: unsupported shape, segments or strides";
     case ISA_ERR_RATIO: return "ISA_ERR_RATIO: ratio outside [0, 1]";
     case ISA_ERR_DTYPE: return "ISA_ERR_DTYPE: unknown dtype";
-    case ISA_ERR_UNSUPPORTED: return "ISA_ERR_UNSUPPORTED: feature not available (gamma must be 0)";
+    case ISA_ERR_UNSUPPORTED: return "ISA_ERR_UNSUPPORTED: feature not available (gamma must be finite)";
     case ISA_ERR_WORKSPACE: return "ISA_ERR_WORKSPACE: workspace missing, misaligned or too small";
     case ISA_ERR_HIP: return "ISA_ERR_HIP: a HIP call failed (see isa_last_hip_error)";
     default: return "unknown isa_status";

@@ -57,6 +57,7 @@ struct Workspace {
   float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key, -inf for padding
   uint16_t* zero_tile;   // 16 KB of zeros, written by the V^T pack kernel
   int4* ktab;            // [B,H,T_max] the btab rows of the blocks of kv_list, in list order
+  float* ocoarse;        // [B,H,T_max,D] pooled attention output (only carved when gamma != 0)
   float* split_o;        // partial outputs of work items split along the key sequence (at most 256 sub-items)
   float* split_ml;       // their running maxima and sums
   size_t bytes;          // total size
@@ -84,6 +85,7 @@ struct AttnArgs {
   const int* blk_start; const int* blk_n;       // [B][T_max]
   const int* kv_list; const int* full_list; const int* flat_list;   // [B,H,T_max]; null in dense mode
   const uint32_t* exact_mask;                   // may be null
+  const float* ocoarse; float gamma;            // coarse residual: out += gamma * ocoarse[block] (ocoarse null when gamma == 0)
   Geometry geo;
   Counts cnt;
   int dense;                                    // 1: every query block attends to every block
@@ -93,7 +95,7 @@ hipError_t launch_layout(const Problem& pr, const Workspace& ws, hipStream_t st)
 hipError_t launch_block_means(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v,
                               float* qc, float* kc, float* vc, hipStream_t st);
 hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc, const float* kc,
-                         float* s_ctx, float* sharp, float* z, hipStream_t st);
+                         float* s_ctx, float* sharp, float* z, const float* vc, float* ocoarse, hipStream_t st);
 hipError_t launch_select(const Problem& pr, const Workspace& ws, const float* s_ctx, const float* sharp, const float* z,
                          int* kv_list, int* full_list, int* flat_list, uint32_t* exact_mask, hipStream_t st);
 hipError_t launch_attn_simt(const Problem& pr, const AttnArgs& a, hipStream_t st);

@@ -167,7 +167,8 @@ constexpr int CROWS = 4;
 template <int D>
 __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, const float* __restrict__ kc,
                                                 float* __restrict__ pctx, float* __restrict__ sharp,
-                                                float* __restrict__ z_out, Counts cnt, int H, int Tsrc_max, int Tctx_max) {
+                                                float* __restrict__ z_out, const float* __restrict__ vc,
+                                                float* __restrict__ ocoarse, Counts cnt, int H, int Tsrc_max, int Tctx_max) {
   extern __shared__ float sm[];
   float* qs = sm;                       // [CROWS][D]
   float* zs = sm + CROWS * D;           // [CROWS][T_max]
@@ -235,6 +236,20 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, co
     var = block_sum(var, redd) / (double)T_src;
     if (threadIdx.x == 0) sharp[bh * T_max + i] = (float)var;
   }
+  // O_coarse = S_coarse V^c (Alg. 1 Stage 1), only when the caller wants the coarse residual: the rows of
+  // S_coarse of this workgroup's query blocks are in LDS; one thread per (row, channel), channels fastest
+  if (ocoarse) {
+    __syncthreads();
+    for (int x = threadIdx.x; x < CROWS * D; x += 256) {
+      const int r = x / D, ch = x % D;
+      if (i0 + r >= T) continue;
+      const float* pr = zs + r * T_max;
+      const float* vcol = vc + bh * T_max * D + ch;
+      double acc = 0.0;
+      for (int j = 0; j < T; ++j) acc += (double)pr[j] * (double)vcol[(long long)j * D];
+      ocoarse[(bh * T_max + i0 + r) * D + ch] = (float)acc;
+    }
+  }
 }
 
 // Eq. 1: mean over the source query blocks of each context column.
@@ -250,15 +265,15 @@ __global__ void k_colmean(const float* __restrict__ pctx, float* __restrict__ s_
 }
 
 hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc, const float* kc, float* s_ctx,
-                         float* sharp, float* z, hipStream_t st) {
+                         float* sharp, float* z, const float* vc, float* ocoarse, hipStream_t st) {
   const int T_max = pr.cnt.T_max;
   const dim3 grid((T_max + CROWS - 1) / CROWS, pr.p.H, pr.p.B);
   const size_t lds = (size_t)CROWS * (pr.p.D + T_max) * sizeof(float);
   if (pr.p.D == 128)
-    hipLaunchKernelGGL((k_coarse<128>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, pr.cnt, pr.p.H, pr.Tsrc_max,
+    hipLaunchKernelGGL((k_coarse<128>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, vc, ocoarse, pr.cnt, pr.p.H, pr.Tsrc_max,
                        pr.Tctx_max);
   else
-    hipLaunchKernelGGL((k_coarse<64>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, pr.cnt, pr.p.H, pr.Tsrc_max,
+    hipLaunchKernelGGL((k_coarse<64>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, vc, ocoarse, pr.cnt, pr.p.H, pr.Tsrc_max,
                        pr.Tctx_max);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

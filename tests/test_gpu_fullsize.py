@@ -81,6 +81,14 @@ def test_split_work_items_isa_full_size(I):
     check_end_to_end(I, wl, q, k, v, q, k, v, heads=(4, 39), blocks_per_head=1, seed=5, last_full=8)
 
 
+def test_coarse_residual_full_size(I):
+    """cfg2 with the coarse residual of Alg. 1 Stage 5 switched on, through the attention kernel's own store (head 7)
+    and through the merge of split work items (head 4)."""
+    wl = W.CONFIGS["cfg2"].with_(gamma=0.5)
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(4, 7), blocks_per_head=1, seed=6, last_full=2)
+
+
 def _split_shape(**kw):
     # 8 heads = one per XCD; 33 + 33 blocks, the last one 122 tokens long
     return W.Workload(name="split", B=1, H=8, D=128, dtype="bf16", block=128, src_grid=(33, 8, 16),

@@ -264,7 +264,7 @@ def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, 
         n = wl.tokens(b)
         for h in (range(wl.H) if heads is None else heads):
             Qh, Kh, Vh = f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n])
-            plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(b), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac)
+            plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(b), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac, wl.gamma)
             kv = kv_g[b, h, :c["T_new"]]
             full = full_g[b, h, :c["n_full"]]
             # validity: the GPU's choices are top-k sets of the oracle's scores up to fp32 score noise
@@ -369,3 +369,69 @@ def test_degenerate_shapes(I):
                                      keep_ratio=keep, full_frac=full, seed=80)
         Q, K, V, q, k, v = gen(wl)
         check_end_to_end(I, wl, Q, K, V, q, k, v)
+
+
+# ------------------------------------------------------------------------------------------------
+# coarse residual gamma * O_coarse (Alg. 1 Stage 1 and Stage 5)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("wl", CASES, ids=IDS)
+def test_coarse_output_stage(I, wl):
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    buf = alloc_stage_buffers(wl, pr, I)
+    oc = torch.full((wl.B, wl.H, buf["T_max"], wl.D), float("nan"), device="cuda", dtype=torch.float32)
+    I.isa_block_means(pr, q, k, v, buf["qc"], buf["kc"], buf["vc"], ws)
+    I.isa_coarse_output(pr, buf["qc"], buf["kc"], buf["vc"], oc, ws)
+    torch.cuda.synchronize()
+    for b in range(wl.B):
+        T = I.isa_get_counts(pr, b)["T"]
+        for h in range(wl.H):
+            plan = oracle_plan(wl, Q, K, V, b, h)
+            got = f64(oc[b, h, :T])
+            np.testing.assert_allclose(got, plan["O_coarse"], rtol=0, atol=2e-5 * max(1.0, np.abs(plan["O_coarse"]).max()))
+        assert torch.isnan(oc[b, :, T:]).all()                       # rows past the batch item's blocks are untouched
+
+
+@pytest.mark.parametrize("wl", CASES, ids=IDS)
+@pytest.mark.parametrize("exact_frac", [0.0, 0.2])
+def test_isa_attention_with_coarse_residual(I, wl, exact_frac):
+    wl = wl.with_(exact_frac=exact_frac, gamma=-0.75)
+    Q, K, V, q, k, v = gen(wl)
+    check_end_to_end(I, wl, Q, K, V, q, k, v)
+
+
+def test_coarse_residual_staged_and_portable(I):
+    """The staged attend with a caller-provided coarse output, on the MFMA kernels and on the portable ones; the
+    residual is gamma times the difference of two runs."""
+    wl = SMALL_BF16.with_(gamma=1.5, exact_frac=0.25)
+    Q, K, V, q, k, v = gen(wl)
+    pr, pr0 = problem_of(wl), problem_of(wl.with_(gamma=0.0))
+    ws = I.new_workspace(pr)
+    buf = alloc_stage_buffers(wl, pr, I)
+    oc = torch.zeros((wl.B, wl.H, buf["T_max"], wl.D), device="cuda", dtype=torch.float32)
+    I.isa_block_means(pr, q, k, v, buf["qc"], buf["kc"], buf["vc"], ws)
+    I.isa_coarse_scores(pr, buf["qc"], buf["kc"], buf["s_ctx"], buf["sharp"], buf["z"], ws)
+    I.isa_select(pr, buf["s_ctx"], buf["sharp"], buf["z"], buf["kv"], buf["full"], buf["flat"], buf["mask"], ws)
+    I.isa_coarse_output(pr, buf["qc"], buf["kc"], buf["vc"], oc, ws)
+    with pytest.raises(I.IsaError):
+        I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], buf["mask"],
+                     torch.empty_like(q), ws)                     # gamma != 0 without the coarse output
+    prev = I.isa_set_mfma(True)
+    try:
+        for mfma in (True, False):
+            I.isa_set_mfma(mfma)
+            o1, o0 = torch.full_like(q, float("nan")), torch.full_like(q, float("nan"))
+            I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], buf["mask"], o1, ws,
+                         o_coarse=oc)
+            I.isa_attend(pr0, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], buf["mask"], o0, ws)
+            torch.cuda.synchronize()
+            n = wl.tokens(0)
+            for h in range(wl.H):
+                plan = oracle_plan(wl, Q, K, V, 0, h)
+                want = np.concatenate([np.tile(wl.gamma * plan["O_coarse"][i], (plan["counts"][i], 1)) for i in range(plan["T"])])
+                diff = f64(o1[0, h, :n]) - f64(o0[0, h, :n])
+                # both runs round to bf16 (2^-9 relative on outputs of size up to ~|v| + gamma |O_coarse|)
+                assert np.abs(diff - want).max() <= 2 * 2.0 ** -8 * max(1.0, np.abs(f64(o1[0, h, :n])).max()), (mfma, h)
+    finally:
+        I.isa_set_mfma(prev)

@@ -49,7 +49,8 @@ def test_validation_errors():
     assert status(base_problem(full_frac=-0.1)) == -3
     assert status(base_problem(exact_frac=float("nan"))) == -3
     assert status(base_problem(dtype="f16")) == -4
-    assert status(base_problem(gamma=0.1)) == -5
+    assert status(base_problem(gamma=0.1)) == 0
+    assert status(base_problem(gamma=float("inf"))) == -5 and status(base_problem(gamma=float("nan"))) == -5
     assert status(base_problem(), strides=(0, 0, 60)) == -2                # stride_t < D
     assert status(base_problem(), strides=(8 * 1024 * 64, 1024 * 64 + 4, 64)) == -2
     assert I.lib().isa_get_counts(None, 0, None) == -1
@@ -68,6 +69,12 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert L.isa_attention(C.byref(cp), one, one, one, one, one, 16, None) == -6
     assert L.isa_dense_attention(C.byref(cp), one, one, one, None, one, 1 << 40, None) == -1
     assert L.isa_attention_simple(one, one, one, 2, 64, 0, 10, 0.5, 0.5, 64, one, None) == -2
+    # the staged attend needs the coarse output exactly when gamma != 0
+    cg, keep_g = base_problem(gamma=0.5).c_struct()
+    assert L.isa_attend(C.byref(cg), one, one, one, one, one, one, one, one, None, None, one, one, 1 << 40, None) == -1
+    assert L.isa_coarse_output(C.byref(cp), one, one, None, one, one, 1 << 40, None) == -1
+    # a problem with a residual asks for room for the coarse output
+    assert I.isa_workspace_bytes(base_problem(gamma=0.5)) > I.isa_workspace_bytes(base_problem())
 
 
 @pytest.mark.parametrize("seg,block,keep,full,exact", [

@@ -13,14 +13,14 @@ def f64(t: torch.Tensor) -> np.ndarray:
 def problem_of(wl: W.Workload, **kw):
     import paper_2605_04569_amd as I
     d = dict(H=wl.H, D=wl.D, dtype=wl.dtype, block=wl.block, seg_len=[wl.seg_len(b) for b in range(wl.B)],
-             keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac)
+             keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac, gamma=wl.gamma)
     d.update(kw)
     return I.Problem(**d)
 
 
 def oracle_plan(wl: W.Workload, Q, K, V, b, h, **kw):
     n = wl.tokens(b)
-    args = dict(keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac)
+    args = dict(keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac, gamma=wl.gamma)
     args.update(kw)
     return O.isa_plan(f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n]), wl.seg_len(b), wl.block, **args)
 

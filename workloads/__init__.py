@@ -41,6 +41,7 @@ class Workload:
     full_frac: float
     seed: int
     exact_frac: float = 0.0
+    gamma: float = 0.0              # coarse stacking factor of Alg. 1 Stage 5 (0 in every named configuration)
 
     def seg_len(self, b: int) -> List[int]:
         """Token counts of batch item b: source first, then each context reference."""
