@@ -197,10 +197,11 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   uint16_t* ldsV = lds + NBUF * K_TILE;     // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T % NBUF
 
   // ---- which work item.  Workgroup ids go round-robin over the 8 XCDs, so XCD x sees ids x, x + 8, ... in
-  // order.  Each XCD owns `hpx` consecutive (batch, head)s, so that the workgroups that run together on it (and
-  // share its L2) read the same head's keys and values; it is handed all their exact-branch pairs first (the long
-  // items) and then all their Taylor pairs (short items, which fill the compute units that the last, incomplete
-  // round of long items leaves idle).
+  // order.  Each XCD owns every 8th (batch, head) (`hpx` of them: batch items of different lengths are spread
+  // evenly over the XCDs), and works through them one after the other, so that the workgroups that run together
+  // on it (and share its L2) read the same head's keys and values; it is handed all their exact-branch pairs first
+  // (the long items) and then all their Taylor pairs (short items, which fill the compute units that the last,
+  // incomplete round of long items leaves idle).
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   // The last n_split long items of the XCD (those of its last, incomplete round) run as `parts` sub-items, each over
   // 1/parts of the key sequence, so that the round fills all compute units; a merge kernel combines their partial
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   const int part = split ? (j - n_whole) % a.parts : 0;
   const int hl = taylor ? item / a.slots_second : item / a.slots_first;
   const int slot = taylor ? item % a.slots_second : item % a.slots_first;           // pair index inside its branch
-  const int bhid = xcd * a.hpx + hl;
+  const int bhid = hl * 8 + xcd;
   if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const BatchCounts c = a.cnt.b[b];
@@ -473,7 +474,7 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
   const int r = (blockIdx.x >> 5) % a.n_split, xcd = (blockIdx.x >> 5) / a.n_split;
   const int item = a.n_long - a.n_split + r;
   const int hl = item / a.slots_first, slot = item % a.slots_first;
-  const int bhid = xcd * a.hpx + hl;
+  const int bhid = hl * 8 + xcd;
   if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const BatchCounts c = a.cnt.b[b];
