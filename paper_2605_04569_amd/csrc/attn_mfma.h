@@ -40,7 +40,6 @@ struct MfmaArgs {
   int Tn_pad;
   int slots;                                // work slots per (batch, head) = T_max
   int total;                                // B * H * slots
-  int taylor_only;                          // k_attn_mfma: process only the Taylor slots (the exact branch ran elsewhere)
   int slots_first, slots_second;            // k_attn_sp: exact / Taylor pair slots per (batch, head), each at least 1
   int hpx, n_long;                          // k_attn_sp: (batch, head)s per XCD; exact-branch items per XCD (0 if none)
   int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges

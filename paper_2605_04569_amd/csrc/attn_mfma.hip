@@ -1,8 +1,10 @@
-// MFMA attention kernels for bf16, D = 128, block = 128 on gfx950 (wave64, v_mfma_f32_32x32x16_bf16).
+// Pack kernels of the MFMA path, and the 4-wave MFMA attention kernel that runs the Taylor branch when its query
+// blocks carry exact sets (exact_frac > 0; Eq. 3 + Eq. 4, Alg. 2 Parts A and B): bf16, D = 128, block = 128 on gfx950
+// (wave64, v_mfma_f32_32x32x16_bf16).  Dense attention, the exact branch and the Taylor branch without exact sets
+// run in the 8-wave kernel of attn_sp.hip.
 //
 // One workgroup (4 waves) owns one query block of 128 rows; wave w owns rows 32w .. 32w+31.  Two
-// workgroups fit a compute unit (<= 256 VGPRs, 64 KB LDS each) so that one wave's softmax VALU work
-// overlaps another wave's MFMA work on the same SIMD.
+// workgroups fit a compute unit (<= 256 VGPRs, 64 KB LDS each).
 //
 // Scores are computed transposed, S^T = K Q^T (M = keys, N = queries), so that the accumulator layout of
 // the MFMA (a lane holds one query column and 16 key rows per 32-key group) is already the B-operand
@@ -238,24 +240,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   const int T_max = a.geo.T_max;
   const long long bh = bhid;
 
-  int qi, n_list;
-  bool taylor = false;
-  const int* kvl = nullptr;
-  if (a.dense) {
-    qi = slot;
-    n_list = c.T;
-  } else {
-    kvl = a.kv_list + bh * T_max;
-    n_list = c.T_new;
-    if (slot < c.n_full) {
-      if (a.taylor_only) return;
-      qi = a.full_list[bh * T_max + slot];
-    } else {
-      qi = a.flat_list[bh * T_max + slot - c.n_full];
-      taylor = true;
-    }
-  }
-  const uint32_t* mrow = (taylor && a.exact_mask && c.k_exact > 0)
+  // only the Taylor slots of the (batch, head): its exact-branch blocks are handled by the 8-wave kernel
+  if (slot < c.n_full) return;
+  const int* kvl = a.kv_list + bh * T_max;
+  const int n_list = c.T_new;
+  const int qi = a.flat_list[bh * T_max + slot - c.n_full];
+  const uint32_t* mrow = (a.exact_mask && c.k_exact > 0)
                              ? a.exact_mask + (bh * T_max + (slot - c.n_full)) * a.cnt.mask_words : nullptr;
   const int* bn = a.blk_n + b * T_max;
   const int* bs = a.blk_start + b * T_max;
@@ -283,18 +273,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   float m_run = M_INIT, l_run = 0.f;
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
-  // ---- tile sequence.  Phase A: the token tiles (two 64-key halves) of the list entries that are evaluated
-  // exactly -- all of them for the exact branch and for dense attention, the marked ones for a Taylor block.
-  // Phase B (Taylor only): tiles of 64 gathered block means.
+  // ---- tile sequence.  Phase A: the token tiles (two 64-key halves) of the list entries in the block's exact set.
+  // Phase B: tiles of 64 gathered block means (the entries of the exact set masked out).
   int it_t = 0, it_sub = 0, it_mean = 0;
-  if (taylor && !mrow) it_t = n_list;
-  const int n_mean_tiles = taylor ? (n_list + KT - 1) / KT : 0;
+  if (!mrow) it_t = n_list;
+  const int n_mean_tiles = (n_list + KT - 1) / KT;
   auto next_tile = [&](Tile& t) -> bool {
     if (mrow) {
       while (it_t < n_list && !((mrow[it_t >> 5] >> (it_t & 31)) & 1u)) ++it_t;
     }
     if (it_t < n_list) {
-      const int j = a.dense ? it_t : kvl[it_t];
+      const int j = kvl[it_t];
       const int n_j = bn[j];
       const int k0 = it_sub * KT;
       t.krows = a.k + tbase + (long long)bs[j] * a.geo.stride_t;

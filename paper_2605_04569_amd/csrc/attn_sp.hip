@@ -530,7 +530,6 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   m.Tn_pad = pr.Tn_pad;
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
   m.taylor_here = exact_sets ? 0 : 1;
-  m.taylor_only = 1;
   // pair slots per (batch, head): the largest counts over the batch
   int sf = 0, ss = 0;
   for (int b = 0; b < pr.p.B; ++b) {
