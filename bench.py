@@ -252,7 +252,7 @@ def main():
         "dense_ms_per_call": None if dense_ms is None else round(dense_ms, 3),
         "dense_tflops": None if dense_ms is None else round(dense_fl / (dense_ms * 1e-3) / 1e12, 1),
         "speedup_vs_dense": None if dense_ms is None else round(dense_ms / ms_per_step, 3),
-        "roofline": {"bound": "mfma", "kernel": "k_attn_sp (exact + Taylor branches, one launch)",
+        "roofline": {"bound": "mfma", "kernel": "k_attn_sp (exact + Taylor branches, one launch) + k_split_merge",
                      "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "kernel_ms": round(kern_ms, 4),
                      "algorithmic_tflop_per_launch": round(isa_fl / 1e12, 3),

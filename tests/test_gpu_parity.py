@@ -435,3 +435,46 @@ def test_coarse_residual_staged_and_portable(I):
                 assert np.abs(diff - want).max() <= 2 * 2.0 ** -8 * max(1.0, np.abs(f64(o1[0, h, :n])).max()), (mfma, h)
     finally:
         I.isa_set_mfma(prev)
+
+
+# ------------------------------------------------------------------------------------------------
+# the whole call inside a HIP graph
+# ------------------------------------------------------------------------------------------------
+def test_isa_attention_replays_from_a_hip_graph(I):
+    """isa_attention only launches kernels on the caller's stream (no allocation, no host synchronisation, no memset
+    nodes), so it can be captured; every replay must reproduce the eager result bit for bit, also after the inputs
+    change between replays."""
+    wl = SMALL_BF16.with_(gamma=0.25)
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    eager = torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, eager, ws)
+    torch.cuda.synchronize()
+    qs, ks, vs, out = q.clone(), k.clone(), v.clone(), torch.zeros_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        I.isa_attention(pr, qs, ks, vs, out, ws)                    # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        I.isa_attention(pr, qs, ks, vs, out, ws)
+    n = wl.tokens(0)
+    for rep in range(3):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out[:, :, :n], eager[:, :, :n]), rep
+        # eager work of our own between the replays
+        I.isa_dense_attention(pr, q, k, v, torch.empty_like(q), ws)
+        torch.cuda.synchronize()
+    # new inputs through the same graph: swap two heads' tensors and compare with a fresh eager call
+    qs.copy_(q.flip(1)); ks.copy_(k.flip(1)); vs.copy_(v.flip(1))
+    graph.replay()
+    torch.cuda.synchronize()
+    eager2 = torch.empty_like(q)
+    I.isa_attention(pr, q.flip(1).contiguous(), k.flip(1).contiguous(), v.flip(1).contiguous(), eager2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:, :, :n], eager2[:, :, :n])
