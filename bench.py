@@ -186,7 +186,9 @@ def main():
     ap.add_argument("--gamma", type=float, default=None, help="coarse stacking factor of Alg. 1 Stage 5 (default 0: no residual)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense attention leg")
-    ap.add_argument("--also", default="cfg1,cfg4", help="other workloads to time briefly after the main one ('' = none)")
+    ap.add_argument("--also", default="cfg1,cfg4,paper_defaults",
+                    help="other workloads to time briefly after the main one ('' = none); paper_defaults = the main "
+                         "workload's shape at the paper's default ratios")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the operator shards by head with no exchange; "
@@ -217,10 +219,17 @@ def main():
     del Q, K, V, r
     torch.cuda.empty_cache()
     others = []
-    for name in [n for n in args.also.split(",") if n and n != args.workload and not over]:
-        o_wl = W.CONFIGS[name]
+    also = [n for n in args.also.split(",") if n and not over]
+    for name in also:
+        if name == "paper_defaults":                # the paper's default ratios (Sec. 4.1) on the main workload's shape
+            o_wl = W.CONFIGS[args.workload].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)
+            label = "%s at the paper's default ratios (keep 0.125, full 0.5, exact 0.0625)" % args.workload
+        elif name == args.workload:
+            continue
+        else:
+            o_wl, label = W.CONFIGS[name], name
         o = measure(o_wl, 5, 2, 0 if args.no_dense else 2)
-        others.append({"workload": name, "tokens": [o_wl.tokens(b) for b in range(o_wl.B)],
+        others.append({"workload": label, "tokens": [o_wl.tokens(b) for b in range(o_wl.B)],
                        "isa_ms_per_call": round(o["ms_per_step"], 3), "kernel_ms": round(o["kern_ms"], 3),
                        "kernel_tflops": round(o["isa_fl"] / (o["kern_ms"] * 1e-3) / 1e12, 1),
                        "dense_ms_per_call": None if o["dense_ms"] is None else round(o["dense_ms"], 3),
