@@ -37,6 +37,7 @@ struct STile {                              // wave-uniform description of one 6
   int row0, kstride, nk, last_row;
 };
 
+typedef short short4v __attribute__((ext_vector_type(4)));
 #define ISA_FENCE() __builtin_amdgcn_sched_barrier(0)
 constexpr int NBUF = 3;                     // LDS tile buffers: the loads of two tiles are in flight while one is consumed
 
@@ -79,10 +80,11 @@ __device__ __forceinline__ float max_raw(float a, float b) {        // v_max_f32
 template <int VU, typename Hook>
 __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[8], bf16x8 (&kf)[8], const f32x16& sin, f32x16& sout,
-                                          f32x16 (&oacc)[4], float m_run, float& l_run, float& tmax_out,
+                                          f32x16 (&oacc)[4], float m_run, f32x4& l_run, float& tmax_out,
                                           const int (&koff)[8], const int (&voff)[2], float cscale, Hook hook
                                           ) {
   const float neg_m = -m_run;
+  const bf16x4 ones4 = {(__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f};
   bf16x2 pw[8];
   bf16x8 pf[2], vf[8];
   f32x16 zero;
@@ -115,14 +117,15 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
     ISA_FENCE();
     kf[c] = *reinterpret_cast<const bf16x8*>(kpre + koff[c]);
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[ks], oacc[db], 0, 0, 0);
-    {
+    if ((c & 3) == 0) {
       // Row sum over the weights as rounded to bf16 (what the value product multiplies), so that the rounding of a
-      // dominant weight cancels between numerator and denominator.  Unpacked and added on the vector ALU: the
-      // packed bf16 dot instruction would do it in one go but executes in the matrix pipe and stalls the MFMAs.
-      const uint32_t w = __builtin_bit_cast(uint32_t, pw[c]);
-      l_run += __uint_as_float(w << 16);
-      l_run += __uint_as_float(w & 0xffff0000u);
-      pin(l_run);
+      // dominant weight cancels between numerator and denominator.  A 4x4x4 MFMA with an all-ones A operand adds up
+      // the four bf16 values each lane holds in its B operand (D[i][j] = sum_k B[k][j], column j = the lane itself):
+      // two of them per 16-key fragment, 8 matrix-pipe cycles each, instead of 16 unpack-and-add vector instructions.
+      const bf16x4 lo = {pf[ks][0], pf[ks][1], pf[ks][2], pf[ks][3]};
+      const bf16x4 hi = {pf[ks][4], pf[ks][5], pf[ks][6], pf[ks][7]};
+      l_run = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, lo), l_run, 0, 0, 0);
+      l_run = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, hi), l_run, 0, 0, 0);
     }
     if (c >= 2 && c < 6) {
       const int e = 4 * (c - 2);
@@ -154,7 +157,7 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
 // (Alg. 2 Part A) with the rare rescale of the accumulators.  Element e of a half is key 8(e/4) + 4g + e%4.
 // `tmax` comes in as the scaled row maximum of a plain half; a special half recomputes it here.
 __device__ __forceinline__ void prepare_half(f32x16& sc, float tmax, bool general, int nk_half, const float* __restrict__ bias,
-                                             int g, float cscale, float& m_run, float& l_run, f32x16 (&oacc)[4]) {
+                                             int g, float cscale, float& m_run, f32x4& l_run, f32x16 (&oacc)[4]) {
   if (general) {
     float addv[16];
 #pragma unroll
@@ -183,7 +186,7 @@ __device__ __forceinline__ void prepare_half(f32x16& sc, float tmax, bool genera
     const float m_new = raise ? tmax : m_run;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
-    l_run *= alpha;
+    l_run *= alpha;                                     // all four elements hold the same sum
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -361,7 +364,8 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
 #pragma unroll
   for (int e = 0; e < 16; ++e) { s0[e] = -INFINITY; s1[e] = -INFINITY; }
-  float m_run = M_INIT, l_run = 0.f, mx0 = -INFINITY, mx1 = -INFINITY;   // mx*: scaled row maxima of s0 / s1
+  float m_run = M_INIT, mx0 = -INFINITY, mx1 = -INFINITY;
+  f32x4 l_run = {0.f, 0.f, 0.f, 0.f};      // mx*: scaled row maxima of s0 / s1
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
   // ---- loop over T = t_begin .. t_end (one extra, fully masked iteration drains the pipeline).  Iteration T:
@@ -426,7 +430,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
   if (split) {
     // partial result of a sub-item: unnormalised fp32 outputs and the {maximum, sum} they refer to
     const long long sid = (((long long)xcd * a.n_split + (item - n_whole)) * a.parts + part) * 2 + grp;
