@@ -25,6 +25,9 @@ __device__ inline uint16_t f2bf(float f) {     // round to nearest even
   return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 __device__ inline int swap23(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
+// Key stored at position p of a 64-key V^T row in the layout of the 16x16x32 kernel: inside each 32-key group,
+// position 8 q + 4 kt + i holds key 16 kt + 4 q + i (the order in which a lane's score registers list its keys).
+__device__ inline int key_of_pos16(int p) { return (p & 32) | ((p & 4) << 2) | ((p >> 1) & 12) | (p & 3); }
 
 struct MfmaArgs {
   const uint16_t* q; const uint16_t* k; uint16_t* out;

@@ -24,10 +24,13 @@ namespace isa {
 // ------------------------------------------------------------------------------------------
 // Pack kernels
 // ------------------------------------------------------------------------------------------
-// V^T copy: vt[((bh*T_max + j)*2 + half)][d][pos], pos = swap23(key % 64); keys past n_j are zero.
+// V^T copies: vt[((bh*T_max + j)*2 + half)][d][pos]; keys past n_j are zero.  `vt` is in the key order of the
+// 16x16x32 kernel (position p holds key key_of_pos16(p)); `vt4`, written only when given, in that of the 4-wave
+// 32x32x16 kernel (position p holds key swap23(p)).
 __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
-                                                 const int* __restrict__ blk_start, const int* __restrict__ blk_n,
-                                                 uint16_t* __restrict__ zero_tile, Geometry g) {
+                                                 uint16_t* __restrict__ vt4, const int* __restrict__ blk_start,
+                                                 const int* __restrict__ blk_n, uint16_t* __restrict__ zero_tile,
+                                                 Geometry g) {
   __shared__ uint16_t tile[128][MD + 2];
   const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (j == 0 && h == 0 && b == 0)                                 // the all-zero V^T tile the attention kernel pads with
@@ -44,32 +47,41 @@ __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v,
     dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
   }
   __syncthreads();
-  uint16_t* out = vt + (((long long)b * g.H + h) * g.T_max + j) * (2 * MD * KT);
+  const long long tile_off = (((long long)b * g.H + h) * g.T_max + j) * (2 * MD * KT);
   for (int x = threadIdx.x; x < 2 * MD * 8; x += 256) {         // one 16-byte chunk = 8 key positions of one channel
     const int half = x / (MD * 8), rem = x % (MD * 8);
     const int d = rem >> 3, pc = rem & 7;
     uint16_t e[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = tile[half * 64 + swap23(pc * 8 + i)][d];    // swap23 is an involution
     uint4 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = tile[half * 64 + key_of_pos16(pc * 8 + i)][d];
     o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
     o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
-    *reinterpret_cast<uint4*>(out + (half * MD + d) * KT + pc * 8) = o;
+    *reinterpret_cast<uint4*>(vt + tile_off + (half * MD + d) * KT + pc * 8) = o;
+    if (vt4) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) e[i] = tile[half * 64 + swap23(pc * 8 + i)][d];    // swap23 is an involution
+      o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
+      o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
+      *reinterpret_cast<uint4*>(vt4 + tile_off + (half * MD + d) * KT + pc * 8) = o;
+    }
   }
 }
 
 hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, hipStream_t st) {
   hipLaunchKernelGGL(k_pack_vt, dim3(pr.cnt.T_max, pr.p.H, pr.p.B), dim3(256), 0, st, (const uint16_t*)v, ws.vt,
-                     ws.blk_start, ws.blk_n, ws.zero_tile, pr.geo);
+                     ws.vt4, ws.blk_start, ws.blk_n, ws.zero_tile, pr.geo);
   return hipGetLastError();
 }
 
 // Mean keys / values gathered in kv_list order, rounded to bf16, in the layouts the attention kernel reads:
-// kcn[bh][t][d]; vcnt[bh][t/64][d][swap23(t%64)]; biasn[bh][t] = ln(n_j) sqrt(D), -inf past T_new.
+// kcn[bh][t][d]; vcnt[bh][t/64][d][pos] with the list position t%64 = key_of_pos16(pos) (and vcnt4, when given, with
+// t%64 = swap23(pos), for the 4-wave kernel); biasn[bh][t] = ln(n_j) sqrt(D), -inf past T_new.
 __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
                                                       const int* __restrict__ kv_list, const int* __restrict__ blk_n,
                                                       const int4* __restrict__ btab, uint16_t* __restrict__ kcn,
-                                                      uint16_t* __restrict__ vcnt, float* __restrict__ biasn,
+                                                      uint16_t* __restrict__ vcnt, uint16_t* __restrict__ vcnt4,
+                                                      float* __restrict__ biasn,
                                                       int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad) {
   __shared__ uint16_t vtile[KT][MD + 2];
   __shared__ int ids[KT];
@@ -98,17 +110,18 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     vtile[r][d] = f2bf(vval);
   }
   __syncthreads();
-  uint16_t* out = vcnt + (bh * (Tn_pad / KT) + tile) * (MD * KT);
+  const long long out_off = (bh * (Tn_pad / KT) + tile) * (MD * KT);
   for (int x = threadIdx.x; x < MD * KT; x += 256) {
     const int d = x / KT, pos = x % KT;
-    out[d * KT + pos] = vtile[swap23(pos)][d];
+    vcnt[out_off + d * KT + pos] = vtile[key_of_pos16(pos)][d];
+    if (vcnt4) vcnt4[out_off + d * KT + pos] = vtile[swap23(pos)][d];
   }
 }
 
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st) {
   hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
-                     ws.btab, ws.kcn, ws.vcnt, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
+                     ws.btab, ws.kcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
   return hipGetLastError();
 }
 

@@ -68,129 +68,154 @@ __device__ __forceinline__ float max_raw(float a, float b) {        // v_max_f32
   return r;
 }
 
+// Register layout (v_mfma_f32_16x16x32_bf16, S^T = K Q^T and O^T = V^T P^T).  With r = lane % 16 and q = lane / 16:
+//   a wave owns 32 query rows = two 16-query tiles qt; lane (r, q) works for queries 16 qt + r;
+//   the scores of a 32-key half are four 16x16 tiles t[kt][qt] of 4 registers: element i is key 16 kt + 4 q + i;
+//   the weights of query tile qt are one B fragment of 8 bf16: position 4 kt + i of the lane, i.e. k index
+//   8 q + 4 kt + i -- the packed V^T copy stores key 16 kt + 4 q + i of a 32-key group at that position, so the
+//   weights go from the score accumulators to the second product without moving;
+//   the output is sixteen 16x16 tiles oacc[ct][qt]: element i is channel 16 ct + 4 q + i.
+struct Scores { f32x4 t[2][2]; };            // [kt][qt]
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// maximum over the four lanes (r, 0..3) that share query r: rows of 16 lanes are exchanged with the two swap
+// instructions, which (unlike a shuffle through the LDS crossbar) do not queue behind the LDS fragment reads
+__device__ __forceinline__ float max_over_q(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // rows 1,3 of the first <-> rows 0,2 of the second
+  const float y = max_raw(__uint_as_float(s16[0]), __uint_as_float(s16[1]));
+  const uint32_t v = __float_as_uint(y);
+  const auto s32 = __builtin_amdgcn_permlane32_swap(v, v, false, false);   // upper half of the first <-> lower half of the second
+  return max_raw(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
+}
+
 // One half step.  Scores of the half that is softmaxed come in `sin` (raw, bias and masks already applied,
-// running maximum already raised); the raw scores of the next half are produced in `sout` from the 8 K
-// fragments in `kf` (32 rows of the K tile, fetched from LDS one phase earlier).  `tmax_out` is the scaled
-// maximum of `sout` over both key halves of the lane's query row (valid when `sout` needs no bias or mask).
-// The value product uses V^T unit VU of the staged V^T tile.
-// LDS fragments are requested a whole phase (8 MFMAs) before the MFMA that consumes them: the V^T fragments
+// running maxima already raised); the raw scores of the next half are produced in `sout` from the 8 K
+// fragments in `kf` (fragment f = key tile f % 2, channels 32 (f / 2) .., fetched from LDS one phase earlier).
+// `tmax_out[qt]` is the scaled maximum of `sout` over all 32 keys of the lane's query of tile qt (valid when `sout`
+// needs no bias or mask).  The value product uses V^T unit VU of the staged V^T tile.
+// LDS fragments are requested a whole phase (16 MFMAs) before the MFMAs that consume them: the V^T fragments
 // during the score MFMAs, and the K fragments of the following half step (32 rows at `kpre`) during the value
-// MFMAs.  Every vector-ALU instruction of the softmax sits between two MFMAs of the same wave, and so does
-// whatever `hook(s)` adds after score MFMA s (tile set-up and tile loads of a later iteration).
+// MFMAs; every fragment feeds two MFMAs (both query tiles).  Every vector-ALU instruction of the softmax sits
+// between MFMAs of the same wave, and so does whatever `hook(f)` adds in score step f (tile set-up and tile loads
+// of a later iteration).
 template <int VU, typename Hook>
 __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, const uint16_t* __restrict__ vbase,
-                                          const bf16x8 (&qf)[8], bf16x8 (&kf)[8], const f32x16& sin, f32x16& sout,
-                                          f32x16 (&oacc)[4], float m_run, f32x4& l_run, float& tmax_out,
-                                          const int (&koff)[8], const int (&voff)[2], float cscale, Hook hook
-                                          ) {
-  const float neg_m = -m_run;
+                                          const bf16x8 (&qf)[2][4], bf16x8 (&kf)[8], const Scores& sin, Scores& sout,
+                                          f32x4 (&oacc)[8][2], const float (&m_run)[2], f32x4 (&l_run)[2],
+                                          float (&tmax_out)[2], const int (&koff)[4], int voff, float cscale, Hook hook) {
+  const float neg_m[2] = {-m_run[0], -m_run[1]};
   const bf16x4 ones4 = {(__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f};
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
   bf16x2 pw[8];
   bf16x8 pf[2], vf[8];
-  f32x16 zero;
+  // 8 score steps, two MFMAs each (the K fragment against both query tiles); behind each MFMA half of one pair of
+  // weights (fma, exp2; the second half also converts the pair), and one LDS read per step.  A 16x16x32 MFMA holds
+  // the matrix pipe for 16 cycles, which two or three vector instructions fill.  Weight pair f: query tile f / 4,
+  // positions 2 (f % 4), +1.
 #pragma unroll
-  for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-  // 8 score MFMAs, each followed by one pair of weights (2 fma, 2 exp2, 1 convert) and one LDS read
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
+  for (int f = 0; f < 8; ++f) {
+    const int kt = f & 1, ks = f >> 1;
+    const int qt = f >> 2, a = (f >> 1) & 1, i0 = 2 * (f & 1);
     ISA_FENCE();
-    vf[s] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + (s & 3) * 32 * 32 + voff[s >> 2]);   // ks = s/4, db = s%4
-    sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], s == 0 ? zero : sout, 0, 0, 0);
-    const float p0 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s], cscale, neg_m));
-    const float p1 = __builtin_amdgcn_exp2f(fmaf(sin[2 * s + 1], cscale, neg_m));
-    pw[s] = bf16x2{(__bf16)p0, (__bf16)p1};
-    pin(pw[s]);
-    hook(s);
+    vf[f] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + f * 16 * 32 + voff);      // channels 16 f ..
+    sout.t[kt][0] = mfma16(kf[f], qf[0][ks], ks == 0 ? zero4 : sout.t[kt][0]);
+    float p0 = __builtin_amdgcn_exp2f(fmaf(sin.t[a][qt][i0], cscale, neg_m[qt]));
+    pin(p0);
+    ISA_FENCE();
+    sout.t[kt][1] = mfma16(kf[f], qf[1][ks], ks == 0 ? zero4 : sout.t[kt][1]);
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(sin.t[a][qt][i0 + 1], cscale, neg_m[qt]));
+    pw[f] = bf16x2{(__bf16)p0, (__bf16)p1};
+    pin(pw[f]);
+    hook(f);
   }
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    pf[s >> 2][2 * (s & 3)] = pw[s][0];
-    pf[s >> 2][2 * (s & 3) + 1] = pw[s][1];
+  for (int f = 0; f < 8; ++f) {
+    pf[f >> 2][2 * (f & 3)] = pw[f][0];
+    pf[f >> 2][2 * (f & 3) + 1] = pw[f][1];
   }
-  // 8 value MFMAs (2 key steps x 4 channel groups).  Their shadows take the row sums of the weights
-  // (every c), the raw maximum of the new scores (c = 2..5; the last score MFMA has retired by then) and the
-  // exchange of that maximum between the two lanes that share a query row (c = 6, 7).
-  float mx = -INFINITY, other = 0.f;
+  // 8 value steps (channel tiles), two MFMAs each (both query tiles).  Their shadows take the row sums of the
+  // weights (c = 0, 1), the raw maxima of the new scores (c = 2..5; the last score MFMAs have retired by then) and
+  // the exchange of those maxima between the four lanes that share a query (c = 6, 7).
+  float mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
-    const int ks = c >> 2, db = c & 3;
     ISA_FENCE();
-    kf[c] = *reinterpret_cast<const bf16x8*>(kpre + koff[c]);
-    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[ks], oacc[db], 0, 0, 0);
-    if ((c & 3) == 0) {
-      // Row sum over the weights as rounded to bf16 (what the value product multiplies), so that the rounding of a
-      // dominant weight cancels between numerator and denominator.  A 4x4x4 MFMA with an all-ones A operand adds up
-      // the four bf16 values each lane holds in its B operand (D[i][j] = sum_k B[k][j], column j = the lane itself):
-      // two of them per 16-key fragment, 8 matrix-pipe cycles each, instead of 16 unpack-and-add vector instructions.
-      const bf16x4 lo = {pf[ks][0], pf[ks][1], pf[ks][2], pf[ks][3]};
-      const bf16x4 hi = {pf[ks][4], pf[ks][5], pf[ks][6], pf[ks][7]};
-      l_run = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, lo), l_run, 0, 0, 0);
-      l_run = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, hi), l_run, 0, 0, 0);
+    kf[c] = *reinterpret_cast<const bf16x8*>(kpre + (c & 1) * 16 * MD + koff[c >> 1]);
+    oacc[c][0] = mfma16(vf[c], pf[0], oacc[c][0]);
+    // Row sums over the weights as rounded to bf16 (what the value product multiplies), so that the rounding of a
+    // dominant weight cancels between numerator and denominator.  A 4x4x4 MFMA with an all-ones A operand adds up
+    // the four bf16 values each lane holds in its B operand (D[i][j] = sum_k B[k][j], column j = the lane itself):
+    // two of them per weight fragment, 8 matrix-pipe cycles each, instead of 16 unpack-and-add vector instructions.
+    if (c < 2) {
+      const bf16x4 lo = {pf[c][0], pf[c][1], pf[c][2], pf[c][3]};
+      l_run[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, lo), l_run[c], 0, 0, 0);
     }
     if (c >= 2 && c < 6) {
-      const int e = 4 * (c - 2);
-      mx = fmaxf(fmaxf(mx, sout[e]), sout[e + 1]);
-      mx = fmaxf(fmaxf(mx, sout[e + 2]), sout[e + 3]);
-      pin(mx);
+      const int qt = (c - 2) >> 1, kt = (c - 2) & 1;
+      mx[qt] = fmaxf(fmaxf(mx[qt], sout.t[kt][qt][0]), sout.t[kt][qt][1]);
+      pin(mx[qt]);
     }
-    if (c == 6) {
-      // lanes l and l ^ 32 hold the two key halves of one query: exchange through v_permlane32_swap, which
-      // (unlike a shuffle through the LDS crossbar) does not queue behind the LDS fragment reads in flight
-      mx *= cscale;
-      const uint32_t u = __float_as_uint(mx);
-      const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-      mx = __uint_as_float(sw[0]);
-      other = __uint_as_float(sw[1]);
-      pin(mx);
-      pin(other);
+    ISA_FENCE();
+    oacc[c][1] = mfma16(vf[c], pf[1], oacc[c][1]);
+    if (c < 2) {
+      const bf16x4 hi = {pf[c][4], pf[c][5], pf[c][6], pf[c][7]};
+      l_run[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, hi), l_run[c], 0, 0, 0);
     }
-    if (c == 7) {
-      mx = max_raw(mx, other);
-      pin(mx);
+    if (c >= 2 && c < 6) {
+      const int qt = (c - 2) >> 1, kt = (c - 2) & 1;
+      mx[qt] = fmaxf(fmaxf(mx[qt], sout.t[kt][qt][2]), sout.t[kt][qt][3]);
+      pin(mx[qt]);
+    }
+    if (c >= 6) {
+      mx[c - 6] = max_over_q(mx[c - 6] * cscale);
+      pin(mx[c - 6]);
     }
   }
   ISA_FENCE();
-  tmax_out = mx;
+  tmax_out[0] = mx[0];
+  tmax_out[1] = mx[1];
 }
 
-// Bias / masks of a special half (block means, ragged tails), then the running maximum of the online softmax
-// (Alg. 2 Part A) with the rare rescale of the accumulators.  Element e of a half is key 8(e/4) + 4g + e%4.
-// `tmax` comes in as the scaled row maximum of a plain half; a special half recomputes it here.
-__device__ __forceinline__ void prepare_half(f32x16& sc, float tmax, bool general, int nk_half, const float* __restrict__ bias,
-                                             int g, float cscale, float& m_run, f32x4& l_run, f32x16 (&oacc)[4]) {
+// Bias / masks of a special half (block means, ragged tails), then the running maxima of the online softmax
+// (Alg. 2 Part A) with the rare rescale of the accumulators.  `tmax` comes in as the scaled row maxima of a plain
+// half; a special half recomputes them here.
+__device__ __forceinline__ void prepare_half(Scores& sc, float (&tmax)[2], bool general, int nk_half,
+                                             const float* __restrict__ bias, int q, float cscale, float (&m_run)[2],
+                                             f32x4 (&l_run)[2], f32x4 (&oacc)[8][2]) {
   if (general) {
-    float addv[16];
+    float m2[2] = {-INFINITY, -INFINITY};
 #pragma unroll
-    for (int e = 0; e < 16; ++e) addv[e] = 0.f;
-    if (bias) {
+    for (int kt = 0; kt < 2; ++kt) {
+      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (bias) bv = *reinterpret_cast<const float4*>(bias + 16 * kt + 4 * q);      // keys 16 kt + 4 q + 0..3
+      const float add[4] = {bv.x, bv.y, bv.z, bv.w};
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {                                    // keys 8*e4 + 4g + 0..3: one 16-byte load
-        const float4 bv = *reinterpret_cast<const float4*>(bias + 8 * e4 + 4 * g);
-        addv[4 * e4] = bv.x; addv[4 * e4 + 1] = bv.y; addv[4 * e4 + 2] = bv.z; addv[4 * e4 + 3] = bv.w;
+      for (int i = 0; i < 4; ++i) {
+        const bool past = 16 * kt + 4 * q + i >= nk_half;
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+          sc.t[kt][qt][i] = past ? -INFINITY : sc.t[kt][qt][i] + add[i];
+          m2[qt] = fmaxf(m2[qt], sc.t[kt][qt][i]);
+        }
       }
     }
-    float m2 = -INFINITY;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int key = 8 * (e >> 2) + 4 * g + (e & 3);
-      sc[e] = key >= nk_half ? -INFINITY : sc[e] + addv[e];
-      m2 = fmaxf(m2, sc[e]);
-    }
-    m2 *= cscale;
-    const uint32_t u = __float_as_uint(m2);
-    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    tmax[0] = max_over_q(m2[0] * cscale);
+    tmax[1] = max_over_q(m2[1] * cscale);
   }
-  const bool raise = tmax > m_run + RESCALE_TAU;
-  if (__ballot(raise) != 0ull) {                       // rare after the first tiles
-    const float m_new = raise ? tmax : m_run;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    l_run *= alpha;                                     // all four elements hold the same sum
+  const bool raise0 = tmax[0] > m_run[0] + RESCALE_TAU, raise1 = tmax[1] > m_run[1] + RESCALE_TAU;
+  if (__ballot(raise0 || raise1) != 0ull) {             // rare after the first tiles
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int qt = 0; qt < 2; ++qt) {
+      const float m_new = (qt ? raise1 : raise0) ? tmax[qt] : m_run[qt];
+      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+      m_run[qt] = m_new;
+      l_run[qt] *= alpha;                                 // all four elements hold the same sum
 #pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+      for (int c = 0; c < 8; ++c) oacc[c][qt] *= alpha;
+    }
   }
 }
 
@@ -239,7 +264,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // 0..7, scalar
   const int grp = wave >> 2, wq = wave & 3;
-  const int col = lane & 31, g = lane >> 5;
+  const int r16 = lane & 15, q = lane >> 4;
   // this wave's query block; the second group idles (computes on block 0, stores nothing) in the last pair of
   // an odd list
   const int entry = 2 * slot + grp;
@@ -298,17 +323,24 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     if (past) { t.nk = 0; t.vt = a.zero_tile; }
   };
 
-  // ---- Q fragments: B operand of S^T = K Q^T; lane holds channels 16s + 8g .. +7 of its query row
-  const int row = wq * 32 + col;
-  const bool row_ok = row < n_q;
-  const uint16_t* qp = a.q + tbase + (long long)(q_start + (row_ok ? row : 0)) * a.geo.stride_t + 8 * g;
-  bf16x8 qf[8];
+  // ---- Q fragments: B operand of S^T = K Q^T; lane (r, q) holds channels 32 ks + 8 q .. +7 of query 16 qt + r
+  int rowq[2];
+  bool row_ok[2];
+  bf16x8 qf[2][4];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+  for (int qt = 0; qt < 2; ++qt) {
+    rowq[qt] = wq * 32 + 16 * qt + r16;
+    row_ok[qt] = rowq[qt] < n_q;
+    const uint16_t* qp = a.q + tbase + (long long)(q_start + (row_ok[qt] ? rowq[qt] : 0)) * a.geo.stride_t + 8 * q;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qf[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 32 * ks);
+  }
   // consume the fragments here: the compiler's own wait for these loads must not land inside the loop, where
   // it would also wait for the tile loads in flight (which it does not know about)
 #pragma unroll
-  for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[qt][ks]));
 
   // ---- global -> LDS, 16 bytes per lane, no staging registers.  One wave instruction fills 1024 contiguous
   // LDS bytes (lane i -> bytes 16i..16i+15), so rows cannot be padded; instead the 16-byte chunk c of a row is
@@ -350,22 +382,29 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   };
   auto load_v = [&](const uint16_t* ta, const uint16_t* tb, int buf) { load_v1(ta, tb, buf, 0); load_v1(ta, tb, buf, 1); };
 
-  // per-lane fragment offsets (bf16 elements): K row = col, chunk (2s+g) ^ (col & 15); V^T unit row = col, chunk (2ks+g) ^ ((col>>2)&3)
-  int koff[8], voff[2];
+  // per-lane fragment offsets (bf16 elements): K row r of a 16-key tile, chunk (4 ks + q) ^ r; V^T unit row r of a
+  // 16-channel tile, chunk q ^ ((r >> 2) & 3)
+  int koff[4];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) koff[s] = col * MD + (((2 * s + g) ^ (col & 15)) * 8);
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) voff[ks] = col * 32 + (((2 * ks + g) ^ ((col >> 2) & 3)) * 8);
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = r16 * MD + (((4 * ks + q) ^ r16) * 8);
+  const int voff = r16 * 32 + ((q ^ ((r16 >> 2) & 3)) * 8);
 
-  f32x16 oacc[4], s0, s1;
+  f32x4 oacc[8][2];
+  Scores s0, s1;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int c = 0; c < 8; ++c)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
+    for (int qt = 0; qt < 2; ++qt) oacc[c][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int e = 0; e < 16; ++e) { s0[e] = -INFINITY; s1[e] = -INFINITY; }
-  float m_run = M_INIT, mx0 = -INFINITY, mx1 = -INFINITY;
-  f32x4 l_run = {0.f, 0.f, 0.f, 0.f};      // mx*: scaled row maxima of s0 / s1
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      s0.t[kt][qt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      s1.t[kt][qt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    }
+  float m_run[2] = {M_INIT, M_INIT};
+  float mx0[2] = {-INFINITY, -INFINITY}, mx1[2] = {-INFINITY, -INFINITY};     // scaled row maxima of s0 / s1
+  f32x4 l_run[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
   // ---- loop over T = t_begin .. t_end (one extra, fully masked iteration drains the pipeline).  Iteration T:
@@ -389,7 +428,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   __syncthreads();
   bf16x8 kf[8];                           // K fragments of the next 32 rows to be multiplied
 #pragma unroll
-  for (int s8 = 0; s8 < 8; ++s8) kf[s8] = *reinterpret_cast<const bf16x8*>(ldsK + koff[s8]);
+  for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const bf16x8*>(ldsK + (f & 1) * 16 * MD + koff[f >> 1]);
   int bcur = 0;                             // T % NBUF
   for (int T = t_begin; T <= t_end; ++T) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -401,7 +440,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     {   // half (T-1, 1): scores in s1
       const int nkh = min(32, max(0, tprev.nk - 32));
       const bool general = tprev.bias != nullptr || nkh < 32;
-      prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, g, cscale, m_run, l_run, oacc);
+      prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, q, cscale, m_run, l_run, oacc);
       half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale, [&](int s) {
         if (s == 0) {
           if ((min(T + 2, t_end - 1) >> 1) >= pbase + 64) refill(pbase + 64);
@@ -417,7 +456,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     {   // half (T, 0): scores in s0
       const int nkh = min(32, tcur.nk);
       const bool general = tcur.bias != nullptr || nkh < 32;
-      prepare_half(s0, mx0, general, nkh, tcur.bias, g, cscale, m_run, l_run, oacc);
+      prepare_half(s0, mx0, general, nkh, tcur.bias, q, cscale, m_run, l_run, oacc);
       half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale, [](int) {}
       );
     }
@@ -429,34 +468,32 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // the loads of the two tiles past the end still target this workgroup's LDS: let them land before the waves end
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
-  const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
-  if (split) {
-    // partial result of a sub-item: unnormalised fp32 outputs and the {maximum, sum} they refer to
-    const long long sid = (((long long)xcd * a.n_split + (item - n_whole)) * a.parts + part) * 2 + grp;
-    if (row_ok) {
-      float* op = a.split_o + (sid * 128 + row) * MD + 4 * g;
+  // ---- normalise and store: element i of oacc[ct][qt] is channel 16 ct + 4 q + i of query 16 qt + r
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+  for (int qt = 0; qt < 2; ++qt) {
+    float l_tot = l_run[qt][0];
+    l_tot += __shfl_xor(l_tot, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    if (!row_ok[qt]) continue;
+    const int row = rowq[qt];
+    if (split) {
+      // partial result of a sub-item: unnormalised fp32 outputs and the {maximum, sum} they refer to
+      const long long sid = (((long long)xcd * a.n_split + (item - n_whole)) * a.parts + part) * 2 + grp;
+      float* op = a.split_o + (sid * 128 + row) * MD + 4 * q;
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4)
-          *reinterpret_cast<float4*>(op + 32 * db + 8 * e4) =
-              make_float4(oacc[db][4 * e4], oacc[db][4 * e4 + 1], oacc[db][4 * e4 + 2], oacc[db][4 * e4 + 3]);
-      if (g == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(m_run, l_tot);
-    }
-  } else if (row_ok) {
-    const float inv = 1.0f / l_tot;
-    uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
-    // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
-    const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * g : nullptr;
+      for (int c = 0; c < 8; ++c)
+        *reinterpret_cast<float4*>(op + 16 * c) = make_float4(oacc[c][qt][0], oacc[c][qt][1], oacc[c][qt][2], oacc[c][qt][3]);
+      if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(m_run[qt], l_tot);
+    } else {
+      const float inv = 1.0f / l_tot;
+      uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * q;
+      // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
+      const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * q : nullptr;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        float4 r = make_float4(oacc[db][4 * e4] * inv, oacc[db][4 * e4 + 1] * inv, oacc[db][4 * e4 + 2] * inv,
-                               oacc[db][4 * e4 + 3] * inv);
+      for (int c = 0; c < 8; ++c) {
+        float4 r = make_float4(oacc[c][qt][0] * inv, oacc[c][qt][1] * inv, oacc[c][qt][2] * inv, oacc[c][qt][3] * inv);
         if (oc) {
-          const float4 c4 = *reinterpret_cast<const float4*>(oc + 32 * db + 8 * e4);
+          const float4 c4 = *reinterpret_cast<const float4*>(oc + 16 * c);
           r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
           r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
         }
@@ -465,8 +502,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
         uint2 o;
         o.x = *reinterpret_cast<uint32_t*>(&lo);
         o.y = *reinterpret_cast<uint32_t*>(&hi);
-        *reinterpret_cast<uint2*>(op + 32 * db + 8 * e4) = o;
+        *reinterpret_cast<uint2*>(op + 16 * c) = o;
       }
+    }
   }
 }
 
@@ -575,7 +613,10 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
       e = hipGetLastError();
     }
   }
-  if (e == hipSuccess && exact_sets) e = launch_attn_mfma4(pr, m, st);
+  if (e == hipSuccess && exact_sets) {
+    m.vt = ws.vt4; m.vcnt = ws.vcnt4;               // the 4-wave kernel reads its own key order
+    e = launch_attn_mfma4(pr, m, st);
+  }
   if (prof) {
     (void)hipEventRecord(g_prof_stop, st);
     g_prof_recorded = 1;

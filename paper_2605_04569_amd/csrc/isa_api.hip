@@ -106,12 +106,14 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->kcn = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
     ws->vcnt = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
     ws->biasn = (float*)take(B * H * (size_t)pr.Tn_pad * 4);
+    ws->vt4 = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * T * D * 128 * 2) : nullptr;
+    ws->vcnt4 = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2) : nullptr;
     ws->zero_tile = (uint16_t*)take(128 * 64 * 2);
     ws->ktab = (int4*)take(B * H * T * 16);
     ws->split_o = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 128 * 4);
     ws->split_ml = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 2 * 4);
   } else {
-    ws->vt = ws->kcn = ws->vcnt = nullptr;
+    ws->vt = ws->kcn = ws->vcnt = ws->vt4 = ws->vcnt4 = nullptr;
     ws->biasn = nullptr;
     ws->zero_tile = nullptr;
     ws->ktab = nullptr;

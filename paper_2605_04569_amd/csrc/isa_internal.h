@@ -55,6 +55,7 @@ struct Workspace {
   uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order
   uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
   float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key, -inf for padding
+  uint16_t* vt4; uint16_t* vcnt4;   // the same two arrays in the key order of the 4-wave kernel (only with exact sets)
   uint16_t* zero_tile;   // 16 KB of zeros, written by the V^T pack kernel
   int4* ktab;            // [B,H,T_max] the btab rows of the blocks of kv_list, in list order
   float* ocoarse;        // [B,H,T_max,D] pooled attention output (only carved when gamma != 0)
