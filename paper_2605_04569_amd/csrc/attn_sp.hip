@@ -2,39 +2,37 @@
 // exact branch of ISA (Alg. 1 Stage 4 / Alg. 2 Part A) and the Taylor branch without exact sets (Eq. 4,
 // Alg. 2 Part B).
 //
-// Why it is shaped this way.  Vector-ALU work overlaps an MFMA best when the same wave issues it right behind
-// that MFMA (measured on a 2-wave SIMD: 8 MFMAs with 2 fma + 2 exp2 + 1 convert behind each run 5 % slower than
-// the MFMAs alone), so each wave runs one instruction stream in which every MFMA is followed by the few VALU
-// instructions and the one LDS read that fit under it, held in place with scheduling fences and value pins:
+// Shape.  One workgroup of 8 waves owns two query blocks (2 x 128 rows) that walk the same tile sequence, so every
+// K / V^T tile is fetched once per 256 query rows; a SIMD holds two waves.  Scores are computed transposed
+// (S^T = K Q^T) with v_mfma_f32_16x16x32_bf16 and V is read from a packed, key-permuted V^T copy, so the softmax
+// weights go from the score accumulators to the second product (O^T = V^T P^T) without leaving their registers.
 //
-//   keys are handled in halves of 32 (one MFMA row group).  While the 8 MFMAs that compute the raw scores of
-//   half h+1 are in flight, the wave exponentiates the scores of half h (computed one step earlier); while
-//   the 8 MFMAs that add V_h^T P_h^T to the output are in flight, it takes the maximum of the new scores.
+// Pipeline.  Keys are handled in halves of 32.  Each wave runs one instruction stream of "steps" of two MFMAs (one
+// LDS fragment against both 16-query tiles of the wave), each followed by one softmax weight (fma + exp2), and every
+// second one by a bf16 conversion; scheduling fences and value pins hold that order.  Three halves are in flight:
+// while the score MFMAs of half g run, the weights of half g-1 are computed, and the value MFMAs add half g-2.  The
+// value product is therefore a whole 64-key tile behind the score product, and the V^T tile staged in LDS lags the
+// K tile by one loop iteration.  One barrier per iteration; three LDS buffers per tensor; tiles arrive by direct
+// global->LDS loads issued inside the MFMA stream two (K) and one (V^T) iterations ahead.
 //
-// The score product of a 64-key K tile is therefore half a tile ahead of the value product, and the V^T tile
-// that is staged in LDS per loop iteration is shifted by 32 keys against the K tile (second half of tile T-1,
-// first half of tile T), which keeps one barrier and one load group per iteration.
-//
-// One workgroup of 8 waves owns two query blocks (2 x 128 rows) that walk the same tile sequence, so every K /
-// V^T tile is fetched once per 256 query rows; a SIMD holds two waves.  Scores are computed transposed
-// (S^T = K Q^T) and V is read from the packed, key-permuted V^T copy, as in the 4-wave kernel: P stays in
-// registers in the layout the second product needs.
-//
-// What bounds it.  With real (non-constant) operands the matrix pipes of this chip are limited by power, not by
-// issue slots: a stream of nothing but 32x32x16 bf16 MFMAs runs at 2.4 PFLOP/s on constant operands and at
-// 1.8 PFLOP/s on random ones, and in this kernel taking stall cycles out of the loop (deeper prefetch, no
-// barrier, fewer vector instructions) lowers the clock the chip holds (1.9 - 2.2 GHz) and leaves the time
-// unchanged.  What does change the time is the energy per tile: bytes moved behind the L2, LDS traffic, and the
-// number of MFMAs themselves.
+// What bounds it (measured).  With real operands the 32x32x16 MFMA is limited by power: a stream of nothing but such
+// MFMAs runs at 2.4 PFLOP/s on constant operands and 1.8 on random ones, and a kernel built on it held 1.9 GHz; the
+// 16x16x32 shape moves fewer accumulator bytes per flop (2.0 PFLOP/s on random operands) and this kernel holds
+// 2.2 - 2.3 GHz with it, where the cycles count again.  Of those, about half are MFMA cycles; the rest is the other
+// work of the two waves of a SIMD, which overlaps the MFMAs only in part.
 #include "attn_mfma.h"
 
 namespace isa {
 
-struct STile {                              // wave-uniform description of one 64-key tile
-  const uint16_t* krows;                    // row 0 of the block (token tiles) or of the tile (mean tiles)
-  const uint16_t* vt;                       // 128 x 64 packed V^T of the tile
-  const float* bias;                        // per-key additive term on the raw score, or null
-  int row0, kstride, nk, last_row;
+// Wave-uniform description of one 64-key tile.  Offsets are 32-bit byte offsets from per-head base pointers that do
+// not change inside the loop, and the description is computed without branches: it is built once per iteration by
+// every wave, in scalar instructions that the wave cannot overlap with its own MFMAs.
+struct STile {
+  uint32_t k_off;                           // bytes from the head's key base to row 0 of the block (token tiles) / tile (mean tiles)
+  uint32_t v_off;                           // bytes from the head's V^T base to the 128 x 64 packed V^T of the tile
+  int bias_off;                             // elements from the head's bias base (mean tiles only)
+  int row0, nk, last_row;
+  bool zero_v;                              // a tile past the end: V^T comes from the all-zero tile
 };
 
 typedef short short4v __attribute__((ext_vector_type(4)));
@@ -91,87 +89,93 @@ __device__ __forceinline__ float max_over_q(float x) {
   return max_raw(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
 }
 
-// One half step.  Scores of the half that is softmaxed come in `sin` (raw, bias and masks already applied,
-// running maxima already raised); the raw scores of the next half are produced in `sout` from the 8 K
-// fragments in `kf` (fragment f = key tile f % 2, channels 32 (f / 2) .., fetched from LDS one phase earlier).
+// One half step g: sixteen steps of two MFMAs each.  Three halves are in flight:
+//   score MFMAs (steps 0..7) produce the raw scores of half g in `sout` from the 8 K fragments in `kf` (fragment f =
+//   key tile f % 2, channels 32 (f / 2) .., fetched from LDS during the previous half step);
+//   the softmax weights of half g-1 are computed from `sin` (raw scores, bias and masks already applied, running maxima
+//   already raised): one weight (fma, exp2) per step, one bf16 pair converted every second step, into `pnew`;
+//   value MFMAs (steps 8..15) add V^T P^T of half g-2 (`pacc`, finished in the previous half step; V^T unit VU of the
+//   staged tile) to the output, and the 4x4x4 MFMAs its row sums.
+// exp2 runs at a quarter of the vector rate on this chip, so the 16 weights of a half have to be spread over all 16
+// steps: bunched behind the score MFMAs they made those steps vector-ALU bound while the value steps had nothing to do.
 // `tmax_out[qt]` is the scaled maximum of `sout` over all 32 keys of the lane's query of tile qt (valid when `sout`
-// needs no bias or mask).  The value product uses V^T unit VU of the staged V^T tile.
-// LDS fragments are requested a whole phase (16 MFMAs) before the MFMAs that consume them: the V^T fragments
-// during the score MFMAs, and the K fragments of the following half step (32 rows at `kpre`) during the value
-// MFMAs; every fragment feeds two MFMAs (both query tiles).  Every vector-ALU instruction of the softmax sits
-// between MFMAs of the same wave, and so does whatever `hook(f)` adds in score step f (tile set-up and tile loads
-// of a later iteration).
+// needs no bias or mask).  LDS fragments are requested a phase before the MFMAs that consume them: the V^T fragments
+// during the score steps, the K fragments of the following half step (32 rows at `kpre`) during the value steps;
+// every fragment feeds two MFMAs (both query tiles).  `hook(f)` adds tile set-up and tile loads of a later iteration
+// in score step f.
 template <int VU, typename Hook>
 __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[2][4], bf16x8 (&kf)[8], const Scores& sin, Scores& sout,
                                           f32x4 (&oacc)[8][2], const float (&m_run)[2], f32x4 (&l_run)[2],
-                                          float (&tmax_out)[2], const int (&koff)[4], int voff, float cscale, Hook hook) {
+                                          float (&tmax_out)[2], const bf16x8 (&pacc)[2], bf16x8 (&pnew)[2],
+                                          const int (&koff)[4], int voff, float cscale, Hook hook
+                                          ) {
   const float neg_m[2] = {-m_run[0], -m_run[1]};
   const bf16x4 ones4 = {(__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f};
   const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-  bf16x2 pw[8];
-  bf16x8 pf[2], vf[8];
-  // 8 score steps, two MFMAs each (the K fragment against both query tiles); behind each MFMA half of one pair of
-  // weights (fma, exp2; the second half also converts the pair), and one LDS read per step.  A 16x16x32 MFMA holds
-  // the matrix pipe for 16 cycles, which two or three vector instructions fill.  Weight pair f: query tile f / 4,
-  // positions 2 (f % 4), +1.
+  bf16x8 vf[8];
+  float pe = 0.f;                            // the even weight of the pair in progress
+  float mx[2] = {-INFINITY, -INFINITY};
+  // weight t of the half: query tile t / 8, position t % 8 of its fragment = element (t / 4) % 2, t % 4 of `sin`
+  auto weight = [&](int t) {
+    const int qt = t >> 3, kt = (t >> 2) & 1, i = t & 3;
+    const float p = __builtin_amdgcn_exp2f(fmaf(sin.t[kt][qt][i], cscale, neg_m[qt]));
+    if (t & 1) {
+      bf16x2 pw = {(__bf16)pe, (__bf16)p};
+      pin(pw);
+      pnew[qt][t & 6] = pw[0];
+      pnew[qt][(t & 6) + 1] = pw[1];
+    } else {
+      pe = p;
+      pin(pe);
+    }
+  };
 #pragma unroll
   for (int f = 0; f < 8; ++f) {
     const int kt = f & 1, ks = f >> 1;
-    const int qt = f >> 2, a = (f >> 1) & 1, i0 = 2 * (f & 1);
     ISA_FENCE();
     vf[f] = *reinterpret_cast<const bf16x8*>(vbase + VU * (V_TILE / 2) + f * 16 * 32 + voff);      // channels 16 f ..
     sout.t[kt][0] = mfma16(kf[f], qf[0][ks], ks == 0 ? zero4 : sout.t[kt][0]);
-    float p0 = __builtin_amdgcn_exp2f(fmaf(sin.t[a][qt][i0], cscale, neg_m[qt]));
-    pin(p0);
-    ISA_FENCE();
     sout.t[kt][1] = mfma16(kf[f], qf[1][ks], ks == 0 ? zero4 : sout.t[kt][1]);
-    const float p1 = __builtin_amdgcn_exp2f(fmaf(sin.t[a][qt][i0 + 1], cscale, neg_m[qt]));
-    pw[f] = bf16x2{(__bf16)p0, (__bf16)p1};
-    pin(pw[f]);
+    weight(f);
     hook(f);
   }
-#pragma unroll
-  for (int f = 0; f < 8; ++f) {
-    pf[f >> 2][2 * (f & 3)] = pw[f][0];
-    pf[f >> 2][2 * (f & 3) + 1] = pw[f][1];
-  }
-  // 8 value steps (channel tiles), two MFMAs each (both query tiles).  Their shadows take the row sums of the
-  // weights (c = 0, 1), the raw maxima of the new scores (c = 2..5; the last score MFMAs have retired by then) and
-  // the exchange of those maxima between the four lanes that share a query (c = 6, 7).
-  float mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
     ISA_FENCE();
     kf[c] = *reinterpret_cast<const bf16x8*>(kpre + (c & 1) * 16 * MD + koff[c >> 1]);
-    oacc[c][0] = mfma16(vf[c], pf[0], oacc[c][0]);
-    // Row sums over the weights as rounded to bf16 (what the value product multiplies), so that the rounding of a
-    // dominant weight cancels between numerator and denominator.  A 4x4x4 MFMA with an all-ones A operand adds up
-    // the four bf16 values each lane holds in its B operand (D[i][j] = sum_k B[k][j], column j = the lane itself):
-    // two of them per weight fragment, 8 matrix-pipe cycles each, instead of 16 unpack-and-add vector instructions.
+    oacc[c][0] = mfma16(vf[c], pacc[0], oacc[c][0]);
+    oacc[c][1] = mfma16(vf[c], pacc[1], oacc[c][1]);
+    weight(8 + c);
     if (c < 2) {
-      const bf16x4 lo = {pf[c][0], pf[c][1], pf[c][2], pf[c][3]};
+      // Row sums over the weights as rounded to bf16 (what the value product multiplies), so that the rounding of a
+      // dominant weight cancels between numerator and denominator.  A 4x4x4 MFMA with an all-ones A operand adds up
+      // the four bf16 values each lane holds in its B operand (D[i][j] = sum_k B[k][j], column j = the lane itself):
+      // two of them per weight fragment, 8 matrix-pipe cycles each, instead of 16 unpack-and-add vector instructions.
+      const bf16x4 lo = {pacc[c][0], pacc[c][1], pacc[c][2], pacc[c][3]};
+      const bf16x4 hi = {pacc[c][4], pacc[c][5], pacc[c][6], pacc[c][7]};
       l_run[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, lo), l_run[c], 0, 0, 0);
-    }
-    if (c >= 2 && c < 6) {
-      const int qt = (c - 2) >> 1, kt = (c - 2) & 1;
-      mx[qt] = fmaxf(fmaxf(mx[qt], sout.t[kt][qt][0]), sout.t[kt][qt][1]);
-      pin(mx[qt]);
-    }
-    ISA_FENCE();
-    oacc[c][1] = mfma16(vf[c], pf[1], oacc[c][1]);
-    if (c < 2) {
-      const bf16x4 hi = {pf[c][4], pf[c][5], pf[c][6], pf[c][7]};
       l_run[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, ones4), __builtin_bit_cast(short4v, hi), l_run[c], 0, 0, 0);
     }
-    if (c >= 2 && c < 6) {
-      const int qt = (c - 2) >> 1, kt = (c - 2) & 1;
+    if (c < 4) {                               // raw maxima of the new scores (their MFMAs have retired by now)
+      const int qt = c >> 1, kt = c & 1;
+      mx[qt] = fmaxf(fmaxf(mx[qt], sout.t[kt][qt][0]), sout.t[kt][qt][1]);
       mx[qt] = fmaxf(fmaxf(mx[qt], sout.t[kt][qt][2]), sout.t[kt][qt][3]);
       pin(mx[qt]);
     }
-    if (c >= 6) {
-      mx[c - 6] = max_over_q(mx[c - 6] * cscale);
-      pin(mx[c - 6]);
+    if (c == 4 || c == 6) {                    // exchange between the four lanes that share a query, in two steps
+      const int qt = (c - 4) >> 1;
+      const uint32_t u = __float_as_uint(mx[qt] * cscale);
+      const auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+      mx[qt] = max_raw(__uint_as_float(s16[0]), __uint_as_float(s16[1]));
+      pin(mx[qt]);
+    }
+    if (c == 5 || c == 7) {
+      const int qt = (c - 5) >> 1;
+      const uint32_t u = __float_as_uint(mx[qt]);
+      const auto s32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+      mx[qt] = max_raw(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
+      pin(mx[qt]);
     }
   }
   ISA_FENCE();
@@ -180,11 +184,12 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
 }
 
 // Bias / masks of a special half (block means, ragged tails), then the running maxima of the online softmax
-// (Alg. 2 Part A) with the rare rescale of the accumulators.  `tmax` comes in as the scaled row maxima of a plain
-// half; a special half recomputes them here.
+// (Alg. 2 Part A).  `tmax` comes in as the scaled row maxima of a plain half; a special half recomputes them here.
+// When a maximum is raised, `alpha[qt]` is the factor the accumulators have to be multiplied with -- after the half
+// step that follows, because that half step still adds weights that were computed against the old maximum.
 __device__ __forceinline__ void prepare_half(Scores& sc, float (&tmax)[2], bool general, int nk_half,
                                              const float* __restrict__ bias, int q, float cscale, float (&m_run)[2],
-                                             f32x4 (&l_run)[2], f32x4 (&oacc)[8][2]) {
+                                             float (&alpha)[2]) {
   if (general) {
     float m2[2] = {-INFINITY, -INFINITY};
 #pragma unroll
@@ -205,16 +210,26 @@ __device__ __forceinline__ void prepare_half(Scores& sc, float (&tmax)[2], bool 
     tmax[0] = max_over_q(m2[0] * cscale);
     tmax[1] = max_over_q(m2[1] * cscale);
   }
+  alpha[0] = alpha[1] = 1.0f;
   const bool raise0 = tmax[0] > m_run[0] + RESCALE_TAU, raise1 = tmax[1] > m_run[1] + RESCALE_TAU;
   if (__ballot(raise0 || raise1) != 0ull) {             // rare after the first tiles
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
       const float m_new = (qt ? raise1 : raise0) ? tmax[qt] : m_run[qt];
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+      alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
       m_run[qt] = m_new;
-      l_run[qt] *= alpha;                                 // all four elements hold the same sum
+    }
+  }
+}
+
+// The deferred rescale of the accumulators after a half step whose prepare_half raised a maximum.
+__device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[2], f32x4 (&oacc)[8][2]) {
+  if (__ballot(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0ull) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) oacc[c][qt] *= alpha;
+    for (int qt = 0; qt < 2; ++qt) {
+      l_run[qt] *= alpha[qt];                             // all four elements hold the same sum
+#pragma unroll
+      for (int c = 0; c < 8; ++c) oacc[c][qt] *= alpha[qt];
     }
   }
 }
@@ -297,30 +312,28 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     return make_int4(__builtin_amdgcn_readlane(ecache.x, l), __builtin_amdgcn_readlane(ecache.y, l),
                      __builtin_amdgcn_readlane(ecache.z, l), 0);
   };
+  // per-head bases of everything a tile description points into (mean tiles read the gathered bf16 means)
+  const char* const k_head = taylor ? reinterpret_cast<const char*>(a.kcn + bh * a.Tn_pad * MD)
+                                    : reinterpret_cast<const char*>(a.k + tbase);
+  const char* const v_head = taylor ? reinterpret_cast<const char*>(a.vcnt + bh * (a.Tn_pad / KT) * (long long)(MD * KT))
+                                    : reinterpret_cast<const char*>(a.vt + bh * T_max * 2 * (long long)(MD * KT));
+  const float* const bias_head = taylor ? a.biasn + bh * a.Tn_pad : nullptr;
+  const uint32_t kstride_b = (uint32_t)(taylor ? MD : (int)a.geo.stride_t) * 2u;
   auto make_tile = [&](int idx, int4 ent, STile& t) {
     const bool past = idx >= t_end;
-    if (past) idx = t_end - 1;
-    if (!taylor) {
-      const int sub = idx & 1;
-      const int n_j = ent.y;
-      t.krows = a.k + tbase + (long long)ent.x * a.geo.stride_t;
-      t.row0 = sub * KT;
-      t.kstride = (int)a.geo.stride_t;
-      t.vt = a.vt + ((bh * T_max + ent.z) * 2 + sub) * (long long)(MD * KT);
-      t.bias = nullptr;
-      t.nk = max(0, min(KT, n_j - sub * KT));
-      t.last_row = max(n_j - 1, 0);
-    } else {
-      const long long row0 = bh * a.Tn_pad + (long long)idx * KT;
-      t.krows = a.kcn + row0 * MD;
-      t.row0 = 0;
-      t.kstride = MD;
-      t.vt = a.vcnt + (bh * (a.Tn_pad / KT) + idx) * (long long)(MD * KT);
-      t.bias = a.biasn + row0;
-      t.nk = min(KT, n_list - idx * KT);
-      t.last_row = KT - 1;                                          // the gathered arrays are padded to whole tiles
-    }
-    if (past) { t.nk = 0; t.vt = a.zero_tile; }
+    idx = past ? t_end - 1 : idx;
+    const int sub = idx & 1, n_j = ent.y;
+    t.k_off = taylor ? (uint32_t)idx * (uint32_t)(KT * MD * 2) : (uint32_t)ent.x * kstride_b;
+    t.v_off = taylor ? (uint32_t)idx * (uint32_t)(MD * KT * 2) : ((uint32_t)ent.z * 2u + (uint32_t)sub) * (uint32_t)(MD * KT * 2);
+    t.bias_off = idx * KT;
+    t.row0 = taylor ? 0 : sub * KT;
+    t.nk = past ? 0 : taylor ? min(KT, n_list - idx * KT) : max(0, min(KT, n_j - sub * KT));
+    t.last_row = taylor ? KT - 1 : max(n_j - 1, 0);      // the gathered mean arrays are padded to whole tiles
+    t.zero_v = past;
+  };
+  auto bias_of = [&](const STile& t) -> const float* { return bias_head ? bias_head + t.bias_off : nullptr; };
+  auto vt_of = [&](const STile& t) -> const uint16_t* {
+    return t.zero_v ? a.zero_tile : reinterpret_cast<const uint16_t*>(v_head + t.v_off);
   };
 
   // ---- Q fragments: B operand of S^T = K Q^T; lane (r, q) holds channels 32 ks + 8 q .. +7 of query 16 qt + r
@@ -350,24 +363,19 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // instructions per tile and tensor; instruction i of wave w fills chunks (2w+i)*64 .. +63, i.e. K rows
   // 8w+4i .. +3.
   const int l16 = lane >> 4;
-  const uint32_t kstride_b = (uint32_t)(taylor ? MD : (int)a.geo.stride_t) * 2u;
-  uint32_t kchunk_b[2], klane_b[2];
+  // Rows past the block's end re-read its last row (they are masked); the row index is never negative.  The row
+  // is clamped per lane (three vector instructions per load) rather than per wave, which would need a branch.
+  uint32_t kchunk_b[2];
+  int krow_l[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    kchunk_b[i] = (uint32_t)((((lane & 15) ^ ((8 * wave + 4 * i + l16) & 15)) * 8) * 2);
-    klane_b[i] = (uint32_t)l16 * kstride_b + kchunk_b[i];
+    krow_l[i] = 8 * wave + 4 * i + l16;
+    kchunk_b[i] = (uint32_t)((((lane & 15) ^ (krow_l[i] & 15)) * 8) * 2);
   }
   auto load_k1 = [&](const STile& t, int buf, int i) {
-    const char* kb = reinterpret_cast<const char*>(t.krows);
-    if (t.row0 + KT - 1 <= t.last_row) {                            // whole tile inside the block: lane-constant offsets
-      const char* kw = kb + (size_t)(t.row0 + wave * 8) * kstride_b;
-      lds_dma16(kw + (size_t)(4 * i) * kstride_b, klane_b[i], lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
-    } else {
-      // rows past the block's end re-read its last row; the row index is never negative
-      const int r = max(min(t.row0 + wave * 8 + 4 * i + l16, t.last_row), 0);
-      const uint32_t koff_b = (uint32_t)r * kstride_b + kchunk_b[i];
-      lds_dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
-    }
+    const int r = min(t.row0 + krow_l[i], t.last_row);
+    lds_dma16(k_head + t.k_off, (uint32_t)r * kstride_b + kchunk_b[i],
+              lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
   };
   auto load_k = [&](const STile& t, int buf) { load_k1(t, buf, 0); load_k1(t, buf, 1); };
   // Shifted V^T tile in LDS, unit-major: unit 0 = key positions 32..63 of tile `ta`, unit 1 = positions 0..31 of
@@ -375,12 +383,12 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // Waves 0-3 fill unit 0 and waves 4-7 unit 1, so the source tile of an instruction is wave-uniform and the
   // per-lane part of the address is one constant: rows 16(2w+i mod 8) + lane/4, chunk (lane & 3) ^ (lane >> 4).
   const uint32_t vlane_b = (uint32_t)(((lane >> 2) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
-  auto load_v1 = [&](const uint16_t* ta, const uint16_t* tb, int buf, int i) {
-    const uint16_t* srcu = wave < 4 ? ta + 32 : tb;
+  auto load_v1 = [&](const uint16_t* vt, int buf, int i) {
+    const uint16_t* srcu = vt + (wave < 4 ? 0 : 32);
     const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 2 + i) & 7) * 16) * KT);
     lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 2 + i) * 512));
   };
-  auto load_v = [&](const uint16_t* ta, const uint16_t* tb, int buf) { load_v1(ta, tb, buf, 0); load_v1(ta, tb, buf, 1); };
+  auto load_v = [&](const uint16_t* vt, int buf) { load_v1(vt, buf, 0); load_v1(vt, buf, 1); };
 
   // per-lane fragment offsets (bf16 elements): K row r of a 16-key tile, chunk (4 ks + q) ^ r; V^T unit row r of a
   // 16-channel tile, chunk q ^ ((r >> 2) & 3)
@@ -408,57 +416,67 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
   // ---- loop over T = t_begin .. t_end (one extra, fully masked iteration drains the pipeline).  Iteration T:
-  //   wait for this wave's loads of tile T+1; barrier (tile T+1 is now complete for every wave);
-  //   softmax of half (T-1,1) under the score MFMAs of half (T,0), with the set-up and the loads of tile T+2 in the
-  //   same shadows; value MFMAs of half (T-1,1);
-  //   softmax of half (T,0) under the score MFMAs of half (T,1); value MFMAs of half (T,0), in whose shadows the K
-  //   fragments of half (T+1,0) are fetched, so that no LDS latency is exposed after the next barrier.
-  // Three buffers: tile T is consumed, tile T+1 is complete and read ahead, tile T+2 is in flight.  Buffer
-  // (T+2) % 3 was last read in iteration T-1, which every wave has left once it is past this iteration's barrier.
+  //   wait for this wave's loads of K tile T+1 and V^T tile T; barrier (both complete for every wave);
+  //   half step 2T:   score MFMAs of half (T,0), weights of half (T-1,1), value MFMAs of half (T-1,0), with the
+  //                   set-up and the loads of K tile T+2 and V^T tile T+1 in the shadows of the score MFMAs;
+  //   half step 2T+1: score MFMAs of half (T,1), weights of half (T,0), value MFMAs of half (T-1,1); in the shadows of
+  //                   its value MFMAs the K fragments of half (T+1,0) are fetched, so that no LDS latency is exposed
+  //                   after the next barrier.
+  // Three buffers each: K tile T is consumed, T+1 complete and read ahead, T+2 in flight; V^T tile T-1 is consumed, T
+  // complete, T+1 in flight.  The buffers that are being filled were last read in iteration T-1, which every wave
+  // has left once it is past this iteration's barrier.
   STile tprev, tcur, tnext, tnn;
   refill(t_begin >> 1);
   make_tile(t_begin, entry_of(t_begin), tcur);
   make_tile(t_begin + 1, entry_of(t_begin + 1), tnext);
-  tprev = tcur; tprev.nk = 0; tprev.bias = nullptr; tprev.vt = a.zero_tile;
+  tprev = tcur; tprev.nk = 0;
   load_k(tcur, 0);
-  load_v(a.zero_tile, tcur.vt, 0);
   load_k(tnext, 1);
-  load_v(tcur.vt, tnext.vt, 1);
+  load_v(a.zero_tile, 2);                   // stands in for V^T tile t_begin - 1: multiplied with zero weights, must be finite
+  load_v(vt_of(tcur), 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   bf16x8 kf[8];                           // K fragments of the next 32 rows to be multiplied
 #pragma unroll
   for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const bf16x8*>(ldsK + (f & 1) * 16 * MD + koff[f >> 1]);
-  int bcur = 0;                             // T % NBUF
+  bf16x8 pa[2], pb[2];                    // weight fragments: one is being filled while the other is multiplied
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { pa[qt][e] = (__bf16)0.f; pb[qt][e] = (__bf16)0.f; }
+  float alpha[2];
+  int bcur = 0;                             // (T - t_begin) % NBUF
   for (int T = t_begin; T <= t_end; ++T) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    const int bnext = bcur == 2 ? 0 : bcur + 1;                     // (T + 1) % 3
-    const int bnn = bcur == 0 ? 2 : bcur - 1;                       // (T + 2) % 3
+    const int bnext = bcur == 2 ? 0 : bcur + 1;                     // buffer of tiles T + 1
+    const int bnn = bcur == 0 ? 2 : bcur - 1;                       // buffer of tiles T + 2 and T - 1
     const uint16_t* kbase = ldsK + bcur * K_TILE;
-    const uint16_t* vbase = ldsV + bcur * V_TILE;
-    {   // half (T-1, 1): scores in s1
+    const uint16_t* vbase = ldsV + bnn * V_TILE;                    // V^T tile T - 1
+    {   // scores of half (T,0) into s0; weights of half (T-1,1) from s1 into pb; value product of pa = half (T-1,0)
       const int nkh = min(32, max(0, tprev.nk - 32));
-      const bool general = tprev.bias != nullptr || nkh < 32;
-      prepare_half(s1, mx1, general, nkh, tprev.bias ? tprev.bias + 32 : nullptr, q, cscale, m_run, l_run, oacc);
-      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, koff, voff, cscale, [&](int s) {
-        if (s == 0) {
+      const bool general = taylor || nkh < 32;
+      prepare_half(s1, mx1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, m_run, alpha);
+      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, pa, pb, koff, voff, cscale, [&](int f) {
+        if (f == 0) {
           if ((min(T + 2, t_end - 1) >> 1) >= pbase + 64) refill(pbase + 64);
           make_tile(T + 2, entry_of(T + 2), tnn);
         }
-        if (s == 2) load_k1(tnn, bnn, 0);
-        if (s == 3) load_k1(tnn, bnn, 1);
-        if (s == 4) load_v1(tnext.vt, tnn.vt, bnn, 0);
-        if (s == 5) load_v1(tnext.vt, tnn.vt, bnn, 1);
+        if (f == 2) load_k1(tnn, bnn, 0);
+        if (f == 3) load_k1(tnn, bnn, 1);
+        if (f == 4) load_v1(vt_of(tnext), bnext, 0);
+        if (f == 5) load_v1(vt_of(tnext), bnext, 1);
       }
       );
+      rescale(alpha, l_run, oacc);
     }
-    {   // half (T, 0): scores in s0
+    {   // scores of half (T,1) into s1; weights of half (T,0) from s0 into pa; value product of pb = half (T-1,1)
       const int nkh = min(32, tcur.nk);
-      const bool general = tcur.bias != nullptr || nkh < 32;
-      prepare_half(s0, mx0, general, nkh, tcur.bias, q, cscale, m_run, l_run, oacc);
-      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, koff, voff, cscale, [](int) {}
+      const bool general = taylor || nkh < 32;
+      prepare_half(s0, mx0, general, nkh, bias_of(tcur), q, cscale, m_run, alpha);
+      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, pb, pa, koff, voff, cscale, [](int) {}
       );
+      rescale(alpha, l_run, oacc);
     }
     tprev = tcur;
     tcur = tnext;

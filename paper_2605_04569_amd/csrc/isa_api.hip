@@ -70,7 +70,11 @@ int validate(const isa_problem* p, Problem* out) {
   pr.Tctx_max = Tctx_max > 0 ? Tctx_max : 1;
   pr.Tn_pad = (Tnew_max + 127) / 128 * 128;
   pr.geo = Geometry{p->B, p->H, p->D, p->block, T_max, p->stride_b, p->stride_h, p->stride_t};
-  pr.mfma_shape = (p->dtype == ISA_BF16 && p->D == 128 && p->block == 128);
+  // the MFMA kernels address a head's keys with 32-bit byte offsets: the tokens of one (batch, head) must span < 4 GiB
+  long long S_max = 0;
+  for (int b = 0; b < p->B; ++b) S_max = pr.cnt.b[b].S > S_max ? pr.cnt.b[b].S : S_max;
+  pr.mfma_shape = (p->dtype == ISA_BF16 && p->D == 128 && p->block == 128 &&
+                   (unsigned long long)S_max * (unsigned long long)p->stride_t * 2ull < (1ull << 32));
   return ISA_OK;
 }
 
