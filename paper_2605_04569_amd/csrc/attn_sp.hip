@@ -18,7 +18,7 @@
 // What bounds it (measured).  With real operands the 32x32x16 MFMA is limited by power: a stream of nothing but such
 // MFMAs runs at 2.4 PFLOP/s on constant operands and 1.8 on random ones, and a kernel built on it held 1.9 GHz; the
 // 16x16x32 shape moves fewer accumulator bytes per flop (2.0 PFLOP/s on random operands) and this kernel holds
-// 2.2 - 2.3 GHz with it, where the cycles count again.  Of those, about half are MFMA cycles; the rest is the other
+// 2.0 - 2.3 GHz with it, where the cycles count again.  Of those, about half are MFMA cycles; the rest is the other
 // work of the two waves of a SIMD, which overlaps the MFMAs only in part.
 #include "attn_mfma.h"
 
