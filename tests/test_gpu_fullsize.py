@@ -50,6 +50,14 @@ def test_paper_default_ratios_sampled(I):
     check_end_to_end(I, wl, q, k, v, q, k, v, heads=(2, 31), blocks_per_head=3, seed=3)
 
 
+def test_paper_default_ratios_480p_sampled(I):
+    """The same operating point at the 480p shape the bench reports it on (both attention kernels in one call: the
+    8-wave kernel for the exact branch, the 4-wave kernel for the Taylor blocks with their exact sets)."""
+    wl = W.CONFIGS["cfg2"].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(12,), blocks_per_head=2, seed=8, last_full=1)
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2"])
 def test_dense_attention_full_size_sampled(I, name):
     wl = W.CONFIGS[name]
