@@ -169,7 +169,8 @@ def measure(wl, steps, warmup, dense_steps):
         log("dense attention: %.3f ms per call" % dense_ms)
 
     del out, ws
-    return {"ms_per_step": ms_per_step, "kern_ms": kern_ms, "dense_ms": dense_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
+    return {"ms_per_step": ms_per_step, "kern_ms": kern_ms, "kern_ms_min": float(np.min(kernel_ms)),
+            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
             "inputs": (Q, K, V)}
 
 
@@ -210,6 +211,7 @@ def main():
         wl = wl.with_(**over)
     r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps)
     ms_per_step, kern_ms, dense_ms = r["ms_per_step"], r["kern_ms"], r["dense_ms"]
+    kern_ms_min, kern_ms_median = r["kern_ms_min"], r["kern_ms_median"]
     isa_fl, dense_fl = r["isa_fl"], r["dense_fl"]
     Q, K, V = r["inputs"]
 
@@ -264,6 +266,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "k_attn_sp (exact + Taylor branches, one launch) + k_split_merge",
                      "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "kernel_ms": round(kern_ms, 4),
+                     "kernel_ms_min": round(kern_ms_min, 4), "kernel_ms_median": round(kern_ms_median, 4),
                      "algorithmic_tflop_per_launch": round(isa_fl / 1e12, 3),
                      "traffic": measured_traffic(wl.name) if not over else None},
         "cpu_baseline": cpu,

@@ -15,7 +15,6 @@ constexpr int MD = 128;           // head dim
 constexpr int KT = 64;            // keys per LDS tile
 constexpr int K_TILE = KT * MD;   // bf16 elements of one K tile in LDS: 64 rows x 256 B, 16-byte chunks XOR-swizzled
 constexpr int V_TILE = MD * KT;   // bf16 elements of one V^T tile in LDS: 128 rows x 128 B, 16-byte chunks XOR-swizzled
-constexpr size_t MFMA_LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;   // 64 KB: two workgroups per compute unit
 constexpr float RESCALE_TAU = 8.0f;    // the running max is only raised when a tile exceeds it by 2^tau
 constexpr float M_INIT = -1.0e30f;
 
