@@ -98,8 +98,9 @@ __device__ __forceinline__ float max_over_q(float x) {
 //   staged tile) to the output, and the 4x4x4 MFMAs its row sums.
 // exp2 runs at a quarter of the vector rate on this chip, so the 16 weights of a half have to be spread over all 16
 // steps: bunched behind the score MFMAs they made those steps vector-ALU bound while the value steps had nothing to do.
-// `tmax_out[qt]` is the scaled maximum of `sout` over all 32 keys of the lane's query of tile qt (valid when `sout`
-// needs no bias or mask).  LDS fragments are requested a phase before the MFMAs that consume them: the V^T fragments
+// `tmax_out[qt]` is the scaled maximum of `sout` over the lane's own 8 keys of its query of tile qt, and `raise_out`
+// the ballot of the lanes in which it exceeds the running maximum by more than 2^tau (both valid when `sout` needs no
+// bias or mask).  LDS fragments are requested a phase before the MFMAs that consume them: the V^T fragments
 // during the score steps, the K fragments of the following half step (32 rows at `kpre`) during the value steps;
 // every fragment feeds two MFMAs (both query tiles).  `hook(f)` adds tile set-up and tile loads of a later iteration
 // in score step f.
@@ -107,7 +108,8 @@ template <int VU, typename Hook>
 __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[2][4], bf16x8 (&kf)[8], const Scores& sin, Scores& sout,
                                           f32x4 (&oacc)[8][2], const float (&m_run)[2], f32x4 (&l_run)[2],
-                                          float (&tmax_out)[2], const bf16x8 (&pacc)[2], bf16x8 (&pnew)[2],
+                                          float (&tmax_out)[2], unsigned long long& raise_out, const bf16x8 (&pacc)[2],
+                                          bf16x8 (&pnew)[2],
                                           const int (&koff)[4], int voff, float cscale, Hook hook
                                           ) {
   const float neg_m[2] = {-m_run[0], -m_run[1]};
@@ -163,33 +165,28 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
       mx[qt] = fmaxf(fmaxf(mx[qt], sout.t[kt][qt][2]), sout.t[kt][qt][3]);
       pin(mx[qt]);
     }
-    if (c == 4 || c == 6) {                    // exchange between the four lanes that share a query, in two steps
-      const int qt = (c - 4) >> 1;
-      const uint32_t u = __float_as_uint(mx[qt] * cscale);
-      const auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-      mx[qt] = max_raw(__uint_as_float(s16[0]), __uint_as_float(s16[1]));
-      pin(mx[qt]);
-    }
-    if (c == 5 || c == 7) {
-      const int qt = (c - 5) >> 1;
-      const uint32_t u = __float_as_uint(mx[qt]);
-      const auto s32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-      mx[qt] = max_raw(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
-      pin(mx[qt]);
+    if (c == 4 || c == 5) {
+      mx[c - 4] *= cscale;
+      pin(mx[c - 4]);
     }
   }
+  // Does any lane see a score that is more than 2^tau above its running maximum?  The lanes that share a query keep
+  // identical running maxima, so "some lane of the query exceeds it" is the condition for raising it; the exchange of
+  // the maxima between those lanes is left to the (rare) case that the answer is yes.
+  raise_out = __ballot(mx[0] > m_run[0] + RESCALE_TAU || mx[1] > m_run[1] + RESCALE_TAU);
   ISA_FENCE();
   tmax_out[0] = mx[0];
   tmax_out[1] = mx[1];
 }
 
 // Bias / masks of a special half (block means, ragged tails), then the running maxima of the online softmax
-// (Alg. 2 Part A).  `tmax` comes in as the scaled row maxima of a plain half; a special half recomputes them here.
-// When a maximum is raised, `alpha[qt]` is the factor the accumulators have to be multiplied with -- after the half
+// (Alg. 2 Part A).  `tmax` comes in as the lane's scaled maxima of a plain half and `raise` as the ballot of the lanes
+// that exceed their running maximum by more than 2^tau; a special half recomputes both here.  Returns whether any
+// maximum was raised; `alpha[qt]` is then the factor the accumulators have to be multiplied with -- after the half
 // step that follows, because that half step still adds weights that were computed against the old maximum.
-__device__ __forceinline__ void prepare_half(Scores& sc, float (&tmax)[2], bool general, int nk_half,
-                                             const float* __restrict__ bias, int q, float cscale, float (&m_run)[2],
-                                             float (&alpha)[2]) {
+__device__ __forceinline__ bool prepare_half(Scores& sc, float (&tmax)[2], unsigned long long raise, bool general,
+                                             int nk_half, const float* __restrict__ bias, int q, float cscale,
+                                             float (&m_run)[2], float (&alpha)[2]) {
   if (general) {
     float m2[2] = {-INFINITY, -INFINITY};
 #pragma unroll
@@ -207,30 +204,28 @@ __device__ __forceinline__ void prepare_half(Scores& sc, float (&tmax)[2], bool 
         }
       }
     }
-    tmax[0] = max_over_q(m2[0] * cscale);
-    tmax[1] = max_over_q(m2[1] * cscale);
+    tmax[0] = m2[0] * cscale;
+    tmax[1] = m2[1] * cscale;
+    raise = __ballot(tmax[0] > m_run[0] + RESCALE_TAU || tmax[1] > m_run[1] + RESCALE_TAU);
   }
-  alpha[0] = alpha[1] = 1.0f;
-  const bool raise0 = tmax[0] > m_run[0] + RESCALE_TAU, raise1 = tmax[1] > m_run[1] + RESCALE_TAU;
-  if (__ballot(raise0 || raise1) != 0ull) {             // rare after the first tiles
+  if (raise == 0ull) return false;                      // the common case after the first tiles
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      const float m_new = (qt ? raise1 : raise0) ? tmax[qt] : m_run[qt];
-      alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-      m_run[qt] = m_new;
-    }
+  for (int qt = 0; qt < 2; ++qt) {
+    const float t = max_over_q(tmax[qt]);               // the query's maximum over all 32 keys of the half
+    const float m_new = t > m_run[qt] + RESCALE_TAU ? t : m_run[qt];
+    alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+    m_run[qt] = m_new;
   }
+  return true;
 }
 
 // The deferred rescale of the accumulators after a half step whose prepare_half raised a maximum.
 __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[2], f32x4 (&oacc)[8][2]) {
-  if (__ballot(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0ull) {
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      l_run[qt] *= alpha[qt];                             // all four elements hold the same sum
+  for (int qt = 0; qt < 2; ++qt) {
+    l_run[qt] *= alpha[qt];                               // all four elements hold the same sum
 #pragma unroll
-      for (int c = 0; c < 8; ++c) oacc[c][qt] *= alpha[qt];
-    }
+    for (int c = 0; c < 8; ++c) oacc[c][qt] *= alpha[qt];
   }
 }
 
@@ -444,7 +439,8 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
     for (int e = 0; e < 8; ++e) { pa[qt][e] = (__bf16)0.f; pb[qt][e] = (__bf16)0.f; }
-  float alpha[2];
+  float alpha[2] = {1.f, 1.f};
+  unsigned long long raise0 = 0ull, raise1 = 0ull;     // ballots that go with mx0 / mx1
   int bcur = 0;                             // (T - t_begin) % NBUF
   for (int T = t_begin; T <= t_end; ++T) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -456,8 +452,8 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
     {   // scores of half (T,0) into s0; weights of half (T-1,1) from s1 into pb; value product of pa = half (T-1,0)
       const int nkh = min(32, max(0, tprev.nk - 32));
       const bool general = taylor || nkh < 32;
-      prepare_half(s1, mx1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, m_run, alpha);
-      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, pa, pb, koff, voff, cscale, [&](int f) {
+      const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, m_run, alpha);
+      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
         if (f == 0) {
           if ((min(T + 2, t_end - 1) >> 1) >= pbase + 64) refill(pbase + 64);
           make_tile(T + 2, entry_of(T + 2), tnn);
@@ -468,15 +464,15 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
         if (f == 5) load_v1(vt_of(tnext), bnext, 1);
       }
       );
-      rescale(alpha, l_run, oacc);
+      if (raised) rescale(alpha, l_run, oacc);
     }
     {   // scores of half (T,1) into s1; weights of half (T,0) from s0 into pa; value product of pb = half (T-1,1)
       const int nkh = min(32, tcur.nk);
       const bool general = taylor || nkh < 32;
-      prepare_half(s0, mx0, general, nkh, bias_of(tcur), q, cscale, m_run, alpha);
-      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, pb, pa, koff, voff, cscale, [](int) {}
+      const bool raised = prepare_half(s0, mx0, raise0, general, nkh, bias_of(tcur), q, cscale, m_run, alpha);
+      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, raise1, pb, pa, koff, voff, cscale, [](int) {}
       );
-      rescale(alpha, l_run, oacc);
+      if (raised) rescale(alpha, l_run, oacc);
     }
     tprev = tcur;
     tcur = tnext;
