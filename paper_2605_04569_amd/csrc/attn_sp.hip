@@ -229,8 +229,10 @@ __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[
   }
 }
 
-__global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t lds[NBUF * K_TILE + NBUF * V_TILE];
+// One work item.  `taylor` is a template parameter so that the tile set-up inside the loop carries no selects or
+// branches between the two kinds of key sequence (token tiles of kept blocks / tiles of gathered block means).
+template <bool taylor>
+__device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
   uint16_t* ldsV = lds + NBUF * K_TILE;     // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T % NBUF
 
@@ -245,7 +247,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // 1/parts of the key sequence, so that the round fills all compute units; a merge kernel combines their partial
   // results afterwards.
   const int n_whole = a.n_long - a.n_split, n_sub = a.n_split * a.parts;
-  const bool taylor = j >= n_whole + n_sub;
   const bool split = !taylor && j >= n_whole;
   const int item = taylor ? j - n_whole - n_sub : split ? n_whole + (j - n_whole) / a.parts : j;
   const int part = split ? (j - n_whole) % a.parts : 0;
@@ -520,6 +521,13 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
       }
     }
   }
+}
+
+__global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[NBUF * K_TILE + NBUF * V_TILE];
+  // the Taylor pairs of an XCD come after all of its exact-branch items (whole and split)
+  if ((int)(blockIdx.x >> 3) >= a.n_long - a.n_split + a.n_split * a.parts) attn_sp_item<true>(a, lds);
+  else attn_sp_item<false>(a, lds);
 }
 
 // Combines the partial results of the split work items: out = sum_p O_p 2^(m_p - m) / sum_p l_p 2^(m_p - m) with
