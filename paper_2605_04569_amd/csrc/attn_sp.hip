@@ -187,7 +187,7 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
 __device__ __forceinline__ bool prepare_half(Scores& sc, float (&tmax)[2], unsigned long long raise, bool general,
                                              int nk_half, const float* __restrict__ bias, int q, float cscale,
                                              float (&m_run)[2], float (&alpha)[2]) {
-  if (general) {
+  if (__builtin_expect(general, 0)) {
     float m2[2] = {-INFINITY, -INFINITY};
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -208,7 +208,7 @@ __device__ __forceinline__ bool prepare_half(Scores& sc, float (&tmax)[2], unsig
     tmax[1] = m2[1] * cscale;
     raise = __ballot(tmax[0] > m_run[0] + RESCALE_TAU || tmax[1] > m_run[1] + RESCALE_TAU);
   }
-  if (raise == 0ull) return false;                      // the common case after the first tiles
+  if (__builtin_expect(raise == 0ull, 1)) return false;                      // the common case after the first tiles
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     const float t = max_over_q(tmax[qt]);               // the query's maximum over all 32 keys of the half
@@ -456,7 +456,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, m_run, alpha);
       half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
         if (f == 0) {
-          if ((min(T + 2, t_end - 1) >> 1) >= pbase + 64) refill(pbase + 64);
+          if (__builtin_expect((min(T + 2, t_end - 1) >> 1) >= pbase + 64, 0)) refill(pbase + 64);
           make_tile(T + 2, entry_of(T + 2), tnn);
         }
         if (f == 2) load_k1(tnn, bnn, 0);
@@ -465,7 +465,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
         if (f == 5) load_v1(vt_of(tnext), bnext, 1);
       }
       );
-      if (raised) rescale(alpha, l_run, oacc);
+      if (__builtin_expect(raised, 0)) rescale(alpha, l_run, oacc);
     }
     {   // scores of half (T,1) into s1; weights of half (T,0) from s0 into pa; value product of pb = half (T-1,1)
       const int nkh = min(32, tcur.nk);
@@ -473,7 +473,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       const bool raised = prepare_half(s0, mx0, raise0, general, nkh, bias_of(tcur), q, cscale, m_run, alpha);
       half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, raise1, pb, pa, koff, voff, cscale, [](int) {}
       );
-      if (raised) rescale(alpha, l_run, oacc);
+      if (__builtin_expect(raised, 0)) rescale(alpha, l_run, oacc);
     }
     tprev = tcur;
     tcur = tnext;
