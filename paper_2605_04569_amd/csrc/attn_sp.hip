@@ -20,6 +20,8 @@
 // 16x16x32 shape moves fewer accumulator bytes per flop (2.0 PFLOP/s on random operands) and this kernel holds
 // 2.0 - 2.3 GHz with it, where the cycles count again.  Of those, about half are MFMA cycles; the rest is the other
 // work of the two waves of a SIMD, which overlaps the MFMAs only in part.
+#include <type_traits>
+
 #include "attn_mfma.h"
 
 namespace isa {
@@ -107,12 +109,11 @@ __device__ __forceinline__ float max_over_q(float x) {
 template <int VU, typename Hook>
 __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[2][4], bf16x8 (&kf)[8], const Scores& sin, Scores& sout,
-                                          f32x4 (&oacc)[8][2], const float (&m_run)[2], f32x4 (&l_run)[2],
+                                          f32x4 (&oacc)[8][2], const float (&neg_m)[2], const float (&thr)[2], f32x4 (&l_run)[2],
                                           float (&tmax_out)[2], unsigned long long& raise_out, const bf16x8 (&pacc)[2],
                                           bf16x8 (&pnew)[2],
                                           const int (&koff)[4], int voff, float cscale, Hook hook
                                           ) {
-  const float neg_m[2] = {-m_run[0], -m_run[1]};
   const bf16x4 ones4 = {(__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f, (__bf16)1.0f};
   const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
   bf16x8 vf[8];
@@ -173,7 +174,7 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
   // Does any lane see a score that is more than 2^tau above its running maximum?  The lanes that share a query keep
   // identical running maxima, so "some lane of the query exceeds it" is the condition for raising it; the exchange of
   // the maxima between those lanes is left to the (rare) case that the answer is yes.
-  raise_out = __ballot(mx[0] > m_run[0] + RESCALE_TAU || mx[1] > m_run[1] + RESCALE_TAU);
+  raise_out = __ballot(mx[0] > thr[0]) | __ballot(mx[1] > thr[1]);
   ISA_FENCE();
   tmax_out[0] = mx[0];
   tmax_out[1] = mx[1];
@@ -186,7 +187,7 @@ __device__ __forceinline__ void half_step(const uint16_t* __restrict__ kpre, con
 // step that follows, because that half step still adds weights that were computed against the old maximum.
 __device__ __forceinline__ bool prepare_half(Scores& sc, float (&tmax)[2], unsigned long long raise, bool general,
                                              int nk_half, const float* __restrict__ bias, int q, float cscale,
-                                             float (&m_run)[2], float (&alpha)[2]) {
+                                             float (&neg_m)[2], float (&thr)[2], float (&alpha)[2]) {
   if (__builtin_expect(general, 0)) {
     float m2[2] = {-INFINITY, -INFINITY};
 #pragma unroll
@@ -206,15 +207,16 @@ __device__ __forceinline__ bool prepare_half(Scores& sc, float (&tmax)[2], unsig
     }
     tmax[0] = m2[0] * cscale;
     tmax[1] = m2[1] * cscale;
-    raise = __ballot(tmax[0] > m_run[0] + RESCALE_TAU || tmax[1] > m_run[1] + RESCALE_TAU);
+    raise = __ballot(tmax[0] > thr[0]) | __ballot(tmax[1] > thr[1]);
   }
   if (__builtin_expect(raise == 0ull, 1)) return false;                      // the common case after the first tiles
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     const float t = max_over_q(tmax[qt]);               // the query's maximum over all 32 keys of the half
-    const float m_new = t > m_run[qt] + RESCALE_TAU ? t : m_run[qt];
-    alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-    m_run[qt] = m_new;
+    const float m_new = t > thr[qt] ? t : -neg_m[qt];
+    alpha[qt] = __builtin_amdgcn_exp2f(-neg_m[qt] - m_new);
+    neg_m[qt] = -m_new;
+    thr[qt] = m_new + RESCALE_TAU;
   }
   return true;
 }
@@ -406,7 +408,9 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       s0.t[kt][qt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
       s1.t[kt][qt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
     }
-  float m_run[2] = {M_INIT, M_INIT};
+  // running maxima of the online softmax, kept as the two values the loop uses: their negative (the addend of the
+  // weights' exponent) and the threshold above which a new score raises them
+  float neg_m[2] = {-M_INIT, -M_INIT}, thr[2] = {M_INIT + RESCALE_TAU, M_INIT + RESCALE_TAU};
   float mx0[2] = {-INFINITY, -INFINITY}, mx1[2] = {-INFINITY, -INFINITY};     // scaled row maxima of s0 / s1
   f32x4 l_run[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
@@ -442,8 +446,10 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     for (int e = 0; e < 8; ++e) { pa[qt][e] = (__bf16)0.f; pb[qt][e] = (__bf16)0.f; }
   float alpha[2] = {1.f, 1.f};
   unsigned long long raise0 = 0ull, raise1 = 0ull;     // ballots that go with mx0 / mx1
-  int bcur = 0;                             // (T - t_begin) % NBUF
-  for (int T = t_begin; T <= t_end; ++T) {
+  // One iteration; `bcur` = (T - t_begin) % NBUF is the buffer of K tile T, either a compile-time constant (the loop
+  // is then unrolled three times and every LDS address is a per-lane constant plus an immediate) or a run-time value.
+  auto iteration = [&](const int T, const auto bcur_c) {
+    const int bcur = bcur_c;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int bnext = bcur == 2 ? 0 : bcur + 1;                     // buffer of tiles T + 1
@@ -453,8 +459,8 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     {   // scores of half (T,0) into s0; weights of half (T-1,1) from s1 into pb; value product of pa = half (T-1,0)
       const int nkh = min(32, max(0, tprev.nk - 32));
       const bool general = taylor || nkh < 32;
-      const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, m_run, alpha);
-      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, m_run, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
+      const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, neg_m, thr, alpha);
+      half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, neg_m, thr, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
         if (f == 0) {
           if (__builtin_expect((min(T + 2, t_end - 1) >> 1) >= pbase + 64, 0)) refill(pbase + 64);
           make_tile(T + 2, entry_of(T + 2), tnn);
@@ -470,15 +476,30 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     {   // scores of half (T,1) into s1; weights of half (T,0) from s0 into pa; value product of pb = half (T-1,1)
       const int nkh = min(32, tcur.nk);
       const bool general = taylor || nkh < 32;
-      const bool raised = prepare_half(s0, mx0, raise0, general, nkh, bias_of(tcur), q, cscale, m_run, alpha);
-      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, m_run, l_run, mx1, raise1, pb, pa, koff, voff, cscale, [](int) {}
+      const bool raised = prepare_half(s0, mx0, raise0, general, nkh, bias_of(tcur), q, cscale, neg_m, thr, alpha);
+      half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, neg_m, thr, l_run, mx1, raise1, pb, pa, koff, voff, cscale, [](int) {}
       );
       if (__builtin_expect(raised, 0)) rescale(alpha, l_run, oacc);
     }
     tprev = tcur;
     tcur = tnext;
     tnext = tnn;
-    bcur = bnext;
+  };
+  if constexpr (taylor) {                   // a handful of iterations per item: not worth three copies of the loop
+    int bcur = 0;
+    for (int T = t_begin; T <= t_end; ++T) {
+      iteration(T, bcur);
+      bcur = bcur == 2 ? 0 : bcur + 1;
+    }
+  } else {
+    for (int T = t_begin;;) {
+      iteration(T, std::integral_constant<int, 0>{});
+      if (++T > t_end) break;
+      iteration(T, std::integral_constant<int, 1>{});
+      if (++T > t_end) break;
+      iteration(T, std::integral_constant<int, 2>{});
+      if (++T > t_end) break;
+    }
   }
   // the loads of the two tiles past the end still target this workgroup's LDS: let them land before the waves end
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -498,7 +519,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
 #pragma unroll
       for (int c = 0; c < 8; ++c)
         *reinterpret_cast<float4*>(op + 16 * c) = make_float4(oacc[c][qt][0], oacc[c][qt][1], oacc[c][qt][2], oacc[c][qt][3]);
-      if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(m_run[qt], l_tot);
+      if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(-neg_m[qt], l_tot);
     } else {
       const float inv = 1.0f / l_tot;
       uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * q;
