@@ -30,10 +30,10 @@ namespace isa {
 // not change inside the loop, and the description is computed without branches: it is built once per iteration by
 // every wave, in scalar instructions that the wave cannot overlap with its own MFMAs.
 struct STile {
-  uint32_t k_off;                           // bytes from the head's key base to row 0 of the block (token tiles) / tile (mean tiles)
+  uint32_t k_off;                           // bytes from the head's key base to the first row of the tile
   uint32_t v_off;                           // bytes from the head's V^T base to the 128 x 64 packed V^T of the tile
   int bias_off;                             // elements from the head's bias base (mean tiles only)
-  int row0, nk, last_row;
+  int nk, last_row;                         // real keys; last row that may be read (rows count from k_off)
   bool zero_v;                              // a tile past the end: V^T comes from the all-zero tile
 };
 
@@ -286,30 +286,12 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   const int n_q = active ? bn[qi] : 0;
   const int q_start = bs[qi];
 
-  // Tile idx of the sequence, built from the table row `ent` = {token offset, real tokens, block index} of its list
-  // entry (token tiles); idx >= t_end (past the end) gives a fully masked tile over valid memory.
+  // Tile idx of the sequence.  Token tiles come from the table row {token offset, real tokens, block index} of their
+  // list entry; idx >= t_end (past the end) gives a fully masked tile over valid memory.
   const int4* tab = a.dense ? a.btab + (long long)b * T_max : a.ktab + bh * T_max;
   // Every workgroup of a head walks the tile sequence from its start: the workgroups that run together on an XCD
   // then stream the same tiles at about the same time and share them in that XCD's L2 (measured: starting them at
   // spread-out points of the sequence multiplies the traffic behind the L2 and is slower).
-  // Table rows are fetched 64 at a time with one vector load (lane L holds the row of list position pbase + L)
-  // and handed out with readlane, so that no load other than the tile loads is in flight inside the loop.
-  int4 ecache = make_int4(0, 0, 0, 0);
-  int pbase = 0;
-  auto refill = [&](int p0) {
-    if (!taylor) {
-      ecache = tab[min(p0 + lane, n_list - 1)];
-      // consume the rows here, so that the wait for this (rare) load sits inside this branch and not at the
-      // loop-wide join, where it would also wait for the tile loads that were just issued
-      asm volatile("" : "+v"(ecache.x), "+v"(ecache.y), "+v"(ecache.z));
-    }
-    pbase = p0;
-  };
-  auto entry_of = [&](int idx) -> int4 {
-    const int l = (min(idx, t_end - 1) >> 1) - pbase;            // 0..63 by construction of the refills
-    return make_int4(__builtin_amdgcn_readlane(ecache.x, l), __builtin_amdgcn_readlane(ecache.y, l),
-                     __builtin_amdgcn_readlane(ecache.z, l), 0);
-  };
   // per-head bases of everything a tile description points into (mean tiles read the gathered bf16 means)
   const char* const k_head = taylor ? reinterpret_cast<const char*>(a.kcn + bh * a.Tn_pad * MD)
                                     : reinterpret_cast<const char*>(a.k + tbase);
@@ -317,16 +299,44 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
                                     : reinterpret_cast<const char*>(a.vt + bh * T_max * 2 * (long long)(MD * KT));
   const float* const bias_head = taylor ? a.biasn + bh * a.Tn_pad : nullptr;
   const uint32_t kstride_b = (uint32_t)(taylor ? MD : (int)a.geo.stride_t) * 2u;
-  auto make_tile = [&](int idx, int4 ent, STile& t) {
+  // The descriptions of 64 token tiles at a time are worked out by the 64 lanes in parallel (lane L: tile cbase + L)
+  // from one vector load of table rows, and handed out with readlane: no load other than the tile loads is in
+  // flight inside the loop, and the per-iteration scalar work is three readlanes and the clamps at the end.
+  uint32_t c_koff = 0, c_voff = 0;
+  int c_nk = 0, cbase = 0;
+  auto refill = [&](int t0) {
+    if constexpr (!taylor) {
+      const int idx = min(t0 + lane, n_tiles - 1), sub = idx & 1;
+      const int4 ent = tab[idx >> 1];
+      const int n_j = ent.y;
+      const bool empty = n_j <= sub * KT;                 // second tile of a short block: masked, reads the block's first rows
+      c_koff = (uint32_t)(ent.x + (empty ? 0 : sub * KT)) * kstride_b;
+      c_voff = ((uint32_t)ent.z * 2u + (uint32_t)sub) * (uint32_t)(MD * KT * 2);
+      c_nk = empty ? 0 : min(KT, n_j - sub * KT);
+      // consume the values here, so that the wait for this (rare) load sits inside this branch and not at the
+      // loop-wide join, where it would also wait for the tile loads that were just issued
+      asm volatile("" : "+v"(c_koff), "+v"(c_voff), "+v"(c_nk));
+    }
+    cbase = t0;
+  };
+  auto make_tile = [&](int idx, STile& t) {
     const bool past = idx >= t_end;
     idx = past ? t_end - 1 : idx;
-    const int sub = idx & 1, n_j = ent.y;
-    t.k_off = taylor ? (uint32_t)idx * (uint32_t)(KT * MD * 2) : (uint32_t)ent.x * kstride_b;
-    t.v_off = taylor ? (uint32_t)idx * (uint32_t)(MD * KT * 2) : ((uint32_t)ent.z * 2u + (uint32_t)sub) * (uint32_t)(MD * KT * 2);
-    t.bias_off = idx * KT;
-    t.row0 = taylor ? 0 : sub * KT;
-    t.nk = past ? 0 : taylor ? min(KT, n_list - idx * KT) : max(0, min(KT, n_j - sub * KT));
-    t.last_row = taylor ? KT - 1 : max(n_j - 1, 0);      // the gathered mean arrays are padded to whole tiles
+    if constexpr (taylor) {
+      t.k_off = (uint32_t)idx * (uint32_t)(KT * MD * 2);
+      t.v_off = (uint32_t)idx * (uint32_t)(MD * KT * 2);
+      t.bias_off = idx * KT;
+      t.nk = past ? 0 : min(KT, n_list - idx * KT);
+      t.last_row = KT - 1;                                // the gathered mean arrays are padded to whole tiles
+    } else {
+      const int l = idx - cbase;                          // 0..63 by construction of the refills
+      t.k_off = __builtin_amdgcn_readlane(c_koff, l);
+      t.v_off = __builtin_amdgcn_readlane(c_voff, l);
+      const int nk = __builtin_amdgcn_readlane(c_nk, l);
+      t.bias_off = 0;
+      t.nk = past ? 0 : nk;
+      t.last_row = max(nk - 1, 0);                        // rows are counted from the tile's first row
+    }
     t.zero_v = past;
   };
   auto bias_of = [&](const STile& t) -> const float* { return bias_head ? bias_head + t.bias_off : nullptr; };
@@ -371,7 +381,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     kchunk_b[i] = (uint32_t)((((lane & 15) ^ (krow_l[i] & 15)) * 8) * 2);
   }
   auto load_k1 = [&](const STile& t, int buf, int i) {
-    const int r = min(t.row0 + krow_l[i], t.last_row);
+    const int r = min(krow_l[i], t.last_row);
     lds_dma16(k_head + t.k_off, (uint32_t)r * kstride_b + kchunk_b[i],
               lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
   };
@@ -426,9 +436,9 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   // complete, T+1 in flight.  The buffers that are being filled were last read in iteration T-1, which every wave
   // has left once it is past this iteration's barrier.
   STile tprev, tcur, tnext, tnn;
-  refill(t_begin >> 1);
-  make_tile(t_begin, entry_of(t_begin), tcur);
-  make_tile(t_begin + 1, entry_of(t_begin + 1), tnext);
+  refill(t_begin);
+  make_tile(t_begin, tcur);
+  make_tile(t_begin + 1, tnext);
   tprev = tcur; tprev.nk = 0;
   load_k(tcur, 0);
   load_k(tnext, 1);
@@ -462,8 +472,8 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, neg_m, thr, alpha);
       half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, neg_m, thr, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
         if (f == 0) {
-          if (__builtin_expect((min(T + 2, t_end - 1) >> 1) >= pbase + 64, 0)) refill(pbase + 64);
-          make_tile(T + 2, entry_of(T + 2), tnn);
+          if (__builtin_expect(min(T + 2, t_end - 1) >= cbase + 64, 0)) refill(cbase + 64);
+          make_tile(T + 2, tnn);
         }
         if (f == 2) load_k1(tnn, bnn, 0);
         if (f == 3) load_k1(tnn, bnn, 1);
