@@ -17,9 +17,10 @@
 //
 // What bounds it (measured).  With real operands the 32x32x16 MFMA is limited by power: a stream of nothing but such
 // MFMAs runs at 2.4 PFLOP/s on constant operands and 1.8 on random ones, and a kernel built on it held 1.9 GHz; the
-// 16x16x32 shape moves fewer accumulator bytes per flop (2.0 PFLOP/s on random operands) and this kernel holds
-// 2.0 - 2.3 GHz with it, where the cycles count again.  Of those, about half are MFMA cycles; the rest is the other
-// work of the two waves of a SIMD, which overlaps the MFMAs only in part.
+// 16x16x32 shape moves fewer accumulator bytes per flop (2.0 PFLOP/s on random operands).  In this kernel the matrix
+// pipe of a SIMD is busy two thirds of the cycles and the vector issue port a little over half; the two waves of a
+// SIMD wait for each other the rest of the time, and every vector instruction taken out of the loop has shown up in
+// the run time, while scalar instructions, waits and barrier latency have not.
 #include <type_traits>
 
 #include "attn_mfma.h"
@@ -98,7 +99,7 @@ __device__ __forceinline__ float max_over_q(float x) {
 //   already raised): one weight (fma, exp2) per step, one bf16 pair converted every second step, into `pnew`;
 //   value MFMAs (steps 8..15) add V^T P^T of half g-2 (`pacc`, finished in the previous half step; V^T unit VU of the
 //   staged tile) to the output, and the 4x4x4 MFMAs its row sums.
-// exp2 runs at a quarter of the vector rate on this chip, so the 16 weights of a half have to be spread over all 16
+// exp2 runs at half the vector rate on this chip, so the 16 weights of a half have to be spread over all 16
 // steps: bunched behind the score MFMAs they made those steps vector-ALU bound while the value steps had nothing to do.
 // `tmax_out[qt]` is the scaled maximum of `sout` over the lane's own 8 keys of its query of tile qt, and `raise_out`
 // the ballot of the lanes in which it exceeds the running maximum by more than 2^tau (both valid when `sout` needs no
