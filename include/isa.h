@@ -157,6 +157,25 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
                const int32_t* kv_list, const int32_t* full_list, const int32_t* flat_list, const uint32_t* exact_mask,
                const float* o_coarse, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Backward pass of isa_attention / isa_attend (the paper states that the operator is trainable and gives no
+ * formulas, Sec. 4 "Implementation Detail and Analysis"): the gradient of Alg. 1 Stages 4-5 with respect to q, k and v
+ * with every index decision of Stages 2-3 held fixed (kept blocks, query groups: piecewise constant in the inputs),
+ * including the gradient through the block means of the Taylor branch (Eq. 4: a mean key's gradient is spread evenly
+ * over its block's tokens).
+ * q, k, v, out: as given to / written by the forward call; d_out: gradient of the loss with respect to `out`;
+ * dq, dk, dv: receive the gradients.  All seven are device bf16 tensors with the layout and strides of the problem;
+ * every row of dq, dk and dv is written (keys and values of context blocks that were not kept get zeros).
+ * kv_list, full_list, flat_list: the device lists the forward call ran with, or all three NULL for the lists that
+ * isa_attention left in the workspace.
+ * The workspace must be the one the forward call used, untouched since: it holds the log-sum-exp of every query row.
+ * Only for bf16, D = 128, block = 128 with exact_frac == 0 and gamma == 0, and only after a forward call that ran the
+ * MFMA kernels (ISA_ERR_UNSUPPORTED otherwise).  Asynchronous on hip_stream; fp32 accumulation, no atomics: results
+ * are reproducible run to run. */
+int isa_attention_backward(const isa_problem* p, const void* q, const void* k, const void* v, const void* out,
+                           const void* d_out, const int32_t* kv_list, const int32_t* full_list,
+                           const int32_t* flat_list, void* dq, void* dk, void* dv, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
 /* Name of a status code; never NULL. */
 const char* isa_strerror(int status);
 

@@ -48,6 +48,7 @@ struct MfmaArgs {
   int hpx, n_long;                          // k_attn_sp: (batch, head)s per XCD; exact-branch items per XCD (0 if none)
   int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges
   float* split_o; float* split_ml;          // their partial results: unnormalised outputs [sub-item][2][128][128], {max, sum} [sub-item][2][128][2]
+  float* nlse; int S_max;                   // k_attn_sp: minus the log-sum-exp (log2 domain) of every query row, [bh][S_max]; may be null
   int taylor_here;                          // k_attn_sp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only
 };
 

@@ -533,6 +533,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(-neg_m[qt], l_tot);
     } else {
       const float inv = 1.0f / l_tot;
+      if (a.nlse && q == 0) a.nlse[bh * a.S_max + q_start + row] = neg_m[qt] - __log2f(l_tot);
       uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * q;
       // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
       const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * q : nullptr;
@@ -596,6 +597,7 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
   }
   const float inv = 1.0f / l;
   const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
+  if (a.nlse && ch == 0) a.nlse[(long long)bhid * a.S_max + q_start + row] = -m - __log2f(l);
   acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
   if (a.ocoarse) {                                           // coarse residual, as in the attention kernel's own store
     const float4 c4 = *reinterpret_cast<const float4*>(a.ocoarse + ((long long)bhid * T_max + qi) * MD + ch);
@@ -624,6 +626,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   m.ocoarse = a.dense ? nullptr : a.ocoarse; m.gamma = a.gamma;
   m.geo = a.geo; m.cnt = a.cnt; m.dense = a.dense;
   m.Tn_pad = pr.Tn_pad;
+  m.nlse = a.dense ? nullptr : ws.nlse; m.S_max = pr.S_max;
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
   m.taylor_here = exact_sets ? 0 : 1;
   // pair slots per (batch, head): the largest counts over the batch

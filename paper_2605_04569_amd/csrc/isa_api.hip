@@ -73,6 +73,7 @@ int validate(const isa_problem* p, Problem* out) {
   // the MFMA kernels address a head's keys with 32-bit byte offsets: the tokens of one (batch, head) must span < 4 GiB
   long long S_max = 0;
   for (int b = 0; b < p->B; ++b) S_max = pr.cnt.b[b].S > S_max ? pr.cnt.b[b].S : S_max;
+  pr.S_max = (int)S_max;
   pr.mfma_shape = (p->dtype == ISA_BF16 && p->D == 128 && p->block == 128 &&
                    (unsigned long long)S_max * (unsigned long long)p->stride_t * 2ull < (1ull << 32));
   return ISA_OK;
@@ -116,7 +117,25 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->ktab = (int4*)take(B * H * T * 16);
     ws->split_o = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 128 * 4);
     ws->split_ml = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 2 * 4);
+    const size_t S = (size_t)pr.S_max, Tn = (size_t)pr.Tn_pad;
+    ws->nlse = (float*)take(B * H * S * 4);
+    ws->delta = (float*)take(B * H * S * 4);
+    ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
+    ws->kcnt = (uint16_t*)take(B * H * Tn * D * 2);
+    ws->dkc = (float*)take(B * H * Tn * D * 4);
+    ws->dvc = (float*)take(B * H * Tn * D * 4);
+    ws->ftab = (int4*)take(B * H * T * 16);
+    ws->ltab = (int4*)take(B * H * T * 16);
+    ws->ybd_kv = (float2*)take(B * H * T * 128 * 8);
+    ws->ybd_full = (float2*)take(B * H * T * 128 * 8);
+    ws->ybd_flat = (float2*)take(B * H * T * 128 * 8);
+    ws->ybd_mean = (float2*)take(B * H * Tn * 8);
+    ws->bx_mean = (float*)take(B * H * Tn * 4);
   } else {
+    ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
+    ws->vcn = ws->kcnt = nullptr;
+    ws->ftab = ws->ltab = nullptr;
+    ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
     ws->vt = ws->kcn = ws->vcnt = ws->vt4 = ws->vcnt4 = nullptr;
     ws->biasn = nullptr;
     ws->zero_tile = nullptr;
@@ -302,6 +321,31 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
   ISA_TRY(launch_layout(pr, ws, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1);
   return run_attend(pr, ws, a, v, false, st);
+}
+
+int isa_attention_backward(const isa_problem* p, const void* q, const void* k, const void* v, const void* out,
+                           const void* d_out, const int32_t* kv_list, const int32_t* full_list,
+                           const int32_t* flat_list, void* dq, void* dk, void* dv, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !out || !d_out || !dq || !dk || !dv) return ISA_ERR_NULL;
+  const int n_lists = (kv_list != nullptr) + (full_list != nullptr) + (flat_list != nullptr);
+  if (n_lists != 0 && n_lists != 3) return ISA_ERR_NULL;
+  if (!pr.mfma_shape || !g_use_mfma.load() || p->exact_frac > 0.0 || p->gamma != 0.0) return ISA_ERR_UNSUPPORTED;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (n_lists == 0) { kv_list = ws.kv_list; full_list = ws.full_list; flat_list = ws.flat_list; }
+  // block table and means are recomputed (cheap, and the staged forward takes its means from the caller); the
+  // log-sum-exp of every query row is what the forward call left in the workspace
+  ISA_TRY(launch_layout(pr, ws, st));
+  ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
+  ISA_TRY(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
+  ISA_TRY(launch_gather_means_bwd(pr, ws, ws.kc, ws.vc, kv_list, st));
+  ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, dq, dk, dv, st));
+  return ISA_OK;
 }
 
 int isa_attention_simple(const void* q, const void* k, const void* v, int H, int D, int n_src, int n_ctx,

@@ -61,6 +61,16 @@ struct Workspace {
   float* ocoarse;        // [B,H,T_max,D] pooled attention output (only carved when gamma != 0)
   float* split_o;        // partial outputs of work items split along the key sequence (at most 256 sub-items)
   float* split_ml;       // their running maxima and sums
+  // backward pass (MFMA path): what the forward leaves for it, and its own scratch
+  float* nlse;           // [B,H,S_max] minus the log-sum-exp of every query row, log2 domain (written by the forward)
+  float* delta;          // [B,H,S_max] rowsum(dO * O)
+  uint16_t* vcn;         // [B,H,Tn_pad][D]: mean values gathered in kv_list order (row-major, bf16)
+  uint16_t* kcnt;        // [B,H,Tn_pad/64][D][64]: mean keys gathered, transposed, key-permuted
+  float* dkc; float* dvc;             // [B,H,Tn_pad][D] gradients of the gathered mean keys / values
+  int4* ftab; int4* ltab;             // [B,H,T_max] table rows of the full-attention / Taylor blocks, in list order
+  float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128] {exponent term, delta} per row position of each list entry
+  float2* ybd_mean;      // [B,H,Tn_pad] the same per gathered mean key
+  float* bx_mean;        // [B,H,Tn_pad] log2(n_j) per gathered mean key
   size_t bytes;          // total size
 };
 
@@ -69,7 +79,7 @@ struct Problem {          // validated problem + everything derived from it
   SegDesc seg;
   Counts cnt;
   Geometry geo;
-  int Tsrc_max, Tctx_max, Tn_pad;
+  int Tsrc_max, Tctx_max, Tn_pad, S_max;
   bool mfma_shape;        // bf16, D = 128, block = 128
 };
 
@@ -106,5 +116,13 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st);
 hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st);
+// packed, transposed, key-permuted copy of a token tensor (the layout of Workspace::vt) into `dst`
+hipError_t launch_pack_t(const Problem& pr, const Workspace& ws, const void* src, uint16_t* dst, hipStream_t st);
+// mean values row-major and mean keys transposed (Workspace::vcn, kcnt), the mirror image of launch_gather_means
+hipError_t launch_gather_means_bwd(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
+                                   const int* kv_list, hipStream_t st);
+hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v,
+                           const void* out, const void* d_out, const int* kv_list, const int* full_list,
+                           const int* flat_list, void* dq, void* dk, void* dv, hipStream_t st);
 
 }  // namespace isa

@@ -1,0 +1,145 @@
+"""Parity of the HIP backward pass with the fp64 backward oracle (analytic gradient of the forward oracle with the
+index decisions frozen), on seeded inputs small enough for the oracle to evaluate every element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import isa_oracle_bwd as OB
+from util import f64, oracle_plan, problem_of
+
+pytestmark = pytest.mark.gpu
+
+# bf16, D=128, block=128: 5 full source blocks + a 20-token tail; two context references with tails
+SMALL = W.CONFIGS["cfg1"].with_(name="small_bf16", H=3, src_grid=(2, 10, 33), ctx_grids=(((1, 10, 33), (1, 9, 20)),),
+                                keep_ratio=0.5, full_frac=0.3, seed=77)
+# ragged batch of two items with different context layouts
+RAGGED = W.CONFIGS["cfg3"].with_(name="ragged_b2", H=2, src_grid=(2, 9, 17), ctx_grids=(((1, 3, 5), (2, 9, 17)), ((1, 9, 17),)),
+                                 keep_ratio=0.4, full_frac=0.35, seed=78)
+CASES = [SMALL, RAGGED,
+         SMALL.with_(name="all_exact_all_kept", keep_ratio=1.0, full_frac=1.0),
+         SMALL.with_(name="all_taylor", full_frac=0.0),
+         SMALL.with_(name="no_context_kept", keep_ratio=0.0, full_frac=0.5),
+         RAGGED.with_(name="ragged_one_exact_block", full_frac=0.1, keep_ratio=0.7)]
+
+# Gradients are compared relative to their own scale: the kernel rounds the weights P and dS to bf16 before the second
+# products (2^-9 relative each, thousands of terms with random signs), reads delta from the bf16 output and rounds the
+# result to bf16 (2^-9 of the value): a few 2^-9 of the largest gradient entry as the bound on any entry, and a
+# fraction of that on average.
+TOL_MAX_REL, TOL_MEAN_REL = 1.5e-2, 2.5e-3
+
+
+@pytest.fixture(scope="module")
+def I():
+    import paper_2605_04569_amd as isa
+    isa.lib()
+    return isa
+
+
+def _inputs(wl):
+    Q, K, V = W.make_inputs(wl, "cpu")
+    g = torch.Generator().manual_seed(wl.seed + 1000)
+    dO = torch.randn(Q.shape, generator=g, dtype=torch.float32).to(Q.dtype)
+    return Q, K, V, dO
+
+
+def _lists(I, wl, pr, Q, K, V):
+    T_max = I.isa_get_counts(pr, 0)["T_max"]
+    i32 = dict(device="cuda", dtype=torch.int32)
+    f32 = dict(device="cuda", dtype=torch.float32)
+    buf = dict(kv=torch.full((wl.B, wl.H, T_max), -1, **i32), full=torch.full((wl.B, wl.H, T_max), -1, **i32),
+               flat=torch.full((wl.B, wl.H, T_max), -1, **i32),
+               kc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32), vc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32))
+    plans = {}
+    for b in range(wl.B):
+        c = I.isa_get_counts(pr, b)
+        for h in range(wl.H):
+            plan = plans[b, h] = oracle_plan(wl, Q, K, V, b, h)
+            T = plan["T"]
+            buf["kc"][b, h, :T] = torch.from_numpy(plan["Kc"]).float()
+            buf["vc"][b, h, :T] = torch.from_numpy(plan["Vc"]).float()
+            buf["kv"][b, h, :c["T_new"]] = torch.from_numpy(np.asarray(plan["kv_list"])).int()
+            buf["full"][b, h, :c["n_full"]] = torch.from_numpy(np.asarray(plan["full_list"])).int()
+            buf["flat"][b, h, :c["n_flat"]] = torch.from_numpy(np.asarray(plan["flat_list"])).int()
+    return buf, plans
+
+
+def _compare(wl, Q, K, V, dO, plans, dq, dk, dv):
+    worst = {}
+    for b in range(wl.B):
+        n = wl.tokens(b)
+        for h in range(wl.H):
+            want = OB.isa_attention_bwd(f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n]), f64(dO[b, h, :n]), plans[b, h])
+            for name, got_t, w in zip(("dQ", "dK", "dV"), (dq, dk, dv), want):
+                got = f64(got_t[b, h, :n])
+                assert np.isfinite(got).all(), (wl.name, name, b, h)
+                scale = np.abs(w).max()
+                err = np.abs(got - w)
+                rel_max, rel_mean = err.max() / scale, err.mean() / scale
+                worst[name] = max(worst.get(name, 0.0), rel_max)
+                assert rel_max <= TOL_MAX_REL and rel_mean <= TOL_MEAN_REL, (wl.name, name, b, h, rel_max, rel_mean)
+        if n < dq.shape[2]:
+            for t in (dq, dk, dv):
+                assert torch.isnan(t[b, :, n:]).all()             # rows past the batch item's end are untouched
+    print(f"\n[backward] {wl.name}: worst max-abs error / max|grad|: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()),
+          flush=True)
+
+
+@pytest.mark.parametrize("wl", CASES, ids=[c.name for c in CASES])
+def test_backward_on_oracle_lists(I, wl):
+    Q, K, V, dO = _inputs(wl)
+    q, k, v, d_out = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    buf, plans = _lists(I, wl, pr, Q, K, V)
+    out = torch.full_like(q, float("nan"))
+    print(f"\n[backward] case {wl.name}: forward on the oracle's lists", flush=True)
+    I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], None, out, ws)
+    torch.cuda.synchronize()
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    print(f"[backward] case {wl.name}: backward", flush=True)
+    I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws, buf["kv"], buf["full"], buf["flat"])
+    torch.cuda.synchronize()
+    _compare(wl, Q, K, V, dO, plans, dq, dk, dv)
+    # kept-out context blocks get exact zeros
+    for b in range(wl.B):
+        for h in range(wl.H):
+            plan = plans[b, h]
+            kept = set(int(j) for j in plan["kv_list"])
+            for j in range(plan["T"]):
+                if j not in kept:
+                    rows = slice(int(plan["starts"][j]), int(plan["starts"][j] + plan["counts"][j]))
+                    assert (dk[b, h, rows] == 0).all() and (dv[b, h, rows] == 0).all(), (b, h, j)
+
+
+def test_backward_after_the_whole_call_and_reproducible(I):
+    """isa_attention leaves lists and log-sum-exps in the workspace; the backward call with NULL lists uses them.  Two
+    runs give bit-identical gradients (no atomics)."""
+    wl = SMALL
+    Q, K, V, dO = _inputs(wl)
+    q, k, v, d_out = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    _, plans = _lists(I, wl, pr, Q, K, V)
+    out = torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, out, ws)
+    grads = []
+    for _ in range(2):
+        dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+        I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws)
+        torch.cuda.synchronize()
+        grads.append((dq, dk, dv))
+    for a, b in zip(*grads):
+        assert torch.equal(a, b)
+    _compare(wl, Q, K, V, dO, plans, *grads[0])          # the GPU's own lists equal the oracle's on this input
+
+
+def test_backward_rejects_what_it_does_not_cover(I):
+    wl = SMALL
+    Q, K, V, dO = _inputs(wl)
+    q = Q.cuda()
+    for kw in (dict(exact_frac=0.25), dict(gamma=0.5)):
+        pr = problem_of(wl.with_(**kw))
+        ws = I.new_workspace(pr)
+        with pytest.raises(I.IsaError):
+            I.isa_attention_backward(pr, q, q, q, q, q, torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), ws)
