@@ -92,7 +92,7 @@ def measured_traffic(workload):
     return None
 
 
-def measure(wl, steps, warmup, dense_steps):
+def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
     """Times isa_attention (whole call and the attention kernel alone) and dense attention on one workload."""
     import numpy as np
     import torch
@@ -153,6 +153,24 @@ def measure(wl, steps, warmup, dense_steps):
     full_fl, taylor_fl, dense_fl = algorithmic_flops(wl, isa, pr, (kv.cpu().numpy(), full.cpu().numpy(), blk_n))
     isa_fl = full_fl + taylor_fl
 
+    # ---- backward pass (right after a forward call: the workspace holds its lists and log-sum-exps) -------------
+    bwd_ms = None
+    if bwd_steps > 0 and wl.exact_frac == 0 and wl.gamma == 0 and wl.dtype == "bf16" and wl.D == 128 and wl.block == 128:
+        g = torch.Generator(device="cuda").manual_seed(wl.seed + 1000)
+        d_out = torch.randn(Q.shape, generator=g, device="cuda", dtype=torch.float32).to(Q.dtype)
+        dq, dk, dv = (torch.empty_like(Q) for _ in range(3))
+        isa.isa_attention(pr, Q, K, V, out, ws)
+        isa.isa_attention_backward(pr, Q, K, V, out, d_out, dq, dk, dv, ws)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(bwd_steps):
+            isa.isa_attention_backward(pr, Q, K, V, out, d_out, dq, dk, dv, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        bwd_ms = e0.elapsed_time(e1) / bwd_steps
+        del d_out, dq, dk, dv
+        log("isa_attention_backward: %.3f ms per call" % bwd_ms)
+
     # ---- dense attention at the same shape --------------------------------------------------------
     dense_ms = None
     if dense_steps > 0:
@@ -170,7 +188,7 @@ def measure(wl, steps, warmup, dense_steps):
 
     del out, ws
     return {"ms_per_step": ms_per_step, "kern_ms": kern_ms, "kern_ms_min": float(np.min(kernel_ms)),
-            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
+            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "bwd_ms": bwd_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
             "inputs": (Q, K, V)}
 
 
@@ -181,6 +199,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 (480p, default) | cfg3 | cfg4 (720p)")
     ap.add_argument("--dense-steps", type=int, default=3)
+    ap.add_argument("--bwd-steps", type=int, default=3, help="timed calls of the backward pass on the main workload (0 = skip)")
     ap.add_argument("--exact-frac", type=float, default=None)
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--full-frac", type=float, default=None)
@@ -209,11 +228,12 @@ def main():
                               ("full_frac", args.full_frac), ("gamma", args.gamma)) if v is not None}
     if over:
         wl = wl.with_(**over)
-    r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps)
+    r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps, args.bwd_steps)
     ms_per_step, kern_ms, dense_ms = r["ms_per_step"], r["kern_ms"], r["dense_ms"]
     kern_ms_min, kern_ms_median = r["kern_ms_min"], r["kern_ms_median"]
     isa_fl, dense_fl = r["isa_fl"], r["dense_fl"]
     Q, K, V = r["inputs"]
+    r_bwd_ms = r["bwd_ms"]
 
     log("CPU oracle sample ...")
     cpu = None if args.no_cpu else cpu_baseline(wl, Q, K, V)
@@ -269,6 +289,13 @@ def main():
                      "kernel_ms_min": round(kern_ms_min, 4), "kernel_ms_median": round(kern_ms_median, 4),
                      "algorithmic_tflop_per_launch": round(isa_fl / 1e12, 3),
                      "traffic": measured_traffic(wl.name) if not over else None},
+        # backward: 5 matrix products per (query, key) pair where the forward has 2 (algorithmic); the kernels execute 8
+        # (scores and dP are recomputed by the dQ, dK and dV launches instead of being exchanged through atomics)
+        "backward": None if r_bwd_ms is None else {
+            "ms_per_call": round(r_bwd_ms, 3), "algorithmic_tflop": round(2.5 * isa_fl / 1e12, 3),
+            "effective_tflops": round(2.5 * isa_fl / (r_bwd_ms * 1e-3) / 1e12, 1),
+            "executed_tflops": round(4.0 * isa_fl / (r_bwd_ms * 1e-3) / 1e12, 1),
+            "frac_of_mfma_peak_algorithmic": round(2.5 * isa_fl / (r_bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
         "cpu_baseline": cpu,
         "other_workloads": others,
         "paper_context": "paper reports ~60% lower attention-module latency vs SDPA/FlashAttention (GPU not stated; Hopper implied)",

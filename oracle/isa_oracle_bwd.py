@@ -58,8 +58,10 @@ def exact_blocks_of(plan, i):
     return O.exact_set(plan["Z"][i], plan["kv_list"], O.exact_count(plan["exact_frac"], len(plan["kv_list"])))
 
 
-def isa_attention_bwd(Q, K, V, dO, plan):
-    """Gradient of forward_with_fixed_indices with respect to Q, K, V, contracted with dO.  Returns (dQ, dK, dV)."""
+def isa_attention_bwd(Q, K, V, dO, plan, query_blocks=None):
+    """Gradient of forward_with_fixed_indices with respect to Q, K, V, contracted with dO.  Returns (dQ, dK, dV).
+    `query_blocks` restricts the sum to the given query blocks (the gradient is a sum of per-query-block terms): the
+    result is then the gradient for a dO that is zero on all other blocks, whatever dO holds there."""
     Q, K, V, dO = (np.asarray(x, dtype=np.float64) for x in (Q, K, V, dO))
     starts, counts, T = plan["starts"], plan["counts"], plan["T"]
     D = Q.shape[1]
@@ -77,7 +79,7 @@ def isa_attention_bwd(Q, K, V, dO, plan):
             return np.zeros(0, dtype=np.int64)
         return np.concatenate([np.arange(starts[j], starts[j] + counts[j]) for j in blocks])
 
-    for i in range(T):
+    for i in (range(T) if query_blocks is None else query_blocks):
         rows = slice(starts[i], starts[i] + counts[i])
         q, do = Q[rows], dO[rows]
         if gamma != 0.0:

@@ -60,13 +60,18 @@ struct BwdArgs {
   int Tn_pad, S_max;
   int stat_kind;                              // token rows: 0 full-attention blocks, 1 Taylor blocks, 2 kept blocks
   int stream_kind;                            // token tiles: 0 kept blocks, 1 full-attention blocks, 2 Taylor blocks
+  int items;                                  // work items (pairs of stationary blocks) per (batch, head) in this launch
 };
 
 // SM: stationary rows are block means; YM: streamed rows are block means; T2: W = P * (T2 - delta), else W = P.
 template <bool SM, bool YM, bool T2>
 __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * STAGE + 2 * SIDE_BYTES / 2];
-  const int item = blockIdx.x, bhid = blockIdx.y;
+  // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
+  // head after the other, so that the workgroups that run together on an XCD (and share its L2) stream the same rows.
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int item = jj % a.items, bhid = (jj / a.items) * 8 + xcd;
+  if (bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const int T_new = a.cnt.b[b].T_new, n_full = a.cnt.b[b].n_full, n_flat = a.cnt.b[b].n_flat;
   const int T_max = a.geo.T_max;
@@ -393,13 +398,15 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   if (sf > 0) {
     a.stat_list = full_list; a.stat_kind = 0;
     a.y1 = K; a.y2 = V; a.yt = ws.vt; a.ytab = ws.ktab; a.ybd = ws.ybd_kv; a.stream_kind = 0;
-    hipLaunchKernelGGL((k_attn_bwd<false, false, true>), dim3((sf + 1) / 2, B * H), dim3(512), 0, st, a);
+    a.items = (sf + 1) / 2;
+    hipLaunchKernelGGL((k_attn_bwd<false, false, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
     ISA_BWD_CHECK();
   }
   if (sl > 0) {
     a.stat_list = flat_list; a.stat_kind = 1;
     a.y1 = ws.kcn; a.y2 = ws.vcn; a.yt = ws.kcnt; a.ytab = nullptr; a.ybd = ws.ybd_mean; a.stream_kind = 0;
-    hipLaunchKernelGGL((k_attn_bwd<false, true, true>), dim3((sl + 1) / 2, B * H), dim3(512), 0, st, a);
+    a.items = (sl + 1) / 2;
+    hipLaunchKernelGGL((k_attn_bwd<false, true, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
     ISA_BWD_CHECK();
   }
 
@@ -411,13 +418,16 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.x1 = ws.kcn; a.x2 = ws.vcn; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
     a.ytab = ws.ltab; a.ybd = ws.ybd_flat; a.stream_kind = 2;
     a.out_bf = nullptr; a.out_f32 = ws.dkc; a.add_rows = nullptr; a.oscale = scale;
-    hipLaunchKernelGGL((k_attn_bwd<true, false, true>), dim3(n_mean_pairs, B * H), dim3(512), 0, st, a);
+    a.items = n_mean_pairs;
+    hipLaunchKernelGGL((k_attn_bwd<true, false, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
     ISA_BWD_CHECK();
   }
   a.x1 = K; a.x2 = V; a.stat_list = kv_list; a.stat_kind = 2; a.bx = nullptr;
   a.ytab = ws.ftab; a.ybd = ws.ybd_full; a.stream_kind = 1;
   a.out_bf = (uint16_t*)dk; a.out_f32 = nullptr; a.add_rows = sl > 0 ? ws.dkc : nullptr; a.oscale = scale;
-  hipLaunchKernelGGL((k_attn_bwd<false, false, true>), dim3((sk + 1) / 2, B * H), dim3(512), 0, st, a);
+  a.items = (sk + 1) / 2;
+  if (a.items > 0)
+    hipLaunchKernelGGL((k_attn_bwd<false, false, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
   ISA_BWD_CHECK();
 
   // ---- dVc and dV (streamed Q, dO^T packed)
@@ -427,13 +437,16 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.x1 = ws.kcn; a.x2 = nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
     a.ytab = ws.ltab; a.ybd = ws.ybd_flat; a.stream_kind = 2;
     a.out_bf = nullptr; a.out_f32 = ws.dvc; a.add_rows = nullptr; a.oscale = 1.0f;
-    hipLaunchKernelGGL((k_attn_bwd<true, false, false>), dim3(n_mean_pairs, B * H), dim3(512), 0, st, a);
+    a.items = n_mean_pairs;
+    hipLaunchKernelGGL((k_attn_bwd<true, false, false>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
     ISA_BWD_CHECK();
   }
   a.x1 = K; a.x2 = nullptr; a.stat_list = kv_list; a.stat_kind = 2; a.bx = nullptr;
   a.ytab = ws.ftab; a.ybd = ws.ybd_full; a.stream_kind = 1;
   a.out_bf = (uint16_t*)dv; a.out_f32 = nullptr; a.add_rows = sl > 0 ? ws.dvc : nullptr; a.oscale = 1.0f;
-  hipLaunchKernelGGL((k_attn_bwd<false, false, false>), dim3((sk + 1) / 2, B * H), dim3(512), 0, st, a);
+  a.items = (sk + 1) / 2;
+  if (a.items > 0)
+    hipLaunchKernelGGL((k_attn_bwd<false, false, false>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
   ISA_BWD_CHECK();
 #undef ISA_BWD_CHECK
   return hipSuccess;

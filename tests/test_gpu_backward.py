@@ -143,3 +143,78 @@ def test_backward_rejects_what_it_does_not_cover(I):
         ws = I.new_workspace(pr)
         with pytest.raises(I.IsaError):
             I.isa_attention_backward(pr, q, q, q, q, q, torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), ws)
+
+
+# ------------------------------------------------------------------------------------------------
+# full size, in the launch configuration the bench times
+# ------------------------------------------------------------------------------------------------
+def _full_size_sampled(I, wl, b, h, seed, last_full=1):
+    """The whole forward call, then the backward call for a dO that is non-zero only on a few query blocks of one head
+    (the gradient is a sum over query blocks, so the oracle then has to evaluate only those): dQ of the sampled blocks
+    and the whole dK, dV of the head against the oracle run on the lists the GPU chose; everything else exactly zero."""
+    from oracle import isa_oracle as O
+    q, k, v = W.make_inputs(wl, "cuda")
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    out = torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, out, ws)
+    # the lists it chose, read back through the staged entry points (same kernels, same inputs -> same lists)
+    T_max = I.isa_get_counts(pr, 0)["T_max"]
+    f32 = dict(device="cuda", dtype=torch.float32)
+    qc, kc, vc = (torch.zeros((wl.B, wl.H, T_max, wl.D), **f32) for _ in range(3))
+    s_ctx, sharp = torch.zeros((wl.B, wl.H, T_max), **f32), torch.zeros((wl.B, wl.H, T_max), **f32)
+    kv_g, full_g, flat_g = (torch.zeros((wl.B, wl.H, T_max), device="cuda", dtype=torch.int32) for _ in range(3))
+    I.isa_block_means(pr, q, k, v, qc, kc, vc, ws)
+    I.isa_coarse_scores(pr, qc, kc, s_ctx, sharp, None, ws)
+    I.isa_select(pr, s_ctx, sharp, None, kv_g, full_g, flat_g, None, ws)
+    torch.cuda.synchronize()
+    del qc, kc, vc
+    c = I.isa_get_counts(pr, b)
+    n = wl.tokens(b)
+    kv = kv_g[b, h, :c["T_new"]].cpu().numpy()
+    full = full_g[b, h, :c["n_full"]].cpu().numpy()
+    flat = flat_g[b, h, :c["n_flat"]].cpu().numpy()
+    Qh, Kh, Vh = f64(q[b, h, :n]), f64(k[b, h, :n]), f64(v[b, h, :n])
+    plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(b), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac, wl.gamma)
+    plan["kv_list"], plan["full_list"], plan["flat_list"] = kv, full, flat          # the oracle runs on the GPU's lists
+    rng = np.random.default_rng(seed)
+    pick = sorted(set(rng.choice(full, min(2, len(full)), replace=False).tolist()) |
+                  set(full[len(full) - min(len(full), last_full):].tolist()) |
+                  set(rng.choice(flat, min(2, len(flat)), replace=False).tolist()))
+    d_out = torch.zeros_like(q)
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    for i in pick:
+        s0, cnt = int(plan["starts"][i]), int(plan["counts"][i])
+        d_out[b, h, s0:s0 + cnt] = torch.randn((cnt, wl.D), generator=g, device="cuda").to(q.dtype)
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    print(f"\n[backward] {wl.name}: backward call, sampled blocks {pick} of batch {b} head {h}", flush=True)
+    I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    want = OB.isa_attention_bwd(Qh, Kh, Vh, f64(d_out[b, h, :n]), plan, query_blocks=pick)
+    for name, got_t, w in zip(("dQ", "dK", "dV"), (dq, dk, dv), want):
+        got = f64(got_t[b, h, :n])
+        assert np.isfinite(got).all(), name
+        scale = np.abs(w).max()
+        err = np.abs(got - w)
+        print(f"[backward] {wl.name} {name}: max-abs error / max|grad| {err.max() / scale:.2e}, mean {err.mean() / scale:.2e}", flush=True)
+        assert err.max() / scale <= TOL_MAX_REL and err.mean() / scale <= TOL_MEAN_REL, (name, err.max() / scale, err.mean() / scale)
+    # no gradient where dO is zero: the other query blocks of this head, and every other head
+    mask = torch.ones(n, dtype=torch.bool, device="cuda")
+    for i in pick:
+        mask[int(plan["starts"][i]):int(plan["starts"][i] + plan["counts"][i])] = False
+    assert (dq[b, h, :n][mask] == 0).all()
+    for t in (dq, dk, dv):
+        for bb in range(wl.B):
+            nb = wl.tokens(bb)
+            other = [hh for hh in range(wl.H) if not (bb == b and hh == h)]
+            assert (t[bb, other, :nb] == 0).all()
+
+
+def test_backward_full_size_480p_sampled(I):
+    """cfg2, head 4: its last exact-branch pair is one of the forward launch's split work items (log-sum-exp written by
+    the merge kernel)."""
+    _full_size_sampled(I, W.CONFIGS["cfg2"], 0, 4, seed=21)
+
+
+def test_backward_full_size_ragged_batch_sampled(I):
+    _full_size_sampled(I, W.CONFIGS["cfg3"].with_(keep_ratio=0.25, full_frac=0.1), 1, 5, seed=22)

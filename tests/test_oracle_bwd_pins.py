@@ -104,3 +104,21 @@ def test_taylor_mean_gradient_is_shared_evenly_inside_a_block():
         rows = slice(plan["starts"][j], plan["starts"][j] + plan["counts"][j])
         np.testing.assert_allclose(dK[rows], np.tile(dK[rows][:1], (plan["counts"][j], 1)), atol=1e-14)
         np.testing.assert_allclose(dV[rows], np.tile(dV[rows][:1], (plan["counts"][j], 1)), atol=1e-14)
+
+
+def test_restriction_to_query_blocks_is_the_gradient_for_a_masked_dO():
+    """The query_blocks argument only drops terms of the sum over query blocks: same result as zeroing dO elsewhere."""
+    rng = np.random.default_rng(11)
+    seg, block, D = [70, 45], 16, 8
+    S = sum(seg)
+    Q, K, V, dO = (rng.standard_normal((S, D)) for _ in range(4))
+    plan = O.isa_plan(Q, K, V, seg, block, 0.5, 0.4, 0.0, 0.0)
+    pick = [int(plan["full_list"][0]), int(plan["flat_list"][-1])]
+    masked = np.zeros_like(dO)
+    for i in pick:
+        rows = slice(plan["starts"][i], plan["starts"][i] + plan["counts"][i])
+        masked[rows] = dO[rows]
+    a = B.isa_attention_bwd(Q, K, V, dO, plan, query_blocks=pick)
+    b = B.isa_attention_bwd(Q, K, V, masked, plan)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, rtol=0, atol=1e-13)
