@@ -297,19 +297,25 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   }
 }
 
-// delta[bh][token] = sum_d dO * O (fp32), one wave per token row.
+// delta[bh][token] = sum_d dO * O (fp32); 16 lanes per token row, 16 bytes per lane and tensor.
 __global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ o, const uint16_t* __restrict__ d_o,
                                                    float* __restrict__ delta, Geometry g, Counts cnt, int S_max) {
   const int h = blockIdx.y, b = blockIdx.z;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (t >= cnt.b[b].S) return;
-  const long long off = (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)t * g.stride_t + 2 * lane;
-  const uint32_t uo = *reinterpret_cast<const uint32_t*>(o + off), ud = *reinterpret_cast<const uint32_t*>(d_o + off);
-  float s = __uint_as_float(uo << 16) * __uint_as_float(ud << 16) +
-            __uint_as_float(uo & 0xffff0000u) * __uint_as_float(ud & 0xffff0000u);
+  const int t = blockIdx.x * 16 + (threadIdx.x >> 4), c16 = threadIdx.x & 15;
+  const bool ok = t < cnt.b[b].S;
+  float s = 0.f;
+  if (ok) {
+    const long long off = (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)t * g.stride_t + 8 * c16;
+    const uint4 uo = *reinterpret_cast<const uint4*>(o + off), ud = *reinterpret_cast<const uint4*>(d_o + off);
+    const uint32_t wo[4] = {uo.x, uo.y, uo.z, uo.w}, wd[4] = {ud.x, ud.y, ud.z, ud.w};
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
-  if (lane == 0) delta[((long long)b * g.H + h) * S_max + t] = s;
+    for (int i = 0; i < 4; ++i)
+      s += __uint_as_float(wo[i] << 16) * __uint_as_float(wd[i] << 16) +
+           __uint_as_float(wo[i] & 0xffff0000u) * __uint_as_float(wd[i] & 0xffff0000u);
+  }
+#pragma unroll
+  for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
+  if (ok && c16 == 0) delta[((long long)b * g.H + h) * S_max + t] = s;
 }
 
 // Per list entry: the table row of its block and the {exponent term, delta} pair of each of its 128 row positions
@@ -369,7 +375,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     if (e__ != hipSuccess) return e__;            \
   } while (0)
   // delta, zero fill, per-list tables and row terms
-  hipLaunchKernelGGL(k_bwd_delta, dim3((S_max + 3) / 4, H, B), dim3(256), 0, st, (const uint16_t*)out,
+  hipLaunchKernelGGL(k_bwd_delta, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (const uint16_t*)out,
                      (const uint16_t*)d_out, ws.delta, pr.geo, pr.cnt, S_max);
   ISA_BWD_CHECK();
   hipLaunchKernelGGL(k_bwd_zero, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (uint16_t*)dk, pr.geo, pr.cnt);
