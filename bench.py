@@ -154,7 +154,7 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
     isa_fl = full_fl + taylor_fl
 
     # ---- backward pass (right after a forward call: the workspace holds its lists and log-sum-exps) -------------
-    bwd_ms = None
+    bwd_ms = dense_bwd_ms = None
     if bwd_steps > 0 and wl.exact_frac == 0 and wl.gamma == 0 and wl.dtype == "bf16" and wl.D == 128 and wl.block == 128:
         g = torch.Generator(device="cuda").manual_seed(wl.seed + 1000)
         d_out = torch.randn(Q.shape, generator=g, device="cuda", dtype=torch.float32).to(Q.dtype)
@@ -168,8 +168,22 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
         e1.record()
         torch.cuda.synchronize()
         bwd_ms = e0.elapsed_time(e1) / bwd_steps
-        del d_out, dq, dk, dv
         log("isa_attention_backward: %.3f ms per call" % bwd_ms)
+        # the same backward kernels with nothing pruned and every query block exact = dense attention's backward
+        if dense_steps > 0:
+            pr_d = isa.Problem(H=wl.H, D=wl.D, dtype=wl.dtype, block=wl.block, seg_len=[wl.seg_len(b) for b in range(wl.B)],
+                               keep_ratio=1.0, full_frac=1.0, exact_frac=0.0, gamma=0.0)
+            ws_d = isa.new_workspace(pr_d)
+            isa.isa_attention(pr_d, Q, K, V, out, ws_d)
+            torch.cuda.synchronize()
+            e0.record()
+            isa.isa_attention_backward(pr_d, Q, K, V, out, d_out, dq, dk, dv, ws_d)
+            e1.record()
+            torch.cuda.synchronize()
+            dense_bwd_ms = e0.elapsed_time(e1)
+            del ws_d
+            log("dense attention backward: %.3f ms per call" % dense_bwd_ms)
+        del d_out, dq, dk, dv
 
     # ---- dense attention at the same shape --------------------------------------------------------
     dense_ms = None
@@ -188,7 +202,7 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
 
     del out, ws
     return {"ms_per_step": ms_per_step, "kern_ms": kern_ms, "kern_ms_min": float(np.min(kernel_ms)),
-            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "bwd_ms": bwd_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
+            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "bwd_ms": bwd_ms, "dense_bwd_ms": dense_bwd_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
             "inputs": (Q, K, V)}
 
 
@@ -238,6 +252,7 @@ def main():
     log("CPU oracle sample ...")
     cpu = None if args.no_cpu else cpu_baseline(wl, Q, K, V)
 
+    r_dense_bwd = r["dense_bwd_ms"]
     del Q, K, V, r
     torch.cuda.empty_cache()
     others = []
@@ -295,7 +310,9 @@ def main():
             "ms_per_call": round(r_bwd_ms, 3), "algorithmic_tflop": round(2.5 * isa_fl / 1e12, 3),
             "effective_tflops": round(2.5 * isa_fl / (r_bwd_ms * 1e-3) / 1e12, 1),
             "executed_tflops": round(4.0 * isa_fl / (r_bwd_ms * 1e-3) / 1e12, 1),
-            "frac_of_mfma_peak_algorithmic": round(2.5 * isa_fl / (r_bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+            "frac_of_mfma_peak_algorithmic": round(2.5 * isa_fl / (r_bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "dense_backward_ms_per_call": None if r_dense_bwd is None else round(r_dense_bwd, 3),
+            "speedup_vs_dense_backward": None if r_dense_bwd is None else round(r_dense_bwd / r_bwd_ms, 3)},
         "cpu_baseline": cpu,
         "other_workloads": others,
         "paper_context": "paper reports ~60% lower attention-module latency vs SDPA/FlashAttention (GPU not stated; Hopper implied)",
