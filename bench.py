@@ -155,7 +155,7 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
 
     # ---- backward pass (right after a forward call: the workspace holds its lists and log-sum-exps) -------------
     bwd_ms = dense_bwd_ms = None
-    if bwd_steps > 0 and wl.exact_frac == 0 and wl.gamma == 0 and wl.dtype == "bf16" and wl.D == 128 and wl.block == 128:
+    if bwd_steps > 0 and wl.gamma == 0 and wl.dtype == "bf16" and wl.D == 128 and wl.block == 128:
         g = torch.Generator(device="cuda").manual_seed(wl.seed + 1000)
         d_out = torch.randn(Q.shape, generator=g, device="cuda", dtype=torch.float32).to(Q.dtype)
         dq, dk, dv = (torch.empty_like(Q) for _ in range(3))
@@ -265,13 +265,15 @@ def main():
             continue
         else:
             o_wl, label = W.CONFIGS[name], name
-        o = measure(o_wl, 5, 2, 0 if args.no_dense else 2)
+        o = measure(o_wl, 5, 2, 0 if args.no_dense else 2, min(args.bwd_steps, 2))
         others.append({"workload": label, "tokens": [o_wl.tokens(b) for b in range(o_wl.B)],
                        "isa_ms_per_call": round(o["ms_per_step"], 3), "kernel_ms": round(o["kern_ms"], 3),
                        "kernel_tflops": round(o["isa_fl"] / (o["kern_ms"] * 1e-3) / 1e12, 1),
                        "dense_ms_per_call": None if o["dense_ms"] is None else round(o["dense_ms"], 3),
                        "dense_tflops": None if o["dense_ms"] is None else round(o["dense_fl"] / (o["dense_ms"] * 1e-3) / 1e12, 1),
                        "speedup_vs_dense": None if o["dense_ms"] is None else round(o["dense_ms"] / o["ms_per_step"], 3),
+                       "backward_ms_per_call": None if o["bwd_ms"] is None else round(o["bwd_ms"], 3),
+                       "dense_backward_ms_per_call": None if o["dense_bwd_ms"] is None else round(o["dense_bwd_ms"], 3),
                        "steps": 5})
         del o
         torch.cuda.empty_cache()

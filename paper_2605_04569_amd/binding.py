@@ -61,7 +61,7 @@ def lib():
         L.isa_select.argtypes = [P, V, V, V, V, V, V, V, V, SZ, ST]
         L.isa_coarse_output.argtypes = [P, V, V, V, V, V, SZ, ST]
         L.isa_attend.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
-        L.isa_attention_backward.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
+        L.isa_attention_backward.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
         L.isa_strerror.argtypes = [C.c_int]
         L.isa_strerror.restype = C.c_char_p
         L.isa_last_hip_error.argtypes = []
@@ -228,10 +228,11 @@ def isa_attend(pr: Problem, q, k, v, kc, vc, kv_list, full_list, flat_list, exac
 
 
 def isa_attention_backward(pr: Problem, q, k, v, out, d_out, dq, dk, dv, workspace, kv_list=None, full_list=None,
-                           flat_list=None):
+                           flat_list=None, exact_mask=None):
     _same_layout(q, k, v, out, d_out, dq, dk, dv)
     cp, keep = pr.c_struct(q)
     _check(lib().isa_attention_backward(C.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(d_out), _ptr(kv_list),
-                                        _ptr(full_list), _ptr(flat_list), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
+                                        _ptr(full_list), _ptr(flat_list), _ptr(exact_mask), _ptr(dq), _ptr(dk), _ptr(dv),
+                                        _ptr(workspace),
                                         workspace.numel(), _stream()), "isa_attention_backward")
     return dq, dk, dv

@@ -36,21 +36,39 @@ __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff_bytes, ui
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
 }
+// A pointer that is wave-uniform by construction, moved to scalar registers explicitly.
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const uint64_t u = (uint64_t)(uintptr_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return reinterpret_cast<const char*>((uintptr_t)(((uint64_t)hi << 32) | lo));
+}
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
 }  // namespace
 
+// One phase of the streamed side of a launch: token tiles of the blocks of a list, or tiles of gathered block means.
+struct BwdStream {
+  const uint16_t* y1; const uint16_t* y2; const uint16_t* yt;   // row-major (scores), row-major (dP; unused without dS), packed transposed
+  const int4* tab;                            // token tiles: [bh][T_max] {token offset, tokens, block id} per list entry; null: mean tiles
+  const float2* ybd;                          // {additive exponent term (-inf: masked), delta} per streamed position
+  int kind;                                   // token tiles: list entries = 0 kept blocks, 1 full-attention blocks, 2 Taylor blocks
+  int masked;                                 // exact sets (Alg. 2 Part A): 0 none; 1 token tiles of the entries whose bit is set for the
+                                              // stationary entry, others skipped; 2 mean tiles, positions whose bit is set are masked;
+                                              // 3 (mean rows stationary) entries whose bit is set for the lane's row are masked
+};
+
 struct BwdArgs {
   // stationary rows: token tensors (strides of `geo`, blocks taken from `stat_list`) or gathered mean rows [bh][Tn_pad][128]
   const uint16_t* x1; const uint16_t* x2;
   const int* stat_list;                       // [bh][T_max] block ids; unused for mean rows
   const float* bx; const float* dx;           // per stationary row: additive exponent term / delta ([bh][S_max] or [bh][Tn_pad]); null = 0
-  // streamed tiles: token tensors (tiles from `ytab`) or gathered mean rows
-  const uint16_t* y1; const uint16_t* y2; const uint16_t* yt;
-  const int4* ytab;                           // [bh][T_max] {token offset, tokens, block id} per list entry; unused for mean rows
-  const float2* ybd;                          // {additive exponent term (-inf: masked), delta} per streamed position
+  BwdStream s[2];
+  int n_phases;
+  // exact sets: bit matrix [bh][T_max][mask_words] whose row is a stationary entry (token blocks) or a stationary mean row,
+  // and whose bit index is a streamed list entry / mean position
+  const uint32_t* bits; int mask_words;
   // outputs
   uint16_t* out_bf; float* out_f32;           // token rows (bf16, strides of `geo`) or mean rows (fp32 [bh][Tn_pad][128])
   const float* add_rows;                      // [bh][Tn_pad][128] or null: row `entry`, divided by the block's tokens, is added to every row
@@ -59,12 +77,11 @@ struct BwdArgs {
   Geometry geo; Counts cnt;
   int Tn_pad, S_max;
   int stat_kind;                              // token rows: 0 full-attention blocks, 1 Taylor blocks, 2 kept blocks
-  int stream_kind;                            // token tiles: 0 kept blocks, 1 full-attention blocks, 2 Taylor blocks
   int items;                                  // work items (pairs of stationary blocks) per (batch, head) in this launch
 };
 
-// SM: stationary rows are block means; YM: streamed rows are block means; T2: W = P * (T2 - delta), else W = P.
-template <bool SM, bool YM, bool T2>
+// SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play.
+template <bool SM, bool T2, bool EX>
 __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * STAGE + 2 * SIDE_BYTES / 2];
   // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
@@ -78,8 +95,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   const long long bh = bhid;
   const int n_stat = SM ? (T_new + 127) / 128 : (a.stat_kind == 0 ? n_full : a.stat_kind == 1 ? n_flat : T_new);
   if (2 * item >= n_stat) return;
-  const int n_ent = YM ? 0 : (a.stream_kind == 0 ? T_new : a.stream_kind == 1 ? n_full : n_flat);
-  const int n_tiles = YM ? (T_new + KT - 1) / KT : 2 * n_ent;
   const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -128,6 +143,15 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     bxv[qt] = (a.bx && row_ok[qt]) ? a.bx[bx_base + rowq[qt]] : 0.f;
     dxv[qt] = (a.dx && row_ok[qt]) ? a.dx[bx_base + rowq[qt]] : 0.f;
   }
+  // Exact-set bits of the stationary token blocks: lane L holds word L of the row of this wave's own entry and of the
+  // pair's other entry (zeros for an entry that does not exist); handed out with readlane.
+  uint32_t bits_own = 0u, bits_other = 0u;
+  if (EX && !SM) {
+    const int e_other = 2 * item + (1 - grp);
+    if (active && lane < a.mask_words) bits_own = a.bits[(bh * T_max + entry) * a.mask_words + lane];
+    if (e_other < n_stat && lane < a.mask_words) bits_other = a.bits[(bh * T_max + e_other) * a.mask_words + lane];
+  }
+  const uint32_t bits_any = bits_own | bits_other;
   // consume the prologue loads here: the waits the compiler places inside the loop must not cover them
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
@@ -138,6 +162,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     }
     asm volatile("" : "+v"(bxv[qt]), "+v"(dxv[qt]));
   }
+  if (EX) asm volatile("" : "+v"(bits_own), "+v"(bits_other));
 
   // ---- tile loads: global -> LDS, 16 bytes per lane, rows XOR-swizzled on the source side (the layouts of the forward
   // kernel: natural tiles 64 rows x 256 B, chunk c of row r at c ^ (r & 15); packed tiles as two units of 128 rows x
@@ -152,27 +177,80 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     nchunk_b[i] = (uint32_t)((((lane & 15) ^ (nrow_l[i] & 15)) * 8) * 2);
     tlane_b[i] = (uint32_t)(((wave < 4 ? 0 : 32) + (((wave * 2 + i) & 7) * 16 + (lane >> 2)) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
   }
-  const uint32_t ystride_b = (uint32_t)(YM ? MD : (int)a.geo.stride_t) * 2u;
-  const char* const y1_head = reinterpret_cast<const char*>(YM ? a.y1 + bh * a.Tn_pad * MD : a.y1 + tbase);
-  const char* const y2_head = T2 ? reinterpret_cast<const char*>(YM ? a.y2 + bh * a.Tn_pad * MD : a.y2 + tbase) : nullptr;
-  const char* const yt_head = reinterpret_cast<const char*>(
-      YM ? a.yt + bh * (a.Tn_pad / KT) * (long long)(MD * KT) : a.yt + bh * T_max * 2 * (long long)(MD * KT));
-  const char* const ybd_head = reinterpret_cast<const char*>(YM ? a.ybd + bh * a.Tn_pad : a.ybd + bh * T_max * 128);
+
+  // ---- the sequence of streamed tiles: phase p, tile T of the phase (token tiles: entry T / 2, half T % 2).
+  // Everything the loop needs to know about the two phases is copied into plain variables here and selected by value:
+  // indexing the kernel argument (or a closure) with a run-time phase number would move it to scratch memory.
+  struct Cursor { int p, T; };
+  const int n_phases = a.n_phases;
+  const int ph_ent0 = a.s[0].kind == 0 ? T_new : a.s[0].kind == 1 ? n_full : n_flat;
+  const int ph_ent1 = a.s[1].kind == 0 ? T_new : a.s[1].kind == 1 ? n_full : n_flat;
+  const int4* const ph_tab0 = a.s[0].tab;
+  const int4* const ph_tab1 = a.s[1].tab;
+  const int ph_tiles0 = ph_tab0 ? 2 * ph_ent0 : (T_new + KT - 1) / KT;
+  const int ph_tiles1 = ph_tab1 ? 2 * ph_ent1 : (T_new + KT - 1) / KT;
+  const int ph_masked0 = a.s[0].masked, ph_masked1 = a.s[1].masked;
+  const uint16_t* const ph_y1_0 = a.s[0].y1; const uint16_t* const ph_y1_1 = a.s[1].y1;
+  const uint16_t* const ph_y2_0 = a.s[0].y2; const uint16_t* const ph_y2_1 = a.s[1].y2;
+  const uint16_t* const ph_yt_0 = a.s[0].yt; const uint16_t* const ph_yt_1 = a.s[1].yt;
+  const float2* const ph_ybd_0 = a.s[0].ybd; const float2* const ph_ybd_1 = a.s[1].ybd;
+#define PH(p, x0, x1) ((p) == 0 ? (x0) : (x1))
+  auto tiles_of = [&](int p) __attribute__((always_inline)) -> int { return PH(p, ph_tiles0, ph_tiles1); };
+  // first entry >= e0 of the phase whose bit is set for either stationary entry of the pair (n_ent if none)
+  auto next_linked = [&](int e0, int n_ent) __attribute__((always_inline)) -> int {
+    int w = e0 >> 5;
+    if (e0 >= n_ent) return n_ent;
+    uint32_t word = (uint32_t)__builtin_amdgcn_readlane((int)bits_any, w) & (~0u << (e0 & 31));
+    const int nw = (n_ent + 31) >> 5;
+    while (word == 0u && ++w < nw) word = (uint32_t)__builtin_amdgcn_readlane((int)bits_any, w);
+    if (word == 0u) return n_ent;
+    return min(n_ent, w * 32 + __builtin_ctz(word));
+  };
+  // normalises a cursor: skips unlinked entries of a masked token phase and moves on to the next phase at the end
+  auto settle = [&](Cursor c) __attribute__((always_inline)) -> Cursor {
+    while (c.p < n_phases) {
+      const int nt = tiles_of(c.p);
+      if (EX && !SM && PH(c.p, ph_masked0, ph_masked1) == 1 && (c.T & 1) == 0 && c.T < nt) c.T = 2 * next_linked(c.T >> 1, nt >> 1);
+      if (c.T < nt) break;
+      c.p += 1;
+      c.T = 0;
+    }
+    return c;
+  };
+  auto advance = [&](Cursor c) __attribute__((always_inline)) -> Cursor { c.T += 1; return settle(c); };
   // The table row of a tile is fetched one iteration before the tile's loads are issued, so that its latency is not
   // waited for inside the loop.
-  auto row_of = [&](int T) -> int4 {
-    if (YM || n_ent == 0) return make_int4(0, 0, 0, 0);
-    return a.ytab[bh * T_max + min(T >> 1, n_ent - 1)];
+  auto row_of = [&](Cursor c) __attribute__((always_inline)) -> int4 {
+    const int4* const tab = PH(c.p, ph_tab0, ph_tab1);
+    if (c.p >= n_phases || !tab) return make_int4(0, 0, 0, 0);
+    return tab[bh * T_max + (c.T >> 1)];
   };
-  auto issue_tile = [&](int T, int stage, const int4 ent) {
-    uint32_t y_off, t_off, bd_off;
+  auto issue_tile = [&](Cursor c, int stage, const int4 ent) __attribute__((always_inline)) {
+    const bool means = PH(c.p, ph_tab0, ph_tab1) == nullptr;
+    const uint16_t* const ph_y1 = PH(c.p, ph_y1_0, ph_y1_1);
+    const uint16_t* const ph_y2 = PH(c.p, ph_y2_0, ph_y2_1);
+    const uint16_t* const ph_yt = PH(c.p, ph_yt_0, ph_yt_1);
+    const float2* const ph_ybd = PH(c.p, ph_ybd_0, ph_ybd_1);
+    const int T = c.T;
+    uint32_t y_off, t_off, bd_off, ystride_b;
     int nk;
-    if (YM) {
+    const char *y1_head, *y2_head, *yt_head, *ybd_head;
+    if (means) {
+      ystride_b = (uint32_t)MD * 2u;
+      y1_head = reinterpret_cast<const char*>(ph_y1 + bh * a.Tn_pad * MD);
+      y2_head = T2 ? reinterpret_cast<const char*>(ph_y2 + bh * a.Tn_pad * MD) : nullptr;
+      yt_head = reinterpret_cast<const char*>(ph_yt + bh * (a.Tn_pad / KT) * (long long)(MD * KT));
+      ybd_head = reinterpret_cast<const char*>(ph_ybd + bh * a.Tn_pad);
       y_off = (uint32_t)T * (uint32_t)(KT * MD * 2);
       t_off = (uint32_t)T * (uint32_t)(MD * KT * 2);
       bd_off = (uint32_t)T * (uint32_t)(KT * 8);
       nk = KT;                                            // the gathered mean arrays are padded to whole tiles
     } else {
+      ystride_b = (uint32_t)a.geo.stride_t * 2u;
+      y1_head = reinterpret_cast<const char*>(ph_y1 + tbase);
+      y2_head = T2 ? reinterpret_cast<const char*>(ph_y2 + tbase) : nullptr;
+      yt_head = reinterpret_cast<const char*>(ph_yt + bh * T_max * 2 * (long long)(MD * KT));
+      ybd_head = reinterpret_cast<const char*>(ph_ybd + bh * T_max * 128);
       const int sub = T & 1;
       const bool empty = ent.y <= sub * KT;               // second tile of a short block: masked, reads the block's first rows
       y_off = (uint32_t)(ent.x + (empty ? 0 : sub * KT)) * ystride_b;
@@ -185,16 +263,21 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     t_off = __builtin_amdgcn_readfirstlane(t_off);
     bd_off = __builtin_amdgcn_readfirstlane(bd_off);
     nk = __builtin_amdgcn_readfirstlane(nk);
+    ystride_b = __builtin_amdgcn_readfirstlane(ystride_b);
+    const char* const y1_tile = uniform_ptr(y1_head + y_off);
+    const char* const y2_tile = T2 ? uniform_ptr(y2_head + y_off) : nullptr;
+    const char* const yt_tile = uniform_ptr(yt_head + t_off);
+    const char* const ybd_tile = uniform_ptr(ybd_head + bd_off);
     uint16_t* sb = lds + stage * STAGE;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const uint32_t ro = (uint32_t)min(nrow_l[i], nk - 1) * ystride_b + nchunk_b[i];     // rows past the end re-read the last one
-      dma16(y1_head + y_off, ro, lds_addr(sb + (wave * 2 + i) * 512));
-      if (T2) dma16(y2_head + y_off, ro, lds_addr(sb + K_TILE + (wave * 2 + i) * 512));
-      dma16(yt_head + t_off, tlane_b[i], lds_addr(sb + 2 * K_TILE + (wave * 2 + i) * 512));
+      dma16(y1_tile, ro, lds_addr(sb + (wave * 2 + i) * 512));
+      if (T2) dma16(y2_tile, ro, lds_addr(sb + K_TILE + (wave * 2 + i) * 512));
+      dma16(yt_tile, tlane_b[i], lds_addr(sb + 2 * K_TILE + (wave * 2 + i) * 512));
     }
     if (wave == 0)                                         // {bias, delta} of the 64 rows: 512 B, lanes 32..63 repeat lanes 0..31
-      dma16(ybd_head + bd_off, (uint32_t)(lane & 31) * 16u, lds_addr(lds + 2 * STAGE + stage * (SIDE_BYTES / 2)));
+      dma16(ybd_tile, (uint32_t)(lane & 31) * 16u, lds_addr(lds + 2 * STAGE + stage * (SIDE_BYTES / 2)));
   };
 
   // per-lane fragment offsets (bf16 elements), as in the forward kernel
@@ -210,18 +293,48 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     for (int qt = 0; qt < 2; ++qt) acc[ct][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
 
-  int4 ent_next = row_of(0);
-  if (n_tiles > 0) issue_tile(0, 0, ent_next);
-  ent_next = row_of(1);
-  for (int T = 0; T < n_tiles; ++T) {
-    // this wave's loads of tile T have landed; after the barrier everybody's have, and everybody has finished reading
-    // the other stage (tile T - 1), which the loads of tile T + 1 now overwrite
+  // cur: tile being multiplied; nxt: tile whose loads are in flight; nn: tile whose table row is being fetched
+  Cursor cur = settle(Cursor{0, 0});
+  Cursor nxt = cur.p < n_phases ? advance(cur) : cur;
+  int4 ent_nxt = row_of(cur);
+  if (cur.p < n_phases) issue_tile(cur, 0, ent_nxt);
+  ent_nxt = row_of(nxt);
+  uint32_t sm_word[2] = {0u, 0u};             // masked == 3: word (entry / 32) of the bit rows of the lane's two mean rows
+  int sm_word_of = -1;
+  for (int it = 0; cur.p < n_phases; ++it) {
+    // this wave's loads of the current tile have landed; after the barrier everybody's have, and everybody has finished
+    // reading the other stage (the previous tile), which the loads of the next tile now overwrite
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (T + 1 < n_tiles) issue_tile(T + 1, (T + 1) & 1, ent_next);
-    ent_next = row_of(T + 2);
-    const uint16_t* sb = lds + (T & 1) * STAGE;
-    const float2* side = reinterpret_cast<const float2*>(lds + 2 * STAGE + (T & 1) * (SIDE_BYTES / 2));
+    if (nxt.p < n_phases) issue_tile(nxt, (it + 1) & 1, ent_nxt);
+    const Cursor nn = nxt.p < n_phases ? advance(nxt) : nxt;
+    ent_nxt = row_of(nn);
+    const uint16_t* sb = lds + (it & 1) * STAGE;
+    const float2* side = reinterpret_cast<const float2*>(lds + 2 * STAGE + (it & 1) * (SIDE_BYTES / 2));
+    // exact sets: what of this tile is masked for this wave's stationary rows
+    float gm_tile[2] = {0.f, 0.f};            // per stationary 16-row tile of the wave
+    uint32_t pos_w0 = 0u, pos_w1 = 0u;        // masked == 2: bits of the tile's 64 positions (set = masked)
+    if (EX) {
+      const int masked = PH(cur.p, ph_masked0, ph_masked1);
+      if (!SM && masked == 1) {
+        const int e = cur.T >> 1;
+        const bool linked = ((uint32_t)__builtin_amdgcn_readlane((int)bits_own, e >> 5) >> (e & 31)) & 1u;
+        gm_tile[0] = gm_tile[1] = linked ? 0.f : -INFINITY;
+      } else if (!SM && masked == 2) {
+        pos_w0 = (uint32_t)__builtin_amdgcn_readlane((int)bits_own, 2 * cur.T);
+        pos_w1 = (uint32_t)__builtin_amdgcn_readlane((int)bits_own, min(2 * cur.T + 1, 63));
+      } else if (SM && masked == 3) {
+        const int e = cur.T >> 1;
+        if ((e >> 5) != sm_word_of) {
+          sm_word_of = e >> 5;
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt)
+            sm_word[qt] = row_ok[qt] ? a.bits[(bh * T_max + entry * 128 + rowq[qt]) * a.mask_words + sm_word_of] : 0u;
+        }
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) gm_tile[qt] = ((sm_word[qt] >> (e & 31)) & 1u) ? -INFINITY : 0.f;
+      }
+    }
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       f32x4 t1[2][2], t2[2][2];
@@ -244,16 +357,21 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         }
       // W: element 4 kt + i of a lane's fragment is streamed row 32 hh + 16 kt + 4 q + i
       bf16x8 w[2];
+      const uint32_t pos_w = hh ? pos_w1 : pos_w0;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
         float2 bd[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bd[i] = side[32 * hh + 16 * kt + 4 * q + i];
+        for (int i = 0; i < 4; ++i) {
+          bd[i] = side[32 * hh + 16 * kt + 4 * q + i];
+          if (EX && ((pos_w >> (16 * kt + 4 * q + i)) & 1u)) bd[i].x = -INFINITY;
+        }
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(t1[kt][qt][i], cscale, bd[i].x + bxv[qt]));
+            const float ex = EX ? bd[i].x + bxv[qt] + gm_tile[qt] : bd[i].x + bxv[qt];
+            const float p = __builtin_amdgcn_exp2f(fmaf(t1[kt][qt][i], cscale, ex));
             const float val = T2 ? p * (t2[kt][qt][i] - dxv[qt] - bd[i].y) : p;
             w[qt][4 * kt + i] = (__bf16)val;
           }
@@ -265,8 +383,11 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         acc[ct][1] = mfma16(ft, w[1], acc[ct][1]);
       }
     }
+    cur = nxt;
+    nxt = nn;
   }
 
+#undef PH
   // ---- store: element i of acc[ct][qt] is channel 16 ct + 4 q + i of stationary row 16 qt + r
   const float inv_n = n_x > 0 ? 1.0f / (float)n_x : 0.f;
   const float* addp = a.add_rows ? a.add_rows + (bh * a.Tn_pad + e_use) * MD + 4 * q : nullptr;
@@ -357,18 +478,46 @@ __global__ __launch_bounds__(256) void k_bwd_zero(uint16_t* __restrict__ x, Geom
       make_uint4(0, 0, 0, 0);
 }
 
+// Transposed exact-set bits: bit r of word r / 32 of row t is bit t of row r of `mask` (r: position in the Taylor list,
+// t: position in the kept list), so that a kept block finds the Taylor blocks that attend to its tokens.
+__global__ __launch_bounds__(64) void k_bwd_tmask(const uint32_t* __restrict__ mask, uint32_t* __restrict__ mask_t,
+                                                  Counts cnt, int H) {
+  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z, w = threadIdx.x;
+  const int T_max = cnt.T_max, mw = cnt.mask_words;
+  if (w >= mw) return;
+  const long long bh = (long long)b * H + h;
+  uint32_t out = 0u;
+  if (t < cnt.b[b].T_new)
+    for (int i = 0; i < 32; ++i) {
+      const int r = 32 * w + i;
+      if (r < cnt.b[b].n_flat) out |= ((mask[(bh * T_max + r) * mw + (t >> 5)] >> (t & 31)) & 1u) << i;
+    }
+  mask_t[(bh * T_max + t) * mw + w] = out;
+}
+
+template <bool SM, bool T2>
+static hipError_t launch_one(const BwdArgs& a, bool ex, int B, int H, hipStream_t st) {
+  if (a.items <= 0) return hipSuccess;
+  const dim3 grid((unsigned)(a.items * 8 * ((B * H + 7) / 8)));
+  if (ex) hipLaunchKernelGGL((k_attn_bwd<SM, T2, true>), grid, dim3(512), 0, st, a);
+  else hipLaunchKernelGGL((k_attn_bwd<SM, T2, false>), grid, dim3(512), 0, st, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v,
                            const void* out, const void* d_out, const int* kv_list, const int* full_list,
-                           const int* flat_list, void* dq, void* dk, void* dv, hipStream_t st) {
+                           const int* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
+                           hipStream_t st) {
   const int B = pr.p.B, H = pr.p.H, T_max = pr.cnt.T_max;
-  int S_max = pr.S_max, sf = 0, sl = 0, sk = 0;
+  int S_max = pr.S_max, sf = 0, sl = 0, sk = 0, kx = 0;
   for (int b = 0; b < B; ++b) {
     const BatchCounts& c = pr.cnt.b[b];
     sf = c.n_full > sf ? c.n_full : sf;
     sl = c.n_flat > sl ? c.n_flat : sl;
     sk = c.T_new > sk ? c.T_new : sk;
+    kx = c.k_exact > kx ? c.k_exact : kx;
   }
-  const dim3 bhg(1, H, B);
+  const bool ex = kx > 0 && sl > 0 && exact_mask != nullptr;      // some Taylor block has a non-empty exact set
 #define ISA_BWD_CHECK()                           \
   do {                                            \
     hipError_t e__ = hipGetLastError();           \
@@ -389,71 +538,70 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, flat_list, 2, ws.btab, ws.nlse, ws.delta, ws.ltab,
                      ws.ybd_flat, ws.ybd_mean, ws.bx_mean, pr.cnt, H, pr.Tn_pad, S_max);
   ISA_BWD_CHECK();
+  if (ex) {
+    hipLaunchKernelGGL(k_bwd_tmask, dim3(T_max, H, B), dim3(64), 0, st, exact_mask, ws.mask_t, pr.cnt, H);
+    ISA_BWD_CHECK();
+  }
 
   BwdArgs a;
   a.blk_start = ws.blk_start; a.blk_n = ws.blk_n;
   a.geo = pr.geo; a.cnt = pr.cnt; a.Tn_pad = pr.Tn_pad; a.S_max = S_max;
+  a.mask_words = pr.cnt.mask_words;
   const float scale = 1.0f / sqrtf((float)MD);
   const uint16_t *Q = (const uint16_t*)q, *K = (const uint16_t*)k, *V = (const uint16_t*)v, *DO = (const uint16_t*)d_out;
+  const BwdStream none = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
   hipError_t e;
 
-  // ---- dQ: exact branch over the kept tokens (needs K^T packed), Taylor branch over the kept blocks' means
+  // ---- dQ: exact branch over the kept tokens (needs K^T packed); Taylor branch over the tokens of each block's exact
+  // set and the means of the other kept blocks
   if ((e = launch_pack_t(pr, ws, K, ws.vt, st)) != hipSuccess) return e;
+  const BwdStream kept_tokens = {K, V, ws.vt, ws.ktab, ws.ybd_kv, 0, 0};
+  const BwdStream kept_means = {ws.kcn, ws.vcn, ws.kcnt, nullptr, ws.ybd_mean, 0, 0};
   a.x1 = Q; a.x2 = DO; a.bx = ws.nlse; a.dx = ws.delta;
   a.out_bf = (uint16_t*)dq; a.out_f32 = nullptr; a.add_rows = nullptr; a.oscale = scale;
-  if (sf > 0) {
-    a.stat_list = full_list; a.stat_kind = 0;
-    a.y1 = K; a.y2 = V; a.yt = ws.vt; a.ytab = ws.ktab; a.ybd = ws.ybd_kv; a.stream_kind = 0;
-    a.items = (sf + 1) / 2;
-    hipLaunchKernelGGL((k_attn_bwd<false, false, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
-    ISA_BWD_CHECK();
+  a.stat_list = full_list; a.stat_kind = 0; a.items = (sf + 1) / 2;
+  a.s[0] = kept_tokens; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
+  if ((e = launch_one<false, true>(a, false, B, H, st)) != hipSuccess) return e;
+  a.stat_list = flat_list; a.stat_kind = 1; a.items = (sl + 1) / 2;
+  if (ex) {
+    a.s[0] = kept_tokens; a.s[0].masked = 1;
+    a.s[1] = kept_means; a.s[1].masked = 2;
+    a.n_phases = 2; a.bits = exact_mask;
+  } else {
+    a.s[0] = kept_means; a.n_phases = 1;
   }
-  if (sl > 0) {
-    a.stat_list = flat_list; a.stat_kind = 1;
-    a.y1 = ws.kcn; a.y2 = ws.vcn; a.yt = ws.kcnt; a.ytab = nullptr; a.ybd = ws.ybd_mean; a.stream_kind = 0;
-    a.items = (sl + 1) / 2;
-    hipLaunchKernelGGL((k_attn_bwd<false, true, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
-    ISA_BWD_CHECK();
-  }
+  if ((e = launch_one<false, true>(a, ex, B, H, st)) != hipSuccess) return e;
 
   // ---- dKc and dK (streamed Q, dO, Q^T packed)
   if ((e = launch_pack_t(pr, ws, Q, ws.vt, st)) != hipSuccess) return e;
-  a.y1 = Q; a.y2 = DO; a.yt = ws.vt; a.dx = nullptr;
   const int n_mean_pairs = ((sk + 127) / 128 + 1) / 2;
-  if (sl > 0) {
-    a.x1 = ws.kcn; a.x2 = ws.vcn; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
-    a.ytab = ws.ltab; a.ybd = ws.ybd_flat; a.stream_kind = 2;
-    a.out_bf = nullptr; a.out_f32 = ws.dkc; a.add_rows = nullptr; a.oscale = scale;
-    a.items = n_mean_pairs;
-    hipLaunchKernelGGL((k_attn_bwd<true, false, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
-    ISA_BWD_CHECK();
+  BwdStream full_q = {Q, DO, ws.vt, ws.ftab, ws.ybd_full, 1, 0};
+  BwdStream flat_q = {Q, DO, ws.vt, ws.ltab, ws.ybd_flat, 2, 0};
+  a.dx = nullptr;
+  for (int pass = 0; pass < 2; ++pass) {          // pass 0: dKc, dK (W = dS); pass 1: dVc, dV (W = P, streamed dO^T)
+    if (pass == 1) {
+      if ((e = launch_pack_t(pr, ws, DO, ws.vt, st)) != hipSuccess) return e;
+      full_q.y2 = flat_q.y2 = nullptr;
+    }
+    float* mean_grad = pass == 0 ? ws.dkc : ws.dvc;
+    const float osc = pass == 0 ? scale : 1.0f;
+    if (sl > 0) {                                 // gradients of the gathered means: every Taylor block, minus its exact set
+      a.x1 = ws.kcn; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
+      a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
+      a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.oscale = osc; a.items = n_mean_pairs;
+      e = pass == 0 ? launch_one<true, true>(a, ex, B, H, st) : launch_one<true, false>(a, ex, B, H, st);
+      if (e != hipSuccess) return e;
+    }
+    // gradients of the kept tokens: every full-attention block, the Taylor blocks whose exact set holds the block, and
+    // the block's share of its mean's gradient
+    a.x1 = K; a.x2 = pass == 0 ? V : nullptr; a.stat_list = kv_list; a.stat_kind = 2; a.bx = nullptr;
+    a.s[0] = full_q; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
+    if (ex) { a.s[1] = flat_q; a.s[1].masked = 1; a.n_phases = 2; a.bits = ws.mask_t; }
+    a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr; a.add_rows = sl > 0 ? mean_grad : nullptr;
+    a.oscale = osc; a.items = (sk + 1) / 2;
+    e = pass == 0 ? launch_one<false, true>(a, ex, B, H, st) : launch_one<false, false>(a, ex, B, H, st);
+    if (e != hipSuccess) return e;
   }
-  a.x1 = K; a.x2 = V; a.stat_list = kv_list; a.stat_kind = 2; a.bx = nullptr;
-  a.ytab = ws.ftab; a.ybd = ws.ybd_full; a.stream_kind = 1;
-  a.out_bf = (uint16_t*)dk; a.out_f32 = nullptr; a.add_rows = sl > 0 ? ws.dkc : nullptr; a.oscale = scale;
-  a.items = (sk + 1) / 2;
-  if (a.items > 0)
-    hipLaunchKernelGGL((k_attn_bwd<false, false, true>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
-  ISA_BWD_CHECK();
-
-  // ---- dVc and dV (streamed Q, dO^T packed)
-  if ((e = launch_pack_t(pr, ws, DO, ws.vt, st)) != hipSuccess) return e;
-  a.y1 = Q; a.y2 = nullptr; a.yt = ws.vt;
-  if (sl > 0) {
-    a.x1 = ws.kcn; a.x2 = nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
-    a.ytab = ws.ltab; a.ybd = ws.ybd_flat; a.stream_kind = 2;
-    a.out_bf = nullptr; a.out_f32 = ws.dvc; a.add_rows = nullptr; a.oscale = 1.0f;
-    a.items = n_mean_pairs;
-    hipLaunchKernelGGL((k_attn_bwd<true, false, false>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
-    ISA_BWD_CHECK();
-  }
-  a.x1 = K; a.x2 = nullptr; a.stat_list = kv_list; a.stat_kind = 2; a.bx = nullptr;
-  a.ytab = ws.ftab; a.ybd = ws.ybd_full; a.stream_kind = 1;
-  a.out_bf = (uint16_t*)dv; a.out_f32 = nullptr; a.add_rows = sl > 0 ? ws.dvc : nullptr; a.oscale = 1.0f;
-  a.items = (sk + 1) / 2;
-  if (a.items > 0)
-    hipLaunchKernelGGL((k_attn_bwd<false, false, false>), dim3((unsigned)(a.items * 8 * ((B * H + 7) / 8))), dim3(512), 0, st, a);
-  ISA_BWD_CHECK();
 #undef ISA_BWD_CHECK
   return hipSuccess;
 }

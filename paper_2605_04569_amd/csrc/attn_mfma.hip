@@ -411,6 +411,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (row_ok) {
     const float inv = 1.0f / l_tot;
+    if (a.nlse && g == 0) a.nlse[bh * a.S_max + q_start + row] = -m_run - __log2f(l_tot);
     uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
     // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
     const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * g : nullptr;

@@ -131,11 +131,13 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->ybd_flat = (float2*)take(B * H * T * 128 * 8);
     ws->ybd_mean = (float2*)take(B * H * Tn * 8);
     ws->bx_mean = (float*)take(B * H * Tn * 4);
+    ws->mask_t = pr.p.exact_frac > 0.0 ? (uint32_t*)take(B * H * T * (size_t)pr.cnt.mask_words * 4) : nullptr;
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
     ws->vcn = ws->kcnt = nullptr;
     ws->ftab = ws->ltab = nullptr;
     ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
+    ws->mask_t = nullptr;
     ws->vt = ws->kcn = ws->vcnt = ws->vt4 = ws->vcnt4 = nullptr;
     ws->biasn = nullptr;
     ws->zero_tile = nullptr;
@@ -325,26 +327,33 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
 
 int isa_attention_backward(const isa_problem* p, const void* q, const void* k, const void* v, const void* out,
                            const void* d_out, const int32_t* kv_list, const int32_t* full_list,
-                           const int32_t* flat_list, void* dq, void* dk, void* dv, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+                           const int32_t* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   Problem pr;
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !out || !d_out || !dq || !dk || !dv) return ISA_ERR_NULL;
   const int n_lists = (kv_list != nullptr) + (full_list != nullptr) + (flat_list != nullptr);
   if (n_lists != 0 && n_lists != 3) return ISA_ERR_NULL;
-  if (!pr.mfma_shape || !g_use_mfma.load() || p->exact_frac > 0.0 || p->gamma != 0.0) return ISA_ERR_UNSUPPORTED;
+  if (n_lists == 3 && p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
+  // the exact-set bits of a list are handed out 64 words at a time: at most 2048 blocks with exact sets
+  if (!pr.mfma_shape || !g_use_mfma.load() || p->gamma != 0.0 || (p->exact_frac > 0.0 && pr.cnt.mask_words > 64))
+    return ISA_ERR_UNSUPPORTED;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (n_lists == 0) { kv_list = ws.kv_list; full_list = ws.full_list; flat_list = ws.flat_list; }
+  if (n_lists == 0) {
+    kv_list = ws.kv_list; full_list = ws.full_list; flat_list = ws.flat_list;
+    exact_mask = ws.exact_mask;
+  }
+  if (p->exact_frac <= 0.0) exact_mask = nullptr;
   // block table and means are recomputed (cheap, and the staged forward takes its means from the caller); the
   // log-sum-exp of every query row is what the forward call left in the workspace
   ISA_TRY(launch_layout(pr, ws, st));
   ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
   ISA_TRY(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
   ISA_TRY(launch_gather_means_bwd(pr, ws, ws.kc, ws.vc, kv_list, st));
-  ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, dq, dk, dv, st));
+  ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, exact_mask, dq, dk, dv, st));
   return ISA_OK;
 }
 

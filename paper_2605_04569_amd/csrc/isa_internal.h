@@ -71,6 +71,7 @@ struct Workspace {
   float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128] {exponent term, delta} per row position of each list entry
   float2* ybd_mean;      // [B,H,Tn_pad] the same per gathered mean key
   float* bx_mean;        // [B,H,Tn_pad] log2(n_j) per gathered mean key
+  uint32_t* mask_t;      // [B,H,T_max,mask_words] exact_mask transposed (only when exact_frac > 0)
   size_t bytes;          // total size
 };
 
@@ -123,6 +124,7 @@ hipError_t launch_gather_means_bwd(const Problem& pr, const Workspace& ws, const
                                    const int* kv_list, hipStream_t st);
 hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v,
                            const void* out, const void* d_out, const int* kv_list, const int* full_list,
-                           const int* flat_list, void* dq, void* dk, void* dv, hipStream_t st);
+                           const int* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
+                           hipStream_t st);
 
 }  // namespace isa

@@ -20,7 +20,11 @@ CASES = [SMALL, RAGGED,
          SMALL.with_(name="all_exact_all_kept", keep_ratio=1.0, full_frac=1.0),
          SMALL.with_(name="all_taylor", full_frac=0.0),
          SMALL.with_(name="no_context_kept", keep_ratio=0.0, full_frac=0.5),
-         RAGGED.with_(name="ragged_one_exact_block", full_frac=0.1, keep_ratio=0.7)]
+         RAGGED.with_(name="ragged_one_exact_block", full_frac=0.1, keep_ratio=0.7),
+         SMALL.with_(name="exact_sets", exact_frac=0.25),
+         RAGGED.with_(name="ragged_exact_sets", exact_frac=0.2, full_frac=0.2, keep_ratio=0.6),
+         SMALL.with_(name="all_taylor_exact_sets", full_frac=0.0, exact_frac=0.5),
+         SMALL.with_(name="paper_default_ratios", keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)]
 
 # Gradients are compared relative to their own scale: the kernel rounds the weights P and dS to bf16 before the second
 # products (2^-9 relative each, thousands of terms with random signs), reads delta from the bf16 output and rounds the
@@ -49,7 +53,8 @@ def _lists(I, wl, pr, Q, K, V):
     f32 = dict(device="cuda", dtype=torch.float32)
     buf = dict(kv=torch.full((wl.B, wl.H, T_max), -1, **i32), full=torch.full((wl.B, wl.H, T_max), -1, **i32),
                flat=torch.full((wl.B, wl.H, T_max), -1, **i32),
-               kc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32), vc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32))
+               kc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32), vc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32),
+               mask=torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), **i32) if wl.exact_frac > 0 else None)
     plans = {}
     for b in range(wl.B):
         c = I.isa_get_counts(pr, b)
@@ -61,6 +66,14 @@ def _lists(I, wl, pr, Q, K, V):
             buf["kv"][b, h, :c["T_new"]] = torch.from_numpy(np.asarray(plan["kv_list"])).int()
             buf["full"][b, h, :c["n_full"]] = torch.from_numpy(np.asarray(plan["full_list"])).int()
             buf["flat"][b, h, :c["n_flat"]] = torch.from_numpy(np.asarray(plan["flat_list"])).int()
+            if wl.exact_frac > 0:                         # bit t of row r: kv_list[t] is in the exact set of flat_list[r]
+                words = np.zeros((T_max, (T_max + 31) // 32), np.uint32)
+                for r, i in enumerate(plan["flat_list"]):
+                    ex = set(int(x) for x in OB.exact_blocks_of(plan, int(i)))
+                    for t, j in enumerate(plan["kv_list"]):
+                        if int(j) in ex:
+                            words[r, t >> 5] |= np.uint32(1 << (t & 31))
+                buf["mask"][b, h] = torch.from_numpy(words.view(np.int32))
     return buf, plans
 
 
@@ -94,11 +107,11 @@ def test_backward_on_oracle_lists(I, wl):
     buf, plans = _lists(I, wl, pr, Q, K, V)
     out = torch.full_like(q, float("nan"))
     print(f"\n[backward] case {wl.name}: forward on the oracle's lists", flush=True)
-    I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], None, out, ws)
+    I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], buf["mask"], out, ws)
     torch.cuda.synchronize()
     dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
     print(f"[backward] case {wl.name}: backward", flush=True)
-    I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws, buf["kv"], buf["full"], buf["flat"])
+    I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws, buf["kv"], buf["full"], buf["flat"], buf["mask"])
     torch.cuda.synchronize()
     _compare(wl, Q, K, V, dO, plans, dq, dk, dv)
     # kept-out context blocks get exact zeros
@@ -112,10 +125,11 @@ def test_backward_on_oracle_lists(I, wl):
                     assert (dk[b, h, rows] == 0).all() and (dv[b, h, rows] == 0).all(), (b, h, j)
 
 
-def test_backward_after_the_whole_call_and_reproducible(I):
-    """isa_attention leaves lists and log-sum-exps in the workspace; the backward call with NULL lists uses them.  Two
-    runs give bit-identical gradients (no atomics)."""
-    wl = SMALL
+@pytest.mark.parametrize("exact_frac", [0.0, 0.25])
+def test_backward_after_the_whole_call_and_reproducible(I, exact_frac):
+    """isa_attention leaves lists, exact-set bits and log-sum-exps in the workspace; the backward call with NULL lists
+    uses them.  Two runs give bit-identical gradients (no atomics)."""
+    wl = SMALL.with_(exact_frac=exact_frac)
     Q, K, V, dO = _inputs(wl)
     q, k, v, d_out = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
     pr = problem_of(wl)
@@ -138,7 +152,7 @@ def test_backward_rejects_what_it_does_not_cover(I):
     wl = SMALL
     Q, K, V, dO = _inputs(wl)
     q = Q.cuda()
-    for kw in (dict(exact_frac=0.25), dict(gamma=0.5)):
+    for kw in (dict(gamma=0.5),):
         pr = problem_of(wl.with_(**kw))
         ws = I.new_workspace(pr)
         with pytest.raises(I.IsaError):
@@ -164,11 +178,14 @@ def _full_size_sampled(I, wl, b, h, seed, last_full=1):
     qc, kc, vc = (torch.zeros((wl.B, wl.H, T_max, wl.D), **f32) for _ in range(3))
     s_ctx, sharp = torch.zeros((wl.B, wl.H, T_max), **f32), torch.zeros((wl.B, wl.H, T_max), **f32)
     kv_g, full_g, flat_g = (torch.zeros((wl.B, wl.H, T_max), device="cuda", dtype=torch.int32) for _ in range(3))
+    ex = wl.exact_frac > 0
+    z = torch.zeros((wl.B, wl.H, T_max, T_max), **f32) if ex else None
+    mask_g = torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), device="cuda", dtype=torch.int32) if ex else None
     I.isa_block_means(pr, q, k, v, qc, kc, vc, ws)
-    I.isa_coarse_scores(pr, qc, kc, s_ctx, sharp, None, ws)
-    I.isa_select(pr, s_ctx, sharp, None, kv_g, full_g, flat_g, None, ws)
+    I.isa_coarse_scores(pr, qc, kc, s_ctx, sharp, z, ws)
+    I.isa_select(pr, s_ctx, sharp, z, kv_g, full_g, flat_g, mask_g, ws)
     torch.cuda.synchronize()
-    del qc, kc, vc
+    del qc, kc, vc, z
     c = I.isa_get_counts(pr, b)
     n = wl.tokens(b)
     kv = kv_g[b, h, :c["T_new"]].cpu().numpy()
@@ -181,6 +198,13 @@ def _full_size_sampled(I, wl, b, h, seed, last_full=1):
     pick = sorted(set(rng.choice(full, min(2, len(full)), replace=False).tolist()) |
                   set(full[len(full) - min(len(full), last_full):].tolist()) |
                   set(rng.choice(flat, min(2, len(flat)), replace=False).tolist()))
+    if ex:          # the exact sets the GPU chose for the sampled Taylor blocks must be the oracle's (it evaluates its own)
+        bits = mask_g[b, h].cpu().numpy().view(np.uint32)
+        for i in pick:
+            if i in set(flat.tolist()):
+                r = int(np.searchsorted(flat, i))
+                got = sorted(int(kv[t]) for t in range(c["T_new"]) if (bits[r, t >> 5] >> (t & 31)) & 1)
+                assert got == sorted(int(x) for x in OB.exact_blocks_of(plan, int(i))), (i, got)
     d_out = torch.zeros_like(q)
     g = torch.Generator(device="cuda").manual_seed(seed)
     for i in pick:
@@ -218,3 +242,9 @@ def test_backward_full_size_480p_sampled(I):
 
 def test_backward_full_size_ragged_batch_sampled(I):
     _full_size_sampled(I, W.CONFIGS["cfg3"].with_(keep_ratio=0.25, full_frac=0.1), 1, 5, seed=22)
+
+
+def test_backward_full_size_paper_default_ratios_sampled(I):
+    """The paper's default operating point (Sec. 4.1: alpha_s = 0.125, alpha_f = 0.5, alpha_ns = 0.0625) at the 480p shape:
+    every Taylor block has an exact set of 18 kept blocks, so all three masked paths of the backward kernels run."""
+    _full_size_sampled(I, W.CONFIGS["cfg2"].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625), 0, 12, seed=23)
