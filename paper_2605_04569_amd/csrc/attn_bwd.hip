@@ -71,7 +71,8 @@ struct BwdArgs {
   const uint32_t* bits; int mask_words;
   // outputs
   uint16_t* out_bf; float* out_f32;           // token rows (bf16, strides of `geo`) or mean rows (fp32 [bh][Tn_pad][128])
-  const float* add_rows;                      // [bh][Tn_pad][128] or null: row `entry`, divided by the block's tokens, is added to every row
+  const float* add_rows;                      // null, or fp32 rows of 128 of which one, divided by the block's tokens, is added to every row:
+  int add_by_block;                           //   0: [bh][Tn_pad] indexed by the stationary entry; 1: [bh][T_max] indexed by its block id
   float oscale;
   const int* blk_start; const int* blk_n;
   Geometry geo; Counts cnt;
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   const int entry = 2 * item + grp;
   const bool active = entry < n_stat;
   const int e_use = active ? entry : 0;
-  int n_x, x_start = 0;
+  int n_x, x_start = 0, x_blk = 0;
   const uint16_t *xb1, *xb2;
   long long xstride;
   long long bx_base;
@@ -119,6 +120,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     bx_base = bh * a.Tn_pad + (long long)e_use * 128;
   } else {
     const int blk = a.stat_list[bh * T_max + e_use];
+    x_blk = blk;
     n_x = active ? a.blk_n[b * T_max + blk] : 0;
     x_start = a.blk_start[b * T_max + blk];
     xb1 = a.x1 + tbase + (long long)x_start * a.geo.stride_t;
@@ -390,7 +392,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
 #undef PH
   // ---- store: element i of acc[ct][qt] is channel 16 ct + 4 q + i of stationary row 16 qt + r
   const float inv_n = n_x > 0 ? 1.0f / (float)n_x : 0.f;
-  const float* addp = a.add_rows ? a.add_rows + (bh * a.Tn_pad + e_use) * MD + 4 * q : nullptr;
+  const float* addp = !a.add_rows ? nullptr
+                      : a.add_by_block ? a.add_rows + (bh * T_max + x_blk) * MD + 4 * q
+                                       : a.add_rows + (bh * a.Tn_pad + e_use) * MD + 4 * q;
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     if (!row_ok[qt]) continue;
@@ -469,13 +473,187 @@ __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, 
   ybd[(bh * T_max + e) * 128 + r] = v;
 }
 
-// Zeroes the rows of a token tensor (gradients of keys and values of context blocks that were not kept).
-__global__ __launch_bounds__(256) void k_bwd_zero(uint16_t* __restrict__ x, Geometry g, Counts cnt) {
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int t = blockIdx.x * 16 + (threadIdx.x >> 4), c16 = threadIdx.x & 15;
-  if (t >= cnt.b[b].S) return;
-  *reinterpret_cast<uint4*>(x + (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)t * g.stride_t + 8 * c16) =
-      make_uint4(0, 0, 0, 0);
+// Rows of a token tensor that no later launch writes (keys and values of context blocks that were not kept): zero, or,
+// with the coarse residual, the block's share `rows[block] / n` of the gradient of its mean.  Written for every block;
+// the launches over the kept blocks overwrite theirs.
+__global__ __launch_bounds__(256) void k_bwd_fill(uint16_t* __restrict__ x, const float* __restrict__ rows,
+                                                  const int4* __restrict__ btab, Geometry g, Counts cnt) {
+  const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (blk >= cnt.b[b].T) return;
+  const int4 ent = btab[b * cnt.T_max + blk];
+  const int c16 = threadIdx.x & 15;
+  uint4 val = make_uint4(0, 0, 0, 0);
+  if (rows) {
+    const float inv = 1.0f / (float)ent.y;
+    const float* rp = rows + (((long long)b * g.H + h) * cnt.T_max + blk) * MD + 8 * c16;
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = f2bf(rp[2 * i] * inv) | ((uint32_t)f2bf(rp[2 * i + 1] * inv) << 16);
+    val = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  for (int r = threadIdx.x >> 4; r < ent.y; r += 16)
+    *reinterpret_cast<uint4*>(x + (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)(ent.x + r) * g.stride_t + 8 * c16) = val;
+}
+
+// ---- coarse residual (Alg. 1 Stage 1 and Stage 5): out += gamma * O_coarse[block], O_coarse = softmax(Qc Kc^T / sqrt D) Vc.
+// Its gradient: dOc[i] = gamma * (sum of dO over block i); dVc = S^T dOc; dS = dOc Vc^T; dZ = S * (dS - rowsum(dS * S));
+// dQc = dZ Kc / sqrt D; dKc = dZ^T Qc / sqrt D; each mean's gradient is spread evenly over its block's tokens.
+
+// One workgroup per (block, head): doc[block] = gamma * column sums of the block's dO rows, and the residual's share is
+// taken out of delta (the attention branches' delta is rowsum(dO * (out - gamma * O_coarse[block]))).
+__global__ __launch_bounds__(128) void k_bwd_docoarse(const uint16_t* __restrict__ d_o, const float* __restrict__ ocoarse,
+                                                      float gamma, float* __restrict__ delta, float* __restrict__ doc,
+                                                      const int4* __restrict__ btab, Geometry g, Counts cnt, int S_max) {
+  __shared__ uint16_t tile[128][MD + 2];
+  __shared__ float oc[MD];
+  const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  if (blk >= cnt.b[b].T) return;
+  const int4 ent = btab[b * cnt.T_max + blk];
+  const long long bh = (long long)b * g.H + h;
+  const long long base = (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)ent.x * g.stride_t;
+  oc[tid] = ocoarse[(bh * cnt.T_max + blk) * MD + tid];
+  for (int x = tid; x < 128 * 16; x += 128) {
+    const int r = x >> 4, c = x & 15;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < ent.y) val = *reinterpret_cast<const uint4*>(d_o + base + (long long)r * g.stride_t + c * 8);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[r][c * 8]);
+    dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
+  }
+  __syncthreads();
+  float sum = 0.f;
+  for (int r = 0; r < ent.y; ++r) sum += __uint_as_float((uint32_t)tile[r][tid] << 16);
+  doc[(bh * cnt.T_max + blk) * MD + tid] = gamma * sum;
+  if (tid < ent.y) {
+    float dot = 0.f;
+    for (int d = 0; d < MD; ++d) dot += __uint_as_float((uint32_t)tile[tid][d] << 16) * oc[d];
+    delta[bh * S_max + ent.x + tid] -= gamma * dot;
+  }
+}
+
+// Row i of the pooled map: softmax statistics {max, sum, rowsum(dS * S)} and dQc[i].  LDS: qc_i, doc_i, T values.
+__global__ __launch_bounds__(256) void k_bwd_coarse_rows(const float* __restrict__ qc, const float* __restrict__ kc,
+                                                         const float* __restrict__ vc, const float* __restrict__ doc,
+                                                         float4* __restrict__ stats, float* __restrict__ dqc, Counts cnt,
+                                                         int H) {
+  extern __shared__ float sm[];
+  float* qi = sm; float* di = sm + MD; float* val = sm + 2 * MD;        // val[T]
+  __shared__ float red[256];
+  const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int T = cnt.b[b].T, T_max = cnt.T_max;
+  if (i >= T) return;
+  const long long row0 = ((long long)b * H + h) * T_max;
+  const float scale = 1.0f / sqrtf((float)MD);
+  if (tid < MD) { qi[tid] = qc[(row0 + i) * MD + tid]; di[tid] = doc[(row0 + i) * MD + tid]; }
+  __syncthreads();
+  auto reduce = [&](float x, bool take_max) -> float {
+    red[tid] = x;
+    __syncthreads();
+    for (int s2 = 128; s2 > 0; s2 >>= 1) {
+      if (tid < s2) red[tid] = take_max ? fmaxf(red[tid], red[tid + s2]) : red[tid] + red[tid + s2];
+      __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+  };
+  float mloc = -INFINITY;
+  for (int j = tid; j < T; j += 256) {
+    const float4* kp = reinterpret_cast<const float4*>(kc + (row0 + j) * MD);
+    float z = 0.f;
+    for (int d4 = 0; d4 < MD / 4; ++d4) {
+      const float4 k4 = kp[d4];
+      z += qi[4 * d4] * k4.x + qi[4 * d4 + 1] * k4.y + qi[4 * d4 + 2] * k4.z + qi[4 * d4 + 3] * k4.w;
+    }
+    val[j] = z * scale;
+    mloc = fmaxf(mloc, z * scale);
+  }
+  const float m = reduce(mloc, true);
+  float lloc = 0.f;
+  for (int j = tid; j < T; j += 256) lloc += __expf(val[j] - m);
+  const float l = reduce(lloc, false);
+  float rloc = 0.f;
+  for (int j = tid; j < T; j += 256) {                  // val[j] <- dZ_ij needs rowdot first: keep S in val, dS in registers twice
+    const float4* vp = reinterpret_cast<const float4*>(vc + (row0 + j) * MD);
+    float ds = 0.f;
+    for (int d4 = 0; d4 < MD / 4; ++d4) {
+      const float4 v4 = vp[d4];
+      ds += di[4 * d4] * v4.x + di[4 * d4 + 1] * v4.y + di[4 * d4 + 2] * v4.z + di[4 * d4 + 3] * v4.w;
+    }
+    const float sj = __expf(val[j] - m) / l;
+    rloc += sj * ds;
+    val[j] = sj * ds;                                   // S * dS for now; turned into dZ below
+  }
+  const float rowdot = reduce(rloc, false);
+  if (tid == 0) stats[row0 + i] = make_float4(m, l, rowdot, 0.f);
+  // dZ_ij = S_ij dS_ij - S_ij rowdot; S_ij is recomputed from the logit, which val no longer holds: recompute it
+  for (int j = tid; j < T; j += 256) {
+    const float4* kp = reinterpret_cast<const float4*>(kc + (row0 + j) * MD);
+    float z = 0.f;
+    for (int d4 = 0; d4 < MD / 4; ++d4) {
+      const float4 k4 = kp[d4];
+      z += qi[4 * d4] * k4.x + qi[4 * d4 + 1] * k4.y + qi[4 * d4 + 2] * k4.z + qi[4 * d4 + 3] * k4.w;
+    }
+    val[j] -= __expf(z * scale - m) / l * rowdot;
+  }
+  __syncthreads();
+  if (tid < MD) {
+    float acc = 0.f;
+    for (int j = 0; j < T; ++j) acc += val[j] * kc[(row0 + j) * MD + tid];
+    dqc[(row0 + i) * MD + tid] = acc * scale;
+  }
+}
+
+// Column j of the pooled map: dKc[j] = sum_i dZ_ij Qc_i / sqrt D, dVc[j] = sum_i S_ij dOc_i, with S and dZ recomputed from the
+// row statistics.  LDS: kc_j, vc_j, 2 T values.
+__global__ __launch_bounds__(256) void k_bwd_coarse_cols(const float* __restrict__ qc, const float* __restrict__ kc,
+                                                         const float* __restrict__ vc, const float* __restrict__ doc,
+                                                         const float4* __restrict__ stats, float* __restrict__ dkc,
+                                                         float* __restrict__ dvc, Counts cnt, int H) {
+  extern __shared__ float sm[];
+  float* kj = sm; float* vj = sm + MD; float* sv = sm + 2 * MD; float* dz = sv + cnt.T_max;
+  const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int T = cnt.b[b].T, T_max = cnt.T_max;
+  if (j >= T) return;
+  const long long row0 = ((long long)b * H + h) * T_max;
+  const float scale = 1.0f / sqrtf((float)MD);
+  if (tid < MD) { kj[tid] = kc[(row0 + j) * MD + tid]; vj[tid] = vc[(row0 + j) * MD + tid]; }
+  __syncthreads();
+  for (int i = tid; i < T; i += 256) {
+    const float4* qp = reinterpret_cast<const float4*>(qc + (row0 + i) * MD);
+    const float4* dp = reinterpret_cast<const float4*>(doc + (row0 + i) * MD);
+    float z = 0.f, ds = 0.f;
+    for (int d4 = 0; d4 < MD / 4; ++d4) {
+      const float4 q4 = qp[d4], o4 = dp[d4];
+      z += q4.x * kj[4 * d4] + q4.y * kj[4 * d4 + 1] + q4.z * kj[4 * d4 + 2] + q4.w * kj[4 * d4 + 3];
+      ds += o4.x * vj[4 * d4] + o4.y * vj[4 * d4 + 1] + o4.z * vj[4 * d4 + 2] + o4.w * vj[4 * d4 + 3];
+    }
+    const float4 st = stats[row0 + i];
+    const float sij = __expf(z * scale - st.x) / st.y;
+    sv[i] = sij;
+    dz[i] = sij * (ds - st.z);
+  }
+  __syncthreads();
+  if (tid < MD) {
+    float ak = 0.f, av = 0.f;
+    for (int i = 0; i < T; ++i) {
+      ak += dz[i] * qc[(row0 + i) * MD + tid];
+      av += sv[i] * doc[(row0 + i) * MD + tid];
+    }
+    dkc[(row0 + j) * MD + tid] = ak * scale;
+    dvc[(row0 + j) * MD + tid] = av;
+  }
+}
+
+// mean_grad[bh][e] (gradient of the gathered mean of kv_list[e], or nothing yet if `fresh`) += coarse[bh][kv_list[e]]
+__global__ __launch_bounds__(128) void k_bwd_add_coarse(float* __restrict__ mean_grad, const float* __restrict__ coarse,
+                                                        const int* __restrict__ kv_list, int fresh, Counts cnt, int H,
+                                                        int Tn_pad) {
+  const int e = blockIdx.x, h = blockIdx.y, b = blockIdx.z, d = threadIdx.x;
+  if (e >= cnt.b[b].T_new) return;
+  const long long bh = (long long)b * H + h;
+  const int blk = kv_list[bh * cnt.T_max + e];
+  const float prev = fresh ? 0.f : mean_grad[(bh * Tn_pad + e) * MD + d];
+  mean_grad[(bh * Tn_pad + e) * MD + d] = prev + coarse[(bh * cnt.T_max + blk) * MD + d];
 }
 
 // Transposed exact-set bits: bit r of word r / 32 of row t is bit t of row r of `mask` (r: position in the Taylor list,
@@ -508,6 +686,8 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
                            const void* out, const void* d_out, const int* kv_list, const int* full_list,
                            const int* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
                            hipStream_t st) {
+  const float gamma = (float)pr.p.gamma;
+  const bool resid = pr.p.gamma != 0.0;               // ws.ocoarse holds O_coarse (recomputed by the caller of this function)
   const int B = pr.p.B, H = pr.p.H, T_max = pr.cnt.T_max;
   int S_max = pr.S_max, sf = 0, sl = 0, sk = 0, kx = 0;
   for (int b = 0; b < B; ++b) {
@@ -527,8 +707,22 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   hipLaunchKernelGGL(k_bwd_delta, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (const uint16_t*)out,
                      (const uint16_t*)d_out, ws.delta, pr.geo, pr.cnt, S_max);
   ISA_BWD_CHECK();
-  hipLaunchKernelGGL(k_bwd_zero, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (uint16_t*)dk, pr.geo, pr.cnt);
-  hipLaunchKernelGGL(k_bwd_zero, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (uint16_t*)dv, pr.geo, pr.cnt);
+  if (resid) {
+    // gradient of the coarse residual with respect to the block means (all blocks, by block id), and delta without
+    // the residual's share
+    hipLaunchKernelGGL(k_bwd_docoarse, dim3(T_max, H, B), dim3(128), 0, st, (const uint16_t*)d_out, ws.ocoarse, gamma,
+                       ws.delta, ws.doc, ws.btab, pr.geo, pr.cnt, S_max);
+    ISA_BWD_CHECK();
+    hipLaunchKernelGGL(k_bwd_coarse_rows, dim3(T_max, H, B), dim3(256), (size_t)(2 * MD + T_max) * 4, st, ws.qc, ws.kc,
+                       ws.vc, ws.doc, ws.cstats, ws.cdq, pr.cnt, H);
+    hipLaunchKernelGGL(k_bwd_coarse_cols, dim3(T_max, H, B), dim3(256), (size_t)(2 * MD + 2 * T_max) * 4, st, ws.qc,
+                       ws.kc, ws.vc, ws.doc, ws.cstats, ws.cdk, ws.cdv, pr.cnt, H);
+    ISA_BWD_CHECK();
+  }
+  hipLaunchKernelGGL(k_bwd_fill, dim3(T_max, H, B), dim3(256), 0, st, (uint16_t*)dk, resid ? ws.cdk : nullptr, ws.btab,
+                     pr.geo, pr.cnt);
+  hipLaunchKernelGGL(k_bwd_fill, dim3(T_max, H, B), dim3(256), 0, st, (uint16_t*)dv, resid ? ws.cdv : nullptr, ws.btab,
+                     pr.geo, pr.cnt);
   ISA_BWD_CHECK();
   const int gx = T_max > pr.Tn_pad ? T_max : pr.Tn_pad;
   hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, kv_list, 0, ws.btab, ws.nlse, ws.delta, ws.ktab,
@@ -558,7 +752,8 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   const BwdStream kept_tokens = {K, V, ws.vt, ws.ktab, ws.ybd_kv, 0, 0};
   const BwdStream kept_means = {ws.kcn, ws.vcn, ws.kcnt, nullptr, ws.ybd_mean, 0, 0};
   a.x1 = Q; a.x2 = DO; a.bx = ws.nlse; a.dx = ws.delta;
-  a.out_bf = (uint16_t*)dq; a.out_f32 = nullptr; a.add_rows = nullptr; a.oscale = scale;
+  a.out_bf = (uint16_t*)dq; a.out_f32 = nullptr; a.oscale = scale;
+  a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
   a.stat_list = full_list; a.stat_kind = 0; a.items = (sf + 1) / 2;
   a.s[0] = kept_tokens; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
   if ((e = launch_one<false, true>(a, false, B, H, st)) != hipSuccess) return e;
@@ -588,16 +783,22 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     if (sl > 0) {                                 // gradients of the gathered means: every Taylor block, minus its exact set
       a.x1 = ws.kcn; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
       a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
-      a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.oscale = osc; a.items = n_mean_pairs;
+      a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.add_by_block = 0; a.oscale = osc; a.items = n_mean_pairs;
       e = pass == 0 ? launch_one<true, true>(a, ex, B, H, st) : launch_one<true, false>(a, ex, B, H, st);
       if (e != hipSuccess) return e;
+    }
+    if (resid) {                                  // the coarse residual's gradient of the same means joins the Taylor branch's
+      hipLaunchKernelGGL(k_bwd_add_coarse, dim3(sk, H, B), dim3(128), 0, st, mean_grad, pass == 0 ? ws.cdk : ws.cdv,
+                         kv_list, sl > 0 ? 0 : 1, pr.cnt, H, pr.Tn_pad);
+      ISA_BWD_CHECK();
     }
     // gradients of the kept tokens: every full-attention block, the Taylor blocks whose exact set holds the block, and
     // the block's share of its mean's gradient
     a.x1 = K; a.x2 = pass == 0 ? V : nullptr; a.stat_list = kv_list; a.stat_kind = 2; a.bx = nullptr;
     a.s[0] = full_q; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
     if (ex) { a.s[1] = flat_q; a.s[1].masked = 1; a.n_phases = 2; a.bits = ws.mask_t; }
-    a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr; a.add_rows = sl > 0 ? mean_grad : nullptr;
+    a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr;
+    a.add_rows = (sl > 0 || resid) ? mean_grad : nullptr; a.add_by_block = 0;
     a.oscale = osc; a.items = (sk + 1) / 2;
     e = pass == 0 ? launch_one<false, true>(a, ex, B, H, st) : launch_one<false, false>(a, ex, B, H, st);
     if (e != hipSuccess) return e;

@@ -132,12 +132,24 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->ybd_mean = (float2*)take(B * H * Tn * 8);
     ws->bx_mean = (float*)take(B * H * Tn * 4);
     ws->mask_t = pr.p.exact_frac > 0.0 ? (uint32_t*)take(B * H * T * (size_t)pr.cnt.mask_words * 4) : nullptr;
+    if (pr.p.gamma != 0.0) {
+      ws->doc = (float*)take(B * H * T * D * 4);
+      ws->cdq = (float*)take(B * H * T * D * 4);
+      ws->cdk = (float*)take(B * H * T * D * 4);
+      ws->cdv = (float*)take(B * H * T * D * 4);
+      ws->cstats = (float4*)take(B * H * T * 16);
+    } else {
+      ws->doc = ws->cdq = ws->cdk = ws->cdv = nullptr;
+      ws->cstats = nullptr;
+    }
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
     ws->vcn = ws->kcnt = nullptr;
     ws->ftab = ws->ltab = nullptr;
     ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
     ws->mask_t = nullptr;
+    ws->doc = ws->cdq = ws->cdk = ws->cdv = nullptr;
+    ws->cstats = nullptr;
     ws->vt = ws->kcn = ws->vcnt = ws->vt4 = ws->vcnt4 = nullptr;
     ws->biasn = nullptr;
     ws->zero_tile = nullptr;
@@ -337,7 +349,7 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
   if (n_lists != 0 && n_lists != 3) return ISA_ERR_NULL;
   if (n_lists == 3 && p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
   // the exact-set bits of a list are handed out 64 words at a time: at most 2048 blocks with exact sets
-  if (!pr.mfma_shape || !g_use_mfma.load() || p->gamma != 0.0 || (p->exact_frac > 0.0 && pr.cnt.mask_words > 64))
+  if (!pr.mfma_shape || !g_use_mfma.load() || (p->exact_frac > 0.0 && pr.cnt.mask_words > 64))
     return ISA_ERR_UNSUPPORTED;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
@@ -352,6 +364,8 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
   ISA_TRY(launch_layout(pr, ws, st));
   ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
   ISA_TRY(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
+  if (p->gamma != 0.0)                              // O_coarse of Alg. 1 Stage 1 again (the staged forward takes it from the caller)
+    ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, nullptr, ws.vc, ws.ocoarse, st));
   ISA_TRY(launch_gather_means_bwd(pr, ws, ws.kc, ws.vc, kv_list, st));
   ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, exact_mask, dq, dk, dv, st));
   return ISA_OK;

@@ -72,6 +72,8 @@ struct Workspace {
   float2* ybd_mean;      // [B,H,Tn_pad] the same per gathered mean key
   float* bx_mean;        // [B,H,Tn_pad] log2(n_j) per gathered mean key
   uint32_t* mask_t;      // [B,H,T_max,mask_words] exact_mask transposed (only when exact_frac > 0)
+  float* doc; float* cdq; float* cdk; float* cdv;   // [B,H,T_max,D] coarse residual: gamma * block sums of dO, gradients of the means (only when gamma != 0)
+  float4* cstats;        // [B,H,T_max] {max, sum, rowsum(dS * S)} of every row of the pooled map (only when gamma != 0)
   size_t bytes;          // total size
 };
 

@@ -24,7 +24,10 @@ CASES = [SMALL, RAGGED,
          SMALL.with_(name="exact_sets", exact_frac=0.25),
          RAGGED.with_(name="ragged_exact_sets", exact_frac=0.2, full_frac=0.2, keep_ratio=0.6),
          SMALL.with_(name="all_taylor_exact_sets", full_frac=0.0, exact_frac=0.5),
-         SMALL.with_(name="paper_default_ratios", keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)]
+         SMALL.with_(name="paper_default_ratios", keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625),
+         SMALL.with_(name="coarse_residual", gamma=0.5),
+         RAGGED.with_(name="ragged_residual_exact_sets", gamma=-0.75, exact_frac=0.2, full_frac=0.2, keep_ratio=0.6),
+         SMALL.with_(name="residual_all_exact_nothing_kept", gamma=1.0, full_frac=1.0, keep_ratio=0.0)]
 
 # Gradients are compared relative to their own scale: the kernel rounds the weights P and dS to bf16 before the second
 # products (2^-9 relative each, thousands of terms with random signs), reads delta from the bf16 output and rounds the
@@ -54,6 +57,8 @@ def _lists(I, wl, pr, Q, K, V):
     buf = dict(kv=torch.full((wl.B, wl.H, T_max), -1, **i32), full=torch.full((wl.B, wl.H, T_max), -1, **i32),
                flat=torch.full((wl.B, wl.H, T_max), -1, **i32),
                kc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32), vc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32),
+               qc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32),
+               oc=torch.zeros((wl.B, wl.H, T_max, wl.D), **f32) if wl.gamma != 0 else None,
                mask=torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), **i32) if wl.exact_frac > 0 else None)
     plans = {}
     for b in range(wl.B):
@@ -61,6 +66,7 @@ def _lists(I, wl, pr, Q, K, V):
         for h in range(wl.H):
             plan = plans[b, h] = oracle_plan(wl, Q, K, V, b, h)
             T = plan["T"]
+            buf["qc"][b, h, :T] = torch.from_numpy(plan["Qc"]).float()
             buf["kc"][b, h, :T] = torch.from_numpy(plan["Kc"]).float()
             buf["vc"][b, h, :T] = torch.from_numpy(plan["Vc"]).float()
             buf["kv"][b, h, :c["T_new"]] = torch.from_numpy(np.asarray(plan["kv_list"])).int()
@@ -107,15 +113,18 @@ def test_backward_on_oracle_lists(I, wl):
     buf, plans = _lists(I, wl, pr, Q, K, V)
     out = torch.full_like(q, float("nan"))
     print(f"\n[backward] case {wl.name}: forward on the oracle's lists", flush=True)
-    I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], buf["mask"], out, ws)
+    if wl.gamma != 0:
+        I.isa_coarse_output(pr, buf["qc"], buf["kc"], buf["vc"], buf["oc"], ws)
+    I.isa_attend(pr, q, k, v, buf["kc"], buf["vc"], buf["kv"], buf["full"], buf["flat"], buf["mask"], out, ws,
+                 o_coarse=buf["oc"])
     torch.cuda.synchronize()
     dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
     print(f"[backward] case {wl.name}: backward", flush=True)
     I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws, buf["kv"], buf["full"], buf["flat"], buf["mask"])
     torch.cuda.synchronize()
     _compare(wl, Q, K, V, dO, plans, dq, dk, dv)
-    # kept-out context blocks get exact zeros
-    for b in range(wl.B):
+    # kept-out context blocks get exact zeros (without the coarse residual, which reaches every block)
+    for b in range(wl.B if wl.gamma == 0 else 0):
         for h in range(wl.H):
             plan = plans[b, h]
             kept = set(int(j) for j in plan["kv_list"])
@@ -125,11 +134,11 @@ def test_backward_on_oracle_lists(I, wl):
                     assert (dk[b, h, rows] == 0).all() and (dv[b, h, rows] == 0).all(), (b, h, j)
 
 
-@pytest.mark.parametrize("exact_frac", [0.0, 0.25])
-def test_backward_after_the_whole_call_and_reproducible(I, exact_frac):
+@pytest.mark.parametrize("exact_frac,gamma", [(0.0, 0.0), (0.25, 0.0), (0.25, 0.5)])
+def test_backward_after_the_whole_call_and_reproducible(I, exact_frac, gamma):
     """isa_attention leaves lists, exact-set bits and log-sum-exps in the workspace; the backward call with NULL lists
     uses them.  Two runs give bit-identical gradients (no atomics)."""
-    wl = SMALL.with_(exact_frac=exact_frac)
+    wl = SMALL.with_(exact_frac=exact_frac, gamma=gamma)
     Q, K, V, dO = _inputs(wl)
     q, k, v, d_out = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
     pr = problem_of(wl)
@@ -149,14 +158,14 @@ def test_backward_after_the_whole_call_and_reproducible(I, exact_frac):
 
 
 def test_backward_rejects_what_it_does_not_cover(I):
-    wl = SMALL
+    """Shapes the MFMA kernels do not cover (here D = 64, block = 64) have no backward pass."""
+    wl = RAGGED.with_(D=64, block=64)
     Q, K, V, dO = _inputs(wl)
     q = Q.cuda()
-    for kw in (dict(gamma=0.5),):
-        pr = problem_of(wl.with_(**kw))
-        ws = I.new_workspace(pr)
-        with pytest.raises(I.IsaError):
-            I.isa_attention_backward(pr, q, q, q, q, q, torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), ws)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    with pytest.raises(I.IsaError):
+        I.isa_attention_backward(pr, q, q, q, q, q, torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), ws)
 
 
 # ------------------------------------------------------------------------------------------------
@@ -248,3 +257,8 @@ def test_backward_full_size_paper_default_ratios_sampled(I):
     """The paper's default operating point (Sec. 4.1: alpha_s = 0.125, alpha_f = 0.5, alpha_ns = 0.0625) at the 480p shape:
     every Taylor block has an exact set of 18 kept blocks, so all three masked paths of the backward kernels run."""
     _full_size_sampled(I, W.CONFIGS["cfg2"].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625), 0, 12, seed=23)
+
+
+def test_backward_full_size_coarse_residual_sampled(I):
+    """cfg2 with the coarse residual of Alg. 1 Stage 5: its gradient reaches the keys and values of every block."""
+    _full_size_sampled(I, W.CONFIGS["cfg2"].with_(gamma=0.5), 0, 7, seed=24)
