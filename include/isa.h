@@ -164,15 +164,16 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
  * over its block's tokens).
  * q, k, v, out: as given to / written by the forward call; d_out: gradient of the loss with respect to `out`;
  * dq, dk, dv: receive the gradients.  All seven are device bf16 tensors with the layout and strides of the problem;
- * every row of dq, dk and dv is written (keys and values of context blocks that were not kept get zeros).
+ * every row of dq, dk and dv is written (with gamma == 0, keys and values of context blocks that were not kept get
+ * zeros).
  * kv_list, full_list, flat_list, exact_mask: the device lists (and, when exact_frac > 0, the exact-set bits, as written
  * by isa_select) the forward call ran with, or all NULL for those that isa_attention left in the workspace.
  * The workspace must be the one the forward call used, untouched since: it holds the log-sum-exp of every query row.
  * With gamma != 0 the gradient of the coarse residual (through the means of all blocks, query blocks included) is part
  * of the result.
  * Only for bf16, D = 128, block = 128 (and, when exact_frac > 0, at most 2048 blocks per batch item), and only after a
- * forward call that ran the MFMA kernels (ISA_ERR_UNSUPPORTED otherwise).  Asynchronous on hip_stream; fp32 accumulation, no atomics: results
- * are reproducible run to run. */
+ * forward call that ran the MFMA kernels (ISA_ERR_UNSUPPORTED otherwise).  Asynchronous on hip_stream; fp32
+ * accumulation, no atomics: results are reproducible run to run. */
 int isa_attention_backward(const isa_problem* p, const void* q, const void* k, const void* v, const void* out,
                            const void* d_out, const int32_t* kv_list, const int32_t* full_list,
                            const int32_t* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,

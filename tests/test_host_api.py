@@ -75,6 +75,18 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert L.isa_coarse_output(C.byref(cp), one, one, None, one, one, 1 << 40, None) == -1
     # a problem with a residual asks for room for the coarse output
     assert I.isa_workspace_bytes(base_problem(gamma=0.5)) > I.isa_workspace_bytes(base_problem())
+    # backward pass: every tensor is required; the lists come all together or not at all; with exact sets the bits come
+    # with them; shapes without MFMA kernels are unsupported (checked before the workspace is looked at)
+    bw = L.isa_attention_backward
+    mf, keep_m = base_problem(D=128, block=128, dtype="bf16").c_struct()
+    assert bw(C.byref(mf), one, one, one, one, None, None, None, None, None, one, one, one, one, 1 << 40, None) == -1
+    assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, None, one, 1 << 40, None) == -1
+    assert bw(C.byref(mf), one, one, one, one, one, one, None, one, None, one, one, one, one, 1 << 40, None) == -1
+    mx, keep_x = base_problem(D=128, block=128, dtype="bf16", exact_frac=0.25).c_struct()
+    assert bw(C.byref(mx), one, one, one, one, one, one, one, one, None, one, one, one, one, 1 << 40, None) == -1
+    assert bw(C.byref(cp), one, one, one, one, one, None, None, None, None, one, one, one, one, 1 << 40, None) == -5
+    assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, one, None, 1 << 40, None) == -6
+    assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, one, one, 16, None) == -6
 
 
 @pytest.mark.parametrize("seg,block,keep,full,exact", [
