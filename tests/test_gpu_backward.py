@@ -262,3 +262,75 @@ def test_backward_full_size_paper_default_ratios_sampled(I):
 def test_backward_full_size_coarse_residual_sampled(I):
     """cfg2 with the coarse residual of Alg. 1 Stage 5: its gradient reaches the keys and values of every block."""
     _full_size_sampled(I, W.CONFIGS["cfg2"].with_(gamma=0.5), 0, 7, seed=24)
+
+
+# ------------------------------------------------------------------------------------------------
+# layouts and graph capture
+# ------------------------------------------------------------------------------------------------
+def _forward_backward(I, pr, ws, q, k, v, d_out):
+    out = torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, out, ws)
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    return out, dq, dk, dv
+
+
+def test_backward_strided_layout(I):
+    """[B, S, H, D] storage viewed as [B, H, S, D]: the strides of the problem are honoured for every tensor."""
+    wl = SMALL.with_(exact_frac=0.25, gamma=0.5)
+    Q, K, V, dO = _inputs(wl)
+    q, k, v, d_out = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    ref = _forward_backward(I, pr, ws, q, k, v, d_out)
+    qs, ks, vs, ds = (t.transpose(1, 2).contiguous().transpose(1, 2) for t in (q, k, v, d_out))
+    assert qs.stride() != q.stride()
+    got = _forward_backward(I, pr, ws, qs, ks, vs, ds)
+    n = wl.tokens(0)
+    for a, b in zip(ref, got):
+        assert b.stride() == qs.stride() and torch.equal(a[:, :, :n], b[:, :, :n])
+
+
+def test_forward_and_backward_replay_from_a_hip_graph(I):
+    """Forward and backward only launch kernels on the caller's stream (no allocation, no host synchronisation, no
+    memset nodes), so the pair can be captured; every replay reproduces the eager gradients bit for bit, also after
+    the inputs change between replays."""
+    wl = SMALL.with_(exact_frac=0.25)
+    Q, K, V, dO = _inputs(wl)
+    q, k, v, d_out = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    eager = _forward_backward(I, pr, ws, q, k, v, d_out)
+    qs, ks, vs, ds = q.clone(), k.clone(), v.clone(), d_out.clone()
+    out, dq, dk, dv = (torch.zeros_like(q) for _ in range(4))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                       # warm-up on the capture stream
+        I.isa_attention(pr, qs, ks, vs, out, ws)
+        I.isa_attention_backward(pr, qs, ks, vs, out, ds, dq, dk, dv, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        I.isa_attention(pr, qs, ks, vs, out, ws)
+        I.isa_attention_backward(pr, qs, ks, vs, out, ds, dq, dk, dv, ws)
+    n = wl.tokens(0)
+    for rep in range(3):
+        for t in (out, dq, dk, dv):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, (out, dq, dk, dv)):
+            assert torch.equal(a[:, :, :n], b[:, :, :n]), rep
+        I.isa_dense_attention(pr, q, k, v, torch.empty_like(q), ws)     # eager work of our own between the replays
+        torch.cuda.synchronize()
+    # new inputs through the same graph: heads flipped
+    for dst, src in ((qs, q), (ks, k), (vs, v), (ds, d_out)):
+        dst.copy_(src.flip(1))
+    graph.replay()
+    torch.cuda.synchronize()
+    eager2 = _forward_backward(I, pr, ws, q.flip(1).contiguous(), k.flip(1).contiguous(), v.flip(1).contiguous(),
+                               d_out.flip(1).contiguous())
+    for a, b in zip(eager2, (out, dq, dk, dv)):
+        assert torch.equal(a[:, :, :n], b[:, :, :n])
