@@ -168,7 +168,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
 
   // ---- tile loads: global -> LDS, 16 bytes per lane, rows XOR-swizzled on the source side (the layouts of the forward
   // kernel: natural tiles 64 rows x 256 B, chunk c of row r at c ^ (r & 15); packed tiles as two units of 128 rows x
-  // 64 B, chunk c of row r at c ^ ((r >> 2) & 3))
+  // 64 B, chunk c of row r at c ^ ((r >> 1) & 3))
   const int l16 = lane >> 4;
   uint32_t nchunk_b[2];
   int nrow_l[2];
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   for (int i = 0; i < 2; ++i) {
     nrow_l[i] = 8 * wave + 4 * i + l16;
     nchunk_b[i] = (uint32_t)((((lane & 15) ^ (nrow_l[i] & 15)) * 8) * 2);
-    tlane_b[i] = (uint32_t)(((wave < 4 ? 0 : 32) + (((wave * 2 + i) & 7) * 16 + (lane >> 2)) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
+    tlane_b[i] = (uint32_t)(((wave < 4 ? 0 : 32) + (((wave * 2 + i) & 7) * 16 + (lane >> 2)) * KT + (((lane & 3) ^ ((lane >> 3) & 3)) * 8)) * 2);
   }
 
   // ---- the sequence of streamed tiles: phase p, tile T of the phase (token tiles: entry T / 2, half T % 2).
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) koff[ks] = r16 * MD + (((4 * ks + q) ^ r16) * 8);
-  const int voff = r16 * 32 + ((q ^ ((r16 >> 2) & 3)) * 8);
+  const int voff = r16 * 32 + ((q ^ ((r16 >> 1) & 3)) * 8);
 
   f32x4 acc[8][2];
 #pragma unroll

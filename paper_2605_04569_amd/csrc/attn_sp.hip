@@ -237,7 +237,7 @@ __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[
 template <bool taylor>
 __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
-  uint16_t* ldsV = lds + NBUF * K_TILE;     // shifted V^T tile T (keys 64T-32 .. 64T+31) lives in buffer T % NBUF
+  uint16_t* ldsV = lds + NBUF * K_TILE;     // V^T tile T lives in buffer T % NBUF
 
   // ---- which work item.  Workgroup ids go round-robin over the 8 XCDs, so XCD x sees ids x, x + 8, ... in
   // order.  Each XCD owns every 8th (batch, head) (`hpx` of them: batch items of different lengths are spread
@@ -387,11 +387,13 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
               lds_addr_of(ldsK + buf * K_TILE + (wave * 2 + i) * 512));
   };
   auto load_k = [&](const STile& t, int buf) { load_k1(t, buf, 0); load_k1(t, buf, 1); };
-  // Shifted V^T tile in LDS, unit-major: unit 0 = key positions 32..63 of tile `ta`, unit 1 = positions 0..31 of
-  // `tb`; a unit is 128 rows (channels) of 64 B, 16-byte chunk c of row r stored at chunk c ^ ((r >> 2) & 3).
-  // Waves 0-3 fill unit 0 and waves 4-7 unit 1, so the source tile of an instruction is wave-uniform and the
-  // per-lane part of the address is one constant: rows 16(2w+i mod 8) + lane/4, chunk (lane & 3) ^ (lane >> 4).
-  const uint32_t vlane_b = (uint32_t)(((lane >> 2) * KT + (((lane & 3) ^ (l16 & 3)) * 8)) * 2);
+  // V^T tile in LDS, unit-major: unit u = key positions 32 u .. 32 u + 31 of the tile; a unit is 128 rows (channels) of
+  // 64 B, 16-byte chunk c of row r stored at chunk c ^ ((r >> 1) & 3): with that swizzle the fragment reads of the value
+  // product are free of bank conflicts (measured with a probe kernel and the LDS bank-conflict counter; the more
+  // obvious c ^ ((r >> 2) & 3) conflicts two-way).  Waves 0-3 fill unit 0 and waves 4-7 unit 1, so the source tile of
+  // an instruction is wave-uniform and the per-lane part of the address is one constant: rows 16(2w+i mod 8) +
+  // lane/4, chunk (lane & 3) ^ ((lane >> 3) & 3).
+  const uint32_t vlane_b = (uint32_t)(((lane >> 2) * KT + (((lane & 3) ^ ((lane >> 3) & 3)) * 8)) * 2);
   auto load_v1 = [&](const uint16_t* vt, int buf, int i) {
     const uint16_t* srcu = vt + (wave < 4 ? 0 : 32);
     const char* sw = reinterpret_cast<const char*>(srcu + (((wave * 2 + i) & 7) * 16) * KT);
@@ -400,11 +402,11 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   auto load_v = [&](const uint16_t* vt, int buf) { load_v1(vt, buf, 0); load_v1(vt, buf, 1); };
 
   // per-lane fragment offsets (bf16 elements): K row r of a 16-key tile, chunk (4 ks + q) ^ r; V^T unit row r of a
-  // 16-channel tile, chunk q ^ ((r >> 2) & 3)
+  // 16-channel tile, chunk q ^ ((r >> 1) & 3)
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) koff[ks] = r16 * MD + (((4 * ks + q) ^ r16) * 8);
-  const int voff = r16 * 32 + ((q ^ ((r16 >> 2) & 3)) * 8);
+  const int voff = r16 * 32 + ((q ^ ((r16 >> 1) & 3)) * 8);
 
   f32x4 oacc[8][2];
   Scores s0, s1;
