@@ -162,7 +162,7 @@ hipError_t launch_block_means(const Problem& pr, const Workspace& ws, const void
 // One workgroup computes ROWS rows; it writes the context columns of the source rows to pctx (for
 // the column means of Eq. 1) and the sharpness of every row.
 // ------------------------------------------------------------------------------------------
-constexpr int CROWS = 4;
+constexpr int CROWS = 8;
 
 template <int D>
 __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, const float* __restrict__ kc,
@@ -269,6 +269,12 @@ hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc
   const int T_max = pr.cnt.T_max;
   const dim3 grid((T_max + CROWS - 1) / CROWS, pr.p.H, pr.p.B);
   const size_t lds = (size_t)CROWS * (pr.p.D + T_max) * sizeof(float);
+  if (lds > 64 * 1024) {                                // beyond the default limit of dynamic LDS (about 1900 blocks): ask for it
+    hipError_t ea = pr.p.D == 128
+        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&k_coarse<128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+        : hipFuncSetAttribute(reinterpret_cast<const void*>(&k_coarse<64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (ea != hipSuccess) return ea;
+  }
   if (pr.p.D == 128)
     hipLaunchKernelGGL((k_coarse<128>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, vc, ocoarse, pr.cnt, pr.p.H, pr.Tsrc_max,
                        pr.Tctx_max);

@@ -130,3 +130,13 @@ def test_split_work_items_small_dense(I):
             emax, emean = err_stats(got, want)
             assert emax <= tol_max and emean <= tol_mean, (h, lo, emax, emean)
     assert torch.isfinite(out[0, :, :n].float()).all()
+
+
+def test_maximum_block_count(I):
+    """4096 blocks per batch item (the library's limit: 524 288 tokens), with exact sets: the pooled-score kernel asks
+    for more than the default 64 KB of dynamic LDS, the exact-set rows are 128 words long."""
+    wl = W.Workload(name="max_blocks", B=1, H=1, D=128, dtype="bf16", block=128, src_grid=(64, 64, 64),
+                    ctx_grids=(((64, 64, 64),),), keep_ratio=0.1, full_frac=0.02, seed=91, exact_frac=0.01)
+    assert wl.tokens(0) == 4096 * 128
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(0,), blocks_per_head=1, seed=9, last_full=1)
