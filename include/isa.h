@@ -171,8 +171,8 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
  * The workspace must be the one the forward call used, untouched since: it holds the log-sum-exp of every query row.
  * With gamma != 0 the gradient of the coarse residual (through the means of all blocks, query blocks included) is part
  * of the result.
- * Only for bf16, D = 128, block = 128 (and, when exact_frac > 0, at most 2048 blocks per batch item), and only after a
- * forward call that ran the MFMA kernels (ISA_ERR_UNSUPPORTED otherwise).  Asynchronous on hip_stream; fp32
+ * Only for bf16, D = 128, block = 128, and only after a forward call that ran the MFMA kernels (ISA_ERR_UNSUPPORTED
+ * otherwise).  Asynchronous on hip_stream; fp32
  * accumulation, no atomics: results are reproducible run to run. */
 int isa_attention_backward(const isa_problem* p, const void* q, const void* k, const void* v, const void* out,
                            const void* d_out, const int32_t* kv_list, const int32_t* full_list,

@@ -147,13 +147,19 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   }
   // Exact-set bits of the stationary token blocks: lane L holds word L of the row of this wave's own entry and of the
   // pair's other entry (zeros for an entry that does not exist); handed out with readlane.
-  uint32_t bits_own = 0u, bits_other = 0u;
+  uint32_t bits_own = 0u, bits_other = 0u, bits_own_hi = 0u, bits_other_hi = 0u;     // words L and 64 + L
   if (EX && !SM) {
     const int e_other = 2 * item + (1 - grp);
     if (active && lane < a.mask_words) bits_own = a.bits[(bh * T_max + entry) * a.mask_words + lane];
+    if (active && lane + 64 < a.mask_words) bits_own_hi = a.bits[(bh * T_max + entry) * a.mask_words + lane + 64];
     if (e_other < n_stat && lane < a.mask_words) bits_other = a.bits[(bh * T_max + e_other) * a.mask_words + lane];
+    if (e_other < n_stat && lane + 64 < a.mask_words) bits_other_hi = a.bits[(bh * T_max + e_other) * a.mask_words + lane + 64];
   }
-  const uint32_t bits_any = bits_own | bits_other;
+  const uint32_t bits_any = bits_own | bits_other, bits_any_hi = bits_own_hi | bits_other_hi;
+  // word w (0..127) of a bit row held as (lo, hi)
+  auto word_of = [&](uint32_t lo, uint32_t hi, int w) __attribute__((always_inline)) -> uint32_t {
+    return w < 64 ? (uint32_t)__builtin_amdgcn_readlane((int)lo, w) : (uint32_t)__builtin_amdgcn_readlane((int)hi, min(w - 64, 63));
+  };
   // consume the prologue loads here: the waits the compiler places inside the loop must not cover them
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
@@ -164,7 +170,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     }
     asm volatile("" : "+v"(bxv[qt]), "+v"(dxv[qt]));
   }
-  if (EX) asm volatile("" : "+v"(bits_own), "+v"(bits_other));
+  if (EX) asm volatile("" : "+v"(bits_own), "+v"(bits_other), "+v"(bits_own_hi), "+v"(bits_other_hi));
 
   // ---- tile loads: global -> LDS, 16 bytes per lane, rows XOR-swizzled on the source side (the layouts of the forward
   // kernel: natural tiles 64 rows x 256 B, chunk c of row r at c ^ (r & 15); packed tiles as two units of 128 rows x
@@ -202,9 +208,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   auto next_linked = [&](int e0, int n_ent) __attribute__((always_inline)) -> int {
     int w = e0 >> 5;
     if (e0 >= n_ent) return n_ent;
-    uint32_t word = (uint32_t)__builtin_amdgcn_readlane((int)bits_any, w) & (~0u << (e0 & 31));
+    uint32_t word = word_of(bits_any, bits_any_hi, w) & (~0u << (e0 & 31));
     const int nw = (n_ent + 31) >> 5;
-    while (word == 0u && ++w < nw) word = (uint32_t)__builtin_amdgcn_readlane((int)bits_any, w);
+    while (word == 0u && ++w < nw) word = word_of(bits_any, bits_any_hi, w);
     if (word == 0u) return n_ent;
     return min(n_ent, w * 32 + __builtin_ctz(word));
   };
@@ -320,11 +326,11 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
       const int masked = PH(cur.p, ph_masked0, ph_masked1);
       if (!SM && masked == 1) {
         const int e = cur.T >> 1;
-        const bool linked = ((uint32_t)__builtin_amdgcn_readlane((int)bits_own, e >> 5) >> (e & 31)) & 1u;
+        const bool linked = (word_of(bits_own, bits_own_hi, e >> 5) >> (e & 31)) & 1u;
         gm_tile[0] = gm_tile[1] = linked ? 0.f : -INFINITY;
       } else if (!SM && masked == 2) {
-        pos_w0 = (uint32_t)__builtin_amdgcn_readlane((int)bits_own, 2 * cur.T);
-        pos_w1 = (uint32_t)__builtin_amdgcn_readlane((int)bits_own, min(2 * cur.T + 1, 63));
+        pos_w0 = word_of(bits_own, bits_own_hi, 2 * cur.T);
+        pos_w1 = word_of(bits_own, bits_own_hi, 2 * cur.T + 1);
       } else if (SM && masked == 3) {
         const int e = cur.T >> 1;
         if ((e >> 5) != sm_word_of) {
@@ -658,7 +664,7 @@ __global__ __launch_bounds__(128) void k_bwd_add_coarse(float* __restrict__ mean
 
 // Transposed exact-set bits: bit r of word r / 32 of row t is bit t of row r of `mask` (r: position in the Taylor list,
 // t: position in the kept list), so that a kept block finds the Taylor blocks that attend to its tokens.
-__global__ __launch_bounds__(64) void k_bwd_tmask(const uint32_t* __restrict__ mask, uint32_t* __restrict__ mask_t,
+__global__ __launch_bounds__(128) void k_bwd_tmask(const uint32_t* __restrict__ mask, uint32_t* __restrict__ mask_t,
                                                   Counts cnt, int H) {
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z, w = threadIdx.x;
   const int T_max = cnt.T_max, mw = cnt.mask_words;
@@ -733,7 +739,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
                      ws.ybd_flat, ws.ybd_mean, ws.bx_mean, pr.cnt, H, pr.Tn_pad, S_max);
   ISA_BWD_CHECK();
   if (ex) {
-    hipLaunchKernelGGL(k_bwd_tmask, dim3(T_max, H, B), dim3(64), 0, st, exact_mask, ws.mask_t, pr.cnt, H);
+    hipLaunchKernelGGL(k_bwd_tmask, dim3(T_max, H, B), dim3(128), 0, st, exact_mask, ws.mask_t, pr.cnt, H);
     ISA_BWD_CHECK();
   }
 

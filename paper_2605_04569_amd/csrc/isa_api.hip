@@ -348,9 +348,7 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
   const int n_lists = (kv_list != nullptr) + (full_list != nullptr) + (flat_list != nullptr);
   if (n_lists != 0 && n_lists != 3) return ISA_ERR_NULL;
   if (n_lists == 3 && p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
-  // the exact-set bits of a list are handed out 64 words at a time: at most 2048 blocks with exact sets
-  if (!pr.mfma_shape || !g_use_mfma.load() || (p->exact_frac > 0.0 && pr.cnt.mask_words > 64))
-    return ISA_ERR_UNSUPPORTED;
+  if (!pr.mfma_shape || !g_use_mfma.load()) return ISA_ERR_UNSUPPORTED;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;

@@ -334,3 +334,10 @@ def test_forward_and_backward_replay_from_a_hip_graph(I):
                                d_out.flip(1).contiguous())
     for a, b in zip(eager2, (out, dq, dk, dv)):
         assert torch.equal(a[:, :, :n], b[:, :, :n])
+
+
+def test_backward_maximum_block_count(I):
+    """4096 blocks per batch item with exact sets: exact-set rows of 128 words, 64 mean tiles."""
+    wl = W.Workload(name="max_blocks", B=1, H=1, D=128, dtype="bf16", block=128, src_grid=(64, 64, 64),
+                    ctx_grids=(((64, 64, 64),),), keep_ratio=0.1, full_frac=0.02, seed=91, exact_frac=0.01)
+    _full_size_sampled(I, wl, 0, 0, seed=25)
