@@ -1,11 +1,14 @@
 // Backward pass of In-Context Sparse Attention for bf16, D = 128, block = 128 on gfx950 (the paper states that the
 // operator is trainable, Sec. 4 "Implementation Detail and Analysis", and gives no formulas: these are the analytic
-// gradients of Alg. 1 Stage 4 with the index decisions of Stages 2 and 3 held fixed, exact sets empty, gamma = 0).
+// gradients of Alg. 1 Stages 4-5 with the index decisions of Stages 2 and 3 held fixed).
 //
 // With P = softmax weights of a query row (exact branch: over the tokens of the kept blocks; Taylor branch, Eq. 4: over
-// the kept blocks' mean keys, each weighted with its token count n_j), delta = rowsum(dO * O) and dP = dO V^T:
+// the kept blocks' mean keys, each weighted with its token count n_j, and, with exact sets, Alg. 2 Part A, over the
+// tokens of the block's exact set instead of their means), delta = rowsum(dO * O) and dP = dO V^T:
 //     dS = P * (dP - delta),   dQ = dS K / sqrt(D),   dK = dS^T Q / sqrt(D),   dV = P^T dO,
 // and the gradient of a block mean is spread evenly over the block's tokens (dK[t] += dKc[j] / n_j, same for V).
+// The coarse residual gamma * O_coarse (Stages 1 and 5) adds the gradient of a small T x T attention over the block
+// means (kernels at the end of this file), which enters the big launches through their epilogues.
 //
 // One kernel does all six products.  A workgroup (8 waves) keeps 2 x 128 "stationary" rows in registers and streams
 // 64-row tiles of the other side through LDS; per tile it forms T1 = Y1 X1^T (the scores) and, where dS is needed,
@@ -13,10 +16,12 @@
 // transposed copy of the streamed rows in the key order of the 16x16x32 accumulators (the same copy kernel and
 // the same operand layouts as the forward kernel).  The six launches:
 //     dQ, exact branch : stationary (Q, dO) of the full-attention blocks,  streamed K, V, K^T of the kept tokens
-//     dQ, Taylor branch: stationary (Q, dO) of the Taylor blocks,          streamed Kc, Vc, Kc^T (block means)
+//     dQ, Taylor branch: stationary (Q, dO) of the Taylor blocks,          streamed Kc, Vc, Kc^T (block means), after the
+//                        K, V, K^T tiles of the blocks' exact sets
 //     dKc, dVc         : stationary (Kc, Vc) / Kc rows,                    streamed Q, dO, Q^T / dO^T of the Taylor blocks
 //     dK, dV           : stationary (K, V) / K of the kept blocks,         streamed Q, dO, Q^T / dO^T of the full-attention
-//                        blocks; the epilogue adds the block's dKc / n_j (dVc / n_j) and writes bf16
+//                        blocks and of the Taylor blocks whose exact set holds the block; the epilogue adds the block's
+//                        dKc / n_j (dVc / n_j) and writes bf16
 // Every output element is written by exactly one workgroup: no atomics, results are reproducible.
 #include "attn_mfma.h"
 
