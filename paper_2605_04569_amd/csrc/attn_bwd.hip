@@ -305,6 +305,13 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) acc[ct][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const float cscale = 1.4426950408889634f / sqrtf((float)MD);       // log2(e) / sqrt(D)
+  f32x4 t1_init[2], t2_init[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float b0 = bxv[qt] / cscale;
+    t1_init[qt] = f32x4{b0, b0, b0, b0};
+    t2_init[qt] = f32x4{-dxv[qt], -dxv[qt], -dxv[qt], -dxv[qt]};
+  }
 
   // cur: tile being multiplied; nxt: tile whose loads are in flight; nn: tile whose table row is being fetched
   Cursor cur = settle(Cursor{0, 0});
@@ -354,7 +361,12 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) { t1[kt][qt] = f32x4{0.f, 0.f, 0.f, 0.f}; t2[kt][qt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        for (int qt = 0; qt < 2; ++qt) {
+          // the per-stationary-row terms ride in the accumulators: T1 starts at b_x / c (so that T1 c = scores c + b_x),
+          // T2 at -delta_x
+          t1[kt][qt] = EX ? t1_init[qt] + f32x4{gm_tile[qt], gm_tile[qt], gm_tile[qt], gm_tile[qt]} : t1_init[qt];
+          t2[kt][qt] = t2_init[qt];
+        }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -383,9 +395,8 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float ex = EX ? bd[i].x + bxv[qt] + gm_tile[qt] : bd[i].x + bxv[qt];
-            const float p = __builtin_amdgcn_exp2f(fmaf(t1[kt][qt][i], cscale, ex));
-            const float val = T2 ? p * (t2[kt][qt][i] - dxv[qt] - bd[i].y) : p;
+            const float p = __builtin_amdgcn_exp2f(fmaf(t1[kt][qt][i], cscale, bd[i].x));
+            const float val = T2 ? p * (t2[kt][qt][i] - bd[i].y) : p;
             w[qt][4 * kt + i] = (__bf16)val;
           }
       }
