@@ -179,6 +179,42 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
                            const int32_t* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- prologue: tile-order flattening and decoupled rotary embedding ------------------------ */
+
+/* Where the tokens of every segment sit and how they are to be embedded.
+ * The paper fixes that tokens are grouped into contiguous spatiotemporal tiles which are flattened in tile order before
+ * the sequence is cut into blocks (Sec. 2 "Block Sparse Attention"), and that the rotary embedding is applied to the
+ * source and to the context independently with the positions of each reset to zero (Sec. 4, third design choice of the
+ * editing model); tile shape and embedding layout are parameters here. */
+typedef struct isa_grid {
+  const int32_t* seg_grid; /* host [number of segments of the problem][3]: (t, h, w) of each segment, in the order of
+                              seg_len; t * h * w must equal the segment's length */
+  int32_t tile[3];         /* (tt, th, tw) >= 1: tile shape.  Tiles are enumerated row-major over tile coordinates
+                              (w fastest), tokens row-major inside a tile; tiles at the far edges of a grid that the shape
+                              does not divide are clipped */
+  int32_t rope_dims[3];    /* channels turned by the t, h and w coordinate: each even and >= 0, sum <= D; they occupy
+                              the head dimension in this order from channel 0, channels past the sum pass through */
+  double rope_theta;       /* base > 0: pair j (channels 2j, 2j+1) of an axis with d channels turns counter-clockwise by
+                              coordinate * rope_theta^(-2j/d) radians */
+} isa_grid;
+
+/* One streaming pass that prepares the operator's inputs.  q_in, k_in, v_in: device tensors of the problem's dtype,
+ * layout and strides whose segments are row-major over their grids (w fastest).  q_out, k_out, v_out (same layout and
+ * strides, distinct from the inputs): position p of a segment receives the p-th token of its tile order; q and k
+ * rotated by their grid coordinates counted from zero inside the segment, v unchanged.  qc, kc, vc: all NULL, or
+ * device fp32 [B, H, T_max, D] that receive the block means of the three outputs (of the stored, i.e. rounded, values),
+ * as isa_block_means would compute them from q_out, k_out, v_out: the first stage of Alg. 1 fused into the same pass.
+ * The ratios of `p` are not used.  Pointers must be 16-byte aligned.  No workspace; asynchronous on hip_stream.
+ * Errors: ISA_ERR_NULL; ISA_ERR_SHAPE for a grid that does not match its segment, a bad tile or rope_dims,
+ * a misaligned or aliased pointer; ISA_ERR_UNSUPPORTED for a non-positive or non-finite rope_theta. */
+int isa_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
+                 void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, void* hip_stream);
+
+/* The inverse reordering for one tensor (the operator's output on its way back to the model): x_tiled in tile order ->
+ * x_raster row-major per segment; same dtype, layout and strides, distinct buffers.  rope_dims and rope_theta are not
+ * used. */
+int isa_untile(const isa_problem* p, const isa_grid* grid, const void* x_tiled, void* x_raster, void* hip_stream);
+
 /* Name of a status code; never NULL. */
 const char* isa_strerror(int status);
 

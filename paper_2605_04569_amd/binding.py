@@ -34,6 +34,11 @@ class _CProblem(C.Structure):
                 ("keep_ratio", C.c_double), ("full_frac", C.c_double), ("exact_frac", C.c_double), ("gamma", C.c_double)]
 
 
+class _CGrid(C.Structure):
+    _fields_ = [("seg_grid", C.POINTER(C.c_int32)), ("tile", C.c_int32 * 3), ("rope_dims", C.c_int32 * 3),
+                ("rope_theta", C.c_double)]
+
+
 class _CCounts(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("S", "T", "T_src", "T_ctx", "k_keep", "T_new", "n_flat", "n_full", "k_exact",
                                          "T_max")]
@@ -62,6 +67,9 @@ def lib():
         L.isa_coarse_output.argtypes = [P, V, V, V, V, V, SZ, ST]
         L.isa_attend.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
         L.isa_attention_backward.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
+        G = C.POINTER(_CGrid)
+        L.isa_prologue.argtypes = [P, G, V, V, V, V, V, V, V, V, V, ST]
+        L.isa_untile.argtypes = [P, G, V, V, ST]
         L.isa_strerror.argtypes = [C.c_int]
         L.isa_strerror.restype = C.c_char_p
         L.isa_last_hip_error.argtypes = []
@@ -112,6 +120,25 @@ class Problem:
                        a_ptr, a_len, strides[0], strides[1], strides[2], self.keep_ratio, self.full_frac,
                        self.exact_frac, self.gamma)
         return cp, (a_ptr, a_len)
+
+
+@dataclass
+class Grid:
+    """Python mirror of isa_grid.  seg_grids[b] lists the (t, h, w) grid of every segment of batch item b."""
+    seg_grids: Sequence[Sequence[Sequence[int]]]
+    tile: Sequence[int]
+    rope_dims: Sequence[int] = (0, 0, 0)
+    rope_theta: float = 10000.0
+
+    def c_struct(self):
+        flat: List[int] = []
+        for grids in self.seg_grids:
+            for g in grids:
+                flat += [int(g[0]), int(g[1]), int(g[2])]
+        arr = (C.c_int32 * max(1, len(flat)))(*flat)
+        cg = _CGrid(arr, (C.c_int32 * 3)(*[int(x) for x in self.tile]),
+                    (C.c_int32 * 3)(*[int(x) for x in self.rope_dims]), float(self.rope_theta))
+        return cg, arr
 
 
 def _ptr(t):
@@ -236,3 +263,20 @@ def isa_attention_backward(pr: Problem, q, k, v, out, d_out, dq, dk, dv, workspa
                                         _ptr(workspace),
                                         workspace.numel(), _stream()), "isa_attention_backward")
     return dq, dk, dv
+
+
+def isa_prologue(pr: Problem, grid: Grid, q_in, k_in, v_in, q_out, k_out, v_out, qc=None, kc=None, vc=None):
+    _same_layout(q_in, k_in, v_in, q_out, k_out, v_out)
+    cp, keep = pr.c_struct(q_in)
+    cg, keep_g = grid.c_struct()
+    _check(lib().isa_prologue(C.byref(cp), C.byref(cg), _ptr(q_in), _ptr(k_in), _ptr(v_in), _ptr(q_out), _ptr(k_out),
+                              _ptr(v_out), _ptr(qc), _ptr(kc), _ptr(vc), _stream()), "isa_prologue")
+    return q_out, k_out, v_out
+
+
+def isa_untile(pr: Problem, grid: Grid, x_tiled, x_raster):
+    _same_layout(x_tiled, x_raster)
+    cp, keep = pr.c_struct(x_tiled)
+    cg, keep_g = grid.c_struct()
+    _check(lib().isa_untile(C.byref(cp), C.byref(cg), _ptr(x_tiled), _ptr(x_raster), _stream()), "isa_untile")
+    return x_raster

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libisa_hip.so")
-SOURCES = ["isa_api.hip", "kernels_small.hip", "attn_simt.hip", "attn_mfma.hip", "attn_sp.hip", "attn_bwd.hip"]
+SOURCES = ["isa_api.hip", "kernels_small.hip", "attn_simt.hip", "attn_mfma.hip", "attn_sp.hip", "attn_bwd.hip", "prologue.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -396,6 +396,61 @@ int isa_attention_simple(const void* q, const void* k, const void* v, int H, int
   return rc;
 }
 
+// Checks an isa_grid against the validated problem.
+static int check_grid(const Problem& pr, const isa_grid* g, bool rope) {
+  if (!g || !g->seg_grid) return ISA_ERR_NULL;
+  const int n_seg = pr.seg.seg_ptr[pr.p.B];
+  for (int s = 0; s < n_seg; ++s) {
+    const long long t = g->seg_grid[3 * s], h = g->seg_grid[3 * s + 1], w = g->seg_grid[3 * s + 2];
+    if (t < 0 || h < 0 || w < 0 || t > 0x7fffffffLL || h > 0x7fffffffLL || w > 0x7fffffffLL) return ISA_ERR_SHAPE;
+    if (t * h > 0x7fffffffLL || t * h * w != (long long)pr.seg.seg_len[s]) return ISA_ERR_SHAPE;
+  }
+  for (int a = 0; a < 3; ++a)
+    if (g->tile[a] < 1) return ISA_ERR_SHAPE;
+  if (rope) {
+    long long sum = 0;
+    for (int a = 0; a < 3; ++a) {
+      if (g->rope_dims[a] < 0 || g->rope_dims[a] % 2) return ISA_ERR_SHAPE;
+      sum += g->rope_dims[a];
+    }
+    if (sum > pr.p.D) return ISA_ERR_SHAPE;
+    if (!(g->rope_theta > 0.0) || !isfinite(g->rope_theta)) return ISA_ERR_UNSUPPORTED;
+  }
+  return ISA_OK;
+}
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int isa_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
+                 void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q_in || !k_in || !v_in || !q_out || !k_out || !v_out) return ISA_ERR_NULL;
+  if ((qc || kc || vc) && !(qc && kc && vc)) return ISA_ERR_NULL;
+  if ((rc = check_grid(pr, grid, true)) != ISA_OK) return rc;
+  const void* ins[3] = {q_in, k_in, v_in};
+  const void* outs[3] = {q_out, k_out, v_out};
+  for (int i = 0; i < 3; ++i) {
+    if (!aligned16(ins[i]) || !aligned16(outs[i])) return ISA_ERR_SHAPE;
+    for (int j = 0; j < 3; ++j)
+      if (outs[i] == ins[j] || (i != j && outs[i] == outs[j])) return ISA_ERR_SHAPE;
+  }
+  ISA_TRY(launch_prologue(pr, grid, q_in, k_in, v_in, q_out, k_out, v_out, qc, kc, vc, (hipStream_t)hip_stream));
+  return ISA_OK;
+}
+
+int isa_untile(const isa_problem* p, const isa_grid* grid, const void* x_tiled, void* x_raster, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!x_tiled || !x_raster) return ISA_ERR_NULL;
+  if ((rc = check_grid(pr, grid, false)) != ISA_OK) return rc;
+  if (!aligned16(x_tiled) || !aligned16(x_raster) || x_tiled == x_raster) return ISA_ERR_SHAPE;
+  ISA_TRY(launch_untile(pr, grid, x_tiled, x_raster, (hipStream_t)hip_stream));
+  return ISA_OK;
+}
+
 const char* isa_strerror(int status) {
   switch (status) {
     case ISA_OK: return "ISA_OK";

@@ -89,6 +89,40 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, one, one, 16, None) == -6
 
 
+def test_prologue_validation_needs_no_gpu():
+    L = I.lib()
+    pr = base_problem()                                   # segments 512 + 512
+    cp, keep = pr.c_struct()
+    a = [C.c_void_p(256 * (i + 1)) for i in range(9)]     # never dereferenced: every case fails before a launch
+
+    def call(grid, ptrs=None, means=(None, None, None)):
+        cg, keep_g = grid.c_struct()
+        ptrs = ptrs or a[:6]
+        return L.isa_prologue(C.byref(cp), C.byref(cg), *ptrs, *means, None)
+
+    good = dict(seg_grids=[[(4, 8, 16), (4, 8, 16)]], tile=(2, 4, 8), rope_dims=(16, 24, 24), rope_theta=10000.0)
+    assert call(I.Grid(**{**good, "seg_grids": [[(4, 8, 16), (4, 8, 15)]]})) == -2          # grid != segment length
+    assert call(I.Grid(**{**good, "tile": (2, 0, 8)})) == -2
+    assert call(I.Grid(**{**good, "rope_dims": (16, 25, 23)})) == -2                        # odd
+    assert call(I.Grid(**{**good, "rope_dims": (32, 24, 24)})) == -2                        # more than D = 64
+    assert call(I.Grid(**{**good, "rope_dims": (-2, 24, 24)})) == -2
+    assert call(I.Grid(**{**good, "rope_theta": 0.0})) == -5
+    assert call(I.Grid(**{**good, "rope_theta": float("nan")})) == -5
+    assert call(I.Grid(**good), ptrs=[a[0], a[1], a[2], a[3], a[4], None]) == -1
+    assert call(I.Grid(**good), ptrs=[a[0], a[1], a[2], a[0], a[4], a[5]]) == -2            # output aliases an input
+    assert call(I.Grid(**good), ptrs=[a[0], a[1], a[2], a[3], a[3], a[5]]) == -2            # two outputs alias
+    assert call(I.Grid(**good), ptrs=[C.c_void_p(264), a[1], a[2], a[3], a[4], a[5]]) == -2  # not 16-byte aligned
+    assert call(I.Grid(**good), means=(a[6], None, a[8])) == -1                             # means: all or none
+    assert L.isa_prologue(C.byref(cp), None, *a[:6], None, None, None, None) == -1
+    cg, keep_g = I.Grid(**good).c_struct()
+    assert L.isa_untile(C.byref(cp), C.byref(cg), a[0], None, None) == -1
+    assert L.isa_untile(C.byref(cp), C.byref(cg), a[0], a[0], None) == -2
+    bad, keep_b = I.Grid(**{**good, "tile": (0, 1, 1)}).c_struct()
+    assert L.isa_untile(C.byref(cp), C.byref(bad), a[0], a[1], None) == -2
+    no_rope, keep_n = I.Grid(**{**good, "rope_theta": -1.0, "rope_dims": (1, 1, 1)}).c_struct()
+    assert L.isa_untile(C.byref(cp), C.byref(no_rope), a[0], None, None) == -1             # embedding fields are not looked at
+
+
 @pytest.mark.parametrize("seg,block,keep,full,exact", [
     ([[512, 512]], 64, 0.5, 0.25, 0.0),
     ([[7800, 7800]], 128, 0.5, 0.25, 0.0625),
