@@ -21,6 +21,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, vendor figure
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E, vendor figure
+PROLOGUE_TILE = {128: (2, 8, 8), 64: (1, 8, 8)}       # one spatiotemporal tile = one block
+PROLOGUE_ROPE = {128: (44, 42, 42), 64: (16, 24, 24)}  # channels turned by the frame, row and column coordinate
 
 
 def log(msg):
@@ -92,7 +95,7 @@ def measured_traffic(workload):
     return None
 
 
-def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
+def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0):
     """Times isa_attention (whole call and the attention kernel alone) and dense attention on one workload."""
     import numpy as np
     import torch
@@ -185,6 +188,54 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
             log("dense attention backward: %.3f ms per call" % dense_bwd_ms)
         del d_out, dq, dk, dv
 
+    # ---- prologue: tile order + rotary embedding + block means in one pass (HBM-bound) ---------------------------
+    pro = None
+    if pro_steps > 0:
+        grid = isa.Grid([[wl.src_grid] + list(wl.ctx_grids[b]) for b in range(wl.B)], PROLOGUE_TILE[wl.block],
+                        PROLOGUE_ROPE[wl.D], 10000.0)
+        qo, ko, vo = (torch.empty_like(Q) for _ in range(3))
+        isa.isa_prologue(pr, grid, Q, K, V, qo, ko, vo, qc, kc, vc)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(pro_steps):
+            isa.isa_prologue(pr, grid, Q, K, V, qo, ko, vo, qc, kc, vc)
+        e1.record()
+        torch.cuda.synchronize()
+        pro_ms = e0.elapsed_time(e1) / pro_steps
+        e0.record()
+        for _ in range(pro_steps):                 # the same work as two passes: reorder + rotate, then the means
+            isa.isa_prologue(pr, grid, Q, K, V, qo, ko, vo)
+            isa.isa_block_means(pr, qo, ko, vo, qc, kc, vc, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        two_pass_ms = e0.elapsed_time(e1) / pro_steps
+        e0.record()
+        for _ in range(pro_steps):                 # the way back for the operator's output
+            isa.isa_untile(pr, grid, out, qo)
+        e1.record()
+        torch.cuda.synchronize()
+        untile_ms = e0.elapsed_time(e1) / pro_steps
+        e0.record()
+        for _ in range(pro_steps):                 # yardstick: a plain device-to-device copy of one tensor
+            qo.copy_(Q)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms = e0.elapsed_time(e1) / pro_steps
+        tokens = sum(wl.tokens(b) for b in range(wl.B))
+        blocks = sum(isa.isa_get_counts(pr, b)["T"] for b in range(wl.B))
+        nbytes = 6 * tokens * wl.H * wl.D * Q.element_size() + 3 * blocks * wl.H * wl.D * 4
+        pro = {"ms_per_call": round(pro_ms, 4), "algorithmic_gb": round(nbytes / 1e9, 3),
+               "achieved_gbs": round(nbytes / (pro_ms * 1e-3) / 1e9, 1), "peak_gbs": PEAK_HBM_GBS,
+               "frac_of_hbm_peak": round(nbytes / (pro_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+               "two_pass_ms_per_call": round(two_pass_ms, 4),
+               "untile_ms_per_call": round(untile_ms, 4),
+               "untile_gbs": round(2 * Q.numel() * Q.element_size() / (untile_ms * 1e-3) / 1e9, 1),
+               "plain_copy_gbs": round(2 * Q.numel() * Q.element_size() / (copy_ms * 1e-3) / 1e9, 1),
+               "tile": list(PROLOGUE_TILE[wl.block]), "rope_dims": list(PROLOGUE_ROPE[wl.D])}
+        del qo, ko, vo
+        log("isa_prologue: %.3f ms per call (%.0f GB/s); as two passes %.3f ms; isa_untile %.3f ms (%.0f GB/s); plain copy %.0f GB/s"
+            % (pro_ms, pro["achieved_gbs"], two_pass_ms, untile_ms, pro["untile_gbs"], pro["plain_copy_gbs"]))
+
     # ---- dense attention at the same shape --------------------------------------------------------
     dense_ms = None
     if dense_steps > 0:
@@ -202,7 +253,7 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0):
 
     del out, ws
     return {"ms_per_step": ms_per_step, "kern_ms": kern_ms, "kern_ms_min": float(np.min(kernel_ms)),
-            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "bwd_ms": bwd_ms, "dense_bwd_ms": dense_bwd_ms, "isa_fl": isa_fl, "dense_fl": dense_fl,
+            "kern_ms_median": float(np.median(kernel_ms)), "dense_ms": dense_ms, "bwd_ms": bwd_ms, "dense_bwd_ms": dense_bwd_ms, "prologue": pro, "isa_fl": isa_fl, "dense_fl": dense_fl,
             "inputs": (Q, K, V)}
 
 
@@ -214,6 +265,7 @@ def main():
     ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 (480p, default) | cfg3 | cfg4 (720p)")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--bwd-steps", type=int, default=3, help="timed calls of the backward pass on the main workload (0 = skip)")
+    ap.add_argument("--pro-steps", type=int, default=10, help="timed calls of the prologue on the main workload (0 = skip)")
     ap.add_argument("--exact-frac", type=float, default=None)
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--full-frac", type=float, default=None)
@@ -242,7 +294,7 @@ def main():
                               ("full_frac", args.full_frac), ("gamma", args.gamma)) if v is not None}
     if over:
         wl = wl.with_(**over)
-    r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps, args.bwd_steps)
+    r = measure(wl, args.steps, args.warmup, 0 if args.no_dense else args.dense_steps, args.bwd_steps, args.pro_steps)
     ms_per_step, kern_ms, dense_ms = r["ms_per_step"], r["kern_ms"], r["dense_ms"]
     kern_ms_min, kern_ms_median = r["kern_ms_min"], r["kern_ms_median"]
     isa_fl, dense_fl = r["isa_fl"], r["dense_fl"]
@@ -253,6 +305,7 @@ def main():
     cpu = None if args.no_cpu else cpu_baseline(wl, Q, K, V)
 
     r_dense_bwd = r["dense_bwd_ms"]
+    r_prologue = r["prologue"]
     del Q, K, V, r
     torch.cuda.empty_cache()
     others = []
@@ -315,6 +368,8 @@ def main():
             "frac_of_mfma_peak_algorithmic": round(2.5 * isa_fl / (r_bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
             "dense_backward_ms_per_call": None if r_dense_bwd is None else round(r_dense_bwd, 3),
             "speedup_vs_dense_backward": None if r_dense_bwd is None else round(r_dense_bwd / r_bwd_ms, 3)},
+        # the operator's inputs prepared from row-major, unrotated tensors: 2 x 3 tensors of traffic, HBM-bound
+        "prologue": r_prologue,
         "cpu_baseline": cpu,
         "other_workloads": others,
         "paper_context": "paper reports ~60% lower attention-module latency vs SDPA/FlashAttention (GPU not stated; Hopper implied)",

@@ -9,10 +9,11 @@
 // channels by the frame coordinate, the next rope_dims[1] by the row, the next rope_dims[2] by the column; pair j of an
 // axis with d channels turns by coordinate * theta^(-2j/d) radians.  V is only reordered.
 //
-// HBM-bound: one workgroup owns one output block (<= 128 tokens) of HPW heads, reads every token row once with 16-byte
+// HBM-bound: one workgroup owns one output block (<= 128 tokens) of a few heads, reads every token row once with 16-byte
 // loads (a row is D contiguous elements wherever it comes from, so the gather costs nothing in coalescing), rotates in
 // registers (the sines and cosines of a thread's pairs are computed once and reused for every head and for Q and K),
-// writes the row once and keeps the running sums for the block means.
+// writes the row once and keeps the running sums for the block means.  The rows of the next (head, tensor) pass are
+// loaded into a second set of registers while the current pass is rotated and stored.
 #include <math.h>
 #include <string.h>
 
@@ -20,7 +21,6 @@
 
 namespace isa {
 
-constexpr int HPW = 4;        // heads per workgroup
 constexpr int PBLOCK = 128;   // largest block
 
 struct GridDesc {             // passed to kernels by value
@@ -82,12 +82,11 @@ __device__ inline void tile_coords(int p, int t, int h, int w, int tt, int th, i
   *cw = c * tw + (p - lh * sw);
 }
 
-template <typename T> struct Row16;
+template <typename T> struct Row16;      // 16 bytes of a token row
 template <> struct Row16<float> {
   static constexpr int N = 4;
-  __device__ static void load(const float* p, float* o) {
-    const float4 v = *reinterpret_cast<const float4*>(p);
-    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  __device__ static void unpack(const uint4& v, float* o) {
+    o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y); o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
   }
   __device__ static void store(float* p, float* o) {       // o is left holding the stored values
     *reinterpret_cast<float4*>(p) = make_float4(o[0], o[1], o[2], o[3]);
@@ -95,8 +94,7 @@ template <> struct Row16<float> {
 };
 template <> struct Row16<uint16_t> {   // bf16 storage
   static constexpr int N = 8;
-  __device__ static void load(const uint16_t* p, float* o) {
-    const uint4 v = *reinterpret_cast<const uint4*>(p);
+  __device__ static void unpack(const uint4& v, float* o) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -122,12 +120,46 @@ template <> struct Row16<uint16_t> {   // bf16 storage
   }
 };
 
+// Loads the thread's 16-byte piece of TPT token rows (all in flight together).
+template <typename T, int TPT>
+__device__ __forceinline__ void load_rows(uint4 (&raw)[TPT], const T* ip, const int (&src)[TPT], long long stride_t) {
+#pragma unroll
+  for (int tk = 0; tk < TPT; ++tk) raw[tk] = *reinterpret_cast<const uint4*>(ip + (long long)src[tk] * stride_t);
+}
+
+// Rotates (if asked), stores and sums the rows that load_rows brought in; acc receives the column sums of what was stored.
+template <typename T, int TPT, int NP>
+__device__ __forceinline__ void finish_rows(const uint4 (&raw)[TPT], const float (&cs)[TPT][NP], const float (&sn)[TPT][NP],
+                                            bool rotate, unsigned valid, T* op, long long row_stride, long long stride_t,
+                                            float (&acc)[2 * NP]) {
+#pragma unroll
+  for (int i = 0; i < 2 * NP; ++i) acc[i] = 0.f;
+#pragma unroll
+  for (int tk = 0; tk < TPT; ++tk) {
+    float x[2 * NP];
+    Row16<T>::unpack(raw[tk], x);
+    if (rotate) {      // uniform
+#pragma unroll
+      for (int i = 0; i < NP; ++i) {
+        const float a0 = x[2 * i], a1 = x[2 * i + 1];
+        x[2 * i] = a0 * cs[tk][i] - a1 * sn[tk][i];
+        x[2 * i + 1] = a0 * sn[tk][i] + a1 * cs[tk][i];
+      }
+    }
+    if (valid >> tk & 1) {
+      Row16<T>::store(op + (long long)tk * row_stride * stride_t, x);
+#pragma unroll
+      for (int i = 0; i < 2 * NP; ++i) acc[i] += x[i];
+    }
+  }
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, const T* __restrict__ k_in,
                                                   const T* __restrict__ v_in, T* __restrict__ q_out,
                                                   T* __restrict__ k_out, T* __restrict__ v_out,
                                                   float* __restrict__ qc, float* __restrict__ kc,
-                                                  float* __restrict__ vc, SegDesc seg, GridDesc gd, Geometry g) {
+                                                  float* __restrict__ vc, SegDesc seg, GridDesc gd, Geometry g, int hpw) {
   constexpr int VEC = Row16<T>::N;
   constexpr int CH = D / VEC;            // 16-byte chunks per row
   constexpr int RP = 256 / CH;           // rows covered per pass
@@ -135,8 +167,8 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
   constexpr int NP = VEC / 2;            // channel pairs per thread
   __shared__ int s_src[PBLOCK];
   __shared__ int s_pos[PBLOCK][3];
-  __shared__ float red[RP][D];
-  const int j = blockIdx.x, b = blockIdx.z, h0 = blockIdx.y * HPW;
+  __shared__ float red[2][RP][D];
+  const int j = blockIdx.x, b = blockIdx.z, h0 = blockIdx.y * hpw;
   const BlockPos bp = locate_block(seg, gd, b, j, g.block);
   if (bp.n == 0) return;
   if (threadIdx.x < bp.n) {
@@ -148,7 +180,25 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
   __syncthreads();
 
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
-  // the thread's channel pairs: which coordinate turns them, and how fast
+  // the thread's rows: source token of each (rows past the block's end read the block's first token and are dropped)
+  int src[TPT];
+  unsigned valid = 0;
+#pragma unroll
+  for (int tk = 0; tk < TPT; ++tk) {
+    const int r = rg + tk * RP;
+    src[tk] = s_src[r < bp.n ? r : 0];
+    valid |= (r < bp.n ? 1u : 0u) << tk;
+  }
+  const int n_it = 3 * min(hpw, g.H - h0);        // (head, tensor) passes of this workgroup, q, k, v of a head in turn
+  const long long base0 = (long long)b * g.stride_b + (long long)h0 * g.stride_h + c * VEC;
+
+  // Two sets of landing registers: the rows of pass it + 1 are in flight while pass it is rotated and stored.
+  uint4 raw0[TPT], raw1[TPT];
+#define ISA_IN_PTR(it) ((((it) % 3) == 0 ? q_in : ((it) % 3) == 1 ? k_in : v_in) + base0 + (long long)((it) / 3) * g.stride_h)
+  load_rows<T, TPT>(raw0, ISA_IN_PTR(0), src, g.stride_t);
+
+  // the thread's channel pairs: which coordinate turns them, and how fast; then the sines and cosines of its rows
+  // (computed while the first rows are on their way)
   int axis[NP];
   double freq[NP];
 #pragma unroll
@@ -160,12 +210,10 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
     else if ((pr -= gd.rope_dims[1] / 2) < gd.rope_dims[2] / 2) { axis[i] = 2; d_a = gd.rope_dims[2]; }
     freq[i] = axis[i] < 0 ? 0.0 : exp2(-2.0 * (double)pr / (double)d_a * gd.log2_theta);
   }
-  int src[TPT];
   float cs[TPT][NP], sn[TPT][NP];
 #pragma unroll
   for (int tk = 0; tk < TPT; ++tk) {
     const int r = rg + tk * RP;
-    src[tk] = r < bp.n ? s_src[r] : -1;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       cs[tk][i] = 1.f; sn[tk][i] = 0.f;
@@ -178,65 +226,51 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
     }
   }
 
-  const T* in[3] = {q_in, k_in, v_in};
-  T* out[3] = {q_out, k_out, v_out};
-  float* mean[3] = {qc, kc, vc};
   const float inv_n = 1.0f / (float)bp.n;
-  for (int hh = 0; hh < HPW; ++hh) {
-    const int h = h0 + hh;
-    if (h >= g.H) break;
-    const long long base = (long long)b * g.stride_b + (long long)h * g.stride_h + c * VEC;
-    const long long mbase = (((long long)b * g.H + h) * g.T_max + j) * D;
-#pragma unroll
-    for (int t = 0; t < 3; ++t) {
-      float x[TPT][VEC];
-#pragma unroll
-      for (int tk = 0; tk < TPT; ++tk)
-        if (src[tk] >= 0) Row16<T>::load(in[t] + base + (long long)src[tk] * g.stride_t, x[tk]);
-      float acc[VEC];
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-#pragma unroll
-      for (int tk = 0; tk < TPT; ++tk) {
-        if (src[tk] < 0) continue;
-        if (t < 2) {
-#pragma unroll
-          for (int i = 0; i < NP; ++i) {
-            const float a0 = x[tk][2 * i], a1 = x[tk][2 * i + 1];
-            x[tk][2 * i] = a0 * cs[tk][i] - a1 * sn[tk][i];
-            x[tk][2 * i + 1] = a0 * sn[tk][i] + a1 * cs[tk][i];
-          }
-        }
-        Row16<T>::store(out[t] + base + (long long)(bp.start + rg + tk * RP) * g.stride_t, x[tk]);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] += x[tk][i];
-      }
-      if (mean[t]) {        // uniform
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) red[rg][c * VEC + i] = acc[i];
-        __syncthreads();
-        if (threadIdx.x < D) {
-          float s = 0.f;
-#pragma unroll
-          for (int r = 0; r < RP; ++r) s += red[r][threadIdx.x];
-          mean[t][mbase + threadIdx.x] = s * inv_n;
-        }
-      }
+  const bool means = qc != nullptr;
+  const long long orow = (long long)(bp.start + rg) * g.stride_t;
+  // the second half of a pass: the block means of what was just stored.  red[B] is next written two passes later,
+  // behind the barrier of the pass in between.
+#define ISA_PASS(RAW, B, it)                                                                                          \
+  {                                                                                                                   \
+    const int t_ = (it) % 3, hh_ = (it) / 3;                                                                          \
+    float acc_[VEC];                                                                                                  \
+    finish_rows<T, TPT, NP>(RAW, cs, sn, t_ < 2, valid,                                                               \
+                            (t_ == 0 ? q_out : t_ == 1 ? k_out : v_out) + base0 + (long long)hh_ * g.stride_h + orow,  \
+                            RP, g.stride_t, acc_);                                                                    \
+    if (means) {                                                                                                      \
+      _Pragma("unroll") for (int i = 0; i < VEC; ++i) red[B][rg][c * VEC + i] = acc_[i];                              \
+      __syncthreads();                                                                                                \
+      if (threadIdx.x < D) {                                                                                          \
+        float sum_ = 0.f;                                                                                             \
+        _Pragma("unroll") for (int r = 0; r < RP; ++r) sum_ += red[B][r][threadIdx.x];                                \
+        float* mp_ = t_ == 0 ? qc : t_ == 1 ? kc : vc;                                                                \
+        mp_[(((long long)b * g.H + h0 + hh_) * g.T_max + j) * D + threadIdx.x] = sum_ * inv_n;                        \
+      }                                                                                                               \
+    }                                                                                                                 \
+  }
+  for (int it = 0; it < n_it; it += 2) {
+    if (it + 1 < n_it) load_rows<T, TPT>(raw1, ISA_IN_PTR(it + 1), src, g.stride_t);
+    ISA_PASS(raw0, 0, it)
+    if (it + 1 < n_it) {
+      if (it + 2 < n_it) load_rows<T, TPT>(raw0, ISA_IN_PTR(it + 2), src, g.stride_t);
+      ISA_PASS(raw1, 1, it + 1)
     }
   }
+#undef ISA_PASS
+#undef ISA_IN_PTR
 }
 
 // Inverse reordering of one tensor: token p of the tile order goes back to its row-major place.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_untile(const T* __restrict__ x_tiled, T* __restrict__ x_raster, SegDesc seg,
-                                                GridDesc gd, Geometry g) {
+                                                GridDesc gd, Geometry g, int hpw) {
   constexpr int VEC = Row16<T>::N;
   constexpr int CH = D / VEC;
   constexpr int RP = 256 / CH;
   constexpr int TPT = PBLOCK / RP;
   __shared__ int s_src[PBLOCK];
-  const int j = blockIdx.x, b = blockIdx.z, h0 = blockIdx.y * HPW;
+  const int j = blockIdx.x, b = blockIdx.z, h0 = blockIdx.y * hpw;
   const BlockPos bp = locate_block(seg, gd, b, j, g.block);
   if (bp.n == 0) return;
   if (threadIdx.x < bp.n) {
@@ -249,7 +283,7 @@ __global__ __launch_bounds__(256) void k_untile(const T* __restrict__ x_tiled, T
   int src[TPT];
 #pragma unroll
   for (int tk = 0; tk < TPT; ++tk) src[tk] = rg + tk * RP < bp.n ? s_src[rg + tk * RP] : -1;
-  for (int hh = 0; hh < HPW; ++hh) {
+  for (int hh = 0; hh < hpw; ++hh) {
     const int h = h0 + hh;
     if (h >= g.H) break;
     const long long base = (long long)b * g.stride_b + (long long)h * g.stride_h + c * VEC;
@@ -263,6 +297,16 @@ __global__ __launch_bounds__(256) void k_untile(const T* __restrict__ x_tiled, T
     for (int tk = 0; tk < TPT; ++tk)
       if (src[tk] >= 0) *reinterpret_cast<uint4*>(x_raster + base + (long long)src[tk] * g.stride_t) = x[tk];
   }
+}
+
+// Heads per workgroup: as many as still leave about eight workgroups per compute unit (the per-block set-up, the sines
+// and cosines above all, is paid once per workgroup).
+static int heads_per_wg(const Problem& pr) {
+  const long long blocks = (long long)pr.cnt.T_max * pr.p.B;
+  long long hpw = blocks * pr.p.H / 2048;
+  if (hpw < 1) hpw = 1;
+  if (hpw > pr.p.H) hpw = pr.p.H;
+  return (int)hpw;
 }
 
 static GridDesc make_desc(const Problem& pr, const isa_grid* gr) {
@@ -279,10 +323,11 @@ static GridDesc make_desc(const Problem& pr, const isa_grid* gr) {
 hipError_t launch_prologue(const Problem& pr, const isa_grid* gr, const void* q_in, const void* k_in, const void* v_in,
                            void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, hipStream_t st) {
   const GridDesc gd = make_desc(pr, gr);
-  const dim3 grid(pr.cnt.T_max, (pr.p.H + HPW - 1) / HPW, pr.p.B), blk(256);
+  const int hpw = heads_per_wg(pr);
+  const dim3 grid(pr.cnt.T_max, (pr.p.H + hpw - 1) / hpw, pr.p.B), blk(256);
 #define ISA_PRO(T, D)                                                                                                \
   hipLaunchKernelGGL((k_prologue<T, D>), grid, blk, 0, st, (const T*)q_in, (const T*)k_in, (const T*)v_in, (T*)q_out, \
-                     (T*)k_out, (T*)v_out, qc, kc, vc, pr.seg, gd, pr.geo)
+                     (T*)k_out, (T*)v_out, qc, kc, vc, pr.seg, gd, pr.geo, hpw)
   if (pr.p.dtype == ISA_BF16) {
     if (pr.p.D == 128) ISA_PRO(uint16_t, 128); else ISA_PRO(uint16_t, 64);
   } else {
@@ -294,9 +339,10 @@ hipError_t launch_prologue(const Problem& pr, const isa_grid* gr, const void* q_
 
 hipError_t launch_untile(const Problem& pr, const isa_grid* gr, const void* x_tiled, void* x_raster, hipStream_t st) {
   const GridDesc gd = make_desc(pr, gr);
-  const dim3 grid(pr.cnt.T_max, (pr.p.H + HPW - 1) / HPW, pr.p.B), blk(256);
+  const int hpw = heads_per_wg(pr);
+  const dim3 grid(pr.cnt.T_max, (pr.p.H + hpw - 1) / hpw, pr.p.B), blk(256);
 #define ISA_UNT(T, D) \
-  hipLaunchKernelGGL((k_untile<T, D>), grid, blk, 0, st, (const T*)x_tiled, (T*)x_raster, pr.seg, gd, pr.geo)
+  hipLaunchKernelGGL((k_untile<T, D>), grid, blk, 0, st, (const T*)x_tiled, (T*)x_raster, pr.seg, gd, pr.geo, hpw)
   if (pr.p.dtype == ISA_BF16) {
     if (pr.p.D == 128) ISA_UNT(uint16_t, 128); else ISA_UNT(uint16_t, 64);
   } else {
