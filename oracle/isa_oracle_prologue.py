@@ -13,6 +13,8 @@ arrive flattened row-major, w fastest.  The prologue
      is cut into blocks);
   3. optionally returns the block means of the result (Alg. 1 Stage 1), which is what the first stage of the operator
      would compute from it.
+prologue_bwd_head is the transpose of steps 1-2 (the prologue's part of the backward pass)  [pinned: adjoint identity
+against the forward, exact inverse because the map is orthogonal, one pair by hand].
 Values are left untouched by step 1 (no positional rotation of V) and reordered by step 2.
 
 Readings taken where the paper is silent (listed with their reasons in the design notes of this repository):
@@ -108,6 +110,30 @@ def prologue_head(Q, K, V, seg_grids, tile, rope_dims, theta):
         outs[2][start:start + n] = V[start:start + n][perm]
         start += n
     assert start == Q.shape[0]
+    return tuple(outs)
+
+
+def prologue_bwd_head(dQo, dKo, dVo, seg_grids, tile, rope_dims, theta):
+    """Gradient of a loss with respect to the prologue's inputs, given its gradient with respect to the outputs, for one
+    (batch, head) slice.  The prologue is linear: a rotation of every channel pair (Q, K only) followed by a reordering
+    of the tokens, so its transpose puts row p back at its row-major place and turns every pair the other way.
+    Returns (dQ, dK, dV) [S, D] in row-major order per segment."""
+    dQo = np.asarray(dQo, dtype=np.float64)
+    dKo = np.asarray(dKo, dtype=np.float64)
+    dVo = np.asarray(dVo, dtype=np.float64)
+    D = dQo.shape[1]
+    outs = [np.empty_like(dQo), np.empty_like(dKo), np.empty_like(dVo)]
+    start = 0
+    for grid in seg_grids:
+        n = grid[0] * grid[1] * grid[2]
+        ang = rope_angles(grid_coords(grid), D, rope_dims, theta)
+        perm = tile_order(grid, tile)
+        for o, g, rotated in ((outs[0], dQo, True), (outs[1], dKo, True), (outs[2], dVo, False)):
+            back = np.empty((n, D), dtype=np.float64)
+            back[perm] = g[start:start + n]                    # row p of the tile order came from row perm[p]
+            o[start:start + n] = rope_rotate(back, -ang) if rotated else back
+        start += n
+    assert start == dQo.shape[0]
     return tuple(outs)
 
 

@@ -144,3 +144,34 @@ def test_rotation_and_reordering_commute_as_stated():
         expect[4:6] = rot2(h * 10000.0 ** (-0.5)) @ Q[src, 4:6]
         expect[6:8] = rot2(w * 1.0) @ Q[src, 6:8]
         np.testing.assert_allclose(Qo[p], expect, atol=1e-13)
+
+
+# ---------------------------------------------------------------- backward of the prologue
+def test_backward_is_the_adjoint_and_the_inverse():
+    rng = np.random.default_rng(8)
+    grids, tile, dims = [(3, 4, 6), (1, 5, 3), (2, 2, 2)], (2, 3, 4), (4, 2, 6)
+    S = 72 + 15 + 8
+    X = [rng.standard_normal((S, 12)) for _ in range(3)]
+    Y = [rng.standard_normal((S, 12)) for _ in range(3)]
+    F = P.prologue_head(*X, grids, tile, dims, 10000.0)
+    G = P.prologue_bwd_head(*Y, grids, tile, dims, 10000.0)
+    for x, y, f, g in zip(X, Y, F, G):
+        np.testing.assert_allclose((f * y).sum(), (x * g).sum(), rtol=1e-12)        # <A x, y> = <x, A^T y>
+    back = P.prologue_bwd_head(*F, grids, tile, dims, 10000.0)                        # orthogonal map: A^T A = I
+    for x, b in zip(X, back):
+        np.testing.assert_allclose(b, x, atol=1e-13)
+
+
+def test_backward_by_hand():
+    # 1 x 1 x 2 grid, whole-grid tile (order unchanged), one pair turning with w at frequency 1: token 1 turns by one
+    # radian forward, so its gradient turns back by one radian: (1, 0) -> (cos 1, -sin 1)
+    g = np.array([[1.0, 0.0], [1.0, 0.0]])
+    dq, dk, dv = P.prologue_bwd_head(g, g, g, [(1, 1, 2)], (1, 1, 2), (0, 0, 2), 10000.0)
+    np.testing.assert_allclose(dq[0], [1.0, 0.0], atol=1e-15)
+    np.testing.assert_allclose(dq[1], [0.5403023058681398, -0.8414709848078965], atol=1e-15)
+    np.testing.assert_allclose(dk, dq, atol=0)
+    np.testing.assert_allclose(dv, g, atol=0)
+    # reordering alone: 1 x 2 x 4 grid with 1 x 2 x 2 tiles; output row p came from input row [0, 1, 4, 5, 2, 3, 6, 7][p]
+    y = np.arange(8, dtype=np.float64).reshape(8, 1) * np.ones((1, 2))
+    _, _, dv = P.prologue_bwd_head(y, y, y, [(1, 2, 4)], (1, 2, 2), (0, 0, 0), 10000.0)
+    assert dv[:, 0].tolist() == [0, 1, 4, 5, 2, 3, 6, 7]      # input row 4 receives the gradient of output row 2, etc.
