@@ -215,6 +215,14 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0):
         e1.record()
         torch.cuda.synchronize()
         untile_ms = e0.elapsed_time(e1) / pro_steps
+        dqi, dki, dvi = (torch.empty_like(Q) for _ in range(3))
+        e0.record()
+        for _ in range(pro_steps):                 # the prologue's backward: its transpose, here applied to its outputs
+            isa.isa_prologue_backward(pr, grid, qo, ko, vo, dqi, dki, dvi)
+        e1.record()
+        torch.cuda.synchronize()
+        pro_bwd_ms = e0.elapsed_time(e1) / pro_steps
+        del dqi, dki, dvi
         e0.record()
         for _ in range(pro_steps):                 # yardstick: a plain device-to-device copy of one tensor
             qo.copy_(Q)
@@ -228,13 +236,15 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0):
                "achieved_gbs": round(nbytes / (pro_ms * 1e-3) / 1e9, 1), "peak_gbs": PEAK_HBM_GBS,
                "frac_of_hbm_peak": round(nbytes / (pro_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                "two_pass_ms_per_call": round(two_pass_ms, 4),
+               "backward_ms_per_call": round(pro_bwd_ms, 4),
+               "backward_gbs": round(6 * Q.numel() * Q.element_size() / (pro_bwd_ms * 1e-3) / 1e9, 1),
                "untile_ms_per_call": round(untile_ms, 4),
                "untile_gbs": round(2 * Q.numel() * Q.element_size() / (untile_ms * 1e-3) / 1e9, 1),
                "plain_copy_gbs": round(2 * Q.numel() * Q.element_size() / (copy_ms * 1e-3) / 1e9, 1),
                "tile": list(PROLOGUE_TILE[wl.block]), "rope_dims": list(PROLOGUE_ROPE[wl.D])}
         del qo, ko, vo
-        log("isa_prologue: %.3f ms per call (%.0f GB/s); as two passes %.3f ms; isa_untile %.3f ms (%.0f GB/s); plain copy %.0f GB/s"
-            % (pro_ms, pro["achieved_gbs"], two_pass_ms, untile_ms, pro["untile_gbs"], pro["plain_copy_gbs"]))
+        log("isa_prologue: %.3f ms per call (%.0f GB/s); as two passes %.3f ms; backward %.3f ms; isa_untile %.3f ms (%.0f GB/s); plain copy %.0f GB/s"
+            % (pro_ms, pro["achieved_gbs"], two_pass_ms, pro_bwd_ms, untile_ms, pro["untile_gbs"], pro["plain_copy_gbs"]))
 
     # ---- dense attention at the same shape --------------------------------------------------------
     dense_ms = None

@@ -210,6 +210,16 @@ typedef struct isa_grid {
 int isa_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
                  void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, void* hip_stream);
 
+/* Backward pass of isa_prologue: the prologue is linear (a rotation of every channel pair of q and k, then a reordering of
+ * the tokens), so the gradient with respect to its inputs is its transpose applied to the gradient with respect to its
+ * outputs: row p of a segment's tile order goes back to its row-major place, and every pair of dq and dk turns the other
+ * way.  dq_out, dk_out, dv_out: gradients with respect to q_out, k_out, v_out (what isa_attention_backward returns when
+ * the operator ran on the prologue's outputs); dq_in, dk_in, dv_in receive the gradients with respect to q_in, k_in, v_in.
+ * Same dtype, layout, strides, alignment and aliasing rules as isa_prologue.  The fused block means need no term of their
+ * own: isa_attention_backward already returns the gradient through the means as part of dq, dk, dv. */
+int isa_prologue_backward(const isa_problem* p, const isa_grid* grid, const void* dq_out, const void* dk_out,
+                          const void* dv_out, void* dq_in, void* dk_in, void* dv_in, void* hip_stream);
+
 /* The inverse reordering for one tensor (the operator's output on its way back to the model): x_tiled in tile order ->
  * x_raster row-major per segment; same dtype, layout and strides, distinct buffers.  rope_dims and rope_theta are not
  * used. */

@@ -69,6 +69,7 @@ def lib():
         L.isa_attention_backward.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, V, SZ, ST]
         G = C.POINTER(_CGrid)
         L.isa_prologue.argtypes = [P, G, V, V, V, V, V, V, V, V, V, ST]
+        L.isa_prologue_backward.argtypes = [P, G, V, V, V, V, V, V, ST]
         L.isa_untile.argtypes = [P, G, V, V, ST]
         L.isa_strerror.argtypes = [C.c_int]
         L.isa_strerror.restype = C.c_char_p
@@ -280,3 +281,12 @@ def isa_untile(pr: Problem, grid: Grid, x_tiled, x_raster):
     cg, keep_g = grid.c_struct()
     _check(lib().isa_untile(C.byref(cp), C.byref(cg), _ptr(x_tiled), _ptr(x_raster), _stream()), "isa_untile")
     return x_raster
+
+
+def isa_prologue_backward(pr: Problem, grid: Grid, dq_out, dk_out, dv_out, dq_in, dk_in, dv_in):
+    _same_layout(dq_out, dk_out, dv_out, dq_in, dk_in, dv_in)
+    cp, keep = pr.c_struct(dq_out)
+    cg, keep_g = grid.c_struct()
+    _check(lib().isa_prologue_backward(C.byref(cp), C.byref(cg), _ptr(dq_out), _ptr(dk_out), _ptr(dv_out), _ptr(dq_in),
+                                       _ptr(dk_in), _ptr(dv_in), _stream()), "isa_prologue_backward")
+    return dq_in, dk_in, dv_in

@@ -421,8 +421,9 @@ static int check_grid(const Problem& pr, const isa_grid* g, bool rope) {
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-int isa_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
-                 void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, void* hip_stream) {
+static int run_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
+                        void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, bool inverse,
+                        void* hip_stream) {
   Problem pr;
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
@@ -436,8 +437,18 @@ int isa_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, c
     for (int j = 0; j < 3; ++j)
       if (outs[i] == ins[j] || (i != j && outs[i] == outs[j])) return ISA_ERR_SHAPE;
   }
-  ISA_TRY(launch_prologue(pr, grid, q_in, k_in, v_in, q_out, k_out, v_out, qc, kc, vc, (hipStream_t)hip_stream));
+  ISA_TRY(launch_prologue(pr, grid, q_in, k_in, v_in, q_out, k_out, v_out, qc, kc, vc, inverse, (hipStream_t)hip_stream));
   return ISA_OK;
+}
+
+int isa_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
+                 void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, void* hip_stream) {
+  return run_prologue(p, grid, q_in, k_in, v_in, q_out, k_out, v_out, qc, kc, vc, false, hip_stream);
+}
+
+int isa_prologue_backward(const isa_problem* p, const isa_grid* grid, const void* dq_out, const void* dk_out,
+                          const void* dv_out, void* dq_in, void* dk_in, void* dv_in, void* hip_stream) {
+  return run_prologue(p, grid, dq_out, dk_out, dv_out, dq_in, dk_in, dv_in, nullptr, nullptr, nullptr, true, hip_stream);
 }
 
 int isa_untile(const isa_problem* p, const isa_grid* grid, const void* x_tiled, void* x_raster, void* hip_stream) {

@@ -129,9 +129,11 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
                            const int* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
                            hipStream_t st);
 
-// prologue (prologue.hip): tile order, rotary embedding and block means in one pass; the inverse reordering
+// prologue (prologue.hip): tile order, rotary embedding and block means in one pass (inverse: its transpose, no means);
+// the inverse reordering of one tensor
 hipError_t launch_prologue(const Problem& pr, const isa_grid* gr, const void* q_in, const void* k_in, const void* v_in,
-                           void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, hipStream_t st);
+                           void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, bool inverse,
+                           hipStream_t st);
 hipError_t launch_untile(const Problem& pr, const isa_grid* gr, const void* x_tiled, void* x_raster, hipStream_t st);
 
 }  // namespace isa

@@ -130,7 +130,7 @@ __device__ __forceinline__ void load_rows(uint4 (&raw)[TPT], const T* ip, const 
 // Rotates (if asked), stores and sums the rows that load_rows brought in; acc receives the column sums of what was stored.
 template <typename T, int TPT, int NP>
 __device__ __forceinline__ void finish_rows(const uint4 (&raw)[TPT], const float (&cs)[TPT][NP], const float (&sn)[TPT][NP],
-                                            bool rotate, unsigned valid, T* op, long long row_stride, long long stride_t,
+                                            bool rotate, unsigned valid, T* op, const int (&dst)[TPT], long long stride_t,
                                             float (&acc)[2 * NP]) {
 #pragma unroll
   for (int i = 0; i < 2 * NP; ++i) acc[i] = 0.f;
@@ -147,7 +147,7 @@ __device__ __forceinline__ void finish_rows(const uint4 (&raw)[TPT], const float
       }
     }
     if (valid >> tk & 1) {
-      Row16<T>::store(op + (long long)tk * row_stride * stride_t, x);
+      Row16<T>::store(op + (long long)dst[tk] * stride_t, x);
 #pragma unroll
       for (int i = 0; i < 2 * NP; ++i) acc[i] += x[i];
     }
@@ -159,7 +159,8 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
                                                   const T* __restrict__ v_in, T* __restrict__ q_out,
                                                   T* __restrict__ k_out, T* __restrict__ v_out,
                                                   float* __restrict__ qc, float* __restrict__ kc,
-                                                  float* __restrict__ vc, SegDesc seg, GridDesc gd, Geometry g, int hpw) {
+                                                  float* __restrict__ vc, SegDesc seg, GridDesc gd, Geometry g, int hpw,
+                                                  int inverse) {
   constexpr int VEC = Row16<T>::N;
   constexpr int CH = D / VEC;            // 16-byte chunks per row
   constexpr int RP = 256 / CH;           // rows covered per pass
@@ -180,13 +181,17 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
   __syncthreads();
 
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
-  // the thread's rows: source token of each (rows past the block's end read the block's first token and are dropped)
-  int src[TPT];
+  // the thread's rows: where each is read and where it is written (rows past the block's end re-read the block's first
+  // row and are dropped).  Forward: gathered from the row-major place, written at the tile-order place; the inverse
+  // direction (the transpose, used for gradients) swaps the two.
+  int src[TPT], dst[TPT];
   unsigned valid = 0;
 #pragma unroll
   for (int tk = 0; tk < TPT; ++tk) {
-    const int r = rg + tk * RP;
-    src[tk] = s_src[r < bp.n ? r : 0];
+    const int r = rg + tk * RP, rc = r < bp.n ? r : 0;
+    const int raster = s_src[rc], tiled = bp.start + rc;
+    src[tk] = inverse ? tiled : raster;
+    dst[tk] = inverse ? raster : tiled;
     valid |= (r < bp.n ? 1u : 0u) << tk;
   }
   const int n_it = 3 * min(hpw, g.H - h0);        // (head, tensor) passes of this workgroup, q, k, v of a head in turn
@@ -219,16 +224,16 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
       cs[tk][i] = 1.f; sn[tk][i] = 0.f;
       if (r < bp.n && axis[i] >= 0) {
         const int pos = axis[i] == 0 ? s_pos[r][0] : axis[i] == 1 ? s_pos[r][1] : s_pos[r][2];
-        double ang = (double)pos * freq[i];
-        ang -= 6.283185307179586476925 * rint(ang * 0.1591549430918953357689);     // into [-pi, pi]
-        sincosf((float)ang, &sn[tk][i], &cs[tk][i]);
+        double turns = (double)pos * freq[i] * 0.1591549430918953357689;          // angle / 2 pi
+        turns -= rint(turns);                                                        // into [-1/2, 1/2]
+        sincospif((float)(2.0 * turns), &sn[tk][i], &cs[tk][i]);
+        if (inverse) sn[tk][i] = -sn[tk][i];                                         // turn back
       }
     }
   }
 
   const float inv_n = 1.0f / (float)bp.n;
   const bool means = qc != nullptr;
-  const long long orow = (long long)(bp.start + rg) * g.stride_t;
   // the second half of a pass: the block means of what was just stored.  red[B] is next written two passes later,
   // behind the barrier of the pass in between.
 #define ISA_PASS(RAW, B, it)                                                                                          \
@@ -236,8 +241,8 @@ __global__ __launch_bounds__(256) void k_prologue(const T* __restrict__ q_in, co
     const int t_ = (it) % 3, hh_ = (it) / 3;                                                                          \
     float acc_[VEC];                                                                                                  \
     finish_rows<T, TPT, NP>(RAW, cs, sn, t_ < 2, valid,                                                               \
-                            (t_ == 0 ? q_out : t_ == 1 ? k_out : v_out) + base0 + (long long)hh_ * g.stride_h + orow,  \
-                            RP, g.stride_t, acc_);                                                                    \
+                            (t_ == 0 ? q_out : t_ == 1 ? k_out : v_out) + base0 + (long long)hh_ * g.stride_h,         \
+                            dst, g.stride_t, acc_);                                                                    \
     if (means) {                                                                                                      \
       _Pragma("unroll") for (int i = 0; i < VEC; ++i) red[B][rg][c * VEC + i] = acc_[i];                              \
       __syncthreads();                                                                                                \
@@ -321,13 +326,14 @@ static GridDesc make_desc(const Problem& pr, const isa_grid* gr) {
 }
 
 hipError_t launch_prologue(const Problem& pr, const isa_grid* gr, const void* q_in, const void* k_in, const void* v_in,
-                           void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, hipStream_t st) {
+                           void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, bool inverse,
+                           hipStream_t st) {
   const GridDesc gd = make_desc(pr, gr);
   const int hpw = heads_per_wg(pr);
   const dim3 grid(pr.cnt.T_max, (pr.p.H + hpw - 1) / hpw, pr.p.B), blk(256);
 #define ISA_PRO(T, D)                                                                                                \
   hipLaunchKernelGGL((k_prologue<T, D>), grid, blk, 0, st, (const T*)q_in, (const T*)k_in, (const T*)v_in, (T*)q_out, \
-                     (T*)k_out, (T*)v_out, qc, kc, vc, pr.seg, gd, pr.geo, hpw)
+                     (T*)k_out, (T*)v_out, qc, kc, vc, pr.seg, gd, pr.geo, hpw, inverse ? 1 : 0)
   if (pr.p.dtype == ISA_BF16) {
     if (pr.p.D == 128) ISA_PRO(uint16_t, 128); else ISA_PRO(uint16_t, 64);
   } else {

@@ -120,6 +120,66 @@ def test_untile_matches_oracle_and_inverts(I, wl):
             assert float((back[b, :, n:] - 9.0).abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("tile", [(2, 8, 8), (3, 5, 7)], ids=lambda t: "x".join(map(str, t)))
+@pytest.mark.parametrize("wl", CASES, ids=lambda c: c.name)
+def test_prologue_backward_matches_oracle_everywhere(I, wl, tile):
+    """The transpose of the prologue on seeded gradients (the generator's Q, K, V stand in for dq_out, dk_out, dv_out)."""
+    G = W.make_inputs(wl.with_(seed=wl.seed + 500), "cpu")
+    pr = problem_of(wl)
+    grid = I.Grid(grids_of(wl), tile, ROPE[wl.D], 10000.0)
+    g_dev = [x.cuda() for x in G]
+    d_in = [torch.full_like(x, 7.0) for x in g_dev]
+    I.isa_prologue_backward(pr, grid, *g_dev, *d_in)
+    torch.cuda.synchronize()
+    for b in range(wl.B):
+        n = wl.tokens(b)
+        for h in range(wl.H):
+            want = P.prologue_bwd_head(*(f64(x[b, h, :n]) for x in G), grids_of(wl)[b], tile, ROPE[wl.D], 10000.0)
+            for name, got_t, w in zip("qkv", d_in, want):
+                got = f64(got_t[b, h, :n])
+                if name == "v":
+                    assert np.array_equal(got, w), (wl.name, b, h)
+                else:
+                    bad = np.abs(got - w) > tolerances(wl, w)
+                    assert not bad.any(), (wl.name, name, b, h, int(bad.sum()), float(np.abs(got - w).max()))
+            if n < d_in[0].shape[2]:
+                assert float((d_in[0][b, h, n:] - 7.0).abs().max()) == 0.0
+
+
+def test_prologue_backward_inverts_the_prologue_at_full_size(I):
+    """480p: the map is orthogonal, so the backward applied to the forward's output returns the input up to the two
+    roundings to bf16 on the way (2^-8 relative of a pair's norm), and V bit for bit; sampled rows against the oracle."""
+    wl = W.CONFIGS["cfg2"]
+    tile, dims = (2, 8, 8), ROPE[128]
+    pr = problem_of(wl)
+    grid = I.Grid(grids_of(wl), tile, dims, 10000.0)
+    q, k, v = W.make_inputs(wl, "cuda")
+    qo, ko, vo = (torch.empty_like(x) for x in (q, k, v))
+    I.isa_prologue(pr, grid, q, k, v, qo, ko, vo)
+    qb, kb, vb = (torch.empty_like(x) for x in (q, k, v))
+    I.isa_prologue_backward(pr, grid, qo, ko, vo, qb, kb, vb)
+    torch.cuda.synchronize()
+    assert torch.equal(vb, v)
+    for x, xb in ((q, qb), (k, kb)):
+        for h in (0, 21, 39):
+            a, bb = x[0, h].float(), xb[0, h].float()
+            norm = (a.view(-1, 64, 2) ** 2).sum(-1).sqrt().repeat_interleave(2, dim=1).view_as(a)
+            assert bool(((a - bb).abs() <= 2.0 ** -7 * norm + 1e-6).all()), h
+    g = wl.src_grid
+    n_seg = g[0] * g[1] * g[2]
+    perm = P.tile_order(g, tile)
+    coords = P.grid_coords(g)
+    rng = np.random.default_rng(6)
+    rows = np.concatenate([[0, 1, 127, 128, n_seg - 1], rng.integers(0, n_seg, 200)])     # positions in tile order
+    src = perm[rows]
+    ang = P.rope_angles(coords[src], wl.D, dims, 10000.0)
+    for h in (3, 38):
+        for seg in range(2):
+            want = P.rope_rotate(f64(qo[0, h, seg * n_seg + torch.from_numpy(rows).cuda()]), -ang)
+            got = f64(qb[0, h, seg * n_seg + torch.from_numpy(src).cuda()])
+            assert not (np.abs(got - want) > tolerances(wl, want)).any(), (h, seg)
+
+
 def test_fused_means_feed_the_staged_operator(I):
     """Prologue means -> isa_coarse_scores -> isa_select -> isa_attend gives what isa_attention computes from the
     prologue's outputs on its own (it recomputes the means in a different summation order)."""

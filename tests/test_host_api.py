@@ -115,6 +115,8 @@ def test_prologue_validation_needs_no_gpu():
     assert call(I.Grid(**good), means=(a[6], None, a[8])) == -1                             # means: all or none
     assert L.isa_prologue(C.byref(cp), None, *a[:6], None, None, None, None) == -1
     cg, keep_g = I.Grid(**good).c_struct()
+    assert L.isa_prologue_backward(C.byref(cp), C.byref(cg), a[0], a[1], a[2], a[3], a[4], None, None) == -1
+    assert L.isa_prologue_backward(C.byref(cp), C.byref(cg), a[0], a[1], a[2], a[1], a[4], a[5], None) == -2
     assert L.isa_untile(C.byref(cp), C.byref(cg), a[0], None, None) == -1
     assert L.isa_untile(C.byref(cp), C.byref(cg), a[0], a[0], None) == -2
     bad, keep_b = I.Grid(**{**good, "tile": (0, 1, 1)}).c_struct()
