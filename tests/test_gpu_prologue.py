@@ -249,3 +249,25 @@ def test_full_size_sampled(I):
                 w = P.rope_rotate(rows64, ang) if rot else rows64
                 wm = f64(torch.from_numpy(w).to(torch.bfloat16)).mean(axis=0)
                 assert np.abs(f64(mean_t[0, h, j]) - wm).max() <= 2.0 ** -9 * np.abs(w).max(), (h, j)
+
+
+@pytest.mark.parametrize("wl", [SMALL_BF16, CFG0], ids=lambda c: c.name)
+def test_prologue_then_operator_against_the_oracle_chain(I, wl):
+    """Row-major, unrotated tensors -> isa_prologue -> isa_attention on the GPU, against the oracle's prologue (rounded to
+    the storage type) followed by the oracle's operator: the lists the GPU chose must be valid selections of the oracle's
+    scores and every output block must match the oracle evaluated on those lists."""
+    from test_gpu_parity import check_end_to_end
+    wl = wl.with_(keep_ratio=0.5, full_frac=0.3)
+    tile = (2, 8, 8)
+    pr, grid, (Q, K, V), _, (qo, ko, vo), _ = run_prologue(I, wl, tile, ROPE[wl.D], means=False)
+    rdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    Qo, Ko, Vo = (torch.zeros_like(x) for x in (Q, K, V))
+    for b in range(wl.B):
+        n = wl.tokens(b)
+        for h in range(wl.H):
+            want = P.prologue_head(f64(Q[b, h, :n]), f64(K[b, h, :n]), f64(V[b, h, :n]), grids_of(wl)[b], tile,
+                                   ROPE[wl.D], 10000.0)
+            for dst, w in zip((Qo, Ko, Vo), want):
+                dst[b, h, :n] = torch.from_numpy(w).to(rdt)
+    a_kv, a_grp = check_end_to_end(I, wl, Qo, Ko, Vo, qo, ko, vo)
+    assert a_kv >= 0.5 and a_grp >= 0.5
