@@ -271,3 +271,83 @@ def test_prologue_then_operator_against_the_oracle_chain(I, wl):
                 dst[b, h, :n] = torch.from_numpy(w).to(rdt)
     a_kv, a_grp = check_end_to_end(I, wl, Qo, Ko, Vo, qo, ko, vo)
     assert a_kv >= 0.5 and a_grp >= 0.5
+
+
+def test_maximum_block_count(I):
+    """The library's limit of 4096 blocks (524 288 tokens in one segment, a 64x64x128 grid): V against the oracle's
+    permutation over the whole tensor, sampled rows of Q, the last block's means, the round trip."""
+    wl = W.CONFIGS["cfg1"].with_(name="max_blocks", H=2, src_grid=(64, 64, 128), ctx_grids=((),), seed=181)
+    tile, dims = (4, 4, 8), ROPE[128]
+    pr = problem_of(wl)
+    assert I.isa_get_counts(pr, 0)["T"] == 4096
+    grid = I.Grid(grids_of(wl), tile, dims, 10000.0)
+    gen_ = torch.Generator(device="cuda").manual_seed(wl.seed)
+    q, k, v = (torch.randn((1, wl.H, 524288, 128), generator=gen_, device="cuda").to(torch.bfloat16) for _ in range(3))
+    qo, ko, vo = (torch.empty_like(x) for x in (q, k, v))
+    qc, kc, vc = (torch.zeros((1, wl.H, 4096, 128), device="cuda") for _ in range(3))
+    I.isa_prologue(pr, grid, q, k, v, qo, ko, vo, qc, kc, vc)
+    back = torch.empty_like(v)
+    I.isa_untile(pr, grid, vo, back)
+    torch.cuda.synchronize()
+    perm = P.tile_order(wl.src_grid, tile)
+    assert torch.equal(vo[0], v[0][:, torch.from_numpy(perm).cuda()])
+    assert torch.equal(back, v)
+    coords = P.grid_coords(wl.src_grid)
+    rows = np.concatenate([[0, 127, 128, 524287], np.random.default_rng(9).integers(0, 524288, 200)])
+    src = perm[rows]
+    ang = P.rope_angles(coords[src], 128, dims, 10000.0)
+    for h in range(wl.H):
+        want = P.rope_rotate(f64(q[0, h, torch.from_numpy(src).cuda()]), ang)
+        got = f64(qo[0, h, torch.from_numpy(rows).cuda()])
+        assert not (np.abs(got - want) > tolerances(wl, want)).any(), h
+        src_last = perm[4095 * 128:]
+        w = P.rope_rotate(f64(k[0, h, torch.from_numpy(src_last).cuda()]), P.rope_angles(coords[src_last], 128, dims, 10000.0))
+        wm = f64(torch.from_numpy(w).to(torch.bfloat16)).mean(axis=0)
+        assert np.abs(f64(kc[0, h, 4095]) - wm).max() <= 2.0 ** -9 * np.abs(w).max()
+
+
+def test_prologue_operator_and_untile_replay_from_a_hip_graph(I):
+    """The three calls only launch kernels on the caller's stream, so they can be captured together; every replay must
+    reproduce the eager result bit for bit, also after the inputs change between replays."""
+    wl = SMALL_BF16.with_(keep_ratio=0.5, full_frac=0.3)
+    pr = problem_of(wl)
+    grid = I.Grid(grids_of(wl), (2, 8, 8), ROPE[wl.D], 10000.0)
+    Q, K, V = W.make_inputs(wl, "cpu")
+    q, k, v = Q.cuda(), K.cuda(), V.cuda()
+    ws = I.new_workspace(pr)
+
+    def run(qi, ki, vi, bufs):
+        qo, ko, vo, o_t, o_r = bufs
+        I.isa_prologue(pr, grid, qi, ki, vi, qo, ko, vo)
+        I.isa_attention(pr, qo, ko, vo, o_t, ws)
+        I.isa_untile(pr, grid, o_t, o_r)
+
+    eager = [torch.zeros_like(q) for _ in range(5)]
+    run(q, k, v, eager)
+    torch.cuda.synchronize()
+    qs, ks, vs = q.clone(), k.clone(), v.clone()
+    bufs = [torch.zeros_like(q) for _ in range(5)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(qs, ks, vs, bufs)                                        # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(qs, ks, vs, bufs)
+    n = wl.tokens(0)
+    for rep in range(3):
+        bufs[4].zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bufs[4][:, :, :n], eager[4][:, :, :n]), rep
+        I.isa_dense_attention(pr, q, k, v, torch.empty_like(q), ws)   # eager work of our own between the replays
+        torch.cuda.synchronize()
+    qs.copy_(q.flip(1)); ks.copy_(k.flip(1)); vs.copy_(v.flip(1))
+    graph.replay()
+    torch.cuda.synchronize()
+    eager2 = [torch.zeros_like(q) for _ in range(5)]
+    run(q.flip(1).contiguous(), k.flip(1).contiguous(), v.flip(1).contiguous(), eager2)
+    torch.cuda.synchronize()
+    assert torch.equal(bufs[4][:, :, :n], eager2[4][:, :, :n])
