@@ -23,14 +23,23 @@
 //                        blocks and of the Taylor blocks whose exact set holds the block; the epilogue adds the block's
 //                        dKc / n_j (dVc / n_j) and writes bf16
 // Every output element is written by exactly one workgroup: no atomics, results are reproducible.
+//
+// The additive terms of a weight ride in the MFMA accumulators: T1 starts at b_x / c (minus the log-sum-exp of a
+// stationary query row, log2 n_j of a stationary mean), T2 at minus delta: of the stationary rows when those are queries,
+// of the streamed rows when these are (read from the tile's side array as the C operand of the first T2 MFMA), so that
+// a weight costs an fma, an exp2, a multiplication and half a packed conversion.  Matrix and vector instructions issue
+// through one port on this chip and a sub-tile's weights take about as long as its MFMAs, so the weights are issued in
+// slices between the MFMAs of the following sub-tile, with the LDS fragments requested a step ahead.
 #include "attn_mfma.h"
 
 namespace isa {
 
+#define ISA_BWD_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 namespace {
 
 constexpr int STAGE = 2 * K_TILE + V_TILE;           // bf16 elements of one LDS stage: Y1, Y2 and Yt tiles
-constexpr int SIDE_BYTES = 1024;                      // per stage: {bias, delta} of the 64 streamed rows (512 B used)
+constexpr int SIDE_BYTES = 1024;                      // per stage: 64 exponent terms, then 64 minus-deltas, of the streamed rows (512 B used)
 
 // 16 bytes per lane from global memory straight into LDS (lane i -> LDS bytes lds_addr + 16 i); inline assembly so
 // that the only wait for these loads is the explicit one at the top of the loop.
@@ -57,7 +66,7 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 struct BwdStream {
   const uint16_t* y1; const uint16_t* y2; const uint16_t* yt;   // row-major (scores), row-major (dP; unused without dS), packed transposed
   const int4* tab;                            // token tiles: [bh][T_max] {token offset, tokens, block id} per list entry; null: mean tiles
-  const float2* ybd;                          // {additive exponent term (-inf: masked), delta} per streamed position
+  const float2* ybd;                          // per tile of 64 streamed positions: 64 additive exponent terms (-inf: masked), then 64 minus-deltas
   int kind;                                   // token tiles: list entries = 0 kept blocks, 1 full-attention blocks, 2 Taylor blocks
   int masked;                                 // exact sets (Alg. 2 Part A): 0 none; 1 token tiles of the entries whose bit is set for the
                                               // stationary entry, others skipped; 2 mean tiles, positions whose bit is set are masked;
@@ -87,7 +96,9 @@ struct BwdArgs {
 };
 
 // SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play.
-template <bool SM, bool T2, bool EX>
+// YD: the streamed rows carry deltas of their own (they are queries) and the stationary rows none; otherwise the other
+// way round.
+template <bool SM, bool T2, bool EX, bool YD>
 __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * STAGE + 2 * SIDE_BYTES / 2];
   // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
@@ -330,7 +341,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     const Cursor nn = nxt.p < n_phases ? advance(nxt) : nxt;
     ent_nxt = row_of(nn);
     const uint16_t* sb = lds + (it & 1) * STAGE;
-    const float2* side = reinterpret_cast<const float2*>(lds + 2 * STAGE + (it & 1) * (SIDE_BYTES / 2));
+    const float* side = reinterpret_cast<const float*>(lds + 2 * STAGE + (it & 1) * (SIDE_BYTES / 2));   // 64 terms, 64 minus-deltas
     // exact sets: what of this tile is masked for this wave's stationary rows
     float gm_tile[2] = {0.f, 0.f};            // per stationary 16-row tile of the wave
     uint32_t pos_w0 = 0u, pos_w1 = 0u;        // masked == 2: bits of the tile's 64 positions (set = masked)
@@ -355,58 +366,90 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         for (int qt = 0; qt < 2; ++qt) gm_tile[qt] = ((sm_word[qt] >> (e & 31)) & 1u) ? -INFINITY : 0.f;
       }
     }
+    // One tile = two halves (hh) of 32 streamed rows, each of two 16-row sub-tiles (kt).  Per sub-tile: the T products
+    // (4 steps of 4 MFMAs, 2 without T2) and then 8 weights per lane on the vector ALU (exp2 runs at a quarter of the
+    // vector rate, so a sub-tile's weights cost about as much as its MFMAs); per half: the C product (8 steps of 2 MFMAs)
+    // once all 16 weights exist.  Back to back these would take turns on the two pipes; instead the weights of a
+    // sub-tile are issued in slices between the MFMAs of the next sub-tile's T steps, and those of the last sub-tile
+    // between the MFMAs of the first half's C steps:
+    //   T(0,0) | T(0,1) + W(0,0) | T(1,0) + W(0,1) | T(1,1) + W(1,0) | C(0) + W(1,1) | C(1)
+    // LDS fragments are requested one step before the MFMAs that read them.
+    f32x4 t1[2][2], t2[2][2];                 // [kt][qt]
+    bf16x8 w[2][2];                           // [hh][qt]; element 4 kt + i = streamed row 32 hh + 16 kt + 4 q + i
+    f32x4 c1[2];
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      f32x4 t1[2][2], t2[2][2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-          // the per-stationary-row terms ride in the accumulators: T1 starts at b_x / c (so that T1 c = scores c + b_x),
-          // T2 at -delta_x
-          t1[kt][qt] = EX ? t1_init[qt] + f32x4{gm_tile[qt], gm_tile[qt], gm_tile[qt], gm_tile[qt]} : t1_init[qt];
-          t2[kt][qt] = t2_init[qt];
-        }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-          const bf16x8 f1 = *reinterpret_cast<const bf16x8*>(sb + (32 * hh + 16 * kt) * MD + koff[ks]);
-          t1[kt][0] = mfma16(f1, x1f[0][ks], t1[kt][0]);
-          t1[kt][1] = mfma16(f1, x1f[1][ks], t1[kt][1]);
-          if (T2) {
-            const bf16x8 f2 = *reinterpret_cast<const bf16x8*>(sb + K_TILE + (32 * hh + 16 * kt) * MD + koff[ks]);
-            t2[kt][0] = mfma16(f2, x2f[0][ks], t2[kt][0]);
-            t2[kt][1] = mfma16(f2, x2f[1][ks], t2[kt][1]);
-          }
-        }
-      // W: element 4 kt + i of a lane's fragment is streamed row 32 hh + 16 kt + 4 q + i
-      bf16x8 w[2];
+    for (int qt = 0; qt < 2; ++qt)
+      c1[qt] = EX ? t1_init[qt] + f32x4{gm_tile[qt], gm_tile[qt], gm_tile[qt], gm_tile[qt]} : t1_init[qt];
+    f32x4 bt[2];                              // exponent terms of the sub-tile whose weights are in progress, [kt]
+    f32x4 nd[2];                              // YD: minus delta of the streamed rows of the sub-tile whose T steps are next
+    auto load_side = [&](int hh, int kt) {
       const uint32_t pos_w = hh ? pos_w1 : pos_w0;
+      bt[kt] = *reinterpret_cast<const f32x4*>(side + 32 * hh + 16 * kt + 4 * q);
+      if (EX) {
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        float2 bd[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          bd[i] = side[32 * hh + 16 * kt + 4 * q + i];
-          if (EX && ((pos_w >> (16 * kt + 4 * q + i)) & 1u)) bd[i].x = -INFINITY;
-        }
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(t1[kt][qt][i], cscale, bd[i].x));
-            const float val = T2 ? p * (t2[kt][qt][i] - bd[i].y) : p;
-            w[qt][4 * kt + i] = (__bf16)val;
-          }
+        for (int i = 0; i < 4; ++i)
+          if ((pos_w >> (16 * kt + 4 * q + i)) & 1u) bt[kt][i] = -INFINITY;
       }
+    };
+    auto load_delta = [&](int hh, int kt) {
+      if (T2 && YD) nd[kt] = *reinterpret_cast<const f32x4*>(side + 64 + 32 * hh + 16 * kt + 4 * q);
+    };
+    auto weight2 = [&](int hh, int kt, int tp) {          // weights 2 tp and 2 tp + 1 of sub-tile (hh, kt): tile qt = tp / 2
+      const int qt = tp >> 1, i0 = (2 * tp) & 3;
+      float val[2];
 #pragma unroll
-      for (int ct = 0; ct < 8; ++ct) {
-        const bf16x8 ft = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + hh * (V_TILE / 2) + ct * 16 * 32 + voff);
-        acc[ct][0] = mfma16(ft, w[0], acc[ct][0]);
-        acc[ct][1] = mfma16(ft, w[1], acc[ct][1]);
+      for (int j = 0; j < 2; ++j) {
+        const float pw = __builtin_amdgcn_exp2f(fmaf(t1[kt][qt][i0 + j], cscale, bt[kt][i0 + j]));
+        val[j] = T2 ? pw * t2[kt][qt][i0 + j] : pw;       // T2 started at minus the deltas: it already is dP - delta
+      }
+      w[hh][qt][4 * kt + i0] = (__bf16)val[0];
+      w[hh][qt][4 * kt + i0 + 1] = (__bf16)val[1];
+    };
+    load_delta(0, 0);
+    bf16x8 fa[2], fb[2];                      // Y1 / Y2 fragments of the T step in progress and of the next one
+    bf16x8 fc[2];                             // the same for the C steps
+    fa[0] = *reinterpret_cast<const bf16x8*>(sb + koff[0]);
+    if (T2) fb[0] = *reinterpret_cast<const bf16x8*>(sb + K_TILE + koff[0]);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {             // sub-tile (hh, kt) = (s / 2, s % 2)
+      const int hh = s >> 1, kt = s & 1;
+      if (s > 0) load_side((s - 1) >> 1, (s - 1) & 1);
+      if (s < 3) load_delta((s + 1) >> 1, (s + 1) & 1);   // read by the first MFMAs of the next sub-tile
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int n = 4 * s + ks, cb = n & 1, nb = cb ^ 1;
+        ISA_BWD_FENCE();
+        if (n + 1 < 16) {
+          const int s2 = (n + 1) >> 2, ks2 = (n + 1) & 3;
+          const uint16_t* rowp = sb + (32 * (s2 >> 1) + 16 * (s2 & 1)) * MD + koff[ks2];
+          fa[nb] = *reinterpret_cast<const bf16x8*>(rowp);
+          if (T2) fb[nb] = *reinterpret_cast<const bf16x8*>(rowp + K_TILE);
+        } else {
+          fc[0] = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + voff);
+        }
+        t1[kt][0] = mfma16(fa[cb], x1f[0][ks], ks == 0 ? c1[0] : t1[kt][0]);
+        t1[kt][1] = mfma16(fa[cb], x1f[1][ks], ks == 0 ? c1[1] : t1[kt][1]);
+        if (T2) {
+          t2[kt][0] = mfma16(fb[cb], x2f[0][ks], ks == 0 ? (YD ? nd[kt] : t2_init[0]) : t2[kt][0]);
+          t2[kt][1] = mfma16(fb[cb], x2f[1][ks], ks == 0 ? (YD ? nd[kt] : t2_init[1]) : t2[kt][1]);
+        }
+        if (s > 0) weight2((s - 1) >> 1, (s - 1) & 1, ks);
       }
     }
+    load_side(1, 1);
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) {
+        const int n = 8 * hh + ct, cb = n & 1, nb = cb ^ 1;
+        ISA_BWD_FENCE();
+        if (n + 1 < 16)
+          fc[nb] = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + ((n + 1) >> 3) * (V_TILE / 2) + ((n + 1) & 7) * 16 * 32 + voff);
+        acc[ct][0] = mfma16(fc[cb], w[hh][0], acc[ct][0]);
+        acc[ct][1] = mfma16(fc[cb], w[hh][1], acc[ct][1]);
+        if (hh == 0 && (ct & 1)) weight2(1, 1, ct >> 1);
+      }
+    ISA_BWD_FENCE();
     cur = nxt;
     nxt = nn;
   }
@@ -465,8 +508,8 @@ __global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ 
   if (ok && c16 == 0) delta[((long long)b * g.H + h) * S_max + t] = s;
 }
 
-// Per list entry: the table row of its block and the {exponent term, delta} pair of each of its 128 row positions
-// (masked positions: -inf, 0).  kind 0: kept blocks as streamed keys (term 0), plus the per-mean arrays of the Taylor
+// Per list entry: the table row of its block and the {exponent term, minus delta} pair of each of its 128 row positions
+// (masked positions: -inf, 0), stored per tile of 64 positions as 64 terms followed by 64 minus-deltas.  kind 0: kept blocks as streamed keys (term 0), plus the per-mean arrays of the Taylor
 // branch (log2 n_j per gathered mean, -inf for the padding); kinds 1, 2: full-attention / Taylor blocks as streamed
 // queries (term = minus the row's log-sum-exp in the log2 domain, delta of the row).
 __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, int kind, const int4* __restrict__ btab,
@@ -481,7 +524,10 @@ __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, 
   if (kind == 0 && e < Tn_pad && r == 0) {
     float l2 = -INFINITY;
     if (e < n_list) l2 = log2f((float)btab[b * T_max + list[bh * T_max + e]].y);
-    ybd_mean[bh * Tn_pad + e] = make_float2(l2, 0.f);
+    const long long m = bh * Tn_pad + e;                      // planar per 64 positions: 64 terms, then 64 deltas
+    float* ym = reinterpret_cast<float*>(ybd_mean);
+    ym[(m >> 6) * 128 + (m & 63)] = l2;
+    ym[(m >> 6) * 128 + 64 + (m & 63)] = 0.f;
     bx_mean[bh * Tn_pad + e] = e < n_list ? l2 : 0.f;
   }
   if (e >= n_list || e >= T_max) return;
@@ -490,9 +536,12 @@ __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, 
   float2 v = make_float2(-INFINITY, 0.f);
   if (r < ent.y) {
     if (kind == 0) v = make_float2(0.f, 0.f);
-    else v = make_float2(nlse[bh * S_max + ent.x + r], delta[bh * S_max + ent.x + r]);
+    else v = make_float2(nlse[bh * S_max + ent.x + r], -delta[bh * S_max + ent.x + r]);
   }
-  ybd[(bh * T_max + e) * 128 + r] = v;
+  const long long pos = (bh * T_max + e) * 128 + r;
+  float* yf = reinterpret_cast<float*>(ybd);
+  yf[(pos >> 6) * 128 + (pos & 63)] = v.x;
+  yf[(pos >> 6) * 128 + 64 + (pos & 63)] = v.y;
 }
 
 // Rows of a token tensor that no later launch writes (keys and values of context blocks that were not kept): zero, or,
@@ -695,12 +744,15 @@ __global__ __launch_bounds__(128) void k_bwd_tmask(const uint32_t* __restrict__ 
   mask_t[(bh * T_max + t) * mw + w] = out;
 }
 
-template <bool SM, bool T2>
+// YD (the streamed rows are queries, which carry deltas; the stationary rows then must not: a.dx == nullptr) is implied
+// by what the launch streams.
+template <bool SM, bool T2, bool YD>
 static hipError_t launch_one(const BwdArgs& a, bool ex, int B, int H, hipStream_t st) {
   if (a.items <= 0) return hipSuccess;
+  if (YD && a.dx != nullptr) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(a.items * 8 * ((B * H + 7) / 8)));
-  if (ex) hipLaunchKernelGGL((k_attn_bwd<SM, T2, true>), grid, dim3(512), 0, st, a);
-  else hipLaunchKernelGGL((k_attn_bwd<SM, T2, false>), grid, dim3(512), 0, st, a);
+  if (ex) hipLaunchKernelGGL((k_attn_bwd<SM, T2, true, YD>), grid, dim3(512), 0, st, a);
+  else hipLaunchKernelGGL((k_attn_bwd<SM, T2, false, YD>), grid, dim3(512), 0, st, a);
   return hipGetLastError();
 }
 
@@ -778,7 +830,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
   a.stat_list = full_list; a.stat_kind = 0; a.items = (sf + 1) / 2;
   a.s[0] = kept_tokens; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
-  if ((e = launch_one<false, true>(a, false, B, H, st)) != hipSuccess) return e;
+  if ((e = launch_one<false, true, false>(a, false, B, H, st)) != hipSuccess) return e;
   a.stat_list = flat_list; a.stat_kind = 1; a.items = (sl + 1) / 2;
   if (ex) {
     a.s[0] = kept_tokens; a.s[0].masked = 1;
@@ -787,7 +839,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   } else {
     a.s[0] = kept_means; a.n_phases = 1;
   }
-  if ((e = launch_one<false, true>(a, ex, B, H, st)) != hipSuccess) return e;
+  if ((e = launch_one<false, true, false>(a, ex, B, H, st)) != hipSuccess) return e;
 
   // ---- dKc and dK (streamed Q, dO, Q^T packed)
   if ((e = launch_pack_t(pr, ws, Q, ws.vt, st)) != hipSuccess) return e;
@@ -806,7 +858,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
       a.x1 = ws.kcn; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
       a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
       a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.add_by_block = 0; a.oscale = osc; a.items = n_mean_pairs;
-      e = pass == 0 ? launch_one<true, true>(a, ex, B, H, st) : launch_one<true, false>(a, ex, B, H, st);
+      e = pass == 0 ? launch_one<true, true, true>(a, ex, B, H, st) : launch_one<true, false, false>(a, ex, B, H, st);
       if (e != hipSuccess) return e;
     }
     if (resid) {                                  // the coarse residual's gradient of the same means joins the Taylor branch's
@@ -822,7 +874,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr;
     a.add_rows = (sl > 0 || resid) ? mean_grad : nullptr; a.add_by_block = 0;
     a.oscale = osc; a.items = (sk + 1) / 2;
-    e = pass == 0 ? launch_one<false, true>(a, ex, B, H, st) : launch_one<false, false>(a, ex, B, H, st);
+    e = pass == 0 ? launch_one<false, true, true>(a, ex, B, H, st) : launch_one<false, false, false>(a, ex, B, H, st);
     if (e != hipSuccess) return e;
   }
 #undef ISA_BWD_CHECK

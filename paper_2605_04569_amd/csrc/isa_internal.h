@@ -68,7 +68,7 @@ struct Workspace {
   uint16_t* kcnt;        // [B,H,Tn_pad/64][D][64]: mean keys gathered, transposed, key-permuted
   float* dkc; float* dvc;             // [B,H,Tn_pad][D] gradients of the gathered mean keys / values
   int4* ftab; int4* ltab;             // [B,H,T_max] table rows of the full-attention / Taylor blocks, in list order
-  float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128] {exponent term, delta} per row position of each list entry
+  float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128 pairs] per tile of 64 row positions of the list entries: 64 exponent terms, then 64 minus-deltas
   float2* ybd_mean;      // [B,H,Tn_pad] the same per gathered mean key
   float* bx_mean;        // [B,H,Tn_pad] log2(n_j) per gathered mean key
   uint32_t* mask_t;      // [B,H,T_max,mask_words] exact_mask transposed (only when exact_frac > 0)
