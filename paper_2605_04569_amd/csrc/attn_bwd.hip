@@ -93,6 +93,9 @@ struct BwdArgs {
   int Tn_pad, S_max;
   int stat_kind;                              // token rows: 0 full-attention blocks, 1 Taylor blocks, 2 kept blocks
   int items;                                  // work items (pairs of stationary blocks) per (batch, head) in this launch
+  // mean rows only: every item runs as `parts` workgroups, each over its share of the streamed entries, and writes its
+  // partial sums to out_f32 + part * part_stride (k_bwd_sum_parts adds them up)
+  int parts; long long part_stride;
 };
 
 // SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play.
@@ -104,7 +107,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
   // head after the other, so that the workgroups that run together on an XCD (and share its L2) stream the same rows.
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
-  const int item = jj % a.items, bhid = (jj / a.items) * 8 + xcd;
+  const int parts = SM ? a.parts : 1;
+  const int item_all = jj % (a.items * parts), bhid = (jj / (a.items * parts)) * 8 + xcd;
+  const int item = item_all / parts, part = item_all - item * parts;
   if (bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const int T_new = a.cnt.b[b].T_new, n_full = a.cnt.b[b].n_full, n_flat = a.cnt.b[b].n_flat;
@@ -211,7 +216,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   const int ph_ent1 = a.s[1].kind == 0 ? T_new : a.s[1].kind == 1 ? n_full : n_flat;
   const int4* const ph_tab0 = a.s[0].tab;
   const int4* const ph_tab1 = a.s[1].tab;
-  const int ph_tiles0 = ph_tab0 ? 2 * ph_ent0 : (T_new + KT - 1) / KT;
+  const int ent_lo = SM ? (int)((long long)part * ph_ent0 / parts) : 0;               // this part's share of the entries
+  const int ent_hi = SM ? (int)((long long)(part + 1) * ph_ent0 / parts) : ph_ent0;
+  const int ph_tiles0 = ph_tab0 ? 2 * ent_hi : (T_new + KT - 1) / KT;
   const int ph_tiles1 = ph_tab1 ? 2 * ph_ent1 : (T_new + KT - 1) / KT;
   const int ph_masked0 = a.s[0].masked, ph_masked1 = a.s[1].masked;
   const uint16_t* const ph_y1_0 = a.s[0].y1; const uint16_t* const ph_y1_1 = a.s[1].y1;
@@ -325,7 +332,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   }
 
   // cur: tile being multiplied; nxt: tile whose loads are in flight; nn: tile whose table row is being fetched
-  Cursor cur = settle(Cursor{0, 0});
+  Cursor cur = settle(Cursor{0, 2 * ent_lo});
   Cursor nxt = cur.p < n_phases ? advance(cur) : cur;
   int4 ent_nxt = row_of(cur);
   if (cur.p < n_phases) issue_tile(cur, 0, ent_nxt);
@@ -474,7 +481,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         r.z = fmaf(m4.z, inv_n, r.z); r.w = fmaf(m4.w, inv_n, r.w);
       }
       if (SM) {
-        *reinterpret_cast<float4*>(a.out_f32 + (bh * a.Tn_pad + (long long)entry * 128 + row) * MD + 16 * ct + 4 * q) = r;
+        *reinterpret_cast<float4*>(a.out_f32 + part * a.part_stride + (bh * a.Tn_pad + (long long)entry * 128 + row) * MD + 16 * ct + 4 * q) = r;
       } else {
         bf16x2 lo = {(__bf16)r.x, (__bf16)r.y};
         bf16x2 hi = {(__bf16)r.z, (__bf16)r.w};
@@ -744,13 +751,24 @@ __global__ __launch_bounds__(128) void k_bwd_tmask(const uint32_t* __restrict__ 
   mask_t[(bh * T_max + t) * mw + w] = out;
 }
 
+// Adds the partial sums of the parts of a mean-row launch into part 0: one workgroup per gathered mean row.
+__global__ __launch_bounds__(128) void k_bwd_sum_parts(float* __restrict__ g, int parts, long long part_stride, Counts cnt,
+                                                       int H, int Tn_pad) {
+  const int e = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (e >= cnt.b[b].T_new) return;
+  const long long i = (((long long)b * H + h) * Tn_pad + e) * MD + threadIdx.x;
+  float sum = g[i];
+  for (int p = 1; p < parts; ++p) sum += g[p * part_stride + i];
+  g[i] = sum;
+}
+
 // YD (the streamed rows are queries, which carry deltas; the stationary rows then must not: a.dx == nullptr) is implied
 // by what the launch streams.
 template <bool SM, bool T2, bool YD>
 static hipError_t launch_one(const BwdArgs& a, bool ex, int B, int H, hipStream_t st) {
   if (a.items <= 0) return hipSuccess;
   if (YD && a.dx != nullptr) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)(a.items * 8 * ((B * H + 7) / 8)));
+  const dim3 grid((unsigned)(a.items * (SM ? a.parts : 1) * 8 * ((B * H + 7) / 8)));
   if (ex) hipLaunchKernelGGL((k_attn_bwd<SM, T2, true, YD>), grid, dim3(512), 0, st, a);
   else hipLaunchKernelGGL((k_attn_bwd<SM, T2, false, YD>), grid, dim3(512), 0, st, a);
   return hipGetLastError();
@@ -815,6 +833,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.blk_start = ws.blk_start; a.blk_n = ws.blk_n;
   a.geo = pr.geo; a.cnt = pr.cnt; a.Tn_pad = pr.Tn_pad; a.S_max = S_max;
   a.mask_words = pr.cnt.mask_words;
+  a.parts = 1; a.part_stride = 0;
   const float scale = 1.0f / sqrtf((float)MD);
   const uint16_t *Q = (const uint16_t*)q, *K = (const uint16_t*)k, *V = (const uint16_t*)v, *DO = (const uint16_t*)d_out;
   const BwdStream none = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
@@ -844,6 +863,17 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   // ---- dKc and dK (streamed Q, dO, Q^T packed)
   if ((e = launch_pack_t(pr, ws, Q, ws.vt, st)) != hipSuccess) return e;
   const int n_mean_pairs = ((sk + 127) / 128 + 1) / 2;
+  // The mean-row launches have few items (one per 256 gathered means and head): each is cut into up to BWD_MEAN_PARTS
+  // parts along the streamed entries, as many as make the launch's rounds over the 256 compute units shortest.
+  int mean_parts = 1;
+  {
+    const long long wgs = (long long)n_mean_pairs * B * H;
+    double best = 1e30;
+    for (int p = 1; p <= BWD_MEAN_PARTS; ++p) {
+      const double rounds = (double)((wgs * p + 255) / 256) / p;
+      if (rounds < best - 1e-9) { best = rounds; mean_parts = p; }
+    }
+  }
   BwdStream full_q = {Q, DO, ws.vt, ws.ftab, ws.ybd_full, 1, 0};
   BwdStream flat_q = {Q, DO, ws.vt, ws.ltab, ws.ybd_flat, 2, 0};
   a.dx = nullptr;
@@ -858,8 +888,15 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
       a.x1 = ws.kcn; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
       a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
       a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.add_by_block = 0; a.oscale = osc; a.items = n_mean_pairs;
+      a.parts = mean_parts; a.part_stride = (long long)B * H * pr.Tn_pad * MD;
       e = pass == 0 ? launch_one<true, true, true>(a, ex, B, H, st) : launch_one<true, false, false>(a, ex, B, H, st);
       if (e != hipSuccess) return e;
+      if (mean_parts > 1) {
+        hipLaunchKernelGGL(k_bwd_sum_parts, dim3(sk, H, B), dim3(128), 0, st, mean_grad, mean_parts, a.part_stride, pr.cnt, H,
+                           pr.Tn_pad);
+        ISA_BWD_CHECK();
+      }
+      a.parts = 1;
     }
     if (resid) {                                  // the coarse residual's gradient of the same means joins the Taylor branch's
       hipLaunchKernelGGL(k_bwd_add_coarse, dim3(sk, H, B), dim3(128), 0, st, mean_grad, pass == 0 ? ws.cdk : ws.cdv,

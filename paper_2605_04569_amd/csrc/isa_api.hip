@@ -122,8 +122,8 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->delta = (float*)take(B * H * S * 4);
     ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
     ws->kcnt = (uint16_t*)take(B * H * Tn * D * 2);
-    ws->dkc = (float*)take(B * H * Tn * D * 4);
-    ws->dvc = (float*)take(B * H * Tn * D * 4);
+    ws->dkc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
+    ws->dvc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->ftab = (int4*)take(B * H * T * 16);
     ws->ltab = (int4*)take(B * H * T * 16);
     ws->ybd_kv = (float2*)take(B * H * T * 128 * 8);

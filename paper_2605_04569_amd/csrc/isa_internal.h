@@ -33,6 +33,7 @@ struct Geometry {
 };
 
 // Workspace carve-up (device pointers into the caller's workspace).
+constexpr int BWD_MEAN_PARTS = 4;    // backward: parts a mean-row work item may be cut into (partial sums in dkc / dvc)
 constexpr int SPLIT_MAX_SUB = 256;   // sub-items of split work items per launch: at most one per compute unit
 
 struct Workspace {
@@ -66,7 +67,7 @@ struct Workspace {
   float* delta;          // [B,H,S_max] rowsum(dO * O)
   uint16_t* vcn;         // [B,H,Tn_pad][D]: mean values gathered in kv_list order (row-major, bf16)
   uint16_t* kcnt;        // [B,H,Tn_pad/64][D][64]: mean keys gathered, transposed, key-permuted
-  float* dkc; float* dvc;             // [B,H,Tn_pad][D] gradients of the gathered mean keys / values
+  float* dkc; float* dvc;             // [BWD_MEAN_PARTS][B,H,Tn_pad][D] gradients of the gathered mean keys / values (part 0: the sum)
   int4* ftab; int4* ltab;             // [B,H,T_max] table rows of the full-attention / Taylor blocks, in list order
   float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128 pairs] per tile of 64 row positions of the list entries: 64 exponent terms, then 64 minus-deltas
   float2* ybd_mean;      // [B,H,Tn_pad] the same per gathered mean key
