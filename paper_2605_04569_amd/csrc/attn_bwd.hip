@@ -344,11 +344,33 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     // reading the other stage (the previous tile), which the loads of the next tile now overwrite
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    const uint16_t* sb = lds + (it & 1) * STAGE;
+    const float* side = reinterpret_cast<const float*>(lds + 2 * STAGE + (it & 1) * (SIDE_BYTES / 2));   // 64 terms, 64 minus-deltas
+    f32x4 nd[2];                              // YD: minus delta of the streamed rows of the sub-tile whose T steps are next
+    auto load_delta = [&](int hh, int kt) {
+      if (T2 && YD) nd[kt] = *reinterpret_cast<const f32x4*>(side + 64 + 32 * hh + 16 * kt + 4 * q);
+    };
+    // LDS fragments are requested PF steps before the MFMAs that read them (a step is 64 or 32 cycles of matrix pipe,
+    // an LDS read takes longer than one of them), in PF + 1 rotating register sets
+    constexpr int PF = 2, NB = PF + 1;
+    bf16x8 fa[NB], fb[NB];                    // Y1 / Y2 fragments of T steps n .. n + PF
+    bf16x8 fc[NB];                            // Yt fragments of C steps
+    auto t_load = [&](int n) {                // fragments of T step n (sub-tile n / 4, k-slice n % 4)
+      const int s2 = n >> 2, ks2 = n & 3;
+      const uint16_t* rowp = sb + (32 * (s2 >> 1) + 16 * (s2 & 1)) * MD + koff[ks2];
+      fa[n % NB] = *reinterpret_cast<const bf16x8*>(rowp);
+      if (T2) fb[n % NB] = *reinterpret_cast<const bf16x8*>(rowp + K_TILE);
+    };
+    auto c_load = [&](int n) {                // fragment of C step n (half n / 8, channel tile n % 8)
+      fc[n % NB] = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + (n >> 3) * (V_TILE / 2) + (n & 7) * 16 * 32 + voff);
+    };
+#pragma unroll
+    for (int n = 0; n < PF; ++n) t_load(n);
+    load_delta(0, 0);
+    // the first fragments are on their way from LDS while the next tile's loads are set up and issued
     if (nxt.p < n_phases) issue_tile(nxt, (it + 1) & 1, ent_nxt);
     const Cursor nn = nxt.p < n_phases ? advance(nxt) : nxt;
     ent_nxt = row_of(nn);
-    const uint16_t* sb = lds + (it & 1) * STAGE;
-    const float* side = reinterpret_cast<const float*>(lds + 2 * STAGE + (it & 1) * (SIDE_BYTES / 2));   // 64 terms, 64 minus-deltas
     // exact sets: what of this tile is masked for this wave's stationary rows
     float gm_tile[2] = {0.f, 0.f};            // per stationary 16-row tile of the wave
     uint32_t pos_w0 = 0u, pos_w1 = 0u;        // masked == 2: bits of the tile's 64 positions (set = masked)
@@ -380,7 +402,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     // sub-tile are issued in slices between the MFMAs of the next sub-tile's T steps, and those of the last sub-tile
     // between the MFMAs of the first half's C steps:
     //   T(0,0) | T(0,1) + W(0,0) | T(1,0) + W(0,1) | T(1,1) + W(1,0) | C(0) + W(1,1) | C(1)
-    // LDS fragments are requested one step before the MFMAs that read them.
     f32x4 t1[2][2], t2[2][2];                 // [kt][qt]
     bf16x8 w[2][2];                           // [hh][qt]; element 4 kt + i = streamed row 32 hh + 16 kt + 4 q + i
     f32x4 c1[2];
@@ -388,7 +409,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     for (int qt = 0; qt < 2; ++qt)
       c1[qt] = EX ? t1_init[qt] + f32x4{gm_tile[qt], gm_tile[qt], gm_tile[qt], gm_tile[qt]} : t1_init[qt];
     f32x4 bt[2];                              // exponent terms of the sub-tile whose weights are in progress, [kt]
-    f32x4 nd[2];                              // YD: minus delta of the streamed rows of the sub-tile whose T steps are next
     auto load_side = [&](int hh, int kt) {
       const uint32_t pos_w = hh ? pos_w1 : pos_w0;
       bt[kt] = *reinterpret_cast<const f32x4*>(side + 32 * hh + 16 * kt + 4 * q);
@@ -397,9 +417,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         for (int i = 0; i < 4; ++i)
           if ((pos_w >> (16 * kt + 4 * q + i)) & 1u) bt[kt][i] = -INFINITY;
       }
-    };
-    auto load_delta = [&](int hh, int kt) {
-      if (T2 && YD) nd[kt] = *reinterpret_cast<const f32x4*>(side + 64 + 32 * hh + 16 * kt + 4 * q);
     };
     auto weight2 = [&](int hh, int kt, int tp) {          // weights 2 tp and 2 tp + 1 of sub-tile (hh, kt): tile qt = tp / 2
       const int qt = tp >> 1, i0 = (2 * tp) & 3;
@@ -412,28 +429,17 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
       w[hh][qt][4 * kt + i0] = (__bf16)val[0];
       w[hh][qt][4 * kt + i0 + 1] = (__bf16)val[1];
     };
-    load_delta(0, 0);
-    bf16x8 fa[2], fb[2];                      // Y1 / Y2 fragments of the T step in progress and of the next one
-    bf16x8 fc[2];                             // the same for the C steps
-    fa[0] = *reinterpret_cast<const bf16x8*>(sb + koff[0]);
-    if (T2) fb[0] = *reinterpret_cast<const bf16x8*>(sb + K_TILE + koff[0]);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {             // sub-tile (hh, kt) = (s / 2, s % 2)
-      const int hh = s >> 1, kt = s & 1;
+      const int kt = s & 1;
       if (s > 0) load_side((s - 1) >> 1, (s - 1) & 1);
       if (s < 3) load_delta((s + 1) >> 1, (s + 1) & 1);   // read by the first MFMAs of the next sub-tile
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const int n = 4 * s + ks, cb = n & 1, nb = cb ^ 1;
+        const int n = 4 * s + ks, cb = n % NB;
         ISA_BWD_FENCE();
-        if (n + 1 < 16) {
-          const int s2 = (n + 1) >> 2, ks2 = (n + 1) & 3;
-          const uint16_t* rowp = sb + (32 * (s2 >> 1) + 16 * (s2 & 1)) * MD + koff[ks2];
-          fa[nb] = *reinterpret_cast<const bf16x8*>(rowp);
-          if (T2) fb[nb] = *reinterpret_cast<const bf16x8*>(rowp + K_TILE);
-        } else {
-          fc[0] = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + voff);
-        }
+        if (n + PF < 16) t_load(n + PF);
+        else c_load(n + PF - 16);
         t1[kt][0] = mfma16(fa[cb], x1f[0][ks], ks == 0 ? c1[0] : t1[kt][0]);
         t1[kt][1] = mfma16(fa[cb], x1f[1][ks], ks == 0 ? c1[1] : t1[kt][1]);
         if (T2) {
@@ -448,10 +454,9 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
       for (int ct = 0; ct < 8; ++ct) {
-        const int n = 8 * hh + ct, cb = n & 1, nb = cb ^ 1;
+        const int n = 8 * hh + ct, cb = n % NB;
         ISA_BWD_FENCE();
-        if (n + 1 < 16)
-          fc[nb] = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + ((n + 1) >> 3) * (V_TILE / 2) + ((n + 1) & 7) * 16 * 32 + voff);
+        if (n + PF < 16) c_load(n + PF);
         acc[ct][0] = mfma16(fc[cb], w[hh][0], acc[ct][0]);
         acc[ct][1] = mfma16(fc[cb], w[hh][1], acc[ct][1]);
         if (hh == 0 && (ct & 1)) weight2(1, 1, ct >> 1);
