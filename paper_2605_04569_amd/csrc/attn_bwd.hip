@@ -98,10 +98,11 @@ struct BwdArgs {
   int parts; long long part_stride;
 };
 
-// SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play.
+// SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play (1: whole
+// tiles are masked or not; 2: also single positions of a tile of gathered means).
 // YD: the streamed rows carry deltas of their own (they are queries) and the stationary rows none; otherwise the other
 // way round.
-template <bool SM, bool T2, bool EX, bool YD>
+template <bool SM, bool T2, int EX, bool YD>
 __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * STAGE + 2 * SIDE_BYTES / 2];
   // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         const int e = cur.T >> 1;
         const bool linked = (word_of(bits_own, bits_own_hi, e >> 5) >> (e & 31)) & 1u;
         gm_tile[0] = gm_tile[1] = linked ? 0.f : -INFINITY;
-      } else if (!SM && masked == 2) {
+      } else if (EX == 2 && !SM && masked == 2) {
         pos_w0 = word_of(bits_own, bits_own_hi, 2 * cur.T);
         pos_w1 = word_of(bits_own, bits_own_hi, 2 * cur.T + 1);
       } else if (SM && masked == 3) {
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     auto load_side = [&](int hh, int kt) {
       const uint32_t pos_w = hh ? pos_w1 : pos_w0;
       bt[kt] = *reinterpret_cast<const f32x4*>(side + 32 * hh + 16 * kt + 4 * q);
-      if (EX) {
+      if (EX == 2) {                          // only the launch that streams gathered means under exact sets has such bits
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           if ((pos_w >> (16 * kt + 4 * q + i)) & 1u) bt[kt][i] = -INFINITY;
@@ -770,12 +771,18 @@ __global__ __launch_bounds__(128) void k_bwd_sum_parts(float* __restrict__ g, in
 // YD (the streamed rows are queries, which carry deltas; the stationary rows then must not: a.dx == nullptr) is implied
 // by what the launch streams.
 template <bool SM, bool T2, bool YD>
-static hipError_t launch_one(const BwdArgs& a, bool ex, int B, int H, hipStream_t st) {
+static hipError_t launch_one(const BwdArgs& a, int ex, int B, int H, hipStream_t st) {
   if (a.items <= 0) return hipSuccess;
   if (YD && a.dx != nullptr) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(a.items * (SM ? a.parts : 1) * 8 * ((B * H + 7) / 8)));
-  if (ex) hipLaunchKernelGGL((k_attn_bwd<SM, T2, true, YD>), grid, dim3(512), 0, st, a);
-  else hipLaunchKernelGGL((k_attn_bwd<SM, T2, false, YD>), grid, dim3(512), 0, st, a);
+  if (ex == 2) {                                // position bits only occur with token rows as stationary rows and dS
+    if (SM || !T2 || YD) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_attn_bwd<false, true, 2, false>), grid, dim3(512), 0, st, a);
+  } else if (ex == 1) {
+    hipLaunchKernelGGL((k_attn_bwd<SM, T2, 1, YD>), grid, dim3(512), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((k_attn_bwd<SM, T2, 0, YD>), grid, dim3(512), 0, st, a);
+  }
   return hipGetLastError();
 }
 
@@ -854,7 +861,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
   a.stat_list = full_list; a.stat_kind = 0; a.items = (sf + 1) / 2;
   a.s[0] = kept_tokens; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
-  if ((e = launch_one<false, true, false>(a, false, B, H, st)) != hipSuccess) return e;
+  if ((e = launch_one<false, true, false>(a, 0, B, H, st)) != hipSuccess) return e;
   a.stat_list = flat_list; a.stat_kind = 1; a.items = (sl + 1) / 2;
   if (ex) {
     a.s[0] = kept_tokens; a.s[0].masked = 1;
@@ -863,7 +870,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   } else {
     a.s[0] = kept_means; a.n_phases = 1;
   }
-  if ((e = launch_one<false, true, false>(a, ex, B, H, st)) != hipSuccess) return e;
+  if ((e = launch_one<false, true, false>(a, ex ? 2 : 0, B, H, st)) != hipSuccess) return e;
 
   // ---- dKc and dK (streamed Q, dO, Q^T packed)
   if ((e = launch_pack_t(pr, ws, Q, ws.vt, st)) != hipSuccess) return e;
@@ -894,7 +901,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
       a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
       a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.add_by_block = 0; a.oscale = osc; a.items = n_mean_pairs;
       a.parts = mean_parts; a.part_stride = (long long)B * H * pr.Tn_pad * MD;
-      e = pass == 0 ? launch_one<true, true, true>(a, ex, B, H, st) : launch_one<true, false, false>(a, ex, B, H, st);
+      e = pass == 0 ? launch_one<true, true, true>(a, ex ? 1 : 0, B, H, st) : launch_one<true, false, false>(a, ex ? 1 : 0, B, H, st);
       if (e != hipSuccess) return e;
       if (mean_parts > 1) {
         hipLaunchKernelGGL(k_bwd_sum_parts, dim3(sk, H, B), dim3(128), 0, st, mean_grad, mean_parts, a.part_stride, pr.cnt, H,
@@ -916,7 +923,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr;
     a.add_rows = (sl > 0 || resid) ? mean_grad : nullptr; a.add_by_block = 0;
     a.oscale = osc; a.items = (sk + 1) / 2;
-    e = pass == 0 ? launch_one<false, true, true>(a, ex, B, H, st) : launch_one<false, false, false>(a, ex, B, H, st);
+    e = pass == 0 ? launch_one<false, true, true>(a, ex ? 1 : 0, B, H, st) : launch_one<false, false, false>(a, ex ? 1 : 0, B, H, st);
     if (e != hipSuccess) return e;
   }
 #undef ISA_BWD_CHECK
