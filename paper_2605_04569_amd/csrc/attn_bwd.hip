@@ -375,12 +375,14 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     // exact sets: what of this tile is masked for this wave's stationary rows
     float gm_tile[2] = {0.f, 0.f};            // per stationary 16-row tile of the wave
     uint32_t pos_w0 = 0u, pos_w1 = 0u;        // masked == 2: bits of the tile's 64 positions (set = masked)
+    bool dead = false;                        // the whole tile is masked for all stationary rows of this wave
     if (EX) {
       const int masked = PH(cur.p, ph_masked0, ph_masked1);
       if (!SM && masked == 1) {
         const int e = cur.T >> 1;
         const bool linked = (word_of(bits_own, bits_own_hi, e >> 5) >> (e & 31)) & 1u;
         gm_tile[0] = gm_tile[1] = linked ? 0.f : -INFINITY;
+        dead = !linked;                       // streamed for the other block of the pair only: every weight would be 0
       } else if (EX == 2 && !SM && masked == 2) {
         pos_w0 = word_of(bits_own, bits_own_hi, 2 * cur.T);
         pos_w1 = word_of(bits_own, bits_own_hi, 2 * cur.T + 1);
@@ -397,12 +399,13 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
       }
     }
     // One tile = two halves (hh) of 32 streamed rows, each of two 16-row sub-tiles (kt).  Per sub-tile: the T products
-    // (4 steps of 4 MFMAs, 2 without T2) and then 8 weights per lane on the vector ALU (exp2 runs at a quarter of the
+    // (4 steps of 4 MFMAs, 2 without T2) and then 8 weights per lane on the vector ALU (exp2 runs at half the
     // vector rate, so a sub-tile's weights cost about as much as its MFMAs); per half: the C product (8 steps of 2 MFMAs)
     // once all 16 weights exist.  Back to back these would take turns on the two pipes; instead the weights of a
     // sub-tile are issued in slices between the MFMAs of the next sub-tile's T steps, and those of the last sub-tile
     // between the MFMAs of the first half's C steps:
     //   T(0,0) | T(0,1) + W(0,0) | T(1,0) + W(0,1) | T(1,1) + W(1,0) | C(0) + W(1,1) | C(1)
+    if (!(EX && dead)) {                      // wave-uniform
     f32x4 t1[2][2], t2[2][2];                 // [kt][qt]
     bf16x8 w[2][2];                           // [hh][qt]; element 4 kt + i = streamed row 32 hh + 16 kt + 4 q + i
     f32x4 c1[2];
@@ -462,6 +465,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
         acc[ct][1] = mfma16(fc[cb], w[hh][1], acc[ct][1]);
         if (hh == 0 && (ct & 1)) weight2(1, 1, ct >> 1);
       }
+    }
     ISA_BWD_FENCE();
     cur = nxt;
     nxt = nn;
