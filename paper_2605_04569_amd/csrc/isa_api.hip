@@ -357,13 +357,16 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
     exact_mask = ws.exact_mask;
   }
   if (p->exact_frac <= 0.0) exact_mask = nullptr;
-  // block table and means are recomputed (cheap, and the staged forward takes its means from the caller); the
-  // log-sum-exp of every query row is what the forward call left in the workspace
-  ISA_TRY(launch_layout(pr, ws, st));
-  ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
-  ISA_TRY(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
-  if (p->gamma != 0.0)                              // O_coarse of Alg. 1 Stage 1 again (the staged forward takes it from the caller)
-    ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, nullptr, ws.vc, ws.ocoarse, st));
+  // The log-sum-exp of every query row is what the forward call left in the workspace.  After isa_attention (lists taken
+  // from the workspace) the block table, the block means, the gathered mean keys and O_coarse are still there as well;
+  // the staged forward takes its means and O_coarse from the caller, so after it they are computed again here.
+  if (n_lists != 0) {
+    ISA_TRY(launch_layout(pr, ws, st));
+    ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
+    ISA_TRY(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
+    if (p->gamma != 0.0)                            // O_coarse of Alg. 1 Stage 1
+      ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, nullptr, ws.vc, ws.ocoarse, st));
+  }
   ISA_TRY(launch_gather_means_bwd(pr, ws, ws.kc, ws.vc, kv_list, st));
   ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, exact_mask, dq, dk, dv, st));
   return ISA_OK;
