@@ -96,6 +96,11 @@ struct BwdArgs {
   // mean rows only: every item runs as `parts` workgroups, each over its share of the streamed entries, and writes its
   // partial sums to out_f32 + part * part_stride (k_bwd_sum_parts adds them up)
   int parts; long long part_stride;
+  // token rows, one phase only: the last tail_items items of every XCD (its last, incomplete round over the compute
+  // units) run as tail_parts workgroups each, every one over its share of the streamed entries; they leave their
+  // unscaled fp32 sums in tail_scratch [XCD][tail item][part][256 rows][128] and k_bwd_tail_merge writes the rows
+  int items_xcd, tail_items, tail_parts;
+  float* tail_scratch;
 };
 
 // SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play (1: whole
@@ -108,9 +113,26 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
   // head after the other, so that the workgroups that run together on an XCD (and share its L2) stream the same rows.
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
-  const int parts = SM ? a.parts : 1;
-  const int item_all = jj % (a.items * parts), bhid = (jj / (a.items * parts)) * 8 + xcd;
-  const int item = item_all / parts, part = item_all - item * parts;
+  int parts = 1, part = 0, item, bhid, tail_slot = -1;
+  if (SM) {
+    parts = a.parts;
+    const int item_all = jj % (a.items * parts);
+    bhid = (jj / (a.items * parts)) * 8 + xcd;
+    item = item_all / parts;
+    part = item_all - item * parts;
+  } else {
+    const int n_reg = a.items_xcd - a.tail_items;         // items_xcd = items x heads of an XCD; no tail: jj itself
+    int idx = jj;
+    if (jj >= n_reg) {
+      const int u = jj - n_reg;
+      tail_slot = u / a.tail_parts;
+      part = u - tail_slot * a.tail_parts;
+      parts = a.tail_parts;
+      idx = n_reg + tail_slot;
+    }
+    item = idx % a.items;
+    bhid = (idx / a.items) * 8 + xcd;
+  }
   if (bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const int T_new = a.cnt.b[b].T_new, n_full = a.cnt.b[b].n_full, n_flat = a.cnt.b[b].n_flat;
@@ -217,8 +239,8 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   const int ph_ent1 = a.s[1].kind == 0 ? T_new : a.s[1].kind == 1 ? n_full : n_flat;
   const int4* const ph_tab0 = a.s[0].tab;
   const int4* const ph_tab1 = a.s[1].tab;
-  const int ent_lo = SM ? (int)((long long)part * ph_ent0 / parts) : 0;               // this part's share of the entries
-  const int ent_hi = SM ? (int)((long long)(part + 1) * ph_ent0 / parts) : ph_ent0;
+  const int ent_lo = parts > 1 ? (int)((long long)part * ph_ent0 / parts) : 0;        // this part's share of the entries
+  const int ent_hi = parts > 1 ? (int)((long long)(part + 1) * ph_ent0 / parts) : ph_ent0;
   const int ph_tiles0 = ph_tab0 ? 2 * ent_hi : (T_new + KT - 1) / KT;
   const int ph_tiles1 = ph_tab1 ? 2 * ph_ent1 : (T_new + KT - 1) / KT;
   const int ph_masked0 = a.s[0].masked, ph_masked1 = a.s[1].masked;
@@ -472,6 +494,15 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   }
 
 #undef PH
+  if (!SM && tail_slot >= 0) {                // a part of a tail item: unscaled sums to scratch, the merge kernel does the rest
+    float* dst = a.tail_scratch + ((((long long)xcd * a.tail_items + tail_slot) * parts + part) * 256 + grp * 128) * MD;
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct)
+        *reinterpret_cast<f32x4*>(dst + rowq[qt] * MD + 16 * ct + 4 * q) = acc[ct][qt];
+    return;
+  }
   // ---- store: element i of acc[ct][qt] is channel 16 ct + 4 q + i of stationary row 16 qt + r
   const float inv_n = n_x > 0 ? 1.0f / (float)n_x : 0.f;
   const float* addp = !a.add_rows ? nullptr
@@ -772,13 +803,62 @@ __global__ __launch_bounds__(128) void k_bwd_sum_parts(float* __restrict__ g, in
   g[i] = sum;
 }
 
+// Adds up the parts of the tail items of a token-row launch and writes their rows: what the attention kernel's own store
+// does for whole items.  One workgroup per (XCD, tail item, block of the pair, 8 rows); 32 threads per row, 4 channels each.
+__global__ __launch_bounds__(256) void k_bwd_tail_merge(BwdArgs a) {
+  const int rows8 = blockIdx.x & 15, grp = (blockIdx.x >> 4) & 1;
+  const int r = (blockIdx.x >> 5) % a.tail_items, xcd = (blockIdx.x >> 5) / a.tail_items;
+  const int idx = a.items_xcd - a.tail_items + r;
+  const int item = idx % a.items, bhid = (idx / a.items) * 8 + xcd;
+  if (bhid >= a.geo.B * a.geo.H) return;
+  const int h = bhid % a.geo.H, b = bhid / a.geo.H;
+  const long long bh = bhid;
+  const int T_max = a.geo.T_max;
+  const int n_stat = a.stat_kind == 0 ? a.cnt.b[b].n_full : a.stat_kind == 1 ? a.cnt.b[b].n_flat : a.cnt.b[b].T_new;
+  const int entry = 2 * item + grp;
+  if (entry >= n_stat) return;
+  const int blk = a.stat_list[bh * T_max + entry];
+  const int n_x = a.blk_n[b * T_max + blk], x_start = a.blk_start[b * T_max + blk];
+  const int row = rows8 * 8 + (threadIdx.x >> 5), ch = (threadIdx.x & 31) * 4;
+  if (row >= n_x) return;
+  const float* src = a.tail_scratch + ((((long long)xcd * a.tail_items + r) * a.tail_parts) * 256 + grp * 128 + row) * MD + ch;
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p = 0; p < a.tail_parts; ++p) {
+    const float4 o = *reinterpret_cast<const float4*>(src + (long long)p * 256 * MD);
+    sum.x += o.x; sum.y += o.y; sum.z += o.z; sum.w += o.w;
+  }
+  sum.x *= a.oscale; sum.y *= a.oscale; sum.z *= a.oscale; sum.w *= a.oscale;
+  if (a.add_rows) {
+    const float inv_n = 1.0f / (float)n_x;
+    const float4 m4 = *reinterpret_cast<const float4*>(a.add_by_block ? a.add_rows + (bh * T_max + blk) * MD + ch
+                                                                      : a.add_rows + (bh * a.Tn_pad + entry) * MD + ch);
+    sum.x = fmaf(m4.x, inv_n, sum.x); sum.y = fmaf(m4.y, inv_n, sum.y);
+    sum.z = fmaf(m4.z, inv_n, sum.z); sum.w = fmaf(m4.w, inv_n, sum.w);
+  }
+  bf16x2 lo = {(__bf16)sum.x, (__bf16)sum.y};
+  bf16x2 hi = {(__bf16)sum.z, (__bf16)sum.w};
+  uint2 o;
+  o.x = *reinterpret_cast<uint32_t*>(&lo);
+  o.y = *reinterpret_cast<uint32_t*>(&hi);
+  const long long tbase = (long long)b * a.geo.stride_b + (long long)h * a.geo.stride_h;
+  *reinterpret_cast<uint2*>(a.out_bf + tbase + (long long)(x_start + row) * a.geo.stride_t + ch) = o;
+}
+
 // YD (the streamed rows are queries, which carry deltas; the stationary rows then must not: a.dx == nullptr) is implied
 // by what the launch streams.
 template <bool SM, bool T2, bool YD>
-static hipError_t launch_one(const BwdArgs& a, int ex, int B, int H, hipStream_t st) {
+static hipError_t launch_one(BwdArgs a, int ex, int B, int H, hipStream_t st, bool split_tail = false) {
   if (a.items <= 0) return hipSuccess;
   if (YD && a.dx != nullptr) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)(a.items * (SM ? a.parts : 1) * 8 * ((B * H + 7) / 8)));
+  const int hpx = (B * H + 7) / 8;                // (batch, head)s per XCD
+  a.items_xcd = a.items * hpx;
+  a.tail_items = 0; a.tail_parts = 1;
+  if (!SM && split_tail && a.n_phases == 1 && ex == 0 && a.tail_scratch) {
+    // the last round of an XCD's 32 compute units: if at most half of them would have an item, cut those items
+    const int t = a.items_xcd % 32;
+    if (t > 0 && t <= 16) { a.tail_items = t; a.tail_parts = 32 / t > 8 ? 8 : 32 / t; }
+  }
+  const dim3 grid((unsigned)(SM ? a.items * a.parts * hpx * 8 : (a.items_xcd - a.tail_items + a.tail_items * a.tail_parts) * 8));
   if (ex == 2) {                                // position bits only occur with token rows as stationary rows and dS
     if (SM || !T2 || YD) return hipErrorInvalidValue;
     hipLaunchKernelGGL((k_attn_bwd<false, true, 2, false>), grid, dim3(512), 0, st, a);
@@ -787,6 +867,8 @@ static hipError_t launch_one(const BwdArgs& a, int ex, int B, int H, hipStream_t
   } else {
     hipLaunchKernelGGL((k_attn_bwd<SM, T2, 0, YD>), grid, dim3(512), 0, st, a);
   }
+  if (a.tail_items > 0)
+    hipLaunchKernelGGL(k_bwd_tail_merge, dim3((unsigned)(8 * a.tail_items * 32)), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -850,6 +932,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.geo = pr.geo; a.cnt = pr.cnt; a.Tn_pad = pr.Tn_pad; a.S_max = S_max;
   a.mask_words = pr.cnt.mask_words;
   a.parts = 1; a.part_stride = 0;
+  a.items_xcd = 0; a.tail_items = 0; a.tail_parts = 1; a.tail_scratch = ws.split_o;   // the forward's partial-result area: 256 x 256 x 128 floats
   const float scale = 1.0f / sqrtf((float)MD);
   const uint16_t *Q = (const uint16_t*)q, *K = (const uint16_t*)k, *V = (const uint16_t*)v, *DO = (const uint16_t*)d_out;
   const BwdStream none = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
@@ -865,7 +948,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
   a.stat_list = full_list; a.stat_kind = 0; a.items = (sf + 1) / 2;
   a.s[0] = kept_tokens; a.s[1] = none; a.n_phases = 1; a.bits = nullptr;
-  if ((e = launch_one<false, true, false>(a, 0, B, H, st)) != hipSuccess) return e;
+  if ((e = launch_one<false, true, false>(a, 0, B, H, st, true)) != hipSuccess) return e;
   a.stat_list = flat_list; a.stat_kind = 1; a.items = (sl + 1) / 2;
   if (ex) {
     a.s[0] = kept_tokens; a.s[0].masked = 1;
