@@ -180,6 +180,23 @@ def test_prologue_backward_inverts_the_prologue_at_full_size(I):
             assert not (np.abs(got - want) > tolerances(wl, want)).any(), (h, seg)
 
 
+def test_random_grids_and_tile_shapes(I):
+    """The closed form that turns a position of the tile order into grid coordinates, against the oracle's explicit
+    enumeration, over random grids and tile shapes (clipped tiles on any axis, tiles larger than the grid, one-token
+    segments): V is a pure reordering, so every element must match bit for bit; Q is checked within the bound."""
+    import random
+    rng = random.Random(20260504)
+    for case in range(60):
+        n_seg = rng.randint(1, 3)
+        grids = [(rng.randint(1, 5), rng.randint(1, 9), rng.randint(1, 21)) for _ in range(n_seg)]
+        tile = (rng.randint(1, 4), rng.randint(1, 10), rng.randint(1, 12))
+        wl = CFG0.with_(name="rand%d" % case, H=1, src_grid=grids[0], ctx_grids=(tuple(grids[1:]),), seed=300 + case)
+        _, _, (Q, K, V), _, (qo, ko, vo), _ = run_prologue(I, wl, tile, ROPE[wl.D], means=False)
+        want = P.prologue_head(f64(Q[0, 0]), f64(K[0, 0]), f64(V[0, 0]), grids, tile, ROPE[wl.D], 10000.0)
+        assert np.array_equal(f64(vo[0, 0]), want[2]), (case, grids, tile)
+        assert not (np.abs(f64(qo[0, 0]) - want[0]) > tolerances(wl, want[0])).any(), (case, grids, tile)
+
+
 def test_fused_means_feed_the_staged_operator(I):
     """Prologue means -> isa_coarse_scores -> isa_select -> isa_attend gives what isa_attention computes from the
     prologue's outputs on its own (it recomputes the means in a different summation order)."""
