@@ -357,12 +357,6 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qf[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 32 * ks);
   }
-  // consume the fragments here: the compiler's own wait for these loads must not land inside the loop, where
-  // it would also wait for the tile loads in flight (which it does not know about)
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[qt][ks]));
 
   // ---- global -> LDS, 16 bytes per lane, no staging registers.  One wave instruction fills 1024 contiguous
   // LDS bytes (lane i -> bytes 16i..16i+15), so rows cannot be padded; instead the 16-byte chunk c of a row is
@@ -447,6 +441,13 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   load_k(tnext, 1);
   load_v(a.zero_tile, 2);                   // stands in for V^T tile t_begin - 1: multiplied with zero weights, must be finite
   load_v(vt_of(tcur), 0);
+  // The Q fragments are consumed here, behind the first tile loads, so that the two latencies overlap: the compiler's
+  // own wait for them must not land inside the loop, where it would also wait for the tile loads in flight (which it
+  // does not know about).
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[qt][ks]));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   bf16x8 kf[8];                           // K fragments of the next 32 rows to be multiplied
