@@ -1010,7 +1010,8 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr;
     a.add_rows = (sl > 0 || resid) ? mean_grad : nullptr; a.add_by_block = 0;
     a.oscale = osc; a.items = (sk + 1) / 2;
-    e = pass == 0 ? launch_one<false, true, true>(a, ex ? 1 : 0, B, H, st) : launch_one<false, false, false>(a, ex ? 1 : 0, B, H, st);
+    e = pass == 0 ? launch_one<false, true, true>(a, ex ? 1 : 0, B, H, st, true)
+                  : launch_one<false, false, false>(a, ex ? 1 : 0, B, H, st, true);
     if (e != hipSuccess) return e;
   }
 #undef ISA_BWD_CHECK
