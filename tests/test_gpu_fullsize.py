@@ -43,6 +43,17 @@ def test_ragged_batch_full_size_sampled(I):
     check_end_to_end(I, wl, q, k, v, q, k, v, heads=(5,), blocks_per_head=2, seed=2)
 
 
+def test_ragged_batch_ratio_sweep_full_size(I):
+    """cfg3 over the corners and the centre of its sweep (keep ratio 0.25 / 0.5 / 0.75, full fraction 0.1 / 0.2 / 0.4),
+    one generation of the inputs, one sampled head and one sampled block of each branch per point."""
+    base = W.CONFIGS["cfg3"]
+    q, k, v = _gen_gpu(base)
+    for i, (keep, full) in enumerate([(0.5, 0.2), (0.75, 0.4), (0.25, 0.4), (0.75, 0.1)]):
+        wl = base.with_(keep_ratio=keep, full_frac=full)
+        print("full-size parity: cfg3 keep %.2f full %.2f" % (keep, full), flush=True)
+        check_end_to_end(I, wl, q, k, v, q, k, v, heads=(7 * i + 3,), blocks_per_head=1, seed=20 + i)
+
+
 def test_paper_default_ratios_sampled(I):
     """The paper's default operating point (Sec. 4.1): alpha_s = 0.125, alpha_f = 0.5, alpha_ns = 0.0625, at cfg1 size."""
     wl = W.CONFIGS["cfg1"].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)
