@@ -302,7 +302,7 @@ def main():
     ap.add_argument("--gamma", type=float, default=None, help="coarse stacking factor of Alg. 1 Stage 5 (default 0: no residual)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense attention leg")
-    ap.add_argument("--also", default="cfg1,cfg4,paper_defaults",
+    ap.add_argument("--also", default="cfg1,cfg3,cfg4,paper_defaults",
                     help="other workloads to time briefly after the main one ('' = none); paper_defaults = the main "
                          "workload's shape at the paper's default ratios")
     args = ap.parse_args()
