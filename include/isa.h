@@ -29,7 +29,8 @@
  *     per-batch block count; per-(batch, head) block arrays are laid out [B, H, T_max].
  *   - Supported shapes: D in {64, 128}; block in {64, 128}; 1 <= B <= ISA_MAX_BATCH; at most
  *     ISA_MAX_SEGMENTS segments over all batch items; at most ISA_MAX_BLOCKS blocks per batch
- *     item; strides multiples of 8 elements; gamma finite.
+ *     item; strides multiples of 8 elements; token tensors and block-mean arrays 16-byte aligned (ISA_ERR_SHAPE
+ *     otherwise); gamma finite.
  */
 #ifndef ISA_H
 #define ISA_H

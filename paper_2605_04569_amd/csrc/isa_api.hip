@@ -15,6 +15,9 @@ int g_prof_on = 0, g_prof_recorded = 0;
 static std::atomic<int> g_use_mfma{1};
 
 static inline bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }   // false for NaN
+// token tensors are read and written 16 bytes at a time
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+template <typename... P> static inline bool all_aligned16(P... ptrs) { return (aligned16(ptrs) && ...); }
 
 int validate(const isa_problem* p, Problem* out) {
   if (!p || !out) return ISA_ERR_NULL;
@@ -238,6 +241,7 @@ int isa_block_means(const isa_problem* p, const void* q, const void* k, const vo
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !qc || !kc || !vc) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, qc, kc, vc)) return ISA_ERR_SHAPE;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -297,6 +301,7 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
   if (!q || !k || !v || !kc || !vc || !kv_list || !full_list || !flat_list || !out) return ISA_ERR_NULL;
   if (p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
   if (p->gamma != 0.0 && !o_coarse) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out, kc, vc)) return ISA_ERR_SHAPE;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -312,6 +317,7 @@ int isa_attention(const isa_problem* p, const void* q, const void* k, const void
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -329,6 +335,7 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -345,6 +352,7 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
   int rc = validate(p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !out || !d_out || !dq || !dk || !dv) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out, d_out, dq, dk, dv)) return ISA_ERR_SHAPE;
   const int n_lists = (kv_list != nullptr) + (full_list != nullptr) + (flat_list != nullptr);
   if (n_lists != 0 && n_lists != 3) return ISA_ERR_NULL;
   if (n_lists == 3 && p->exact_frac > 0.0 && !exact_mask) return ISA_ERR_NULL;
@@ -389,6 +397,7 @@ int isa_attention_simple(const void* q, const void* k, const void* v, int H, int
   int rc = validate(&p, &pr);
   if (rc != ISA_OK) return rc;
   if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
   const size_t bytes = isa_workspace_bytes(&p);
   hipStream_t st = (hipStream_t)hip_stream;
   void* ws = nullptr;
@@ -421,8 +430,6 @@ static int check_grid(const Problem& pr, const isa_grid* g, bool rope) {
   }
   return ISA_OK;
 }
-
-static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 static int run_prologue(const isa_problem* p, const isa_grid* grid, const void* q_in, const void* k_in, const void* v_in,
                         void* q_out, void* k_out, void* v_out, float* qc, float* kc, float* vc, bool inverse,

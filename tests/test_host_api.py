@@ -68,6 +68,10 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert L.isa_attention(C.byref(cp), one, one, one, one, C.c_void_p(264), 1 << 40, None) == -6
     assert L.isa_attention(C.byref(cp), one, one, one, one, one, 16, None) == -6
     assert L.isa_dense_attention(C.byref(cp), one, one, one, None, one, 1 << 40, None) == -1
+    odd = C.c_void_p(264)   # 8-byte aligned only: token tensors are read 16 bytes at a time
+    assert L.isa_attention(C.byref(cp), one, odd, one, one, one, 1 << 40, None) == -2
+    assert L.isa_dense_attention(C.byref(cp), one, one, one, odd, one, 1 << 40, None) == -2
+    assert L.isa_block_means(C.byref(cp), odd, one, one, one, one, one, one, 1 << 40, None) == -2
     assert L.isa_attention_simple(one, one, one, 2, 64, 0, 10, 0.5, 0.5, 64, one, None) == -2
     # the staged attend needs the coarse output exactly when gamma != 0
     cg, keep_g = base_problem(gamma=0.5).c_struct()
