@@ -153,7 +153,8 @@ int isa_select(const isa_problem* p, const float* s_ctx, const float* sharp, con
  * token's position in `out`.  kc, vc: block means as written by isa_block_means.  exact_mask may be NULL when
  * exact_frac == 0.  o_coarse: as written by isa_coarse_output; read only when gamma != 0 (then required), in which
  * case gamma * o_coarse[block] is added to every token of the block (Stage 5).  The lists must be valid (in range,
- * no duplicates); they are not checked. */
+ * no duplicates); they are not checked: an entry out of range is forced into range (a wrong result, no access outside
+ * the tensors). */
 int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v, const float* kc, const float* vc,
                const int32_t* kv_list, const int32_t* full_list, const int32_t* flat_list, const uint32_t* exact_mask,
                const float* o_coarse, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);

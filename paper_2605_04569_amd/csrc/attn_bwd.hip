@@ -163,7 +163,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     xstride = MD;
     bx_base = bh * a.Tn_pad + (long long)e_use * 128;
   } else {
-    const int blk = a.stat_list[bh * T_max + e_use];
+    const int blk = block_in_range(a.stat_list[bh * T_max + e_use], a.cnt.b[b].T);
     x_blk = blk;
     n_x = active ? a.blk_n[b * T_max + blk] : 0;
     x_start = a.blk_start[b * T_max + blk];
@@ -571,7 +571,7 @@ __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, 
   const int n_list = kind == 0 ? cnt.b[b].T_new : kind == 1 ? cnt.b[b].n_full : cnt.b[b].n_flat;
   if (kind == 0 && e < Tn_pad && r == 0) {
     float l2 = -INFINITY;
-    if (e < n_list) l2 = log2f((float)btab[b * T_max + list[bh * T_max + e]].y);
+    if (e < n_list) l2 = log2f((float)btab[b * T_max + block_in_range(list[bh * T_max + e], cnt.b[b].T)].y);
     const long long m = bh * Tn_pad + e;                      // planar per 64 positions: 64 terms, then 64 deltas
     float* ym = reinterpret_cast<float*>(ybd_mean);
     ym[(m >> 6) * 128 + (m & 63)] = l2;
@@ -579,7 +579,7 @@ __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, 
     bx_mean[bh * Tn_pad + e] = e < n_list ? l2 : 0.f;
   }
   if (e >= n_list || e >= T_max) return;
-  const int4 ent = btab[b * T_max + list[bh * T_max + e]];
+  const int4 ent = btab[b * T_max + block_in_range(list[bh * T_max + e], cnt.b[b].T)];
   if (r == 0) tab[bh * T_max + e] = ent;
   float2 v = make_float2(-INFINITY, 0.f);
   if (r < ent.y) {
@@ -770,7 +770,7 @@ __global__ __launch_bounds__(128) void k_bwd_add_coarse(float* __restrict__ mean
   const int e = blockIdx.x, h = blockIdx.y, b = blockIdx.z, d = threadIdx.x;
   if (e >= cnt.b[b].T_new) return;
   const long long bh = (long long)b * H + h;
-  const int blk = kv_list[bh * cnt.T_max + e];
+  const int blk = block_in_range(kv_list[bh * cnt.T_max + e], cnt.b[b].T);
   const float prev = fresh ? 0.f : mean_grad[(bh * Tn_pad + e) * MD + d];
   mean_grad[(bh * Tn_pad + e) * MD + d] = prev + coarse[(bh * cnt.T_max + blk) * MD + d];
 }
@@ -817,7 +817,7 @@ __global__ __launch_bounds__(256) void k_bwd_tail_merge(BwdArgs a) {
   const int n_stat = a.stat_kind == 0 ? a.cnt.b[b].n_full : a.stat_kind == 1 ? a.cnt.b[b].n_flat : a.cnt.b[b].T_new;
   const int entry = 2 * item + grp;
   if (entry >= n_stat) return;
-  const int blk = a.stat_list[bh * T_max + entry];
+  const int blk = block_in_range(a.stat_list[bh * T_max + entry], a.cnt.b[b].T);
   const int n_x = a.blk_n[b * T_max + blk], x_start = a.blk_start[b * T_max + blk];
   const int row = rows8 * 8 + (threadIdx.x >> 5), ch = (threadIdx.x & 31) * 4;
   if (row >= n_x) return;

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
   const int t0 = tile * KT;
   if (threadIdx.x < KT) {
     const int t = t0 + threadIdx.x;
-    const int j = t < T_new ? kv_list[bh * T_max + t] : -1;
+    const int j = t < T_new ? block_in_range(kv_list[bh * T_max + t], cnt.b[b].T) : -1;
     ids[threadIdx.x] = j;
     if (j >= 0) ktab[bh * T_max + t] = btab[b * T_max + j];
     // ln(n_j) * sqrt(D): added to the raw score q.k, it becomes ln(n_j) after the 1/sqrt(D) scaling
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   if (slot < c.n_full) return;
   const int* kvl = a.kv_list + bh * T_max;
   const int n_list = c.T_new;
-  const int qi = a.flat_list[bh * T_max + slot - c.n_full];
+  const int qi = block_in_range(a.flat_list[bh * T_max + slot - c.n_full], c.T);
   const uint32_t* mrow = (a.exact_mask && c.k_exact > 0)
                              ? a.exact_mask + (bh * T_max + (slot - c.n_full)) * a.cnt.mask_words : nullptr;
   const int* bn = a.blk_n + b * T_max;
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
       while (it_t < n_list && !((mrow[it_t >> 5] >> (it_t & 31)) & 1u)) ++it_t;
     }
     if (it_t < n_list) {
-      const int j = kvl[it_t];
+      const int j = block_in_range(kvl[it_t], c.T);
       const int n_j = bn[j];
       const int k0 = it_sub * KT;
       t.krows = a.k + tbase + (long long)bs[j] * a.geo.stride_t;

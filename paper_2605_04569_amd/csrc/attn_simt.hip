@@ -54,8 +54,8 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnArgs a) {
   } else {
     kvl = a.kv_list + bh * T_max;
     n_kv = c.T_new;
-    if (slot < c.n_full) qi = a.full_list[bh * T_max + slot];
-    else { qi = a.flat_list[bh * T_max + slot - c.n_full]; taylor = true; }
+    if (slot < c.n_full) qi = block_in_range(a.full_list[bh * T_max + slot], c.T);
+    else { qi = block_in_range(a.flat_list[bh * T_max + slot - c.n_full], c.T); taylor = true; }
   }
   const uint32_t* mrow = (taylor && a.exact_mask && c.k_exact > 0)
                              ? a.exact_mask + (bh * T_max + (slot - c.n_full)) * a.cnt.mask_words : nullptr;
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnArgs a) {
   // Part A: blocks evaluated token by token
   for (int t = 0; t < n_kv; ++t) {
     if (taylor && !(mrow && ((mrow[t >> 5] >> (t & 31)) & 1u))) continue;
-    const int j = a.dense ? t : kvl[t];
+    const int j = a.dense ? t : block_in_range(kvl[t], c.T);
     const int n_j = a.blk_n[b * T_max + j];
     const int k_start = a.blk_start[b * T_max + j];
     for (int k0 = 0; k0 < n_j; k0 += KT) {
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnArgs a) {
       __syncthreads();
       for (int x = threadIdx.x; x < nk * (D / 4); x += 256) {
         const int r = x / (D / 4), c4 = x % (D / 4);
-        const long long off = (bh * T_max + kvl[t0 + r]) * D + c4 * 4;
+        const long long off = (bh * T_max + block_in_range(kvl[t0 + r], c.T)) * D + c4 * 4;
         store4(&Ks[r][c4 * 4], *reinterpret_cast<const float4*>(a.kc + off));
         store4(&Vs[r][c4 * 4], *reinterpret_cast<const float4*>(a.vc + off));
       }
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnArgs a) {
         if (threadIdx.x < nk) {
           const int t = t0 + threadIdx.x;
           const bool exact = mrow && ((mrow[t >> 5] >> (t & 31)) & 1u);
-          w = exact ? 0.f : (float)a.blk_n[b * T_max + kvl[t]];
+          w = exact ? 0.f : (float)a.blk_n[b * T_max + block_in_range(kvl[t], c.T)];
         }
         Ws[threadIdx.x] = w;
       }

@@ -283,7 +283,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   // an odd list
   const int entry = 2 * slot + grp;
   const bool active = entry < (taylor ? n_second_blocks : n_first_blocks);
-  const int qi = !active ? 0 : a.dense ? entry : (taylor ? a.flat_list[bh * T_max + entry] : a.full_list[bh * T_max + entry]);
+  const int qi = !active ? 0 : a.dense ? entry : block_in_range(taylor ? a.flat_list[bh * T_max + entry] : a.full_list[bh * T_max + entry], c.T);
   const int n_q = active ? bn[qi] : 0;
   const int q_start = bs[qi];
 
@@ -582,7 +582,7 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
   const int n_blocks = a.dense ? c.T : c.n_full;
   const int entry = 2 * slot + grp;
   if (entry >= n_blocks) return;
-  const int qi = a.dense ? entry : a.full_list[(long long)bhid * T_max + entry];
+  const int qi = a.dense ? entry : block_in_range(a.full_list[(long long)bhid * T_max + entry], c.T);
   const int n_q = a.blk_n[b * T_max + qi], q_start = a.blk_start[b * T_max + qi];
   const int row = rows8 * 8 + (threadIdx.x >> 5), ch = (threadIdx.x & 31) * 4;
   if (row >= n_q) return;

@@ -87,6 +87,10 @@ struct Problem {          // validated problem + everything derived from it
   bool mfma_shape;        // bf16, D = 128, block = 128
 };
 
+// A block index read from a caller-provided list, forced into the batch item's range: the lists of the staged entry
+// points are not validated, and an entry out of range must give a wrong result, not an access outside the tensors.
+__device__ __forceinline__ int block_in_range(int j, int T) { return j < 0 ? 0 : (j >= T ? T - 1 : j); }
+
 extern hipEvent_t g_prof_start, g_prof_stop;   // events recorded around the MFMA attention kernel when g_prof_on
 extern int g_prof_on, g_prof_recorded;
 

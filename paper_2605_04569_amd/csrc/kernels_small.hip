@@ -368,9 +368,9 @@ __global__ __launch_bounds__(256) void k_exact_sets(const float* __restrict__ z,
   const BatchCounts c = cnt.b[b];
   if (r >= c.n_flat) return;
   const long long bh = (long long)b * H + h;
-  const int i = flat_list[bh * cnt.T_max + r];
+  const int i = block_in_range(flat_list[bh * cnt.T_max + r], c.T);
   const float* zr = z + (bh * cnt.T_max + i) * cnt.T_max;
-  for (int t = threadIdx.x; t < c.T_new; t += 256) sm[t] = zr[kv_list[bh * cnt.T_max + t]];
+  for (int t = threadIdx.x; t < c.T_new; t += 256) sm[t] = zr[block_in_range(kv_list[bh * cnt.T_max + t], c.T)];
   __syncthreads();
   uint32_t* mrow = mask + (bh * cnt.T_max + r) * cnt.mask_words;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
