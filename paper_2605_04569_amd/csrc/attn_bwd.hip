@@ -12,14 +12,14 @@
 //
 // One kernel does all six products.  A workgroup (8 waves) keeps 2 x 128 "stationary" rows in registers and streams
 // 64-row tiles of the other side through LDS; per tile it forms T1 = Y1 X1^T (the scores) and, where dS is needed,
-// T2 = Y2 X2^T (dP), turns them into W = P or dS in registers and accumulates acc^T += Yt W^T, where Yt is a packed,
-// transposed copy of the streamed rows in the key order of the 16x16x32 accumulators (the same copy kernel and
-// the same operand layouts as the forward kernel).  The six launches:
-//     dQ, exact branch : stationary (Q, dO) of the full-attention blocks,  streamed K, V, K^T of the kept tokens
-//     dQ, Taylor branch: stationary (Q, dO) of the Taylor blocks,          streamed Kc, Vc, Kc^T (block means), after the
-//                        K, V, K^T tiles of the blocks' exact sets
-//     dKc, dVc         : stationary (Kc, Vc) / Kc rows,                    streamed Q, dO, Q^T / dO^T of the Taylor blocks
-//     dK, dV           : stationary (K, V) / K of the kept blocks,         streamed Q, dO, Q^T / dO^T of the full-attention
+// T2 = Y2 X2^T (dP), turns them into W = P or dS in registers and accumulates acc^T += Yt W^T, where Yt is the
+// transpose of a streamed tile: its fragments are read out of the row-major tile in LDS with ds_read_b64_tr_b16, in the
+// key order of the 16x16x32 accumulators, so no transposed copy of any tensor exists.  The six launches:
+//     dQ, exact branch : stationary (Q, dO) of the full-attention blocks,  streamed K, V of the kept tokens (Yt = K^T)
+//     dQ, Taylor branch: stationary (Q, dO) of the Taylor blocks,          streamed Kc, Vc (block means), after the
+//                        K, V tiles of the blocks' exact sets
+//     dKc, dVc         : stationary (Kc, Vc) / Kc rows,                    streamed Q, dO of the Taylor blocks (Yt = Q^T / dO^T)
+//     dK, dV           : stationary (K, V) / K of the kept blocks,         streamed Q, dO of the full-attention
 //                        blocks and of the Taylor blocks whose exact set holds the block; the epilogue adds the block's
 //                        dKc / n_j (dVc / n_j) and writes bf16
 // Every output element is written by exactly one workgroup: no atomics, results are reproducible.
@@ -38,7 +38,7 @@ namespace isa {
 
 namespace {
 
-constexpr int STAGE = 2 * K_TILE + V_TILE;           // bf16 elements of one LDS stage: Y1, Y2 and Yt tiles
+constexpr int STAGE = 2 * K_TILE;                    // bf16 elements of one LDS stage: the Y1 and Y2 tiles
 constexpr int SIDE_BYTES = 1024;                      // per stage: 64 exponent terms, then 64 minus-deltas, of the streamed rows (512 B used)
 
 // 16 bytes per lane from global memory straight into LDS (lane i -> LDS bytes lds_addr + 16 i); inline assembly so
@@ -56,6 +56,8 @@ __device__ __forceinline__ const char* uniform_ptr(const void* p) {
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
   return reinterpret_cast<const char*>((uintptr_t)(((uint64_t)hi << 32) | lo));
 }
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v* lds_s4_ptr;
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
@@ -64,7 +66,8 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 
 // One phase of the streamed side of a launch: token tiles of the blocks of a list, or tiles of gathered block means.
 struct BwdStream {
-  const uint16_t* y1; const uint16_t* y2; const uint16_t* yt;   // row-major (scores), row-major (dP; unused without dS), packed transposed
+  const uint16_t* y1; const uint16_t* y2;     // row-major rows for the scores / for dP; the accumulation product reads
+                                              // the transpose of y1 (launches that need dS) or of y2 (the others: dO)
   const int4* tab;                            // token tiles: [bh][T_max] {token offset, tokens, block id} per list entry; null: mean tiles
   const float2* ybd;                          // per tile of 64 streamed positions: 64 additive exponent terms (-inf: masked), then 64 minus-deltas
   int kind;                                   // token tiles: list entries = 0 kept blocks, 1 full-attention blocks, 2 Taylor blocks
@@ -216,18 +219,15 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   }
   if (EX) asm volatile("" : "+v"(bits_own), "+v"(bits_other), "+v"(bits_own_hi), "+v"(bits_other_hi));
 
-  // ---- tile loads: global -> LDS, 16 bytes per lane, rows XOR-swizzled on the source side (the layouts of the forward
-  // kernel: natural tiles 64 rows x 256 B, chunk c of row r at c ^ (r & 15); packed tiles as two units of 128 rows x
-  // 64 B, chunk c of row r at c ^ ((r >> 1) & 3))
+  // ---- tile loads: global -> LDS, 16 bytes per lane, rows XOR-swizzled on the source side (the row-major layout of
+  // the forward kernel: tiles of 64 rows x 256 B, chunk c of row r at c ^ (r & 15))
   const int l16 = lane >> 4;
   uint32_t nchunk_b[2];
   int nrow_l[2];
-  uint32_t tlane_b[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     nrow_l[i] = 8 * wave + 4 * i + l16;
     nchunk_b[i] = (uint32_t)((((lane & 15) ^ (nrow_l[i] & 15)) * 8) * 2);
-    tlane_b[i] = (uint32_t)(((wave < 4 ? 0 : 32) + (((wave * 2 + i) & 7) * 16 + (lane >> 2)) * KT + (((lane & 3) ^ ((lane >> 3) & 3)) * 8)) * 2);
   }
 
   // ---- the sequence of streamed tiles: phase p, tile T of the phase (token tiles: entry T / 2, half T % 2).
@@ -246,7 +246,6 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   const int ph_masked0 = a.s[0].masked, ph_masked1 = a.s[1].masked;
   const uint16_t* const ph_y1_0 = a.s[0].y1; const uint16_t* const ph_y1_1 = a.s[1].y1;
   const uint16_t* const ph_y2_0 = a.s[0].y2; const uint16_t* const ph_y2_1 = a.s[1].y2;
-  const uint16_t* const ph_yt_0 = a.s[0].yt; const uint16_t* const ph_yt_1 = a.s[1].yt;
   const float2* const ph_ybd_0 = a.s[0].ybd; const float2* const ph_ybd_1 = a.s[1].ybd;
 #define PH(p, x0, x1) ((p) == 0 ? (x0) : (x1))
   auto tiles_of = [&](int p) __attribute__((always_inline)) -> int { return PH(p, ph_tiles0, ph_tiles1); };
@@ -283,52 +282,44 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     const bool means = PH(c.p, ph_tab0, ph_tab1) == nullptr;
     const uint16_t* const ph_y1 = PH(c.p, ph_y1_0, ph_y1_1);
     const uint16_t* const ph_y2 = PH(c.p, ph_y2_0, ph_y2_1);
-    const uint16_t* const ph_yt = PH(c.p, ph_yt_0, ph_yt_1);
     const float2* const ph_ybd = PH(c.p, ph_ybd_0, ph_ybd_1);
     const int T = c.T;
-    uint32_t y_off, t_off, bd_off, ystride_b;
+    uint32_t y_off, bd_off, ystride_b;
     int nk;
-    const char *y1_head, *y2_head, *yt_head, *ybd_head;
+    const char *y1_head, *y2_head, *ybd_head;
     if (means) {
       ystride_b = (uint32_t)MD * 2u;
       y1_head = reinterpret_cast<const char*>(ph_y1 + bh * a.Tn_pad * MD);
-      y2_head = T2 ? reinterpret_cast<const char*>(ph_y2 + bh * a.Tn_pad * MD) : nullptr;
-      yt_head = reinterpret_cast<const char*>(ph_yt + bh * (a.Tn_pad / KT) * (long long)(MD * KT));
+      y2_head = reinterpret_cast<const char*>(ph_y2 + bh * a.Tn_pad * MD);
       ybd_head = reinterpret_cast<const char*>(ph_ybd + bh * a.Tn_pad);
       y_off = (uint32_t)T * (uint32_t)(KT * MD * 2);
-      t_off = (uint32_t)T * (uint32_t)(MD * KT * 2);
       bd_off = (uint32_t)T * (uint32_t)(KT * 8);
       nk = KT;                                            // the gathered mean arrays are padded to whole tiles
     } else {
       ystride_b = (uint32_t)a.geo.stride_t * 2u;
       y1_head = reinterpret_cast<const char*>(ph_y1 + tbase);
-      y2_head = T2 ? reinterpret_cast<const char*>(ph_y2 + tbase) : nullptr;
-      yt_head = reinterpret_cast<const char*>(ph_yt + bh * T_max * 2 * (long long)(MD * KT));
+      y2_head = reinterpret_cast<const char*>(ph_y2 + tbase);
       ybd_head = reinterpret_cast<const char*>(ph_ybd + bh * T_max * 128);
       const int sub = T & 1;
       const bool empty = ent.y <= sub * KT;               // second tile of a short block: masked, reads the block's first rows
       y_off = (uint32_t)(ent.x + (empty ? 0 : sub * KT)) * ystride_b;
-      t_off = ((uint32_t)ent.z * 2u + (uint32_t)sub) * (uint32_t)(MD * KT * 2);
       bd_off = (uint32_t)((T >> 1) * 128 + sub * KT) * 8u;
       nk = empty ? 1 : min(KT, ent.y - sub * KT);
     }
     // wave-uniform by construction; made scalar explicitly so that the bases of the loads live in scalar registers
     y_off = __builtin_amdgcn_readfirstlane(y_off);
-    t_off = __builtin_amdgcn_readfirstlane(t_off);
     bd_off = __builtin_amdgcn_readfirstlane(bd_off);
     nk = __builtin_amdgcn_readfirstlane(nk);
     ystride_b = __builtin_amdgcn_readfirstlane(ystride_b);
     const char* const y1_tile = uniform_ptr(y1_head + y_off);
-    const char* const y2_tile = T2 ? uniform_ptr(y2_head + y_off) : nullptr;
-    const char* const yt_tile = uniform_ptr(yt_head + t_off);
+    const char* const y2_tile = uniform_ptr(y2_head + y_off);
     const char* const ybd_tile = uniform_ptr(ybd_head + bd_off);
     uint16_t* sb = lds + stage * STAGE;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const uint32_t ro = (uint32_t)min(nrow_l[i], nk - 1) * ystride_b + nchunk_b[i];     // rows past the end re-read the last one
       dma16(y1_tile, ro, lds_addr(sb + (wave * 2 + i) * 512));
-      if (T2) dma16(y2_tile, ro, lds_addr(sb + K_TILE + (wave * 2 + i) * 512));
-      dma16(yt_tile, tlane_b[i], lds_addr(sb + 2 * K_TILE + (wave * 2 + i) * 512));
+      dma16(y2_tile, ro, lds_addr(sb + K_TILE + (wave * 2 + i) * 512));
     }
     if (wave == 0)                                         // {bias, delta} of the 64 rows: 512 B, lanes 32..63 repeat lanes 0..31
       dma16(ybd_tile, (uint32_t)(lane & 31) * 16u, lds_addr(lds + 2 * STAGE + stage * (SIDE_BYTES / 2)));
@@ -338,7 +329,17 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) koff[ks] = r16 * MD + (((4 * ks + q) ^ r16) * 8);
-  const int voff = r16 * 32 + ((q ^ ((r16 >> 1) & 3)) * 8);
+  // Transposed fragments of the accumulation product (A operand: 16 channels x 32 streamed rows) come straight out of
+  // a row-major tile with ds_read_b64_tr_b16: in every group of 16 lanes, lane s points at 4 consecutive channels
+  // 16 ct + 4 (s & 3) .. of row 4 q + (s >> 2) of a 16-row sub-tile, and lane l receives, for i = 0..3, channel 16 ct + l
+  // of row 4 q + i -- the four rows whose weights the lane group holds in elements 4 kt + i of its W fragment.
+  const int tr_row = 4 * q + (r16 >> 2);
+  int tr_base[2];                              // sub-tile kt: row offset plus the lane's half of a 16-byte chunk
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) tr_base[kt] = (16 * kt + tr_row) * MD + 4 * (r16 & 1);
+  int tr_pos[8];                               // channel tile ct: swizzled position of the lane's chunk in its row
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) tr_pos[ct] = ((2 * ct + ((r16 & 3) >> 1)) ^ (tr_row & 15)) * 8;
 
   f32x4 acc[8][2];
 #pragma unroll
@@ -385,7 +386,10 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
       if (T2) fb[n % NB] = *reinterpret_cast<const bf16x8*>(rowp + K_TILE);
     };
     auto c_load = [&](int n) {                // fragment of C step n (half n / 8, channel tile n % 8)
-      fc[n % NB] = *reinterpret_cast<const bf16x8*>(sb + 2 * K_TILE + (n >> 3) * (V_TILE / 2) + (n & 7) * 16 * 32 + voff);
+      const uint16_t* src = sb + (T2 ? 0 : K_TILE) + (n >> 3) * 32 * MD + tr_pos[n & 7];      // the tile whose transpose is Yt
+      const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(src + tr_base[0]));
+      const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(src + tr_base[1]));
+      fc[n % NB] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
 #pragma unroll
     for (int n = 0; n < PF; ++n) t_load(n);
@@ -935,14 +939,13 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.items_xcd = 0; a.tail_items = 0; a.tail_parts = 1; a.tail_scratch = ws.split_o;   // the forward's partial-result area: 256 x 256 x 128 floats
   const float scale = 1.0f / sqrtf((float)MD);
   const uint16_t *Q = (const uint16_t*)q, *K = (const uint16_t*)k, *V = (const uint16_t*)v, *DO = (const uint16_t*)d_out;
-  const BwdStream none = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
+  const BwdStream none = {nullptr, nullptr, nullptr, nullptr, 0, 0};
   hipError_t e;
 
-  // ---- dQ: exact branch over the kept tokens (needs K^T packed); Taylor branch over the tokens of each block's exact
+  // ---- dQ: exact branch over the kept tokens; Taylor branch over the tokens of each block's exact
   // set and the means of the other kept blocks
-  if ((e = launch_pack_t(pr, ws, K, ws.vt, st)) != hipSuccess) return e;
-  const BwdStream kept_tokens = {K, V, ws.vt, ws.ktab, ws.ybd_kv, 0, 0};
-  const BwdStream kept_means = {ws.kcn, ws.vcn, ws.kcnt, nullptr, ws.ybd_mean, 0, 0};
+  const BwdStream kept_tokens = {K, V, ws.ktab, ws.ybd_kv, 0, 0};
+  const BwdStream kept_means = {ws.kcn, ws.vcn, nullptr, ws.ybd_mean, 0, 0};
   a.x1 = Q; a.x2 = DO; a.bx = ws.nlse; a.dx = ws.delta;
   a.out_bf = (uint16_t*)dq; a.out_f32 = nullptr; a.oscale = scale;
   a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
@@ -959,8 +962,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   }
   if ((e = launch_one<false, true, false>(a, ex ? 2 : 0, B, H, st)) != hipSuccess) return e;
 
-  // ---- dKc and dK (streamed Q, dO, Q^T packed)
-  if ((e = launch_pack_t(pr, ws, Q, ws.vt, st)) != hipSuccess) return e;
+  // ---- dKc and dK (streamed Q, dO)
   const int n_mean_pairs = ((sk + 127) / 128 + 1) / 2;
   // The mean-row launches have few items (one per 256 gathered means and head): each is cut into up to BWD_MEAN_PARTS
   // parts along the streamed entries, as many as make the launch's rounds over the 256 compute units shortest.
@@ -973,14 +975,10 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
       if (rounds < best - 1e-9) { best = rounds; mean_parts = p; }
     }
   }
-  BwdStream full_q = {Q, DO, ws.vt, ws.ftab, ws.ybd_full, 1, 0};
-  BwdStream flat_q = {Q, DO, ws.vt, ws.ltab, ws.ybd_flat, 2, 0};
+  const BwdStream full_q = {Q, DO, ws.ftab, ws.ybd_full, 1, 0};
+  const BwdStream flat_q = {Q, DO, ws.ltab, ws.ybd_flat, 2, 0};
   a.dx = nullptr;
-  for (int pass = 0; pass < 2; ++pass) {          // pass 0: dKc, dK (W = dS); pass 1: dVc, dV (W = P, streamed dO^T)
-    if (pass == 1) {
-      if ((e = launch_pack_t(pr, ws, DO, ws.vt, st)) != hipSuccess) return e;
-      full_q.y2 = flat_q.y2 = nullptr;
-    }
+  for (int pass = 0; pass < 2; ++pass) {          // pass 0: dKc, dK (W = dS, read Q transposed); pass 1: dVc, dV (W = P, dO transposed)
     float* mean_grad = pass == 0 ? ws.dkc : ws.dvc;
     const float osc = pass == 0 ? scale : 1.0f;
     if (sl > 0) {                                 // gradients of the gathered means: every Taylor block, minus its exact set
