@@ -74,19 +74,14 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
   return hipGetLastError();
 }
 
-hipError_t launch_pack_t(const Problem& pr, const Workspace& ws, const void* src, uint16_t* dst, hipStream_t st) {
-  hipLaunchKernelGGL(k_pack_vt, dim3(pr.cnt.T_max, pr.p.H, pr.p.B), dim3(256), 0, st, (const uint16_t*)src, dst,
-                     (uint16_t*)nullptr, ws.blk_start, ws.blk_n, ws.zero_tile, pr.geo);
-  return hipGetLastError();
-}
-
 // Mean keys / values gathered in kv_list order, rounded to bf16, in the layouts the attention kernel reads:
-// kcn[bh][t][d]; vcnt[bh][t/64][d][pos] with the list position t%64 = key_of_pos16(pos) (and vcnt4, when given, with
+// kcn[bh][t][d], vcn[bh][t][d]; vcnt[bh][t/64][d][pos] with the list position t%64 = key_of_pos16(pos) (and vcnt4, when given, with
 // t%64 = swap23(pos), for the 4-wave kernel); biasn[bh][t] = ln(n_j) sqrt(D), -inf past T_new.
 __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
                                                       const int* __restrict__ kv_list, const int* __restrict__ blk_n,
                                                       const int4* __restrict__ btab, uint16_t* __restrict__ kcn,
-                                                      uint16_t* __restrict__ vcnt, uint16_t* __restrict__ vcnt4,
+                                                      uint16_t* __restrict__ vcn, uint16_t* __restrict__ vcnt,
+                                                      uint16_t* __restrict__ vcnt4,
                                                       float* __restrict__ biasn,
                                                       int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad) {
   __shared__ uint16_t vtile[KT][MD + 2];
@@ -113,6 +108,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
       vval = vc[(bh * T_max + j) * MD + d];
     }
     kcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kval);
+    vcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(vval);       // row-major mean values: the backward pass streams them
     vtile[r][d] = f2bf(vval);
   }
   __syncthreads();
@@ -127,15 +123,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st) {
   hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
-                     ws.btab, ws.kcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
-  return hipGetLastError();
-}
-
-hipError_t launch_gather_means_bwd(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
-                                   const int* kv_list, hipStream_t st) {
-  // the same kernel with the two tensors swapped: row-major copy of the mean values, transposed copy of the mean keys
-  hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, vc, kc, kv_list, ws.blk_n,
-                     ws.btab, ws.vcn, ws.kcnt, (uint16_t*)nullptr, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
+                     ws.btab, ws.kcn, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
   return hipGetLastError();
 }
 

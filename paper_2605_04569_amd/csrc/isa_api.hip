@@ -124,7 +124,6 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->nlse = (float*)take(B * H * S * 4);
     ws->delta = (float*)take(B * H * S * 4);
     ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
-    ws->kcnt = (uint16_t*)take(B * H * Tn * D * 2);
     ws->dkc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->dvc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->ftab = (int4*)take(B * H * T * 16);
@@ -147,7 +146,7 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     }
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
-    ws->vcn = ws->kcnt = nullptr;
+    ws->vcn = nullptr;
     ws->ftab = ws->ltab = nullptr;
     ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
     ws->mask_t = nullptr;
@@ -375,7 +374,6 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
     if (p->gamma != 0.0)                            // O_coarse of Alg. 1 Stage 1
       ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, nullptr, ws.vc, ws.ocoarse, st));
   }
-  ISA_TRY(launch_gather_means_bwd(pr, ws, ws.kc, ws.vc, kv_list, st));
   ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, exact_mask, dq, dk, dv, st));
   return ISA_OK;
 }

@@ -66,7 +66,6 @@ struct Workspace {
   float* nlse;           // [B,H,S_max] minus the log-sum-exp of every query row, log2 domain (written by the forward)
   float* delta;          // [B,H,S_max] rowsum(dO * O)
   uint16_t* vcn;         // [B,H,Tn_pad][D]: mean values gathered in kv_list order (row-major, bf16)
-  uint16_t* kcnt;        // [B,H,Tn_pad/64][D][64]: mean keys gathered, transposed, key-permuted
   float* dkc; float* dvc;             // [BWD_MEAN_PARTS][B,H,Tn_pad][D] gradients of the gathered mean keys / values (part 0: the sum)
   int4* ftab; int4* ltab;             // [B,H,T_max] table rows of the full-attention / Taylor blocks, in list order
   float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128 pairs] per tile of 64 row positions of the list entries: 64 exponent terms, then 64 minus-deltas
@@ -124,11 +123,6 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st);
 hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st);
-// packed, transposed, key-permuted copy of a token tensor (the layout of Workspace::vt) into `dst`
-hipError_t launch_pack_t(const Problem& pr, const Workspace& ws, const void* src, uint16_t* dst, hipStream_t st);
-// mean values row-major and mean keys transposed (Workspace::vcn, kcnt), the mirror image of launch_gather_means
-hipError_t launch_gather_means_bwd(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
-                                   const int* kv_list, hipStream_t st);
 hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v,
                            const void* out, const void* d_out, const int* kv_list, const int* full_list,
                            const int* flat_list, const uint32_t* exact_mask, void* dq, void* dk, void* dv,
