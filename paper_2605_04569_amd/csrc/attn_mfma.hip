@@ -82,10 +82,13 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
                                                       const int4* __restrict__ btab, uint16_t* __restrict__ kcn,
                                                       uint16_t* __restrict__ vcn, uint16_t* __restrict__ vcnt,
                                                       uint16_t* __restrict__ vcnt4,
-                                                      float* __restrict__ biasn,
-                                                      int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad) {
+                                                      float* __restrict__ biasn, int* __restrict__ tflag,
+                                                      int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad, int block) {
   __shared__ uint16_t vtile[KT][MD + 2];
   __shared__ int ids[KT];
+  __shared__ int plain;                       // every mean key of the tile exists and stands for a full block
+  if (threadIdx.x == 0) plain = 1;
+  __syncthreads();
   const int tile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int T_new = cnt.b[b].T_new, T_max = cnt.T_max;
   const long long bh = (long long)b * H + h;
@@ -95,8 +98,14 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     const int j = t < T_new ? block_in_range(kv_list[bh * T_max + t], cnt.b[b].T) : -1;
     ids[threadIdx.x] = j;
     if (j >= 0) ktab[bh * T_max + t] = btab[b * T_max + j];
-    // ln(n_j) * sqrt(D): added to the raw score q.k, it becomes ln(n_j) after the 1/sqrt(D) scaling
-    biasn[bh * Tn_pad + t] = j >= 0 ? logf((float)blk_n[b * T_max + j]) * sqrtf((float)MD) : -INFINITY;
+    // ln(n_j) * sqrt(D): added to the raw score q.k, it becomes ln(n_j) after the 1/sqrt(D) scaling.  Without exact sets
+    // (no token keys beside the mean keys) a common factor of the weights cancels in the softmax: ln(n_j / block) is
+    // stored instead, which is exactly 0 for full blocks, and tiles of nothing but full blocks take the kernel's plain path
+    // (the log-sum-exp the forward hands to the backward is then short of ln(block); the backward uses the same terms).
+    const int n_j = j >= 0 ? blk_n[b * T_max + j] : 0;
+    const float shift = vcnt4 ? 0.f : logf((float)block);
+    biasn[bh * Tn_pad + t] = j >= 0 ? (n_j == block && !vcnt4 ? 0.f : (logf((float)n_j) - shift) * sqrtf((float)MD)) : -INFINITY;
+    if (j < 0 || n_j != block || vcnt4) plain = 0;          // benign race: every writer stores 0
   }
   __syncthreads();
   for (int x = threadIdx.x; x < KT * MD; x += 256) {
@@ -112,6 +121,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     vtile[r][d] = f2bf(vval);
   }
   __syncthreads();
+  if (threadIdx.x == 0) tflag[bh * (Tn_pad / KT) + tile] = plain ? 0 : 1;
   const long long out_off = (bh * (Tn_pad / KT) + tile) * (MD * KT);
   for (int x = threadIdx.x; x < MD * KT; x += 256) {
     const int d = x / KT, pos = x % KT;
@@ -123,7 +133,8 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st) {
   hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
-                     ws.btab, ws.kcn, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad);
+                     ws.btab, ws.kcn, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.tflag, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad,
+                     pr.p.block);
   return hipGetLastError();
 }
 

@@ -349,6 +349,9 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   int rowq[2];
   bool row_ok[2];
   bf16x8 qf[2][4];
+  // mean tiles only: lane L fetches whether tile L needs its bias and masks (tiles past the 64th are taken to)
+  int tile_flag = 1;
+  if constexpr (taylor) tile_flag = a.tflag[bh * (a.Tn_pad / KT) + min(lane, n_tiles - 1)];
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     rowq[qt] = wq * 32 + 16 * qt + r16;
@@ -449,6 +452,11 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[qt][ks]));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  const unsigned long long gen_mask = taylor ? __ballot(tile_flag != 0) : 0ull;
+  auto needs_general = [&](const STile& t) -> bool {
+    const int idx = t.bias_off / KT;
+    return idx >= 64 || ((gen_mask >> idx) & 1ull) != 0ull;
+  };
   __syncthreads();
   bf16x8 kf[8];                           // K fragments of the next 32 rows to be multiplied
 #pragma unroll
@@ -472,7 +480,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     const uint16_t* vbase = ldsV + bnn * V_TILE;                    // V^T tile T - 1
     {   // scores of half (T,0) into s0; weights of half (T-1,1) from s1 into pb; value product of pa = half (T-1,0)
       const int nkh = min(32, max(0, tprev.nk - 32));
-      const bool general = taylor || nkh < 32;
+      const bool general = (taylor && needs_general(tprev)) || nkh < 32;
       const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, neg_m, thr, alpha);
       half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, neg_m, thr, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
         if (f == 0) {
@@ -489,7 +497,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     }
     {   // scores of half (T,1) into s1; weights of half (T,0) from s0 into pa; value product of pb = half (T-1,1)
       const int nkh = min(32, tcur.nk);
-      const bool general = taylor || nkh < 32;
+      const bool general = (taylor && needs_general(tcur)) || nkh < 32;
       const bool raised = prepare_half(s0, mx0, raise0, general, nkh, bias_of(tcur), q, cscale, neg_m, thr, alpha);
       half_step<1>(ldsK + bnext * K_TILE, vbase, qf, kf, s0, s1, oacc, neg_m, thr, l_run, mx1, raise1, pb, pa, koff, voff, cscale, [](int) {}
       );
@@ -536,7 +544,8 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(-neg_m[qt], l_tot);
     } else {
       const float inv = 1.0f / l_tot;
-      if (a.nlse && q == 0) a.nlse[bh * a.S_max + q_start + row] = neg_m[qt] - __log2f(l_tot);
+      // the mean keys' biases may be stored short of a common term (see k_gather_means): the log-sum-exp gets it back
+      if (a.nlse && q == 0) a.nlse[bh * a.S_max + q_start + row] = neg_m[qt] - __log2f(l_tot) - (taylor ? a.lse_shift : 0.f);
       uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * q;
       // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
       const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * q : nullptr;
@@ -620,7 +629,8 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
 hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st) {
   MfmaArgs m;
   m.q = (const uint16_t*)a.q; m.k = (const uint16_t*)a.k; m.out = (uint16_t*)a.out;
-  m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn;
+  m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn; m.tflag = ws.tflag;
+  m.lse_shift = ws.vcnt4 ? 0.f : log2f((float)pr.p.block);
   m.zero_tile = ws.zero_tile;
   m.blk_start = a.blk_start; m.blk_n = a.blk_n;
   m.btab = ws.btab; m.ktab = ws.ktab;

@@ -114,6 +114,7 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->kcn = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
     ws->vcnt = (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2);
     ws->biasn = (float*)take(B * H * (size_t)pr.Tn_pad * 4);
+    ws->tflag = (int*)take(B * H * (size_t)(pr.Tn_pad / 64) * 4);
     ws->vt4 = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * T * D * 128 * 2) : nullptr;
     ws->vcnt4 = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2) : nullptr;
     ws->zero_tile = (uint16_t*)take(128 * 64 * 2);
@@ -154,6 +155,7 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->cstats = nullptr;
     ws->vt = ws->kcn = ws->vcnt = ws->vt4 = ws->vcnt4 = nullptr;
     ws->biasn = nullptr;
+    ws->tflag = nullptr;
     ws->zero_tile = nullptr;
     ws->ktab = nullptr;
     ws->split_o = ws->split_ml = nullptr;

@@ -55,7 +55,8 @@ struct Workspace {
   uint16_t* vt;          // [B,H,T_max][D][128]: V of each block, transposed and key-permuted
   uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order
   uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
-  float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key, -inf for padding
+  float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key (without exact sets: ln(n_j / block) sqrt(D)), -inf for padding
+  int* tflag;            // [B,H,Tn_pad/64]: 1 if a tile of mean keys needs its bias or masks (padding, a short block, exact sets)
   uint16_t* vt4; uint16_t* vcnt4;   // the same two arrays in the key order of the 4-wave kernel (only with exact sets)
   uint16_t* zero_tile;   // 16 KB of zeros, written by the V^T pack kernel
   int4* ktab;            // [B,H,T_max] the btab rows of the blocks of kv_list, in list order

@@ -27,7 +27,10 @@ CASES = [SMALL, RAGGED,
          SMALL.with_(name="paper_default_ratios", keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625),
          SMALL.with_(name="coarse_residual", gamma=0.5),
          RAGGED.with_(name="ragged_residual_exact_sets", gamma=-0.75, exact_frac=0.2, full_frac=0.2, keep_ratio=0.6),
-         SMALL.with_(name="residual_all_exact_nothing_kept", gamma=1.0, full_frac=1.0, keep_ratio=0.0)]
+         SMALL.with_(name="residual_all_exact_nothing_kept", gamma=1.0, full_frac=1.0, keep_ratio=0.0),
+         # 65 full source blocks + 5 full context blocks and a tail, all kept: a tile of 64 mean keys of full blocks (which the
+         # forward kernel treats without bias or masks) beside a ragged one; the backward depends on the forward's log-sum-exp
+         SMALL.with_(name="plain_mean_tile", H=2, src_grid=(4, 32, 65), ctx_grids=(((2, 10, 33),),), keep_ratio=1.0, seed=81)]
 
 # Gradients are compared relative to their own scale: the kernel rounds the weights P and dS to bf16 before the second
 # products (2^-9 relative each, thousands of terms with random signs), reads delta from the bf16 output and rounds the

@@ -209,6 +209,18 @@ def test_attend_on_oracle_lists(I, wl, exact_frac):
     _attend_with_oracle_lists(I, wl, exact_frac)
 
 
+def test_mean_tiles_of_full_blocks_beside_ragged_ones(I):
+    # 65 full source blocks, then 5 full context blocks and a 20-token tail, everything kept: the first 64 gathered means
+    # all stand for full blocks (their tile needs no bias and no mask), the second tile holds a short block and padding
+    wl = W.CONFIGS["cfg1"].with_(name="full_then_ragged", H=2, src_grid=(4, 32, 65), ctx_grids=(((2, 10, 33),),),
+                                 keep_ratio=1.0, full_frac=0.3, seed=81)
+    Q, K, V = W.make_inputs(wl, "cpu")
+    plan = oracle_plan(wl, Q, K, V, 0, 0)
+    kv, counts = np.asarray(plan["kv_list"]), np.asarray(plan["counts"])
+    assert len(kv) > 64 and (counts[kv[:64]] == wl.block).all() and (counts[kv[64:]] < wl.block).any()      # the premise
+    _attend_with_oracle_lists(I, wl)
+
+
 @pytest.mark.parametrize("exact_frac", [0.0, 0.25])
 def test_attend_on_oracle_lists_portable_kernels(I, exact_frac):
     _attend_with_oracle_lists(I, SMALL_BF16, exact_frac, mfma=False)
