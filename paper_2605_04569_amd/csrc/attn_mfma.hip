@@ -26,12 +26,14 @@ namespace isa {
 // ------------------------------------------------------------------------------------------
 // V^T copies: vt[((bh*T_max + j)*2 + half)][d][pos]; keys past n_j are zero.  `vt` is in the key order of the
 // 16x16x32 kernel (position p holds key key_of_pos16(p)); `vt4`, written only when given, in that of the 4-wave
-// 32x32x16 kernel (position p holds key swap23(p)).
+// 32x32x16 kernel (position p holds key swap23(p)).  With `vc` the block's mean value (fp32, Alg. 1 Stage 1) is written
+// as well: the tile is in LDS anyway, and the block-mean kernel then need not read V a second time.
 __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
                                                  uint16_t* __restrict__ vt4, const int* __restrict__ blk_start,
                                                  const int* __restrict__ blk_n, uint16_t* __restrict__ zero_tile,
-                                                 Geometry g) {
+                                                 float* __restrict__ vc, Geometry g) {
   __shared__ uint16_t tile[128][MD + 2];
+  __shared__ float colsum[MD];
   const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (j == 0 && h == 0 && b == 0)                                 // the all-zero V^T tile the attention kernel pads with
     for (int x = threadIdx.x; x < MD * KT / 8; x += 256) reinterpret_cast<uint4*>(zero_tile)[x] = make_uint4(0, 0, 0, 0);
@@ -47,6 +49,15 @@ __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v,
     dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
   }
   __syncthreads();
+  if (vc) {                                 // rows past n are zero: both halves of the threads add 64 rows of a channel
+    const int d = threadIdx.x & (MD - 1), r0 = (threadIdx.x >> 7) * 64;
+    float s = 0.f;
+#pragma unroll 8
+    for (int r = 0; r < 64; ++r) s += __uint_as_float((uint32_t)tile[r0 + r][d] << 16);
+    if (r0) colsum[d] = s;
+    __syncthreads();
+    if (!r0) vc[(((long long)b * g.H + h) * g.T_max + j) * MD + d] = (s + colsum[d]) / (float)n;
+  }
   const long long tile_off = (((long long)b * g.H + h) * g.T_max + j) * (2 * MD * KT);
   for (int x = threadIdx.x; x < 2 * MD * 8; x += 256) {         // one 16-byte chunk = 8 key positions of one channel
     const int half = x / (MD * 8), rem = x % (MD * 8);
@@ -68,9 +79,9 @@ __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v,
   }
 }
 
-hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, hipStream_t st) {
+hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, float* vc, hipStream_t st) {
   hipLaunchKernelGGL(k_pack_vt, dim3(pr.cnt.T_max, pr.p.H, pr.p.B), dim3(256), 0, st, (const uint16_t*)v, ws.vt,
-                     ws.vt4, ws.blk_start, ws.blk_n, ws.zero_tile, pr.geo);
+                     ws.vt4, ws.blk_start, ws.blk_n, ws.zero_tile, vc, pr.geo);
   return hipGetLastError();
 }
 

@@ -205,7 +205,7 @@ static int run_attend(const Problem& pr, const Workspace& ws, const AttnArgs& a,
     ISA_TRY(launch_attn_simt(pr, a, st));
     return ISA_OK;
   }
-  if (!vt_ready) ISA_TRY(launch_pack_vt(pr, ws, v, st));
+  if (!vt_ready) ISA_TRY(launch_pack_vt(pr, ws, v, nullptr, st));
   if (!a.dense) ISA_TRY(launch_gather_means(pr, ws, a.kc, a.vc, a.kv_list, st));
   ISA_TRY(launch_attn_mfma(pr, ws, a, st));
   return ISA_OK;
@@ -323,11 +323,15 @@ int isa_attention(const isa_problem* p, const void* q, const void* k, const void
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   ISA_TRY(launch_layout(pr, ws, st));
-  ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
+  // the matrix-core kernels want a packed V^T copy: the kernel that writes it has every block of V in LDS and writes the
+  // block's mean value too, so the block-mean kernel reads Q and K only
+  const bool pack_first = pr.mfma_shape && g_use_mfma.load();
+  if (pack_first) ISA_TRY(launch_pack_vt(pr, ws, v, ws.vc, st));
+  ISA_TRY(launch_block_means(pr, ws, q, k, pack_first ? nullptr : v, ws.qc, ws.kc, ws.vc, st));
   ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, ws.z, ws.vc, ws.ocoarse, st));
   ISA_TRY(launch_select(pr, ws, ws.s_ctx, ws.sharp, ws.z, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, ws.kc, ws.vc, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, ws.ocoarse, 0);
-  return run_attend(pr, ws, a, v, false, st);
+  return run_attend(pr, ws, a, v, pack_first, st);
 }
 
 int isa_dense_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* workspace,

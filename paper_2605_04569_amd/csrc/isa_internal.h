@@ -120,7 +120,8 @@ hipError_t launch_select(const Problem& pr, const Workspace& ws, const float* s_
 hipError_t launch_attn_simt(const Problem& pr, const AttnArgs& a, hipStream_t st);
 
 // MFMA path (bf16, D = 128, block = 128)
-hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, hipStream_t st);
+// vc (may be null): also writes the fp32 block means of V, [B,H,T_max,D]
+hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, float* vc, hipStream_t st);
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st);
 hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnArgs& a, hipStream_t st);

@@ -119,7 +119,8 @@ __global__ __launch_bounds__(256) void k_block_means(const T* __restrict__ q, co
   const long long obase = (((long long)b * g.H + h) * g.T_max + j) * D;
   const T* src[3] = {q, k, v};
   float* dst[3] = {qc, kc, vc};
-  for (int t = 0; t < 3; ++t) {
+  const int n_tensors = v ? 3 : 2;        // without v: its means come from the kernel that packs V^T
+  for (int t = 0; t < n_tensors; ++t) {
     float acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
