@@ -173,8 +173,6 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, co
   extern __shared__ float sm[];
   float* qs = sm;                       // [CROWS][D]
   float* zs = sm + CROWS * D;           // [CROWS][T_max]
-  __shared__ float redf[4];
-  __shared__ double redd[4];
   const int b = blockIdx.z, h = blockIdx.y, i0 = blockIdx.x * CROWS;
   const int T = cnt.b[b].T, T_src = cnt.b[b].T_src, T_max = cnt.T_max;
   if (i0 >= T) return;
@@ -204,38 +202,41 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, co
     for (int r = 0; r < CROWS; ++r) zs[r * T_max + j] = acc[r] * scale;
   }
   __syncthreads();
-  for (int r = 0; r < CROWS; ++r) {
+  // softmax, context columns and sharpness of a row: one wave per row (waves take rows wave, wave + 4), a lane owns the
+  // columns lane, lane + 64, ... from here on, so that nothing has to be synchronised between the passes over a row
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int r = wave; r < CROWS; r += 4) {
     const int i = i0 + r;
-    if (i >= T) break;                                  // uniform over the workgroup
+    if (i >= T) break;                                  // uniform over the wave
     float* zr = zs + r * T_max;
     if (z_out)
-      for (int j = threadIdx.x; j < T; j += 256) z_out[(bh * T_max + i) * T_max + j] = zr[j];
+      for (int j = lane; j < T; j += 64) z_out[(bh * T_max + i) * T_max + j] = zr[j];
     float m = -INFINITY;
-    for (int j = threadIdx.x; j < T; j += 256) m = fmaxf(m, zr[j]);
-    m = block_max(m, redf);
+    for (int j = lane; j < T; j += 64) m = fmaxf(m, zr[j]);
+    m = wave_max(m);
     double l = 0.0;
-    for (int j = threadIdx.x; j < T; j += 256) {
+    for (int j = lane; j < T; j += 64) {
       const float e = expf(zr[j] - m);
       zr[j] = e;
       l += (double)e;
     }
-    l = block_sum(l, redd);
+    l = wave_sum(l);
     const float inv = (float)(1.0 / l);
     double mu = 0.0;
-    for (int j = threadIdx.x; j < T; j += 256) {
+    for (int j = lane; j < T; j += 64) {
       const float p = zr[j] * inv;
       zr[j] = p;
       if (j < T_src) mu += (double)p;
       else if (i < T_src) pctx[(bh * Tsrc_max + i) * Tctx_max + (j - T_src)] = p;
     }
-    mu = block_sum(mu, redd) / (double)T_src;
+    mu = wave_sum(mu) / (double)T_src;
     double var = 0.0;
-    for (int j = threadIdx.x; j < T_src; j += 256) {
+    for (int j = lane; j < T_src; j += 64) {
       const double d = (double)zr[j] - mu;
       var += d * d;
     }
-    var = block_sum(var, redd) / (double)T_src;
-    if (threadIdx.x == 0) sharp[bh * T_max + i] = (float)var;
+    var = wave_sum(var) / (double)T_src;
+    if (lane == 0) sharp[bh * T_max + i] = (float)var;
   }
   // O_coarse = S_coarse V^c (Alg. 1 Stage 1), only when the caller wants the coarse residual: the rows of
   // S_coarse of this workgroup's query blocks are in LDS; one thread per (row, channel), channels fastest
@@ -253,16 +254,23 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, co
   }
 }
 
-// Eq. 1: mean over the source query blocks of each context column.
-__global__ void k_colmean(const float* __restrict__ pctx, float* __restrict__ s_ctx, Counts cnt, int H, int Tsrc_max,
-                          int Tctx_max) {
-  const int b = blockIdx.z, h = blockIdx.y, j = blockIdx.x * blockDim.x + threadIdx.x;
+// Eq. 1: mean over the source query blocks of each context column.  64 columns per workgroup; the four waves each add a
+// quarter of the rows, and the quarters are added in a fixed order.
+__global__ __launch_bounds__(256) void k_colmean(const float* __restrict__ pctx, float* __restrict__ s_ctx, Counts cnt,
+                                                 int H, int Tsrc_max, int Tctx_max) {
+  __shared__ double part[4][64];
+  const int b = blockIdx.z, h = blockIdx.y, lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
   const int T_src = cnt.b[b].T_src, T_ctx = cnt.b[b].T_ctx;
-  if (j >= T_ctx) return;
   const long long bh = (long long)b * H + h;
+  const int per = (T_src + 3) / 4, i_lo = quarter * per, i_hi = min(T_src, i_lo + per);
   double acc = 0.0;
-  for (int i = 0; i < T_src; ++i) acc += (double)pctx[(bh * Tsrc_max + i) * Tctx_max + j];
-  s_ctx[bh * cnt.T_max + j] = (float)(acc / (double)T_src);
+  if (j < T_ctx)
+    for (int i = i_lo; i < i_hi; ++i) acc += (double)pctx[(bh * Tsrc_max + i) * Tctx_max + j];
+  part[quarter][lane] = acc;
+  __syncthreads();
+  if (quarter == 0 && j < T_ctx)
+    s_ctx[bh * cnt.T_max + j] = (float)((((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) / (double)T_src);
 }
 
 hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc, const float* kc, float* s_ctx,
@@ -284,7 +292,7 @@ hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc
                        pr.Tctx_max);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_colmean, dim3((pr.Tctx_max + 255) / 256, pr.p.H, pr.p.B), dim3(256), 0, st, ws.pctx, s_ctx, pr.cnt,
+  hipLaunchKernelGGL(k_colmean, dim3((pr.Tctx_max + 63) / 64, pr.p.H, pr.p.B), dim3(256), 0, st, ws.pctx, s_ctx, pr.cnt,
                      pr.p.H, pr.Tsrc_max, pr.Tctx_max);
   return hipGetLastError();
 }
