@@ -160,7 +160,7 @@ struct Tile {                               // wave-uniform description of one 6
   const float* bias;                        // per-key additive term on the raw score, or null
   int nk;                                   // valid keys (0..64); rows past it are masked
   int last_row;                             // last row relative to krows that may be read (>= 0)
-  int tpos;                                 // position of key 0 in kv_list (mean tiles), for the exact mask
+  uint32_t mw0, mw1;                        // mean tiles: the exact-mask bits of the tile's 64 list entries (masked out)
 };
 
 // One 64-key tile for the 32 query columns of a wave: S^T = K Q^T, online softmax in the log2 domain
@@ -279,7 +279,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
 
   // only the Taylor slots of the (batch, head): its exact-branch blocks are handled by the 8-wave kernel
   if (slot < c.n_full) return;
-  const int* kvl = a.kv_list + bh * T_max;
   const int n_list = c.T_new;
   const int qi = block_in_range(a.flat_list[bh * T_max + slot - c.n_full], c.T);
   const uint32_t* mrow = (a.exact_mask && c.k_exact > 0)
@@ -312,26 +311,42 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
 
   // ---- tile sequence.  Phase A: the token tiles (two 64-key halves) of the list entries in the block's exact set.
   // Phase B: tiles of 64 gathered block means (the entries of the exact set masked out).
-  int it_t = 0, it_sub = 0, it_mean = 0;
-  if (!mrow) it_t = n_list;
+  // Everything a tile's description needs is one mask word and one table row {token offset, tokens, block} of the list
+  // entry, and the description is worked out one iteration before its loads are issued: none of these (dependent) loads
+  // is waited for between the tile loads and the tile's arithmetic.
+  int it_sub = 0, it_mean = 0;
+  uint32_t word = 0u;                       // bits of the mask word at wbase that are still to be visited
+  int wbase = -32;
+  int4 erow = make_int4(0, 0, 0, 0);        // table row of the current entry of the exact set
+  const int4* const tab = a.ktab + bh * T_max;
+  auto next_exact = [&]() -> bool {         // moves on to the next entry of the exact set; false when there is none left
+    if (!mrow) return false;
+    while (word == 0u) {
+      wbase += 32;
+      if (wbase >= n_list) return false;
+      word = mrow[wbase >> 5];
+    }
+    const int e = wbase + __builtin_ctz(word);
+    word &= word - 1u;
+    if (e >= n_list) { word = 0u; wbase = n_list; return false; }
+    erow = tab[e];
+    return true;
+  };
+  bool in_exact = next_exact();
   const int n_mean_tiles = (n_list + KT - 1) / KT;
   auto next_tile = [&](Tile& t) -> bool {
-    if (mrow) {
-      while (it_t < n_list && !((mrow[it_t >> 5] >> (it_t & 31)) & 1u)) ++it_t;
-    }
-    if (it_t < n_list) {
-      const int j = block_in_range(kvl[it_t], c.T);
-      const int n_j = bn[j];
+    if (in_exact) {
+      const int n_j = erow.y;
       const int k0 = it_sub * KT;
-      t.krows = a.k + tbase + (long long)bs[j] * a.geo.stride_t;
+      t.krows = a.k + tbase + (long long)erow.x * a.geo.stride_t;
       t.row0 = k0;
       t.kstride = (int)a.geo.stride_t;
-      t.vt = a.vt + ((bh * T_max + j) * 2 + it_sub) * (long long)(MD * KT);
+      t.vt = a.vt + ((bh * T_max + erow.z) * 2 + it_sub) * (long long)(MD * KT);
       t.bias = nullptr;
       t.nk = max(0, min(KT, n_j - k0));
       t.last_row = max(n_j - 1, 0);
-      t.tpos = 0;
-      it_t += it_sub;
+      t.mw0 = t.mw1 = 0u;
+      if (it_sub) in_exact = next_exact();
       it_sub ^= 1;
       return true;
     }
@@ -344,7 +359,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
       t.bias = a.biasn + row0;
       t.nk = min(KT, n_list - it_mean * KT);
       t.last_row = KT - 1;                                          // the gathered arrays are padded to whole tiles
-      t.tpos = it_mean * KT;
+      const int w = 2 * it_mean;
+      t.mw0 = mrow ? mrow[w] : 0u;
+      t.mw1 = (mrow && w + 1 < a.cnt.mask_words) ? mrow[w + 1] : 0u;
       ++it_mean;
       return true;
     }
@@ -391,30 +408,27 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) voff[ks] = col * KT + (((2 * ks + g) ^ ((col >> 1) & 7)) * 8);
 
-  Tile cur, nxt;
+  Tile cur, nxt, nn;
   bool have = next_tile(cur);
+  bool have_next = next_tile(nxt);          // (returns false again once the sequence has ended)
   if (have) load_tile(cur, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int buf = 0;
   while (have) {
-    const bool have_next = next_tile(nxt);
     if (have_next) load_tile(nxt, buf ^ 1);
+    const bool have_nn = next_tile(nn);
     const uint16_t* kbase = ldsK + buf * K_TILE;
     const uint16_t* vbase = ldsV + buf * V_TILE;
     const bool general = cur.bias != nullptr || cur.nk < KT;
-    uint32_t mw0 = 0, mw1 = 0;
-    if (mrow && cur.bias) {
-      const int w = cur.tpos >> 5;
-      mw0 = mrow[w];
-      mw1 = (w + 1 < a.cnt.mask_words) ? mrow[w + 1] : 0u;
-    }
-    tile_body(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, general, cur.nk, cur.bias, mw0, mw1);
+    tile_body(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, general, cur.nk, cur.bias, cur.mw0, cur.mw1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     buf ^= 1;
     cur = nxt;
+    nxt = nn;
     have = have_next;
+    have_next = have_nn;
   }
 
   // ---- normalise and store: element e of channel group db is channel 32db + 8(e/4) + 4g + e%4
