@@ -351,7 +351,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   bf16x8 qf[2][4];
   // mean tiles only: lane L fetches whether tile L needs its bias and masks (tiles past the 64th are taken to)
   int tile_flag = 1;
-  if constexpr (taylor) tile_flag = a.tflag[bh * (a.Tn_pad / KT) + min(lane, n_tiles - 1)];
+  if constexpr (taylor) tile_flag = a.tflag[bh * (a.Tn_pad / KT) + max(min(lane, n_tiles - 1), 0)];
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     rowq[qt] = wq * 32 + 16 * qt + r16;
