@@ -45,6 +45,7 @@ extern "C" {
 #define ISA_MAX_BATCH 8
 #define ISA_MAX_SEGMENTS 32
 #define ISA_MAX_BLOCKS 4096
+#define ISA_STATIC_SCRATCH_BYTES (128u << 20) /* device scratch held by the library itself, see isa_attention_static */
 
 typedef enum {
   ISA_OK = 0,
@@ -112,6 +113,18 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
  * `hip_stream` and releases it with hipFreeAsync, so it is not for callers that must not allocate. */
 int isa_attention_simple(const void* q, const void* k, const void* v, int H, int D, int n_src, int n_ctx,
                          double keep_ratio, double full_frac, int block, void* out, void* hip_stream);
+
+/* isa_attention for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same result as
+ * isa_attention, but the scratch memory is a fixed array of ISA_STATIC_SCRATCH_BYTES inside the library's own device
+ * image (every GPU the library runs on holds one copy until the process ends); the call allocates and frees nothing.
+ * Limits: the forward-only workspace of `p` (the arrays isa_attention needs, without those it would leave for
+ * isa_attention_backward) must fit that array, else ISA_ERR_WORKSPACE and nothing is launched; at D = 128 in bf16 that is
+ * about 330 000 head-tokens (H * S), e.g. 40 heads of 8 000 tokens.  No backward call can follow it.  The array is shared
+ * by every call on the same GPU and keeps the previous call's contents (no call relies on them): two calls that overlap on
+ * one GPU (different streams, different threads) race; calls on one stream are ordered.  The first call on a device
+ * looks the array's address up (hipGetSymbolAddress), so make it before a stream capture begins. */
+int isa_attention_static(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* hip_stream);
 
 /* ---- staged entry points: one per stage, so each can be checked on its own ---------------- */
 

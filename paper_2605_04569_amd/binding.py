@@ -59,6 +59,7 @@ def lib():
         L.isa_workspace_bytes.restype = C.c_size_t
         L.isa_attention.argtypes = [P, V, V, V, V, V, SZ, ST]
         L.isa_dense_attention.argtypes = [P, V, V, V, V, V, SZ, ST]
+        L.isa_attention_static.argtypes = [P, V, V, V, V, ST]
         L.isa_attention_simple.argtypes = [V, V, V, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double,
                                            C.c_int, V, ST]
         L.isa_block_means.argtypes = [P, V, V, V, V, V, V, V, SZ, ST]
@@ -201,6 +202,13 @@ def isa_attention(pr: Problem, q, k, v, out, workspace):
     cp, keep = pr.c_struct(q)
     _check(lib().isa_attention(C.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(workspace), workspace.numel(),
                                _stream()), "isa_attention")
+    return out
+
+
+def isa_attention_static(pr: Problem, q, k, v, out):
+    _same_layout(q, k, v, out)
+    cp, keep = pr.c_struct(q)
+    _check(lib().isa_attention_static(C.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _stream()), "isa_attention_static")
     return out
 
 

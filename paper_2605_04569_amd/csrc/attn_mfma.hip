@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
       vval = vc[(bh * T_max + j) * MD + d];
     }
     kcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kval);
-    vcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(vval);       // row-major mean values: the backward pass streams them
+    if (vcn) vcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(vval);       // row-major mean values: the backward pass streams them
     vtile[r][d] = f2bf(vval);
   }
   __syncthreads();

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "isa_internal.h"
 
@@ -84,7 +85,7 @@ int validate(const isa_problem* p, Problem* out) {
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-void carve(const Problem& pr, void* base, Workspace* ws) {
+void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
   const size_t B = pr.p.B, H = pr.p.H, D = pr.p.D, T = pr.cnt.T_max;
   size_t off = 0;
   char* b0 = (char*)base;
@@ -121,6 +122,8 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->ktab = (int4*)take(B * H * T * 16);
     ws->split_o = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 128 * 4);
     ws->split_ml = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 2 * 4);
+  }
+  if (pr.mfma_shape && !forward_only) {       // what the forward leaves for the backward pass, and the backward's own scratch
     const size_t S = (size_t)pr.S_max, Tn = (size_t)pr.Tn_pad;
     ws->nlse = (float*)take(B * H * S * 4);
     ws->delta = (float*)take(B * H * S * 4);
@@ -153,6 +156,8 @@ void carve(const Problem& pr, void* base, Workspace* ws) {
     ws->mask_t = nullptr;
     ws->doc = ws->cdq = ws->cdk = ws->cdv = nullptr;
     ws->cstats = nullptr;
+  }
+  if (!pr.mfma_shape) {
     ws->vt = ws->kcn = ws->vcnt = ws->vt4 = ws->vcnt4 = nullptr;
     ws->biasn = nullptr;
     ws->tflag = nullptr;
@@ -312,16 +317,9 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
   return run_attend(pr, ws, a, v, false, st);
 }
 
-int isa_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* workspace,
-                  size_t workspace_bytes, void* hip_stream) {
-  Problem pr;
-  int rc = validate(p, &pr);
-  if (rc != ISA_OK) return rc;
-  if (!q || !k || !v || !out) return ISA_ERR_NULL;
-  if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
-  Workspace ws;
-  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
-  hipStream_t st = (hipStream_t)hip_stream;
+// Alg. 1, all stages, on a carved workspace (the body of isa_attention and of its allocation-free twin).
+static int run_attention(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v, void* out,
+                         hipStream_t st) {
   ISA_TRY(launch_layout(pr, ws, st));
   // the matrix-core kernels want a packed V^T copy: the kernel that writes it has every block of V in LDS and writes the
   // block's mean value too, so the block-mean kernel reads Q and K only
@@ -332,6 +330,61 @@ int isa_attention(const isa_problem* p, const void* q, const void* k, const void
   ISA_TRY(launch_select(pr, ws, ws.s_ctx, ws.sharp, ws.z, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, ws.kc, ws.vc, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, ws.ocoarse, 0);
   return run_attend(pr, ws, a, v, pack_first, st);
+}
+
+int isa_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
+  Workspace ws;
+  if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
+  return run_attention(pr, ws, q, k, v, out, (hipStream_t)hip_stream);
+}
+
+// ---- the entry point that allocates nothing and takes no workspace -------------------------------------------------------
+// Its scratch is this file-scope device array: every GPU the library's code object is loaded on holds one copy, at its own
+// address, until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the device
+// address obtained from it (once per device, kept in g_static_ptr) is what kernels and carve() are given.
+static __device__ __align__(256) unsigned char scratch[ISA_STATIC_SCRATCH_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+static void* g_static_ptr[STATIC_MAX_DEVICES];          // device address of `scratch` on each device; null = not asked yet
+static std::mutex g_static_mu;
+
+static int static_scratch(void** ptr) {
+  int dev = -1;
+  ISA_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return ISA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* d = nullptr;
+    size_t bytes = 0;
+    ISA_TRY(hipGetSymbolAddress(&d, HIP_SYMBOL(scratch)));      // of the current device's copy
+    ISA_TRY(hipGetSymbolSize(&bytes, HIP_SYMBOL(scratch)));
+    if (!d || bytes < (size_t)ISA_STATIC_SCRATCH_BYTES || ((uintptr_t)d & 255)) return ISA_ERR_WORKSPACE;
+    g_static_ptr[dev] = d;
+  }
+  *ptr = g_static_ptr[dev];
+  return ISA_OK;
+}
+
+int isa_attention_static(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* hip_stream) {
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  if (!q || !k || !v || !out) return ISA_ERR_NULL;
+  if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
+  Workspace ws;
+  carve(pr, nullptr, &ws, true);                       // the forward pass only: nothing is kept for a backward call
+  if (ws.bytes > (size_t)ISA_STATIC_SCRATCH_BYTES) return ISA_ERR_WORKSPACE;
+  void* base = nullptr;
+  if ((rc = static_scratch(&base)) != ISA_OK) return rc;
+  carve(pr, base, &ws, true);
+  // every array of the carve-up is written by a kernel of this call before any kernel reads it, so what the previous
+  // call left in the scratch does not matter and nothing has to be cleared
+  return run_attention(pr, ws, q, k, v, out, (hipStream_t)hip_stream);
 }
 
 int isa_dense_attention(const isa_problem* p, const void* q, const void* k, const void* v, void* out, void* workspace,

@@ -95,7 +95,8 @@ extern hipEvent_t g_prof_start, g_prof_stop;   // events recorded around the MFM
 extern int g_prof_on, g_prof_recorded;
 
 int validate(const isa_problem* p, Problem* out);
-void carve(const Problem& pr, void* base, Workspace* ws);
+// forward_only: without the arrays that the forward pass leaves for, and that are scratch of, the backward pass
+void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only = false);
 
 // ---- kernel launchers (each returns hipError_t of the launch) -------------------------------
 struct AttnArgs {

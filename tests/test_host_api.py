@@ -93,6 +93,19 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, one, one, 16, None) == -6
 
 
+def test_static_scratch_entry_point_checks_before_it_touches_the_gpu():
+    """isa_attention_static: argument errors and a problem whose forward-only workspace exceeds the library's fixed
+    scratch array are refused before any HIP call."""
+    L = I.lib()
+    one = C.c_void_p(256)
+    big, keep_b = base_problem(H=40, D=128, block=128, dtype="bf16", seg_len=[[32760, 32760]]).c_struct()
+    assert L.isa_attention_static(C.byref(big), one, one, one, one, None) == -6
+    assert L.isa_attention_static(C.byref(big), one, None, one, one, None) == -1
+    assert L.isa_attention_static(C.byref(big), one, one, C.c_void_p(264), one, None) == -2
+    bad, keep_x = base_problem(keep_ratio=2.0).c_struct()
+    assert L.isa_attention_static(C.byref(bad), one, one, one, one, None) == -3
+
+
 def test_prologue_validation_needs_no_gpu():
     L = I.lib()
     pr = base_problem()                                   # segments 512 + 512
