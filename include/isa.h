@@ -183,8 +183,9 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
  * zeros).
  * kv_list, full_list, flat_list, exact_mask: the device lists (and, when exact_frac > 0, the exact-set bits, as written
  * by isa_select) the forward call ran with, or all NULL for those that isa_attention left in the workspace.
- * The workspace must be the one the forward call used, untouched since: it holds the log-sum-exp of every query row
- * (and, when the lists are taken from it, the block table, the block means and O_coarse, which are then not computed again).
+ * The workspace must be the one the forward call used, untouched since: it holds the log-sum-exp of every query row and
+ * the part of every output element that its rounding to bf16 cut off (so that rowsum(d_out * out) is taken from the
+ * unrounded result) (and, when the lists are taken from it, the block table, the block means and O_coarse, which are then not computed again).
  * With gamma != 0 the gradient of the coarse residual (through the means of all blocks, query blocks included) is part
  * of the result.
  * Only for bf16, D = 128, block = 128, and only after a forward call that ran the MFMA kernels (ISA_ERR_UNSUPPORTED

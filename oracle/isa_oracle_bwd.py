@@ -12,7 +12,7 @@ Stages 1 and 5).
 
 Pinned by central finite differences of the forward oracle with the same
 indices frozen, by the dense special case, and by closed forms
-(tests/test_oracle_bwd_pins.py).  No GPU kernel exists for it yet.
+(tests/test_oracle_bwd_pins.py).
 """
 import math
 

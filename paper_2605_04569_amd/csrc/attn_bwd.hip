@@ -539,9 +539,13 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   }
 }
 
-// delta[bh][token] = sum_d dO * O (fp32); 16 lanes per token row, 16 bytes per lane and tensor.
-__global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ o, const uint16_t* __restrict__ d_o,
-                                                   float* __restrict__ delta, Geometry g, Counts cnt, int S_max) {
+// delta[bh][token] = sum_d dO * O (fp32); 16 lanes per token row, 16 bytes per lane and tensor.  O is taken as out + olo:
+// the bf16 output plus what its rounding cut off, which the forward kernels keep for this purpose.  With the bf16 output
+// alone, delta carries that rounding (2^-9 |dO||O|) into dS = P (dP - delta), which for a query that attends almost
+// one-hot is a difference of nearly equal numbers.
+__global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ o, const uint16_t* __restrict__ olo,
+                                                   const uint16_t* __restrict__ d_o, float* __restrict__ delta, Geometry g,
+                                                   Counts cnt, int S_max) {
   const int h = blockIdx.y, b = blockIdx.z;
   const int t = blockIdx.x * 16 + (threadIdx.x >> 4), c16 = threadIdx.x & 15;
   const bool ok = t < cnt.b[b].S;
@@ -549,11 +553,13 @@ __global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ 
   if (ok) {
     const long long off = (long long)b * g.stride_b + (long long)h * g.stride_h + (long long)t * g.stride_t + 8 * c16;
     const uint4 uo = *reinterpret_cast<const uint4*>(o + off), ud = *reinterpret_cast<const uint4*>(d_o + off);
-    const uint32_t wo[4] = {uo.x, uo.y, uo.z, uo.w}, wd[4] = {ud.x, ud.y, ud.z, ud.w};
+    uint4 ul = make_uint4(0u, 0u, 0u, 0u);
+    if (olo) ul = *reinterpret_cast<const uint4*>(olo + (((long long)b * g.H + h) * S_max + t) * MD + 8 * c16);
+    const uint32_t wo[4] = {uo.x, uo.y, uo.z, uo.w}, wd[4] = {ud.x, ud.y, ud.z, ud.w}, wl[4] = {ul.x, ul.y, ul.z, ul.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      s += __uint_as_float(wo[i] << 16) * __uint_as_float(wd[i] << 16) +
-           __uint_as_float(wo[i] & 0xffff0000u) * __uint_as_float(wd[i] & 0xffff0000u);
+      s += (__uint_as_float(wo[i] << 16) + __uint_as_float(wl[i] << 16)) * __uint_as_float(wd[i] << 16) +
+           (__uint_as_float(wo[i] & 0xffff0000u) + __uint_as_float(wl[i] & 0xffff0000u)) * __uint_as_float(wd[i] & 0xffff0000u);
   }
 #pragma unroll
   for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
@@ -899,7 +905,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   } while (0)
   // delta, zero fill, per-list tables and row terms
   hipLaunchKernelGGL(k_bwd_delta, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (const uint16_t*)out,
-                     (const uint16_t*)d_out, ws.delta, pr.geo, pr.cnt, S_max);
+                     ws.olo, (const uint16_t*)d_out, ws.delta, pr.geo, pr.cnt, S_max);
   ISA_BWD_CHECK();
   if (resid) {
     // gradient of the coarse residual with respect to the block means (all blocks, by block id), and delta without

@@ -23,6 +23,19 @@ __device__ inline uint16_t f2bf(float f) {     // round to nearest even
   if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
   return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
+// Four fp32 results as stored: `hi` the bf16 roundings that go to `out`, `lo` the bf16 roundings of what those cut off.
+__device__ __forceinline__ void split_bf16x4(const float4 r, uint2& hi, uint2& lo) {
+  const float x[4] = {r.x, r.y, r.z, r.w};
+  uint16_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const __bf16 hb = (__bf16)x[i];
+    h[i] = __builtin_bit_cast(uint16_t, hb);
+    l[i] = __builtin_bit_cast(uint16_t, (__bf16)(x[i] - (float)hb));
+  }
+  hi = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+  lo = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+}
 __device__ inline int swap23(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
 // Key stored at position p of a 64-key V^T row in the layout of the 16x16x32 kernel: inside each 32-key group,
 // position 8 q + 4 kt + i holds key 16 kt + 4 q + i (the order in which a lane's score registers list its keys).
@@ -50,7 +63,9 @@ struct MfmaArgs {
   int hpx, n_long;                          // k_attn_sp: (batch, head)s per XCD; exact-branch items per XCD (0 if none)
   int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges
   float* split_o; float* split_ml;          // their partial results: unnormalised outputs [sub-item][2][128][128], {max, sum} [sub-item][2][128][2]
-  float* nlse; int S_max;                   // k_attn_sp: minus the log-sum-exp (log2 domain) of every query row, [bh][S_max]; may be null
+  float* nlse; int S_max;                   // minus the log-sum-exp (log2 domain) of every query row, [bh][S_max]; may be null
+  uint16_t* olo;                            // [bh][S_max][128] bf16, may be null: what the rounding of `out` to bf16 cut off
+                                            // (out + olo is the fp32 result to about 2^-17), for the backward's delta
   int taylor_here;                          // k_attn_sp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only
 };
 

@@ -439,6 +439,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
     uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
     // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
     const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * g : nullptr;
+    uint16_t* lp = a.olo ? a.olo + (bh * a.S_max + q_start + row) * MD + 4 * g : nullptr;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -450,12 +451,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
           r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
           r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
         }
-        bf16x2 lo = {(__bf16)r.x, (__bf16)r.y};
-        bf16x2 hi = {(__bf16)r.z, (__bf16)r.w};
-        uint2 o;
-        o.x = *reinterpret_cast<uint32_t*>(&lo);
-        o.y = *reinterpret_cast<uint32_t*>(&hi);
+        uint2 o, cut;
+        split_bf16x4(r, o, cut);
         *reinterpret_cast<uint2*>(op + 32 * db + 8 * e4) = o;
+        if (lp) *reinterpret_cast<uint2*>(lp + 32 * db + 8 * e4) = cut;
       }
   }
 }

@@ -549,6 +549,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * q;
       // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
       const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * q : nullptr;
+      uint16_t* lp = a.olo ? a.olo + (bh * a.S_max + q_start + row) * MD + 4 * q : nullptr;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         float4 r = make_float4(oacc[c][qt][0] * inv, oacc[c][qt][1] * inv, oacc[c][qt][2] * inv, oacc[c][qt][3] * inv);
@@ -557,12 +558,10 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
           r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
           r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
         }
-        bf16x2 lo = {(__bf16)r.x, (__bf16)r.y};
-        bf16x2 hi = {(__bf16)r.z, (__bf16)r.w};
-        uint2 o;
-        o.x = *reinterpret_cast<uint32_t*>(&lo);
-        o.y = *reinterpret_cast<uint32_t*>(&hi);
+        uint2 o, cut;
+        split_bf16x4(r, o, cut);
         *reinterpret_cast<uint2*>(op + 16 * c) = o;
+        if (lp) *reinterpret_cast<uint2*>(lp + 16 * c) = cut;
       }
     }
   }
@@ -616,12 +615,10 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
     acc.x = fmaf(a.gamma, c4.x, acc.x); acc.y = fmaf(a.gamma, c4.y, acc.y);
     acc.z = fmaf(a.gamma, c4.z, acc.z); acc.w = fmaf(a.gamma, c4.w, acc.w);
   }
-  bf16x2 lo = {(__bf16)acc.x, (__bf16)acc.y};
-  bf16x2 hi = {(__bf16)acc.z, (__bf16)acc.w};
-  uint2 o;
-  o.x = *reinterpret_cast<uint32_t*>(&lo);
-  o.y = *reinterpret_cast<uint32_t*>(&hi);
+  uint2 o, cut;
+  split_bf16x4(acc, o, cut);
   *reinterpret_cast<uint2*>(a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + ch) = o;
+  if (a.olo) *reinterpret_cast<uint2*>(a.olo + ((long long)bhid * a.S_max + q_start + row) * MD + ch) = cut;
 }
 
 // Launches the attention kernels of the MFMA path: the software-pipelined kernel for dense attention, the
@@ -640,6 +637,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   m.geo = a.geo; m.cnt = a.cnt; m.dense = a.dense;
   m.Tn_pad = pr.Tn_pad;
   m.nlse = a.dense ? nullptr : ws.nlse; m.S_max = pr.S_max;
+  m.olo = a.dense ? nullptr : ws.olo;
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
   m.taylor_here = exact_sets ? 0 : 1;
   // pair slots per (batch, head): the largest counts over the batch

@@ -126,6 +126,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
   if (pr.mfma_shape && !forward_only) {       // what the forward leaves for the backward pass, and the backward's own scratch
     const size_t S = (size_t)pr.S_max, Tn = (size_t)pr.Tn_pad;
     ws->nlse = (float*)take(B * H * S * 4);
+    ws->olo = (uint16_t*)take(B * H * S * D * 2);
     ws->delta = (float*)take(B * H * S * 4);
     ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
     ws->dkc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
@@ -150,7 +151,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     }
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
-    ws->vcn = nullptr;
+    ws->vcn = ws->olo = nullptr;
     ws->ftab = ws->ltab = nullptr;
     ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
     ws->mask_t = nullptr;

@@ -65,6 +65,7 @@ struct Workspace {
   float* split_ml;       // their running maxima and sums
   // backward pass (MFMA path): what the forward leaves for it, and its own scratch
   float* nlse;           // [B,H,S_max] minus the log-sum-exp of every query row, log2 domain (written by the forward)
+  uint16_t* olo;         // [B,H,S_max,D] bf16: what the rounding of the output to bf16 cut off (written by the forward)
   float* delta;          // [B,H,S_max] rowsum(dO * O)
   uint16_t* vcn;         // [B,H,Tn_pad][D]: mean values gathered in kv_list order (row-major, bf16)
   float* dkc; float* dvc;             // [BWD_MEAN_PARTS][B,H,Tn_pad][D] gradients of the gathered mean keys / values (part 0: the sum)
