@@ -3,7 +3,9 @@
 
 One "step" is one isa_attention() call: every stage of the operator (block means, pooled scores,
 selection, grouping, exact branch, Taylor branch, merge) over one batch of synthetic input that is
-already resident in HBM.  The same process also times our dense MFMA attention at the same shape
+already resident in HBM.  The default workload is the largest configuration (720p, 151 200 tokens);
+the others (short clip, 480p, the ragged batch at the nine points of its ratio sweep, 480p at the
+paper's default ratios) are timed briefly afterwards and reported under "other_workloads".  The same process also times our dense MFMA attention at the same shape
 (the speedup denominator), times the dominant kernel alone with HIP events recorded around its
 launch inside the library, and times the CPU oracle on a bounded sample of the same workload.
 
@@ -95,18 +97,21 @@ def measured_traffic(workload):
     return None
 
 
-def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0):
-    """Times isa_attention (whole call and the attention kernel alone) and dense attention on one workload."""
+def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0, inputs=None):
+    """Times isa_attention (whole call and the attention kernel alone) and dense attention on one workload.
+    `inputs`: Q, K, V already on the GPU (the ratios are not part of the input recipe), else they are generated."""
     import numpy as np
     import torch
 
     import paper_2605_04569_amd as isa
     import workloads as W
 
-    log("generating %s on the GPU" % wl.name)
-    Q, K, V = W.make_inputs(wl, "cuda")
-    torch.cuda.synchronize()
-    log("inputs ready")
+    if inputs is None:
+        log("generating %s on the GPU" % wl.name)
+        inputs = W.make_inputs(wl, "cuda")
+        torch.cuda.synchronize()
+        log("inputs ready")
+    Q, K, V = inputs
     pr = isa.Problem(H=wl.H, D=wl.D, dtype=wl.dtype, block=wl.block, seg_len=[wl.seg_len(b) for b in range(wl.B)],
                      keep_ratio=wl.keep_ratio, full_frac=wl.full_frac, exact_frac=wl.exact_frac, gamma=wl.gamma)
     ws = isa.new_workspace(pr)
@@ -137,23 +142,17 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0):
     kern_ms = float(np.mean(kernel_ms))
     log("attention kernel alone: %.3f ms" % kern_ms)
 
-    # ---- lists actually chosen (for the algorithmic flop count) -----------------------------------
-    T_max = isa.isa_get_counts(pr, 0)["T_max"]
-    f = dict(device="cuda", dtype=torch.float32)
-    qc, kc, vc = (torch.zeros((wl.B, wl.H, T_max, wl.D), **f) for _ in range(3))
-    s_ctx, sharp = torch.zeros((wl.B, wl.H, T_max), **f), torch.zeros((wl.B, wl.H, T_max), **f)
-    z = torch.zeros((wl.B, wl.H, T_max, T_max), **f) if wl.exact_frac > 0 else None
-    mask = torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), device="cuda", dtype=torch.int32) if wl.exact_frac > 0 else None
-    kv, full, flat = (torch.zeros((wl.B, wl.H, T_max), device="cuda", dtype=torch.int32) for _ in range(3))
-    isa.isa_block_means(pr, Q, K, V, qc, kc, vc, ws)
-    isa.isa_coarse_scores(pr, qc, kc, s_ctx, sharp, z, ws)
-    isa.isa_select(pr, s_ctx, sharp, z, kv, full, flat, mask, ws)
+    # ---- the lists this call chose, read from its workspace (for the algorithmic flop count) -----------------------
     torch.cuda.synchronize()
+    T_max = isa.isa_get_counts(pr, 0)["T_max"]
+    lay = isa.isa_workspace_layout(pr)
+    kv_np, full_np = (isa.workspace_array(ws, lay[n], (wl.B, wl.H, T_max), torch.int32).cpu().numpy()
+                      for n in ("kv_list", "full_list"))
     blk_n = np.zeros((wl.B, T_max), np.int64)
     for b in range(wl.B):
         counts = [min(wl.block, L - s) for L in wl.seg_len(b) for s in range(0, L, wl.block)]
         blk_n[b, :len(counts)] = counts
-    full_fl, taylor_fl, dense_fl = algorithmic_flops(wl, isa, pr, (kv.cpu().numpy(), full.cpu().numpy(), blk_n))
+    full_fl, taylor_fl, dense_fl = algorithmic_flops(wl, isa, pr, (kv_np, full_np, blk_n))
     isa_fl = full_fl + taylor_fl
 
     # ---- backward pass (right after a forward call: the workspace holds its lists and log-sum-exps) -------------
@@ -194,6 +193,12 @@ def measure(wl, steps, warmup, dense_steps, bwd_steps=0, pro_steps=0):
         grid = isa.Grid([[wl.src_grid] + list(wl.ctx_grids[b]) for b in range(wl.B)], PROLOGUE_TILE[wl.block],
                         PROLOGUE_ROPE[wl.D], 10000.0)
         qo, ko, vo = (torch.empty_like(Q) for _ in range(3))
+        f = dict(device="cuda", dtype=torch.float32)
+        qc, kc, vc = (torch.zeros((wl.B, wl.H, T_max, wl.D), **f) for _ in range(3))
+        s_ctx, sharp = torch.zeros((wl.B, wl.H, T_max), **f), torch.zeros((wl.B, wl.H, T_max), **f)
+        z = torch.zeros((wl.B, wl.H, T_max, T_max), **f) if wl.exact_frac > 0 else None
+        mask = torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), device="cuda", dtype=torch.int32) if wl.exact_frac > 0 else None
+        kv, full, flat = (torch.zeros((wl.B, wl.H, T_max), device="cuda", dtype=torch.int32) for _ in range(3))
         isa.isa_prologue(pr, grid, Q, K, V, qo, ko, vo, qc, kc, vc)
         torch.cuda.synchronize()
         e0.record()
@@ -292,7 +297,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 (480p, default) | cfg3 | cfg4 (720p)")
+    ap.add_argument("--workload", default="cfg4", help="cfg1 | cfg2 (480p) | cfg3 | cfg4 (720p, default: the largest configuration)")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--bwd-steps", type=int, default=3, help="timed calls of the backward pass on the main workload (0 = skip)")
     ap.add_argument("--pro-steps", type=int, default=10, help="timed calls of the prologue on the main workload (0 = skip)")
@@ -302,9 +307,9 @@ def main():
     ap.add_argument("--gamma", type=float, default=None, help="coarse stacking factor of Alg. 1 Stage 5 (default 0: no residual)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense attention leg")
-    ap.add_argument("--also", default="cfg1,cfg3,cfg4,paper_defaults",
-                    help="other workloads to time briefly after the main one ('' = none); paper_defaults = the main "
-                         "workload's shape at the paper's default ratios")
+    ap.add_argument("--also", default="cfg1,cfg2,cfg3_sweep,paper_defaults",
+                    help="other workloads to time briefly after the main one ('' = none); cfg3_sweep = the ragged batch at "
+                         "the nine points of its ratio sweep; paper_defaults = the 480p shape at the paper's default ratios")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the operator shards by head with no exchange; "
@@ -340,24 +345,46 @@ def main():
     torch.cuda.empty_cache()
     others = []
     also = [n for n in args.also.split(",") if n and not over]
+
+    def entry(o_wl, label, o, n_steps):
+        return {"workload": label, "tokens": [o_wl.tokens(b) for b in range(o_wl.B)],
+                "isa_ms_per_call": round(o["ms_per_step"], 3), "kernel_ms": round(o["kern_ms"], 3),
+                "kernel_tflops": round(o["isa_fl"] / (o["kern_ms"] * 1e-3) / 1e12, 1),
+                "dense_ms_per_call": None if o["dense_ms"] is None else round(o["dense_ms"], 3),
+                "dense_tflops": None if o["dense_ms"] is None else round(o["dense_fl"] / (o["dense_ms"] * 1e-3) / 1e12, 1),
+                "speedup_vs_dense": None if o["dense_ms"] is None else round(o["dense_ms"] / o["ms_per_step"], 3),
+                "backward_ms_per_call": None if o["bwd_ms"] is None else round(o["bwd_ms"], 3),
+                "dense_backward_ms_per_call": None if o["dense_bwd_ms"] is None else round(o["dense_bwd_ms"], 3),
+                "steps": n_steps}
+
     for name in also:
-        if name == "paper_defaults":                # the paper's default ratios (Sec. 4.1) on the main workload's shape
-            o_wl = W.CONFIGS[args.workload].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)
-            label = "%s at the paper's default ratios (keep 0.125, full 0.5, exact 0.0625)" % args.workload
+        if name == "cfg3_sweep":                    # the ragged batch of two at every point of its sweep, one set of inputs
+            base = W.CONFIGS["cfg3"]
+            inputs = W.make_inputs(base, "cuda")
+            sweep_dense = None
+            for keep in (0.25, 0.5, 0.75):
+                for full in (0.1, 0.2, 0.4):
+                    o_wl = base.with_(keep_ratio=keep, full_frac=full)
+                    first = sweep_dense is None and not args.no_dense
+                    o = measure(o_wl, 5, 1, 2 if first else 0, 0, inputs=inputs)
+                    if first:
+                        sweep_dense = o["dense_ms"]
+                    o["dense_ms"] = sweep_dense      # dense attention does not depend on the ratios
+                    others.append(entry(o_wl, "cfg3 keep_ratio=%g full_frac=%g" % (keep, full), o, 5))
+                    del o
+            del inputs
+            torch.cuda.empty_cache()
+            continue
+        if name == "paper_defaults":                # the paper's default ratios (Sec. 4.1) at the 480p shape
+            o_wl = W.CONFIGS["cfg2"].with_(keep_ratio=0.125, full_frac=0.5, exact_frac=0.0625)
+            label = "cfg2 at the paper's default ratios (keep 0.125, full 0.5, exact 0.0625)"
         elif name == args.workload:
             continue
         else:
             o_wl, label = W.CONFIGS[name], name
-        o = measure(o_wl, 5, 2, 0 if args.no_dense else 2, min(args.bwd_steps, 2))
-        others.append({"workload": label, "tokens": [o_wl.tokens(b) for b in range(o_wl.B)],
-                       "isa_ms_per_call": round(o["ms_per_step"], 3), "kernel_ms": round(o["kern_ms"], 3),
-                       "kernel_tflops": round(o["isa_fl"] / (o["kern_ms"] * 1e-3) / 1e12, 1),
-                       "dense_ms_per_call": None if o["dense_ms"] is None else round(o["dense_ms"], 3),
-                       "dense_tflops": None if o["dense_ms"] is None else round(o["dense_fl"] / (o["dense_ms"] * 1e-3) / 1e12, 1),
-                       "speedup_vs_dense": None if o["dense_ms"] is None else round(o["dense_ms"] / o["ms_per_step"], 3),
-                       "backward_ms_per_call": None if o["bwd_ms"] is None else round(o["bwd_ms"], 3),
-                       "dense_backward_ms_per_call": None if o["dense_bwd_ms"] is None else round(o["dense_bwd_ms"], 3),
-                       "steps": 5})
+        n_steps = 10 if name == "cfg2" else 5
+        o = measure(o_wl, n_steps, 2, 0 if args.no_dense else 2, min(args.bwd_steps, 2))
+        others.append(entry(o_wl, label, o, n_steps))
         del o
         torch.cuda.empty_cache()
 

@@ -96,6 +96,26 @@ int isa_get_counts(const isa_problem* p, int b, isa_counts* out);
  * The workspace must be 256-byte aligned.  Its contents are scratch: undefined before and after. */
 size_t isa_workspace_bytes(const isa_problem* p);
 
+/* Where isa_attention leaves its intermediate results inside the workspace: byte offsets from the workspace pointer.
+ * They let a caller (a test, a profiler, a model that logs sparsity patterns) read the block means, scores and index
+ * lists the call actually used instead of recomputing them with the staged entry points.  Arrays that the problem does
+ * not need are reported as ISA_NO_ARRAY. */
+#define ISA_NO_ARRAY ((size_t)-1)
+typedef struct isa_ws_layout {
+  size_t bytes;                          /* = isa_workspace_bytes(p) */
+  size_t qc, kc, vc;                     /* fp32 [B, H, T_max, D]: block means (Alg. 1 Stage 1) */
+  size_t s_ctx, sharp;                   /* fp32 [B, H, T_max]: Eq. 1 saliency of the context blocks; sharpness (Stage 3) */
+  size_t kv_list, full_list, flat_list;  /* int32 [B, H, T_max], as isa_select writes them */
+  size_t exact_mask;                     /* uint32 [B, H, T_max, ceil(T_max/32)]; only when exact_frac > 0 */
+  size_t o_coarse;                       /* fp32 [B, H, T_max, D]; only when gamma != 0 */
+  size_t nlse;                           /* fp32 [B, H, S_max]: minus the base-2 log-sum-exp of every query row's scaled
+                                            logits (Taylor rows: with the n_j weights of Eq. 4); only for bf16, D = 128,
+                                            block = 128 */
+} isa_ws_layout;
+
+/* Host only.  Fills `out` for `p`; the layout is a function of the problem alone.  Needs no GPU. */
+int isa_workspace_layout(const isa_problem* p, isa_ws_layout* out);
+
 /* Algorithm 1, all stages, for every (batch, head): out = ISA(q, k, v).
  * With gamma != 0 the coarse residual of Stage 5 is added: every token of query block i receives
  * gamma * O_coarse[i], where O_coarse = S_coarse vc (Stage 1; O_coarse has one row per block, so a block's row is

@@ -44,6 +44,11 @@ class _CCounts(C.Structure):
                                          "T_max")]
 
 
+class _CLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("bytes", "qc", "kc", "vc", "s_ctx", "sharp", "kv_list", "full_list", "flat_list",
+                                          "exact_mask", "o_coarse", "nlse")]
+
+
 def lib():
     """The loaded library; raises if it has not been built (python -m paper_2605_04569_amd.build)."""
     global _LIB
@@ -57,6 +62,7 @@ def lib():
         L.isa_get_counts.argtypes = [P, C.c_int, C.POINTER(_CCounts)]
         L.isa_workspace_bytes.argtypes = [P]
         L.isa_workspace_bytes.restype = C.c_size_t
+        L.isa_workspace_layout.argtypes = [P, C.POINTER(_CLayout)]
         L.isa_attention.argtypes = [P, V, V, V, V, V, SZ, ST]
         L.isa_dense_attention.argtypes = [P, V, V, V, V, V, SZ, ST]
         L.isa_attention_static.argtypes = [P, V, V, V, V, ST]
@@ -184,6 +190,23 @@ def isa_get_counts(pr: Problem, b: int = 0) -> dict:
 def isa_workspace_bytes(pr: Problem) -> int:
     cp, keep = pr.c_struct()
     return int(lib().isa_workspace_bytes(C.byref(cp)))
+
+
+def isa_workspace_layout(pr: Problem) -> dict:
+    """Byte offsets of the arrays isa_attention leaves in its workspace; None for arrays the problem does not have."""
+    cp, keep = pr.c_struct()
+    out = _CLayout()
+    _check(lib().isa_workspace_layout(C.byref(cp), C.byref(out)), "isa_workspace_layout")
+    none = C.c_size_t(-1).value
+    return {n: (None if getattr(out, n) == none else int(getattr(out, n))) for n, _ in _CLayout._fields_}
+
+
+def workspace_array(workspace: torch.Tensor, offset: int, shape, dtype: torch.dtype) -> torch.Tensor:
+    """A view (no copy) of `shape` x `dtype` at byte `offset` of a workspace tensor."""
+    n = 1
+    for d in shape:
+        n *= int(d)
+    return workspace[offset:offset + n * torch.empty((), dtype=dtype).element_size()].view(dtype).view(*shape)
 
 
 def new_workspace(pr: Problem, device="cuda") -> torch.Tensor:

@@ -242,6 +242,26 @@ size_t isa_workspace_bytes(const isa_problem* p) {
   return ws.bytes;
 }
 
+int isa_workspace_layout(const isa_problem* p, isa_ws_layout* out) {
+  if (!out) return ISA_ERR_NULL;
+  Problem pr;
+  int rc = validate(p, &pr);
+  if (rc != ISA_OK) return rc;
+  Workspace ws;
+  carve(pr, nullptr, &ws);                              // base 0: every pointer is its own offset
+  auto off = [](const void* ptr) { return ptr ? (size_t)(uintptr_t)ptr : ISA_NO_ARRAY; };
+  out->bytes = ws.bytes;
+  // the first array sits at offset 0, which a null check would take for "absent"
+  out->qc = (size_t)(uintptr_t)ws.qc; out->kc = (size_t)(uintptr_t)ws.kc; out->vc = (size_t)(uintptr_t)ws.vc;
+  out->s_ctx = (size_t)(uintptr_t)ws.s_ctx; out->sharp = (size_t)(uintptr_t)ws.sharp;
+  out->kv_list = (size_t)(uintptr_t)ws.kv_list; out->full_list = (size_t)(uintptr_t)ws.full_list;
+  out->flat_list = (size_t)(uintptr_t)ws.flat_list;
+  out->exact_mask = off(ws.exact_mask);
+  out->o_coarse = off(ws.ocoarse);
+  out->nlse = off(ws.nlse);
+  return ISA_OK;
+}
+
 int isa_block_means(const isa_problem* p, const void* q, const void* k, const void* v, float* qc, float* kc, float* vc,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
   Problem pr;

@@ -222,20 +222,14 @@ def _full_size_sampled(I, wl, b, h, seed, last_full=1):
     ws = I.new_workspace(pr)
     out = torch.empty_like(q)
     I.isa_attention(pr, q, k, v, out, ws)
-    # the lists it chose, read back through the staged entry points (same kernels, same inputs -> same lists)
-    T_max = I.isa_get_counts(pr, 0)["T_max"]
-    f32 = dict(device="cuda", dtype=torch.float32)
-    qc, kc, vc = (torch.zeros((wl.B, wl.H, T_max, wl.D), **f32) for _ in range(3))
-    s_ctx, sharp = torch.zeros((wl.B, wl.H, T_max), **f32), torch.zeros((wl.B, wl.H, T_max), **f32)
-    kv_g, full_g, flat_g = (torch.zeros((wl.B, wl.H, T_max), device="cuda", dtype=torch.int32) for _ in range(3))
-    ex = wl.exact_frac > 0
-    z = torch.zeros((wl.B, wl.H, T_max, T_max), **f32) if ex else None
-    mask_g = torch.zeros((wl.B, wl.H, T_max, (T_max + 31) // 32), device="cuda", dtype=torch.int32) if ex else None
-    I.isa_block_means(pr, q, k, v, qc, kc, vc, ws)
-    I.isa_coarse_scores(pr, qc, kc, s_ctx, sharp, z, ws)
-    I.isa_select(pr, s_ctx, sharp, z, kv_g, full_g, flat_g, mask_g, ws)
+    # the lists (and exact-set bits) this call chose, read from its workspace before the backward call reuses it
     torch.cuda.synchronize()
-    del qc, kc, vc, z
+    lay = I.isa_workspace_layout(pr)
+    T_max = I.isa_get_counts(pr, 0)["T_max"]
+    shape = (wl.B, wl.H, T_max)
+    kv_g, full_g, flat_g = (I.workspace_array(ws, lay[n], shape, torch.int32).clone() for n in ("kv_list", "full_list", "flat_list"))
+    ex = wl.exact_frac > 0
+    mask_g = I.workspace_array(ws, lay["exact_mask"], shape + ((T_max + 31) // 32,), torch.int32).clone() if ex else None
     c = I.isa_get_counts(pr, b)
     n = wl.tokens(b)
     kv = kv_g[b, h, :c["T_new"]].cpu().numpy()

@@ -249,25 +249,31 @@ def test_dense_attention(I, wl):
 # ------------------------------------------------------------------------------------------------
 # (iv) the whole operator
 # ------------------------------------------------------------------------------------------------
-def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, seed=0, last_full=0):
-    """Runs isa_attention, reads back the lists it chose, checks that they are valid selections of the oracle's
+def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, seed=0, last_full=0, check_means=True):
+    """Runs isa_attention, reads the lists it chose out of its workspace, checks that they are valid selections of the oracle's
     scores, and checks outputs against the oracle evaluated on those lists.  Returns the index agreement rates.
     `last_full` adds the last entries of each head's exact-branch list to the sampled blocks (the work items a launch
-    may cut into key ranges and merge)."""
+    may cut into key ranges and merge).  `check_means`: off when the oracle's inputs (Q, K, V) are not the very values the
+    GPU read (q, k, v)."""
     pr = problem_of(wl)
     ws = I.new_workspace(pr)
     out = torch.full_like(q, float("nan"))
     I.isa_attention(pr, q, k, v, out, ws)
     torch.cuda.synchronize()
-    # re-run the staged entry points to read the lists (same kernels, same inputs -> same lists)
-    buf = alloc_stage_buffers(wl, pr, I)
-    I.isa_block_means(pr, q, k, v, buf["qc"], buf["kc"], buf["vc"], ws)
-    I.isa_coarse_scores(pr, buf["qc"], buf["kc"], buf["s_ctx"], buf["sharp"], buf["z"] if wl.exact_frac > 0 else None, ws)
-    I.isa_select(pr, buf["s_ctx"], buf["sharp"], buf["z"], buf["kv"], buf["full"], buf["flat"],
-                 buf["mask"] if wl.exact_frac > 0 else None, ws)
-    torch.cuda.synchronize()
-    kv_g, full_g = buf["kv"].cpu().numpy(), buf["full"].cpu().numpy()
-    mask_g = buf["mask"].cpu().numpy()
+    # every real row has been written, whatever is sampled below
+    for b in range(wl.B):
+        assert torch.isfinite(out[b, :, :wl.tokens(b)].float()).all(), b
+        if wl.tokens(b) < out.shape[2]:
+            assert torch.isnan(out[b, :, wl.tokens(b):]).all(), b
+    # the lists, exact-set bits and block means this very call used, read from its workspace
+    lay = I.isa_workspace_layout(pr)
+    T_max = I.isa_get_counts(pr, 0)["T_max"]
+    lists = (wl.B, wl.H, T_max)
+    kv_g, full_g, flat_g = (I.workspace_array(ws, lay[n], lists, torch.int32).cpu().numpy()
+                            for n in ("kv_list", "full_list", "flat_list"))
+    mask_g = (I.workspace_array(ws, lay["exact_mask"], lists + ((T_max + 31) // 32,), torch.int32).cpu().numpy()
+              if wl.exact_frac > 0 else None)
+    means_g = {n: I.workspace_array(ws, lay[n], lists + (wl.D,), torch.float32) for n in ("qc", "kc", "vc")}
     rng = np.random.default_rng(seed)
     tol_max, tol_mean = TOL[wl.dtype]
     agree_kv = agree_grp = total = 0
@@ -279,6 +285,10 @@ def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, 
             plan = O.isa_plan(Qh, Kh, Vh, wl.seg_len(b), wl.block, wl.keep_ratio, wl.full_frac, wl.exact_frac, wl.gamma)
             kv = kv_g[b, h, :c["T_new"]]
             full = full_g[b, h, :c["n_full"]]
+            # the whole call takes the means of V from the kernel that packs V^T, not from the block-mean kernel
+            for name, key in (("qc", "Qc"), ("kc", "Kc"), ("vc", "Vc")) if check_means else ():
+                np.testing.assert_allclose(f64(means_g[name][b, h, :c["T"]]), plan[key], rtol=2e-6, atol=2e-6)
+            assert (kv_g[b, h, c["T_new"]:] == -1).all() and (full_g[b, h, c["n_full"]:] == -1).all()
             # validity: the GPU's choices are top-k sets of the oracle's scores up to fp32 score noise
             assert kv[:c["T_src"]].tolist() == list(range(c["T_src"]))
             assert selection_is_valid(plan["s_ctx"], kv[c["T_src"]:] - c["T_src"], c["k_keep"], 1e-4), (b, h)
@@ -288,6 +298,7 @@ def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, 
             agree_kv += kv.tolist() == plan["kv_list"].tolist()
             agree_grp += full.tolist() == plan["full_list"].tolist()
             flat = np.setdiff1d(np.arange(c["T"]), full)
+            assert flat_g[b, h, :c["n_flat"]].tolist() == flat.tolist() and (flat_g[b, h, c["n_flat"]:] == -1).all()
             blocks = range(c["T"]) if blocks_per_head is None else \
                 sorted(set(rng.choice(full, min(len(full), blocks_per_head), replace=False).tolist() if len(full) else []) |
                        set(rng.choice(flat, min(len(flat), blocks_per_head), replace=False).tolist() if len(flat) else []) |
@@ -317,6 +328,40 @@ def test_isa_attention_end_to_end(I, wl, exact_frac):
     Q, K, V, q, k, v = gen(wl)
     a_kv, a_grp = check_end_to_end(I, wl, Q, K, V, q, k, v)
     assert a_kv >= 0.5 and a_grp >= 0.5
+
+
+@pytest.mark.parametrize("wl", [SMALL_BF16.with_(exact_frac=0.2, gamma=0.5), RAGGED_B2, CFG0], ids=["small_bf16", "ragged_b2", "cfg0"])
+def test_staged_entry_points_reproduce_the_whole_calls_intermediates(I, wl):
+    """The lists, exact-set bits, scores and means that isa_attention leaves in its workspace against those of the staged
+    entry points on the same inputs: integer results identical; the means of V, which the whole call takes from another
+    kernel on the MFMA path, to fp32 rounding."""
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws, ws2 = I.new_workspace(pr), I.new_workspace(pr)
+    I.isa_attention(pr, q, k, v, torch.empty_like(q), ws)
+    buf = alloc_stage_buffers(wl, pr, I)
+    I.isa_block_means(pr, q, k, v, buf["qc"], buf["kc"], buf["vc"], ws2)
+    I.isa_coarse_scores(pr, buf["qc"], buf["kc"], buf["s_ctx"], buf["sharp"], buf["z"], ws2)
+    I.isa_select(pr, buf["s_ctx"], buf["sharp"], buf["z"], buf["kv"], buf["full"], buf["flat"], buf["mask"], ws2)
+    torch.cuda.synchronize()
+    lay = I.isa_workspace_layout(pr)
+    T_max = buf["T_max"]
+    shape = (wl.B, wl.H, T_max)
+    for name, key in (("kv_list", "kv"), ("full_list", "full"), ("flat_list", "flat")):
+        assert torch.equal(I.workspace_array(ws, lay[name], shape, torch.int32), buf[key]), name
+    if wl.exact_frac > 0:
+        got = I.workspace_array(ws, lay["exact_mask"], shape + ((T_max + 31) // 32,), torch.int32)
+        for b in range(wl.B):
+            n_flat = I.isa_get_counts(pr, b)["n_flat"]
+            assert torch.equal(got[b, :, :n_flat], buf["mask"][b, :, :n_flat])
+    for b in range(wl.B):
+        c = I.isa_get_counts(pr, b)
+        T = c["T"]
+        for name, rows in (("qc", T), ("kc", T), ("s_ctx", c["T_ctx"]), ("sharp", T)):
+            tail = (wl.D,) if name in ("qc", "kc") else ()
+            assert torch.equal(I.workspace_array(ws, lay[name], shape + tail, torch.float32)[b, :, :rows], buf[name][b, :, :rows]), name
+        torch.testing.assert_close(I.workspace_array(ws, lay["vc"], shape + (wl.D,), torch.float32)[b, :, :T], buf["vc"][b, :, :T],
+                                   rtol=2e-6, atol=2e-6)
 
 
 def test_all_exact_equals_dense(I):

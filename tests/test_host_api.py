@@ -93,6 +93,33 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, one, one, 16, None) == -6
 
 
+def test_workspace_layout_is_consistent():
+    """isa_workspace_layout: every array lies inside the workspace, 256-byte aligned, no two overlap; optional arrays
+    are reported absent exactly when the problem does not have them."""
+    for kw in (dict(), dict(exact_frac=0.25), dict(gamma=0.5), dict(D=128, block=128, dtype="bf16", exact_frac=0.1, gamma=1.0),
+               dict(D=128, block=128, dtype="bf16", seg_len=[[700, 300, 41], [700, 900]])):
+        pr = base_problem(**kw)
+        lay = I.isa_workspace_layout(pr)
+        assert lay["bytes"] == I.isa_workspace_bytes(pr)
+        c = I.isa_get_counts(pr, 0)
+        B, H, T, D = pr.B, pr.H, c["T_max"], pr.D
+        size = dict(qc=B * H * T * D * 4, kc=B * H * T * D * 4, vc=B * H * T * D * 4, s_ctx=B * H * T * 4, sharp=B * H * T * 4,
+                    kv_list=B * H * T * 4, full_list=B * H * T * 4, flat_list=B * H * T * 4,
+                    exact_mask=B * H * T * ((T + 31) // 32) * 4, o_coarse=B * H * T * D * 4, nlse=B * H * pr.S_max * 4)
+        assert (lay["exact_mask"] is None) == (pr.exact_frac == 0)
+        assert (lay["o_coarse"] is None) == (pr.gamma == 0)
+        assert (lay["nlse"] is None) == (not (pr.dtype == "bf16" and pr.D == 128 and pr.block == 128))
+        spans = sorted((lay[n], lay[n] + size[n]) for n in size if lay[n] is not None)
+        for lo, hi in spans:
+            assert lo % 256 == 0 and hi <= lay["bytes"]
+        for (lo0, hi0), (lo1, hi1) in zip(spans, spans[1:]):
+            assert hi0 <= lo1
+    bad, keep_b = base_problem(D=96).c_struct()
+    assert I.lib().isa_workspace_layout(C.byref(bad), C.byref(I.binding._CLayout())) == -2
+    ok, keep_o = base_problem().c_struct()
+    assert I.lib().isa_workspace_layout(C.byref(ok), None) == -1
+
+
 def test_static_scratch_entry_point_checks_before_it_touches_the_gpu():
     """isa_attention_static: argument errors and a problem whose forward-only workspace exceeds the library's fixed
     scratch array are refused before any HIP call."""
