@@ -109,8 +109,10 @@ typedef struct isa_ws_layout {
   size_t exact_mask;                     /* uint32 [B, H, T_max, ceil(T_max/32)]; only when exact_frac > 0 */
   size_t o_coarse;                       /* fp32 [B, H, T_max, D]; only when gamma != 0 */
   size_t nlse;                           /* fp32 [B, H, S_max]: minus the base-2 log-sum-exp of every query row's scaled
-                                            logits (Taylor rows: with the n_j weights of Eq. 4); only for bf16, D = 128,
-                                            block = 128 */
+                                            logits, as isa_attention_backward wants it (Taylor rows: with the n_j weights
+                                            of Eq. 4, and, when exact_frac == 0, of the logits against the mean keys minus
+                                            the mean key of block 0, which is what the kernels multiply); only for bf16,
+                                            D = 128, block = 128 */
 } isa_ws_layout;
 
 /* Host only.  Fills `out` for `p`; the layout is a function of the problem alone.  Needs no GPU. */

@@ -85,7 +85,8 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
   return hipGetLastError();
 }
 
-// Mean keys / values gathered in kv_list order, rounded to bf16, in the layouts the attention kernel reads:
+// Mean keys (without exact sets: minus the mean key of block 0) / values gathered in kv_list order, rounded to bf16, in the
+// layouts the attention kernel reads:
 // kcn[bh][t][d], vcn[bh][t][d]; vcnt[bh][t/64][d][pos] with the list position t%64 = key_of_pos16(pos) (and vcnt4, when given, with
 // t%64 = swap23(pos), for the 4-wave kernel); biasn[bh][t] = ln(n_j) sqrt(D), -inf past T_new.
 __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
@@ -124,7 +125,12 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     const int j = ids[r];
     float kval = 0.f, vval = 0.f;
     if (j >= 0) {
-      kval = kc[(bh * T_max + j) * MD + d];
+      // Without exact sets the mean keys are the only keys of a Taylor row, and a vector added to all keys of a softmax
+      // changes nothing: the mean key of block 0 (a source block, always kept) is subtracted before the rounding to bf16,
+      // so that a component common to all keys (an offset of many standard deviations costs 2^-9 of itself per channel
+      // otherwise) does not eat the precision of what distinguishes them.  The backward pass streams the same array and
+      // the forward's log-sum-exp refers to the same shifted scores.
+      kval = kc[(bh * T_max + j) * MD + d] - (vcnt4 ? 0.f : kc[bh * T_max * MD + d]);
       vval = vc[(bh * T_max + j) * MD + d];
     }
     kcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kval);

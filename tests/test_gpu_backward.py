@@ -30,6 +30,11 @@ CASES = [SMALL, RAGGED,
          SMALL.with_(name="residual_all_exact_nothing_kept", gamma=1.0, full_frac=1.0, keep_ratio=0.0),
          # 65 full source blocks + 5 full context blocks and a tail, all kept: a tile of 64 mean keys of full blocks (which the
          # forward kernel treats without bias or masks) beside a ragged one; the backward depends on the forward's log-sum-exp
+         # keys with a common component of several standard deviations (cancels in the softmax, costs bf16 precision)
+         SMALL.with_(name="key_offset_3", key_offset=3.0),
+         SMALL.with_(name="key_offset_3_exact_sets", key_offset=3.0, exact_frac=0.25),
+         SMALL.with_(name="key_offset_8_all_taylor", key_offset=8.0, full_frac=0.0),
+         SMALL.with_(name="uncentred", centred=False, gamma=0.5),
          SMALL.with_(name="plain_mean_tile", H=2, src_grid=(4, 32, 65), ctx_grids=(((2, 10, 33),),), keep_ratio=1.0, seed=81)]
 
 # Gradients are compared relative to their own scale: the kernel rounds the weights P and dS to bf16 before the second

@@ -26,7 +26,7 @@ _INPUTS = {}
 def _gen_gpu(wl):
     """Inputs of a workload, generated on the GPU once per (shape, seed) and kept for the tests that share them (the
     ratios are not part of the recipe)."""
-    key = (wl.B, wl.H, wl.D, wl.dtype, wl.src_grid, wl.ctx_grids, wl.seed)
+    key = (wl.B, wl.H, wl.D, wl.dtype, wl.src_grid, wl.ctx_grids, wl.seed, wl.centred, wl.key_offset)
     if key not in _INPUTS:
         if len(_INPUTS) >= 6:                       # the four full-size input sets together are under 12 GB
             _INPUTS.pop(next(iter(_INPUTS)))
@@ -60,6 +60,14 @@ def test_isa_attention_720p_sampled_heads_of_three_xcds(I):
     q, k, v = _gen_gpu(wl)
     a_kv, a_grp = check_end_to_end(I, wl, q, k, v, q, k, v, heads=(5, 18, 39), blocks_per_head=3, seed=1, last_full=2)
     print("  list agreement with the oracle: kv %.2f, grouping %.2f" % (a_kv, a_grp), flush=True)
+
+
+def test_isa_attention_480p_keys_with_offset_sampled(I):
+    """cfg2's shape with every key channel shifted by three standard deviations (a component common to all keys cancels
+    in the softmax, but costs bf16 precision): two heads, three blocks of each branch."""
+    wl = W.CONFIGS["cfg2"].with_(name="cfg2_key_offset", key_offset=3.0, seed=20260599)
+    q, k, v = _gen_gpu(wl)
+    check_end_to_end(I, wl, q, k, v, q, k, v, heads=(9, 30), blocks_per_head=3, seed=11, last_full=1)
 
 
 def test_ragged_batch_full_size_sampled(I):

@@ -42,6 +42,8 @@ class Workload:
     seed: int
     exact_frac: float = 0.0
     gamma: float = 0.0              # coarse stacking factor of Alg. 1 Stage 5 (0 in every named configuration)
+    centred: bool = True            # subtract each smooth field's mean before rescaling it (every named configuration)
+    key_offset: float = 0.0         # a constant added to every channel of every key (0 in every named configuration)
 
     def seg_len(self, b: int) -> List[int]:
         """Token counts of batch item b: source first, then each context reference."""
@@ -101,15 +103,18 @@ def _smooth_axis(x: torch.Tensor, axis: int, w: torch.Tensor) -> torch.Tensor:
     return y / norm.view(shape)
 
 
-def smooth_field(n_fields: int, grid: Grid, gen: torch.Generator, device, sigma=2.0, radius=6, noise=0.3):
-    """[n_fields, t*h*w] fp32: unit-variance smooth fields plus white noise."""
+def smooth_field(n_fields: int, grid: Grid, gen: torch.Generator, device, sigma=2.0, radius=6, noise=0.3, centred=True):
+    """[n_fields, t*h*w] fp32: unit-variance smooth fields plus white noise.  Not `centred`: the filtered field keeps
+    whatever mean its few independent samples happen to have (on a grid of a few tokens that mean is as large as the
+    field's variation) and is only rescaled."""
     t, h, w_ = grid
     f = torch.randn((n_fields, t, h, w_), generator=gen, device=device, dtype=torch.float32)
     wts = _gauss_weights(sigma, radius, device)
     for axis in (1, 2, 3):
         f = _smooth_axis(f, axis, wts)
     f = f.reshape(n_fields, -1)
-    f = f - f.mean(dim=1, keepdim=True)            # small grids: keep the field centred before rescaling
+    if centred:
+        f = f - f.mean(dim=1, keepdim=True)        # small grids: keep the field centred before rescaling
     f = f / f.std(dim=1, unbiased=False, keepdim=True).clamp_min(1e-6)
     f = f + noise * torch.randn(f.shape, generator=gen, device=device, dtype=torch.float32)
     return f
@@ -136,9 +141,11 @@ def make_inputs(wl: Workload, device="cpu", heads_per_chunk: int = 8):
             for si, grid in enumerate(segs):
                 n = math.prod(grid)
                 for which, dst in (("k", K), ("v", V)):
-                    f = smooth_field(nh * wl.D, grid, gen, device)            # [nh*D, n]
+                    f = smooth_field(nh * wl.D, grid, gen, device, centred=wl.centred)            # [nh*D, n]
                     if which == "k" and si > 0:
                         f = f * 0.5
+                    if which == "k" and wl.key_offset != 0.0:
+                        f = f + wl.key_offset
                     dst[b, h0:h0 + nh, off:off + n, :] = f.view(nh, wl.D, n).transpose(1, 2).to(dt)
                 qn = torch.randn((nh, n, wl.D), generator=gen, device=device, dtype=torch.float32)
                 u = torch.rand((nh, n, 1), generator=gen, device=device, dtype=torch.float32)
