@@ -18,8 +18,10 @@
  *     device pointers owned by the caller.  `isa_problem` and the arrays it points to
  *     (`seg_ptr`, `seg_len`) are host memory, read during the call only.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream)
- *     and the call returns without synchronising.  The library allocates no memory and keeps
- *     no state between calls (isa_attention_simple excepted, see there).
+ *     and the call returns without synchronising.  The library allocates no memory (isa_attention_simple excepted,
+ *     see there) and keeps no per-problem state between calls: everything a later call needs is in the caller's
+ *     workspace.  Process-wide switches exist for tests and measurement only (isa_set_mfma,
+ *     isa_time_attention_kernel, at the end of this file) and are not meant to be flipped while calls are in flight.
  *   - Tensors q, k, v, out are [B, H, S_max, D] with element strides stride_b, stride_h,
  *     stride_t and a contiguous last dimension.  Batch item b holds S_b = sum of its segment
  *     lengths tokens, source segment first; rows S_b .. S_max-1 are neither read nor written.
@@ -53,7 +55,10 @@ typedef enum {
   ISA_ERR_SHAPE = -2,       /* B, H, D, block, segments or strides outside the supported set */
   ISA_ERR_RATIO = -3,       /* a ratio outside [0, 1] or not finite */
   ISA_ERR_DTYPE = -4,       /* dtype is neither ISA_BF16 nor ISA_F32 */
-  ISA_ERR_UNSUPPORTED = -5, /* a non-finite gamma, or a feature this build does not carry */
+  ISA_ERR_UNSUPPORTED = -5, /* a non-finite gamma; a bf16, D = 128, block = 128 problem whose tokens of one (batch, head)
+                               span 4 GiB or more (S_max * stride_t * 2 bytes: the matrix-core kernels use 32-bit byte
+                               offsets; isa_set_mfma(0) selects the portable kernels, which have no such limit); a call
+                               that is not available in the stream's state (isa_attention_simple under capture) */
   ISA_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than required */
   ISA_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed */
 } isa_status;
@@ -132,7 +137,8 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
 
 /* Convenience form: B = 1, bf16, contiguous [H, n_src + n_ctx, D] tensors, one context segment,
  * exact_frac = 0.  Unlike every other entry point it obtains its workspace with hipMallocAsync on
- * `hip_stream` and releases it with hipFreeAsync, so it is not for callers that must not allocate. */
+ * `hip_stream` and releases it with hipFreeAsync, so it is not for callers that must not allocate (isa_attention_static
+ * is), and it returns ISA_ERR_UNSUPPORTED when `hip_stream` is being captured into a graph. */
 int isa_attention_simple(const void* q, const void* k, const void* v, int H, int D, int n_src, int n_ctx,
                          double keep_ratio, double full_frac, int block, void* out, void* hip_stream);
 
@@ -210,8 +216,10 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
  * unrounded result) (and, when the lists are taken from it, the block table, the block means and O_coarse, which are then not computed again).
  * With gamma != 0 the gradient of the coarse residual (through the means of all blocks, query blocks included) is part
  * of the result.
- * Only for bf16, D = 128, block = 128, and only after a forward call that ran the MFMA kernels (ISA_ERR_UNSUPPORTED
- * otherwise).  Asynchronous on hip_stream; fp32
+ * Only for bf16, D = 128, block = 128 with the MFMA kernels selected (ISA_ERR_UNSUPPORTED otherwise).  The library keeps
+ * no record of the forward call, so it cannot check the following and the gradients are undefined (no access outside the
+ * tensors and the workspace) if it does not hold: the forward call ran the MFMA kernels (isa_set_mfma was 1), was
+ * isa_attention when the lists are NULL here, and nothing else has used the workspace since.  Asynchronous on hip_stream; fp32
  * accumulation, no atomics: results are reproducible run to run. */
 int isa_attention_backward(const isa_problem* p, const void* q, const void* k, const void* v, const void* out,
                            const void* d_out, const int32_t* kv_list, const int32_t* full_list,

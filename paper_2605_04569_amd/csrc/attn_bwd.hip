@@ -45,7 +45,7 @@ constexpr int SIDE_BYTES = 1024;                      // per stage: 64 exponent 
 // that the only wait for these loads is the explicit one at the top of the loop.
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff_bytes, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_addr), "v"(voff_bytes), "s"(sbase) : "memory");
+               :: "s"(lds_addr), "v"(voff_bytes), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;

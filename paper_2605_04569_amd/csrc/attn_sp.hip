@@ -46,10 +46,10 @@ constexpr int NBUF = 3;                     // LDS tile buffers: the loads of tw
 // Written as inline assembly on purpose.  Issued through the compiler's builtin, every later LDS read is
 // preceded by a wait for all such loads in flight (the compiler cannot tell that they fill the *other*
 // buffer), which puts the whole memory latency in front of the first MFMA of each iteration.  Here the only
-// wait is the explicit one at the top of the loop.  M0 is not used by anything else in this kernel.
+// wait is the explicit one at the top of the loop.  M0 is declared clobbered, so the compiler keeps nothing of its own there.
 __device__ __forceinline__ void lds_dma16(const void* sbase, uint32_t voff_bytes, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_addr), "v"(voff_bytes), "s"(sbase) : "memory");
+               :: "s"(lds_addr), "v"(voff_bytes), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;

@@ -1,6 +1,7 @@
 // Host side of libisa_hip: argument validation, count derivation, workspace carve-up and the
 // sequence of kernel launches behind each C-ABI entry point declared in include/isa.h.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <atomic>
@@ -78,8 +79,13 @@ int validate(const isa_problem* p, Problem* out) {
   long long S_max = 0;
   for (int b = 0; b < p->B; ++b) S_max = pr.cnt.b[b].S > S_max ? pr.cnt.b[b].S : S_max;
   pr.S_max = (int)S_max;
-  pr.mfma_shape = (p->dtype == ISA_BF16 && p->D == 128 && p->block == 128 &&
-                   (unsigned long long)S_max * (unsigned long long)p->stride_t * 2ull < (1ull << 32));
+  pr.mfma_shape = p->dtype == ISA_BF16 && p->D == 128 && p->block == 128;
+  if (pr.mfma_shape && (unsigned long long)S_max * (unsigned long long)p->stride_t * 2ull >= (1ull << 32)) {
+    // Not a silent drop to the portable kernels (50 times slower, and no backward pass): the caller is told, and can
+    // still ask for those kernels explicitly with isa_set_mfma(0).
+    if (g_use_mfma.load()) return ISA_ERR_UNSUPPORTED;
+    pr.mfma_shape = false;
+  }
   return ISA_OK;
 }
 
@@ -88,8 +94,9 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
   const size_t B = pr.p.B, H = pr.p.H, D = pr.p.D, T = pr.cnt.T_max;
   size_t off = 0;
-  char* b0 = (char*)base;
-  auto take = [&](size_t bytes) { char* r = b0 + off; off += align256(bytes); return (void*)r; };
+  // integer arithmetic: `base` may be null (size and layout queries), and offsetting a null pointer is undefined
+  const uintptr_t b0 = (uintptr_t)base;
+  auto take = [&](size_t bytes) { const uintptr_t r = b0 + off; off += align256(bytes); return (void*)r; };
   ws->blk_start = (int*)take(B * T * 4);
   ws->blk_n = (int*)take(B * T * 4);
   ws->btab = (int4*)take(B * T * 16);
@@ -187,6 +194,28 @@ static int hip_fail(hipError_t e) {
     if (e__ != hipSuccess) return hip_fail(e__); \
   } while (0)
 
+// Debug mode (environment variable ISA_DEBUG=1, read once): every stage of an entry point is followed by a wait for the
+// stream and a check of the error state, so that a failing kernel is reported by the call that launched it (ISA_ERR_HIP
+// right after the stage, isa_last_hip_error() for the code) instead of by some later, unrelated HIP call.  Entry points
+// then block the host, and must not be called on a stream that is being captured.
+static bool debug_mode() {
+  static const bool on = [] {
+    const char* v = getenv("ISA_DEBUG");
+    return v && v[0] && !(v[0] == '0' && !v[1]);
+  }();
+  return on;
+}
+// A stage: one launcher call on the stream `st` of the enclosing function.
+#define ISA_STAGE(expr)                                                  \
+  do {                                                                   \
+    hipError_t e__ = (expr);                                             \
+    if (e__ == hipSuccess && debug_mode()) {                             \
+      e__ = hipStreamSynchronize(st);                                    \
+      if (e__ == hipSuccess) e__ = hipGetLastError();                    \
+    }                                                                    \
+    if (e__ != hipSuccess) return hip_fail(e__);                         \
+  } while (0)
+
 static AttnArgs attn_args(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v, void* out,
                           const float* kc, const float* vc, const int* kv, const int* full, const int* flat,
                           const uint32_t* mask, const float* ocoarse, int dense) {
@@ -208,12 +237,12 @@ static int run_attend(const Problem& pr, const Workspace& ws, const AttnArgs& a,
                       hipStream_t st) {
   const bool mfma = pr.mfma_shape && g_use_mfma.load();
   if (!mfma) {
-    ISA_TRY(launch_attn_simt(pr, a, st));
+    ISA_STAGE(launch_attn_simt(pr, a, st));
     return ISA_OK;
   }
-  if (!vt_ready) ISA_TRY(launch_pack_vt(pr, ws, v, nullptr, st));
-  if (!a.dense) ISA_TRY(launch_gather_means(pr, ws, a.kc, a.vc, a.kv_list, st));
-  ISA_TRY(launch_attn_mfma(pr, ws, a, st));
+  if (!vt_ready) ISA_STAGE(launch_pack_vt(pr, ws, v, nullptr, st));
+  if (!a.dense) ISA_STAGE(launch_gather_means(pr, ws, a.kc, a.vc, a.kv_list, st));
+  ISA_STAGE(launch_attn_mfma(pr, ws, a, st));
   return ISA_OK;
 }
 
@@ -272,8 +301,8 @@ int isa_block_means(const isa_problem* p, const void* q, const void* k, const vo
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  ISA_TRY(launch_layout(pr, ws, st));
-  ISA_TRY(launch_block_means(pr, ws, q, k, v, qc, kc, vc, st));
+  ISA_STAGE(launch_layout(pr, ws, st));
+  ISA_STAGE(launch_block_means(pr, ws, q, k, v, qc, kc, vc, st));
   return ISA_OK;
 }
 
@@ -286,7 +315,7 @@ int isa_coarse_scores(const isa_problem* p, const float* qc, const float* kc, fl
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  ISA_TRY(launch_coarse(pr, ws, qc, kc, s_ctx, sharp, z, nullptr, nullptr, st));
+  ISA_STAGE(launch_coarse(pr, ws, qc, kc, s_ctx, sharp, z, nullptr, nullptr, st));
   return ISA_OK;
 }
 
@@ -300,7 +329,7 @@ int isa_coarse_output(const isa_problem* p, const float* qc, const float* kc, co
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   // the same kernel as isa_coarse_scores; its scores land in the workspace's own arrays
-  ISA_TRY(launch_coarse(pr, ws, qc, kc, ws.s_ctx, ws.sharp, nullptr, vc, o_coarse, st));
+  ISA_STAGE(launch_coarse(pr, ws, qc, kc, ws.s_ctx, ws.sharp, nullptr, vc, o_coarse, st));
   return ISA_OK;
 }
 
@@ -315,7 +344,7 @@ int isa_select(const isa_problem* p, const float* s_ctx, const float* sharp, con
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  ISA_TRY(launch_select(pr, ws, s_ctx, sharp, z, kv_list, full_list, flat_list, exact_mask, st));
+  ISA_STAGE(launch_select(pr, ws, s_ctx, sharp, z, kv_list, full_list, flat_list, exact_mask, st));
   return ISA_OK;
 }
 
@@ -332,7 +361,7 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  ISA_TRY(launch_layout(pr, ws, st));
+  ISA_STAGE(launch_layout(pr, ws, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, kc, vc, kv_list, full_list, flat_list,
                          p->exact_frac > 0.0 ? exact_mask : nullptr, o_coarse, 0);
   return run_attend(pr, ws, a, v, false, st);
@@ -341,14 +370,14 @@ int isa_attend(const isa_problem* p, const void* q, const void* k, const void* v
 // Alg. 1, all stages, on a carved workspace (the body of isa_attention and of its allocation-free twin).
 static int run_attention(const Problem& pr, const Workspace& ws, const void* q, const void* k, const void* v, void* out,
                          hipStream_t st) {
-  ISA_TRY(launch_layout(pr, ws, st));
+  ISA_STAGE(launch_layout(pr, ws, st));
   // the matrix-core kernels want a packed V^T copy: the kernel that writes it has every block of V in LDS and writes the
   // block's mean value too, so the block-mean kernel reads Q and K only
   const bool pack_first = pr.mfma_shape && g_use_mfma.load();
-  if (pack_first) ISA_TRY(launch_pack_vt(pr, ws, v, ws.vc, st));
-  ISA_TRY(launch_block_means(pr, ws, q, k, pack_first ? nullptr : v, ws.qc, ws.kc, ws.vc, st));
-  ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, ws.z, ws.vc, ws.ocoarse, st));
-  ISA_TRY(launch_select(pr, ws, ws.s_ctx, ws.sharp, ws.z, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, st));
+  if (pack_first) ISA_STAGE(launch_pack_vt(pr, ws, v, ws.vc, st));
+  ISA_STAGE(launch_block_means(pr, ws, q, k, pack_first ? nullptr : v, ws.qc, ws.kc, ws.vc, st));
+  ISA_STAGE(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, ws.z, ws.vc, ws.ocoarse, st));
+  ISA_STAGE(launch_select(pr, ws, ws.s_ctx, ws.sharp, ws.z, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, ws.kc, ws.vc, ws.kv_list, ws.full_list, ws.flat_list, ws.exact_mask, ws.ocoarse, 0);
   return run_attend(pr, ws, a, v, pack_first, st);
 }
@@ -418,7 +447,7 @@ int isa_dense_attention(const isa_problem* p, const void* q, const void* k, cons
   Workspace ws;
   if ((rc = check_ws(pr, workspace, workspace_bytes, &ws)) != ISA_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  ISA_TRY(launch_layout(pr, ws, st));
+  ISA_STAGE(launch_layout(pr, ws, st));
   AttnArgs a = attn_args(pr, ws, q, k, v, out, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1);
   return run_attend(pr, ws, a, v, false, st);
 }
@@ -448,13 +477,13 @@ int isa_attention_backward(const isa_problem* p, const void* q, const void* k, c
   // from the workspace) the block table, the block means, the gathered mean keys and O_coarse are still there as well;
   // the staged forward takes its means and O_coarse from the caller, so after it they are computed again here.
   if (n_lists != 0) {
-    ISA_TRY(launch_layout(pr, ws, st));
-    ISA_TRY(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
-    ISA_TRY(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
+    ISA_STAGE(launch_layout(pr, ws, st));
+    ISA_STAGE(launch_block_means(pr, ws, q, k, v, ws.qc, ws.kc, ws.vc, st));
+    ISA_STAGE(launch_gather_means(pr, ws, ws.kc, ws.vc, kv_list, st));
     if (p->gamma != 0.0)                            // O_coarse of Alg. 1 Stage 1
-      ISA_TRY(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, nullptr, ws.vc, ws.ocoarse, st));
+      ISA_STAGE(launch_coarse(pr, ws, ws.qc, ws.kc, ws.s_ctx, ws.sharp, nullptr, ws.vc, ws.ocoarse, st));
   }
-  ISA_TRY(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, exact_mask, dq, dk, dv, st));
+  ISA_STAGE(launch_attn_bwd(pr, ws, q, k, v, out, d_out, kv_list, full_list, flat_list, exact_mask, dq, dk, dv, st));
   return ISA_OK;
 }
 
@@ -478,6 +507,10 @@ int isa_attention_simple(const void* q, const void* k, const void* v, int H, int
   if (!all_aligned16(q, k, v, out)) return ISA_ERR_SHAPE;
   const size_t bytes = isa_workspace_bytes(&p);
   hipStream_t st = (hipStream_t)hip_stream;
+  // it allocates: not for a stream that is being captured into a graph (isa_attention and isa_attention_static are)
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  ISA_TRY(hipStreamIsCapturing(st, &cap));
+  if (cap != hipStreamCaptureStatusNone) return ISA_ERR_UNSUPPORTED;
   void* ws = nullptr;
   ISA_TRY(hipMallocAsync(&ws, bytes, st));
   rc = isa_attention(&p, q, k, v, out, ws, bytes, hip_stream);
@@ -525,7 +558,8 @@ static int run_prologue(const isa_problem* p, const isa_grid* grid, const void* 
     for (int j = 0; j < 3; ++j)
       if (outs[i] == ins[j] || (i != j && outs[i] == outs[j])) return ISA_ERR_SHAPE;
   }
-  ISA_TRY(launch_prologue(pr, grid, q_in, k_in, v_in, q_out, k_out, v_out, qc, kc, vc, inverse, (hipStream_t)hip_stream));
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_STAGE(launch_prologue(pr, grid, q_in, k_in, v_in, q_out, k_out, v_out, qc, kc, vc, inverse, st));
   return ISA_OK;
 }
 
@@ -546,7 +580,8 @@ int isa_untile(const isa_problem* p, const isa_grid* grid, const void* x_tiled, 
   if (!x_tiled || !x_raster) return ISA_ERR_NULL;
   if ((rc = check_grid(pr, grid, false)) != ISA_OK) return rc;
   if (!aligned16(x_tiled) || !aligned16(x_raster) || x_tiled == x_raster) return ISA_ERR_SHAPE;
-  ISA_TRY(launch_untile(pr, grid, x_tiled, x_raster, (hipStream_t)hip_stream));
+  hipStream_t st = (hipStream_t)hip_stream;
+  ISA_STAGE(launch_untile(pr, grid, x_tiled, x_raster, st));
   return ISA_OK;
 }
 
@@ -557,7 +592,7 @@ const char* isa_strerror(int status) {
     case ISA_ERR_SHAPE: return "ISA_ERR_SHAPE: unsupported shape, segments or strides";
     case ISA_ERR_RATIO: return "ISA_ERR_RATIO: ratio outside [0, 1]";
     case ISA_ERR_DTYPE: return "ISA_ERR_DTYPE: unknown dtype";
-    case ISA_ERR_UNSUPPORTED: return "ISA_ERR_UNSUPPORTED: feature not available (gamma must be finite)";
+    case ISA_ERR_UNSUPPORTED: return "ISA_ERR_UNSUPPORTED: not available for this problem or in this state (see isa.h)";
     case ISA_ERR_WORKSPACE: return "ISA_ERR_WORKSPACE: workspace missing, misaligned or too small";
     case ISA_ERR_HIP: return "ISA_ERR_HIP: a HIP call failed (see isa_last_hip_error)";
     default: return "unknown isa_status";

@@ -470,6 +470,64 @@ def test_simple_entry_point(I):
     assert torch.equal(out, ref)
 
 
+def test_simple_entry_point_refuses_a_capturing_stream(I):
+    """isa_attention_simple allocates its workspace, which a stream under capture must not: it says so and launches
+    nothing; the capture goes on, and the graph replays what was captured around the refused call."""
+    wl = SMALL_BF16.with_(ctx_grids=(((1, 10, 33),),))
+    Q, K, V, q, k, v = gen(wl)
+    seg = wl.seg_len(0)
+    out = torch.zeros_like(q)
+    marker = torch.zeros(4, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        marker.add_(0.0)                                            # warm-up of the kernel that gets captured
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        marker.add_(1.0)
+        with pytest.raises(I.IsaError) as err:
+            I.isa_attention_simple(q[0], k[0], v[0], seg[0], seg[1], wl.keep_ratio, wl.full_frac, wl.block, out[0])
+        assert err.value.code == -5
+    graph.replay()
+    torch.cuda.synchronize()
+    assert (marker == 1.0).all() and (out == 0).all()
+
+
+def test_debug_mode_checks_every_stage_and_changes_no_result(I, tmp_path):
+    """ISA_DEBUG=1 (read when the library is loaded, hence a process of its own): the calls synchronise after every
+    stage and give the same bits."""
+    import subprocess
+    import sys
+    wl = SMALL_BF16.with_(exact_frac=0.2, gamma=0.5)
+    Q, K, V, q, k, v = gen(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    ref = torch.empty_like(q)
+    I.isa_attention(pr, q, k, v, ref, ws)
+    torch.cuda.synchronize()
+    path = str(tmp_path / "debug_out.pt")
+    code = (
+        "import sys, torch\n"
+        "sys.path[:0] = %r\n"
+        "import workloads as W, paper_2605_04569_amd as I\n"
+        "from util import problem_of\n"
+        "from test_gpu_parity import SMALL_BF16\n"
+        "wl = SMALL_BF16.with_(exact_frac=0.2, gamma=0.5)\n"
+        "q, k, v = (t.cuda() for t in W.make_inputs(wl, 'cpu'))\n"
+        "pr = problem_of(wl); ws = I.new_workspace(pr); out = torch.empty_like(q)\n"
+        "I.isa_attention(pr, q, k, v, out, ws)\n"
+        "dq, dk, dv = (torch.empty_like(q) for _ in range(3))\n"
+        "I.isa_attention_backward(pr, q, k, v, out, q, dq, dk, dv, ws)\n"
+        "torch.save(out.cpu(), %r)\n" % ([p for p in sys.path if p], path))
+    import os
+    env = dict(os.environ, ISA_DEBUG="1")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert torch.equal(torch.load(path, weights_only=True), ref.cpu())
+
+
 def test_degenerate_shapes(I):
     """No context at all; a source shorter than one block; keep_ratio = 0 (source-only keys)."""
     for seg_grids, keep, full in ((((1, 1, 130), ()), 0.5, 0.5), (((1, 1, 7), ((1, 1, 3),)), 1.0, 0.0),

@@ -93,6 +93,23 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert bw(C.byref(mf), one, one, one, one, one, None, None, None, None, one, one, one, one, 16, None) == -6
 
 
+def test_token_span_of_4_gib_is_refused_not_rerouted():
+    """bf16, D = 128, block = 128 with the tokens of one head spanning 4 GiB or more (here q, k, v as views of a fused
+    [S, 3, H, D] tensor at 720p): the matrix-core kernels cannot address it, and the call says so instead of running the
+    portable kernels behind the caller's back; with those selected explicitly the problem is accepted."""
+    pr = base_problem(H=40, D=128, block=128, dtype="bf16", seg_len=[[75600, 75600]])
+    fused = (151200 * 3 * 40 * 128, 128, 3 * 40 * 128)
+    assert status(pr) == 0 and status(pr, strides=fused) == -5
+    cp, keep = pr.c_struct(strides=fused)
+    assert I.lib().isa_workspace_bytes(C.byref(cp)) == 0
+    prev = I.isa_set_mfma(False)
+    try:
+        assert status(pr, strides=fused) == 0
+    finally:
+        I.isa_set_mfma(prev)
+    assert status(base_problem(H=40, D=128, block=128, dtype="bf16", seg_len=[[32760, 32760]]), strides=(65520 * 15360, 128, 15360)) == 0
+
+
 def test_workspace_layout_is_consistent():
     """isa_workspace_layout: every array lies inside the workspace, 256-byte aligned, no two overlap; optional arrays
     are reported absent exactly when the problem does not have them."""
