@@ -231,27 +231,73 @@ def taylor_branch(q, K, V, Kc, Vc, starts, counts, kv_list, exact_blocks, return
 # --------------------------------------------------------------------------
 # Whole operator for one (batch, head) slice (Alg. 1)
 # --------------------------------------------------------------------------
-def isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0, gamma=0.0):
+# The places where the paper prints two different things, and the alternative to the reading this oracle (and the HIP
+# path) takes.  The alternatives exist to measure what the choice changes (design notes); nothing else uses them.
+READINGS = {
+    # pooled map used by Eq. 1 and by the sharpness: "softmax_scaled" = row softmax of Q^c K^c^T / sqrt(D) (taken: Sec. 2
+    # "Pooling Attention" says standard attention is performed on the pooled tensors); "softmax_unscaled" = the formula as
+    # printed there, softmax(Q^c K^c^T) without the 1 / sqrt(D); "raw" = Alg. 1 Stage 1 as printed, Q^c K^c^T with neither
+    "coarse_map": ("softmax_scaled", "softmax_unscaled", "raw"),
+    # kept context blocks: "floor_of_ratio_times_blocks" = floor(alpha_s * T_ctx) with T_ctx the number of context blocks,
+    # short tail blocks included (taken; Sec. 3 prints alpha_s * ceil(L_ctx / b)); "ratio_times_whole_blocks" = Alg. 1
+    # Stage 2 as printed, alpha_s * int(L_ctx / b), the product cut to an integer
+    "keep_rounding": ("floor_of_ratio_times_blocks", "ratio_times_whole_blocks"),
+    # columns of a pooled row whose variance is the sharpness: "source" (taken; Alg. 1 Stage 3 slices the source key
+    # blocks) or "all" (Sec. 3 "Grouped Computation" prints the variance of the whole row)
+    "sharpness_columns": ("source", "all"),
+}
+
+
+def pooled_map(Z_scaled, D, reading):
+    """The pooled attention map under one of the READINGS["coarse_map"]; Z_scaled = Q^c K^c^T / sqrt(D)."""
+    if reading == "softmax_scaled":
+        return coarse_map(Z_scaled)
+    if reading == "softmax_unscaled":
+        return coarse_map(Z_scaled * math.sqrt(D))
+    if reading == "raw":
+        return Z_scaled * math.sqrt(D)
+    raise ValueError(reading)
+
+
+def keep_count_reading(keep_ratio, seg_len, block, reading):
+    """Kept context blocks under one of the READINGS["keep_rounding"]."""
+    ctx = [int(x) for x in seg_len[1:]]
+    if reading == "floor_of_ratio_times_blocks":
+        return keep_count(keep_ratio, sum(-(-x // block) for x in ctx))
+    if reading == "ratio_times_whole_blocks":
+        return int(float(keep_ratio) * (sum(ctx) // block))
+    raise ValueError(reading)
+
+
+def isa_plan(Q, K, V, seg_len, block, keep_ratio, full_frac, exact_frac=0.0, gamma=0.0, readings=None):
     """Stages 1-3 of Alg. 1: everything up to and including the index lists,
     plus the coarse output O_coarse and the stacking factor gamma that Stage 5
-    uses."""
+    uses.  `readings` (a dict over the keys of READINGS) swaps in the paper's
+    other printed form at the places where it prints two; the default is the
+    reading documented in the header, the one the HIP path implements."""
+    rd = {k: v[0] for k, v in READINGS.items()}
+    rd.update(readings or {})
+    for k, v in rd.items():
+        if v not in READINGS[k]:
+            raise ValueError("unknown reading %s=%s" % (k, v))
     starts, counts, T_src = block_layout(seg_len, block)
     T = len(starts)
     Qc = block_means(Q, starts, counts)
     Kc = block_means(K, starts, counts)
     Vc = block_means(V, starts, counts)
     Z = coarse_logits(Qc, Kc)
-    S = coarse_map(Z)
+    S = pooled_map(Z, Qc.shape[1], rd["coarse_map"])
     s_ctx = context_saliency(S, T_src)
-    k_keep = keep_count(keep_ratio, T - T_src)
+    k_keep = min(T - T_src, keep_count_reading(keep_ratio, seg_len, block, rd["keep_rounding"]))
     kv_list = preselect(s_ctx, k_keep, T_src)
-    M = sharpness(S, T_src)
+    M = sharpness(S, T_src if rd["sharpness_columns"] == "source" else T)
     n_full, n_flat = group_counts(full_frac, T)
     full_list, flat_list = group_queries(M, n_full)
+    S_softmax = S if rd["coarse_map"] == "softmax_scaled" else coarse_map(Z)       # Stage 1's O_coarse is attention output
     return dict(starts=starts, counts=counts, T_src=T_src, T=T, Qc=Qc, Kc=Kc, Vc=Vc, Z=Z,
-                S_coarse=S, O_coarse=coarse_output(S, Vc), gamma=float(gamma), s_ctx=s_ctx, k_keep=k_keep, kv_list=kv_list, sharp=M,
+                S_coarse=S, O_coarse=coarse_output(S_softmax, Vc), gamma=float(gamma), s_ctx=s_ctx, k_keep=k_keep, kv_list=kv_list, sharp=M,
                 n_full=n_full, n_flat=n_flat, full_list=full_list, flat_list=flat_list,
-                exact_frac=float(exact_frac), k_exact=exact_count(exact_frac, len(kv_list)))
+                exact_frac=float(exact_frac), k_exact=exact_count(exact_frac, len(kv_list)), readings=rd)
 
 
 def attend_block(i, plan, Q, K, V, kv_list=None, in_full=None, exact_blocks=None):

@@ -540,3 +540,62 @@ def test_coarse_output_closed_forms():
     # a transposed operand or a column softmax would fail this: asymmetric map, distinct values
     S2 = np.array([[0.9, 0.1], [0.2, 0.8]])
     np.testing.assert_allclose(O.coarse_output(S2, np.array([[1.0], [3.0]])), [[1.2], [2.6]], atol=1e-15)
+
+
+# ------------------------------------------------------------------------------------------------
+# the paper's other printed forms (READINGS): each switch does what its name says, on cases small enough to do by hand
+# ------------------------------------------------------------------------------------------------
+def _hand_case():
+    """Two source blocks and three context blocks of one token each (block size 1), D = 4: pooled tensors = the tokens."""
+    Q = np.array([[2.0, 0, 0, 0], [0, 2.0, 0, 0], [1, 1, 0, 0], [0, 0, 3.0, 0], [0, 0, 0, 1.0]])
+    K = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [4.0, 0, 0, 0], [0, 1.0, 0, 0], [-1.0, -1.0, 0, 0]])
+    V = np.arange(20, dtype=np.float64).reshape(5, 4)
+    return Q, K, V, [2, 3]
+
+
+def test_reading_of_the_pooled_map():
+    Q, K, V, seg = _hand_case()
+    raw = O.isa_plan(Q, K, V, seg, 1, 1 / 3, 0.4, readings={"coarse_map": "raw"})
+    # raw reading: Eq. 1 on Q^c K^c^T itself: context columns of the source rows are [[8, 0, -2], [0, 2, -2]] -> means [4, 1, -2]
+    np.testing.assert_allclose(raw["s_ctx"], [4.0, 1.0, -2.0], atol=1e-14)
+    assert raw["kv_list"].tolist() == [0, 1, 2]
+    # variance over the two source columns of Q K^T rows [2,0], [0,2], [1,1], [0,0], [0,0] = [1, 1, 0, 0, 0]
+    np.testing.assert_allclose(raw["sharp"], [1.0, 1.0, 0.0, 0.0, 0.0], atol=1e-14)
+    uns = O.isa_plan(Q, K, V, seg, 1, 1 / 3, 0.4, readings={"coarse_map": "softmax_unscaled"})
+    row0 = np.exp([2.0, 0, 8.0, 0, -2.0]); row0 /= row0.sum()
+    np.testing.assert_allclose(uns["S_coarse"][0], row0, rtol=1e-13)
+    dflt = O.isa_plan(Q, K, V, seg, 1, 1 / 3, 0.4)
+    row0 = np.exp(np.array([2.0, 0, 8.0, 0, -2.0]) / 2.0); row0 /= row0.sum()          # sqrt(D) = 2
+    np.testing.assert_allclose(dflt["S_coarse"][0], row0, rtol=1e-13)
+    # the pooled output of Stage 1 is an attention output under every reading
+    np.testing.assert_allclose(raw["O_coarse"], dflt["O_coarse"], rtol=1e-13)
+    with pytest.raises(ValueError):
+        O.isa_plan(Q, K, V, seg, 1, 0.5, 0.5, readings={"coarse_map": "nonsense"})
+
+
+def test_reading_of_the_kept_block_count():
+    # context of 300 tokens in blocks of 128: 3 context blocks (one short) but only 2 whole ones
+    assert O.keep_count_reading(0.5, [256, 300], 128, "floor_of_ratio_times_blocks") == 1          # floor(0.5 * 3)
+    assert O.keep_count_reading(0.5, [256, 300], 128, "ratio_times_whole_blocks") == 1             # int(0.5 * 2)
+    assert O.keep_count_reading(0.7, [256, 300], 128, "floor_of_ratio_times_blocks") == 2          # floor(2.1)
+    assert O.keep_count_reading(0.7, [256, 300], 128, "ratio_times_whole_blocks") == 1             # int(1.4)
+    # two references: the printed form pools the context length before dividing, the taken one cuts every reference
+    assert O.keep_count_reading(1.0, [128, 100, 100], 128, "floor_of_ratio_times_blocks") == 2
+    assert O.keep_count_reading(1.0, [128, 100, 100], 128, "ratio_times_whole_blocks") == 1
+    rng = np.random.default_rng(3)
+    Q, K, V = (rng.standard_normal((556, 8)) for _ in range(3))
+    a = O.isa_plan(Q, K, V, [256, 300], 128, 0.7, 0.5)
+    b = O.isa_plan(Q, K, V, [256, 300], 128, 0.7, 0.5, readings={"keep_rounding": "ratio_times_whole_blocks"})
+    assert (a["k_keep"], b["k_keep"]) == (2, 1) and set(b["kv_list"]) <= set(a["kv_list"])
+
+
+def test_reading_of_the_sharpness_columns():
+    Q, K, V, seg = _hand_case()
+    src = O.isa_plan(Q, K, V, seg, 1, 1.0, 0.4, readings={"coarse_map": "raw"})
+    allc = O.isa_plan(Q, K, V, seg, 1, 1.0, 0.4, readings={"coarse_map": "raw", "sharpness_columns": "all"})
+    rows = Q @ K.T
+    np.testing.assert_allclose(allc["sharp"], rows.var(axis=1), rtol=1e-13)
+    np.testing.assert_allclose(src["sharp"], rows[:, :2].var(axis=1), rtol=1e-13)
+    # row 0 = [2, 0, 8, 0, -2]: flat over the source columns compared with row 1 = [0, 2, 0, 2, -2] only once the
+    # context columns count
+    assert allc["sharp"][0] > allc["sharp"][1] and src["sharp"][0] == src["sharp"][1]
