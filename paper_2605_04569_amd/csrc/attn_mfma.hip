@@ -163,7 +163,7 @@ struct Tile {                               // wave-uniform description of one 6
   int row0;                                 // first row of the tile relative to krows
   int kstride;                              // elements between key rows
   const uint16_t* vt;                       // 128 x 64 packed V^T
-  const float* bias;                        // per-key additive term on the raw score, or null
+  const float* bias;                        // per-key additive terms on the raw scores (global memory; staged in LDS with the tile), or null
   int nk;                                   // valid keys (0..64); rows past it are masked
   int last_row;                             // last row relative to krows that may be read (>= 0)
   uint32_t mw0, mw1;                        // mean tiles: the exact-mask bits of the tile's 64 list entries (masked out)
@@ -265,9 +265,10 @@ __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, co
 }
 
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE + 2 * 512];
   uint16_t* ldsK = lds;                     // [2][K_TILE]
   uint16_t* ldsV = lds + 2 * K_TILE;        // [2][V_TILE]
+  float* ldsB = reinterpret_cast<float*>(lds + 2 * K_TILE + 2 * V_TILE);      // [2][256]: per-key additive terms of a mean tile
 
   // ---- which work item: consecutive logical ids go to the same XCD, so that the workgroups that run
   // together on one XCD (and share its L2) read the same head's keys and values
@@ -317,42 +318,65 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
 
   // ---- tile sequence.  Phase A: the token tiles (two 64-key halves) of the list entries in the block's exact set.
   // Phase B: tiles of 64 gathered block means (the entries of the exact set masked out).
-  // Everything a tile's description needs is one mask word and one table row {token offset, tokens, block} of the list
-  // entry, and the description is worked out one iteration before its loads are issued: none of these (dependent) loads
-  // is waited for between the tile loads and the tile's arithmetic.
-  int it_sub = 0, it_mean = 0;
-  uint32_t word = 0u;                       // bits of the mask word at wbase that are still to be visited
-  int wbase = -32;
-  int4 erow = make_int4(0, 0, 0, 0);        // table row of the current entry of the exact set
+  // Nothing in the loop below may wait on a global load: the counter such a wait uses also counts the next tile's loads
+  // in flight.  So the block's row of exact-set bits lives in two registers (lane L: words L and 64 + L, handed out with
+  // readlane), and the table rows {token offset, tokens, block} of 64 entries of the exact set at a time live in three
+  // registers (lane L: entry ebase + L), fetched before the loop and, for exact sets of more than 64 entries, in a
+  // branch that consumes its own loads.
   const int4* const tab = a.ktab + bh * T_max;
-  auto next_exact = [&]() -> bool {         // moves on to the next entry of the exact set; false when there is none left
-    if (!mrow) return false;
-    while (word == 0u) {
-      wbase += 32;
-      if (wbase >= n_list) return false;
-      word = mrow[wbase >> 5];
-    }
-    const int e = wbase + __builtin_ctz(word);
-    word &= word - 1u;
-    if (e >= n_list) { word = 0u; wbase = n_list; return false; }
-    erow = tab[e];
-    return true;
+  uint32_t bits_lo = 0u, bits_hi = 0u;
+  if (mrow) {
+    if (lane < a.cnt.mask_words) bits_lo = mrow[lane];
+    if (lane + 64 < a.cnt.mask_words) bits_hi = mrow[lane + 64];
+  }
+  auto word_of = [&](int w) __attribute__((always_inline)) -> uint32_t {      // word w of the row, bits past the list cleared
+    w = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t x = w < 64 ? (uint32_t)__builtin_amdgcn_readlane((int)bits_lo, w)
+                              : (uint32_t)__builtin_amdgcn_readlane((int)bits_hi, min(w - 64, 63));
+    const int left = n_list - 32 * w;
+    return left >= 32 ? x : (left <= 0 ? 0u : x & ((1u << left) - 1u));
   };
-  bool in_exact = next_exact();
+  asm volatile("" : "+v"(bits_lo), "+v"(bits_hi));
+  const int n_words = (n_list + 31) >> 5;
+  int n_exact = 0;                          // entries of the exact set
+  if (mrow)
+    for (int w = 0; w < n_words; ++w) n_exact += __builtin_popcount(word_of(w));
+  int ent_off = 0, ent_n = 0, ent_blk = 0, ebase = 0;
+  auto refill = [&](int e0) {               // lane L <- table row of entry e0 + L of the exact set
+    int my_e = 0, cnt = 0;
+    for (int w = 0; w < n_words && cnt < e0 + 64; ++w) {
+      uint32_t x = word_of(w);
+      while (x != 0u && cnt < e0 + 64) {
+        const int e = 32 * w + __builtin_ctz(x);
+        x &= x - 1u;
+        if (cnt - e0 == lane) my_e = e;
+        ++cnt;
+      }
+    }
+    const int4 r = tab[my_e];
+    ent_off = r.x; ent_n = r.y; ent_blk = r.z;
+    asm volatile("" : "+v"(ent_off), "+v"(ent_n), "+v"(ent_blk));      // the wait for this load stays here
+    ebase = e0;
+  };
+  if (n_exact > 0) refill(0);
+  int ei = 0, it_sub = 0, it_mean = 0;      // next token tile: half it_sub of entry ei; next mean tile
   const int n_mean_tiles = (n_list + KT - 1) / KT;
   auto next_tile = [&](Tile& t) -> bool {
-    if (in_exact) {
-      const int n_j = erow.y;
+    if (ei < n_exact) {
+      if (__builtin_expect(ei - ebase >= 64, 0)) refill(ebase + 64);
+      const int l = ei - ebase;
+      const int off = __builtin_amdgcn_readlane(ent_off, l), n_j = __builtin_amdgcn_readlane(ent_n, l);
+      const int blk = __builtin_amdgcn_readlane(ent_blk, l);
       const int k0 = it_sub * KT;
-      t.krows = a.k + tbase + (long long)erow.x * a.geo.stride_t;
+      t.krows = a.k + tbase + (long long)off * a.geo.stride_t;
       t.row0 = k0;
       t.kstride = (int)a.geo.stride_t;
-      t.vt = a.vt + ((bh * T_max + erow.z) * 2 + it_sub) * (long long)(MD * KT);
+      t.vt = a.vt + ((bh * T_max + blk) * 2 + it_sub) * (long long)(MD * KT);
       t.bias = nullptr;
       t.nk = max(0, min(KT, n_j - k0));
       t.last_row = max(n_j - 1, 0);
       t.mw0 = t.mw1 = 0u;
-      if (it_sub) in_exact = next_exact();
+      ei += it_sub;
       it_sub ^= 1;
       return true;
     }
@@ -366,8 +390,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
       t.nk = min(KT, n_list - it_mean * KT);
       t.last_row = KT - 1;                                          // the gathered arrays are padded to whole tiles
       const int w = 2 * it_mean;
-      t.mw0 = mrow ? mrow[w] : 0u;
-      t.mw1 = (mrow && w + 1 < a.cnt.mask_words) ? mrow[w + 1] : 0u;
+      t.mw0 = mrow ? word_of(w) : 0u;
+      t.mw1 = mrow ? word_of(w + 1) : 0u;
       ++it_mean;
       return true;
     }
@@ -391,20 +415,38 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
     const int r = ch >> 3;
     vsrc_b[i] = (uint32_t)((r * KT + (((ch & 7) ^ ((r >> 1) & 7)) * 8)) * 2);
   }
+  // The loads are written as inline assembly (16 bytes per lane straight into LDS, wave-uniform base in scalar
+  // registers, M0 = LDS address): issued through the compiler's builtin, every later LDS read is preceded by a wait for
+  // all such loads in flight (the compiler cannot tell that they fill the other buffer), so that the loads of the next
+  // tile would be waited for before the arithmetic of the current one.  Here the only wait is the explicit one at the
+  // end of an iteration; the compiler's own waits for its own loads can only wait longer than needed, never shorter.
+  auto dma16 = [](const char* sbase, uint32_t voff_bytes, uint32_t lds_addr) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff_bytes), "s"(sbase) : "memory", "m0");
+  };
+  auto uniform = [](const void* ptr) __attribute__((always_inline)) -> const char* {       // wave-uniform by construction
+    const uint64_t u = (uint64_t)(uintptr_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return reinterpret_cast<const char*>((uintptr_t)(((uint64_t)hi << 32) | lo));
+  };
+  auto lds_addr_of = [](const void* ptr) __attribute__((always_inline)) -> uint32_t {
+    return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)ptr;
+  };
   auto load_tile = [&](const Tile& t, int buf) {
-    const char* kb = reinterpret_cast<const char*>(t.krows);
-    const char* vb = reinterpret_cast<const char*>(t.vt);
-    const uint32_t kstride_b = (uint32_t)t.kstride * 2u;
+    const char* kb = uniform(t.krows);
+    const char* vb = uniform(t.vt);
+    const uint32_t kstride_b = (uint32_t)__builtin_amdgcn_readfirstlane(t.kstride) * 2u;
+    const int row0 = __builtin_amdgcn_readfirstlane(t.row0), last_row = __builtin_amdgcn_readfirstlane(t.last_row);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int wchunk = (wave * 4 + i) * 64;                       // first chunk this wave instruction fills
       // rows past the block's end re-read its last row; the row index is never negative
-      const uint32_t koff_b = (uint32_t)max(min(t.row0 + krow[i], t.last_row), 0) * kstride_b + kchunk_b[i];
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + koff_b),
-                                       (__attribute__((address_space(3))) void*)(ldsK + buf * K_TILE + wchunk * 8), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + vsrc_b[i]),
-                                       (__attribute__((address_space(3))) void*)(ldsV + buf * V_TILE + wchunk * 8), 16, 0, 0);
+      const uint32_t koff_b = (uint32_t)max(min(row0 + krow[i], last_row), 0) * kstride_b + kchunk_b[i];
+      dma16(kb, koff_b, lds_addr_of(ldsK + buf * K_TILE + wchunk * 8));
+      dma16(vb, vsrc_b[i], lds_addr_of(ldsV + buf * V_TILE + wchunk * 8));
     }
+    // the 64 additive terms of a tile of gathered means come along into LDS (256 B; lanes 16..63 repeat lanes 0..15)
+    if (t.bias != nullptr && wave == 0) dma16(uniform(t.bias), (uint32_t)(lane & 15) * 16u, lds_addr_of(ldsB + buf * 256));
   };
 
   // per-lane fragment offsets (bf16 elements): K row = col, chunk (2s+g) ^ (col & 15); V^T row = col, chunk (2ks+g) ^ ((col>>1)&7)
@@ -418,16 +460,22 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   bool have = next_tile(cur);
   bool have_next = next_tile(nxt);          // (returns false again once the sequence has ended)
   if (have) load_tile(cur, 0);
+  // The Q fragments are consumed here, so that the compiler's waits for them stay out of the loop (inside it they would
+  // also wait for the tile loads in flight, which the compiler does not know about).
+#pragma unroll
+  for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int buf = 0;
   while (have) {
-    if (have_next) load_tile(nxt, buf ^ 1);
+    // the description of the tile after next (register work only, see above), then the loads of the next tile
     const bool have_nn = next_tile(nn);
+    if (have_next) load_tile(nxt, buf ^ 1);
     const uint16_t* kbase = ldsK + buf * K_TILE;
     const uint16_t* vbase = ldsV + buf * V_TILE;
     const bool general = cur.bias != nullptr || cur.nk < KT;
-    tile_body(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, general, cur.nk, cur.bias, cur.mw0, cur.mw1);
+    tile_body(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, general, cur.nk,
+              cur.bias != nullptr ? ldsB + buf * 256 : nullptr, cur.mw0, cur.mw1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     buf ^= 1;
