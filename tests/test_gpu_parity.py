@@ -416,6 +416,45 @@ def test_keys_with_a_common_offset(I, wl):
             assert emax <= tol_max * vs and emean <= tol_mean * vs, (wl.name, b, h, emax, emean, vs)
 
 
+def forward_sweep_cases(seed, n):
+    """A seeded stream of small random problems for the whole call: batch 1-3, 1-9 heads, ragged grids, 0-3 context
+    references, every corner of the three ratios, with and without the coarse residual, bf16 D = 128 (MFMA kernels), bf16
+    D = 64 and fp32 (portable kernels)."""
+    import random
+    rng = random.Random(seed)
+
+    def grid(lo, hi):
+        while True:
+            g = (rng.randint(1, 3), rng.randint(2, 12), rng.randint(3, 40))
+            if lo <= g[0] * g[1] * g[2] <= hi:
+                return g
+
+    cases = []
+    for case in range(n):
+        kind = rng.choice(["bf16_128", "bf16_128", "bf16_128", "bf16_64", "f32_64", "f32_128"])
+        D, block = (128, 128) if kind.endswith("128") else (64, 64)
+        B = rng.choice([1, 1, 2, 3])
+        src = grid(60, 2200)
+        ctx = tuple(tuple(grid(10, 1500) for _ in range(rng.randint(0, 3))) for _ in range(B))
+        cases.append(W.CONFIGS["cfg1"].with_(
+            name="fwd_sweep%d_%d_%s" % (seed, case, kind), B=B, H=rng.choice([1, 2, 3, 5, 8, 9]), D=D, block=block,
+            dtype="bf16" if kind.startswith("bf16") else "f32", src_grid=src, ctx_grids=ctx,
+            keep_ratio=rng.choice([0.0, 0.125, 0.3, 0.5, 0.8, 1.0]), full_frac=rng.choice([0.0, 0.1, 0.2, 0.5, 0.9, 1.0]),
+            exact_frac=rng.choice([0.0, 0.0, 0.0625, 0.3, 1.0]), gamma=rng.choice([0.0, 0.0, 0.5, -1.0]), seed=3000 + case))
+    return cases
+
+
+FWD_SWEEP = forward_sweep_cases(11, 24) + forward_sweep_cases(12, 24)
+
+
+@pytest.mark.parametrize("wl", FWD_SWEEP, ids=[c.name for c in FWD_SWEEP])
+def test_isa_attention_random_sweep(I, wl):
+    """Every output element of the whole call against the oracle evaluated on the lists the call chose (which must be
+    valid selections of the oracle's scores), for every head of every batch item."""
+    Q, K, V, q, k, v = gen(wl)
+    check_end_to_end(I, wl, Q, K, V, q, k, v)
+
+
 def test_all_exact_equals_dense(I):
     """full_frac = 1 and keep_ratio = 1: ISA must reproduce dense attention (GPU vs GPU, and vs the oracle)."""
     wl = SMALL_BF16.with_(keep_ratio=1.0, full_frac=1.0)
