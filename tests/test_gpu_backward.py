@@ -289,6 +289,11 @@ def test_backward_full_size_480p_sampled(I):
     _full_size_sampled(I, W.CONFIGS["cfg2"], 0, 4, seed=21)
 
 
+def test_backward_full_size_720p_sampled(I):
+    """cfg4 (151 200 tokens), head 39: the last head its XCD works through."""
+    _full_size_sampled(I, W.CONFIGS["cfg4"], 0, 39, seed=26)
+
+
 def test_backward_full_size_ragged_batch_sampled(I):
     _full_size_sampled(I, W.CONFIGS["cfg3"].with_(keep_ratio=0.25, full_frac=0.1), 1, 5, seed=22)
 

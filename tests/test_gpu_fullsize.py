@@ -131,6 +131,26 @@ def test_dense_attention_full_size_sampled(I, name):
     assert torch.isfinite(out[0, :, :n].float()).all()
 
 
+def test_full_size_runs_are_bitwise_reproducible(I):
+    """cfg2, forward and backward twice on the same inputs: no atomics anywhere, so every bit repeats (split work items
+    and their merge included)."""
+    wl = W.CONFIGS["cfg2"]
+    q, k, v = _gen_gpu(wl)
+    pr = problem_of(wl)
+    ws = I.new_workspace(pr)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    d_out = torch.randn(q.shape, generator=g, device="cuda", dtype=torch.float32).to(q.dtype)
+    runs = []
+    for _ in range(2):
+        out, dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(4))
+        I.isa_attention(pr, q, k, v, out, ws)
+        I.isa_attention_backward(pr, q, k, v, out, d_out, dq, dk, dv, ws)
+        torch.cuda.synchronize()
+        runs.append((out, dq, dk, dv))
+    for a, b in zip(*runs):
+        assert torch.isfinite(a.float()).all() and torch.equal(a, b)
+
+
 def test_split_work_items_isa_full_size(I):
     """cfg2 gives every XCD 260 exact-branch work items for 32 compute units, so the launch cuts the last 4 items of the
     XCD's last head (heads 4, 9, .. 39) into key ranges and merges them: check exactly those query blocks."""

@@ -50,6 +50,38 @@ def test_static_scratch_matches_workspace_call_twice_in_a_row(variant):
             assert torch.isnan(out[:, :, n:]).all()
 
 
+def test_static_scratch_call_replays_from_a_hip_graph():
+    """What the entry point is for: it can be captured (no allocation, no workspace argument to keep alive).  The first
+    call on the device is made before the capture (it looks the scratch array's address up); every replay reproduces the
+    eager result bit for bit, with eager work of the same library between the replays."""
+    import paper_2605_04569_amd as I
+    I.lib()
+    wl = SMALL.with_(gamma=0.25)
+    q, k, v = (t.cuda() for t in W.make_inputs(wl, "cpu"))
+    ref = _reference(I, wl, q, k, v)
+    pr = problem_of(wl)
+    out = torch.zeros_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        I.isa_attention_static(pr, q, k, v, out)                    # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        I.isa_attention_static(pr, q, k, v, out)
+    n = wl.tokens(0)
+    for rep in range(3):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out[:, :, :n], ref[:, :, :n]), rep
+        big = BIG
+        qb, kb, vb = (t.cuda() for t in W.make_inputs(big, "cpu"))
+        I.isa_attention_static(problem_of(big), qb, kb, vb, torch.empty_like(qb))    # another problem through the same scratch
+        torch.cuda.synchronize()
+
+
 def test_static_scratch_rejects_what_does_not_fit():
     """cfg2's forward-only workspace (0.7 GB) is beyond the array: a clear error, nothing launched."""
     import paper_2605_04569_amd as I
