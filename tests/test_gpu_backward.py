@@ -386,3 +386,33 @@ def test_backward_maximum_block_count(I):
     wl = W.Workload(name="max_blocks", B=1, H=1, D=128, dtype="bf16", block=128, src_grid=(64, 64, 64),
                     ctx_grids=(((64, 64, 64),),), keep_ratio=0.1, full_frac=0.02, seed=91, exact_frac=0.01)
     _full_size_sampled(I, wl, 0, 0, seed=25)
+
+
+# ------------------------------------------------------------------------------------------------
+# torch.autograd glue
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("layout", ["bhsd", "bshd"])
+def test_autograd_module_matches_the_oracle(I, layout):
+    """InContextSparseAttention: loss.backward() through the module gives the oracle's gradients (the GPU's own lists
+    equal the oracle's on this input), for contiguous [B, H, S, D] tensors and for [B, S, H, D] storage viewed as such."""
+    wl = SMALL.with_(exact_frac=0.25, gamma=0.5)
+    Q, K, V, dO = _inputs(wl)
+    pr = problem_of(wl)
+    _, plans = _lists(I, wl, pr, Q, K, V)
+
+    def leaf(t):
+        t = t.cuda()
+        if layout == "bshd":
+            t = t.transpose(1, 2).contiguous().transpose(1, 2)
+        return t.requires_grad_(True)
+
+    q, k, v = leaf(Q), leaf(K), leaf(V)
+    attn = I.InContextSparseAttention([wl.seg_len(b) for b in range(wl.B)], keep_ratio=wl.keep_ratio, full_frac=wl.full_frac,
+                                      exact_frac=wl.exact_frac, gamma=wl.gamma)
+    out = attn(q, k, v)
+    (out.float() * dO.cuda().float()).sum().backward()
+    torch.cuda.synchronize()
+    want = torch.empty_like(out)
+    I.isa_attention(pr, q.detach(), k.detach(), v.detach(), want, I.new_workspace(pr))
+    assert torch.equal(out.detach(), want)
+    _compare(wl, Q, K, V, dO, plans, q.grad, k.grad, v.grad)
