@@ -951,7 +951,10 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   // ---- dQ: exact branch over the kept tokens; Taylor branch over the tokens of each block's exact
   // set and the means of the other kept blocks
   const BwdStream kept_tokens = {K, V, ws.ktab, ws.ybd_kv, 0, 0};
-  const BwdStream kept_means = {ws.kcn, ws.vcn, nullptr, ws.ybd_mean, 0, 0};
+  // mean keys: minus the mean key of block 0 where they are a Taylor row's only keys (the forward's log-sum-exp refers to
+  // those), the unshifted copy where exact sets put them in one softmax with token keys
+  const uint16_t* mean_keys = pr.p.exact_frac > 0.0 ? ws.kcnb : ws.kcn;      // as the forward chose its Taylor kernel
+  const BwdStream kept_means = {mean_keys, ws.vcn, nullptr, ws.ybd_mean, 0, 0};
   a.x1 = Q; a.x2 = DO; a.bx = ws.nlse; a.dx = ws.delta;
   a.out_bf = (uint16_t*)dq; a.out_f32 = nullptr; a.oscale = scale;
   a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
@@ -988,7 +991,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     float* mean_grad = pass == 0 ? ws.dkc : ws.dvc;
     const float osc = pass == 0 ? scale : 1.0f;
     if (sl > 0) {                                 // gradients of the gathered means: every Taylor block, minus its exact set
-      a.x1 = ws.kcn; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
+      a.x1 = mean_keys; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
       a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
       a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.add_by_block = 0; a.oscale = osc; a.items = n_mean_pairs;
       a.parts = mean_parts; a.part_stride = (long long)B * H * pr.Tn_pad * MD;

@@ -45,6 +45,7 @@ struct MfmaArgs {
   const uint16_t* q; const uint16_t* k; uint16_t* out;
   const uint16_t* vt;                       // packed V^T
   const uint16_t* kcn; const uint16_t* vcnt; const float* biasn;
+  const float* kc;                          // fp32 block means of K, [bh][T_max][128]: row 0 is what kcn is stored short of
   const int* tflag;                         // per tile of gathered means: 1 = needs the bias / mask path (k_attn_sp)
   float lse_shift;                          // log2 of the factor the mean keys' weights are stored short of (0 with exact sets)
   const uint16_t* zero_tile;                // 16 KB of zeros (a V^T tile that contributes nothing)

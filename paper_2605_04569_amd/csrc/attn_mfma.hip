@@ -92,7 +92,7 @@ hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v,
 __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ kc, const float* __restrict__ vc,
                                                       const int* __restrict__ kv_list, const int* __restrict__ blk_n,
                                                       const int4* __restrict__ btab, uint16_t* __restrict__ kcn,
-                                                      uint16_t* __restrict__ vcn, uint16_t* __restrict__ vcnt,
+                                                      uint16_t* __restrict__ kcnb, uint16_t* __restrict__ vcn, uint16_t* __restrict__ vcnt,
                                                       uint16_t* __restrict__ vcnt4,
                                                       float* __restrict__ biasn, int* __restrict__ tflag,
                                                       int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad, int block) {
@@ -125,15 +125,20 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
     const int j = ids[r];
     float kval = 0.f, vval = 0.f;
     if (j >= 0) {
-      // Without exact sets the mean keys are the only keys of a Taylor row, and a vector added to all keys of a softmax
-      // changes nothing: the mean key of block 0 (a source block, always kept) is subtracted before the rounding to bf16,
-      // so that a component common to all keys (an offset of many standard deviations costs 2^-9 of itself per channel
-      // otherwise) does not eat the precision of what distinguishes them.  The backward pass streams the same array and
-      // the forward's log-sum-exp refers to the same shifted scores.
-      kval = kc[(bh * T_max + j) * MD + d] - (vcnt4 ? 0.f : kc[bh * T_max * MD + d]);
+      // A vector common to all keys of a softmax changes nothing, so the mean key of block 0 (a source block, always
+      // kept) is subtracted before the rounding to bf16: a component common to all keys (an offset of many standard
+      // deviations costs 2^-9 of itself per channel otherwise) then does not eat the precision of what distinguishes
+      // them.  Without exact sets the mean keys are the only keys of a Taylor row and nothing else is needed (the
+      // forward's log-sum-exp and the backward's recomputed scores refer to the same shifted keys).  With exact sets
+      // they share a softmax with token keys: the 4-wave kernel adds each query's product with the subtracted vector
+      // back onto its mean-key scores, and the backward pass streams the unshifted copy kcnb.
+      const float kraw = kc[(bh * T_max + j) * MD + d];
+      kval = kraw - kc[bh * T_max * MD + d];
+      if (kcnb) kcnb[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kraw);
       vval = vc[(bh * T_max + j) * MD + d];
     }
     kcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kval);
+    if (kcnb && j < 0) kcnb[(bh * Tn_pad + t0 + r) * MD + d] = 0;
     if (vcn) vcn[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(vval);       // row-major mean values: the backward pass streams them
     vtile[r][d] = f2bf(vval);
   }
@@ -150,7 +155,7 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st) {
   hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
-                     ws.btab, ws.kcn, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.tflag, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad,
+                     ws.btab, ws.kcn, ws.kcnb, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.tflag, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad,
                      pr.p.block);
   return hipGetLastError();
 }
@@ -170,13 +175,13 @@ struct Tile {                               // wave-uniform description of one 6
 };
 
 // One 64-key tile for the 32 query columns of a wave: S^T = K Q^T, online softmax in the log2 domain
-// (Alg. 2 Part A / Part B), O^T += V^T P^T.  When `general` (wave-uniform) the per-key bias and the masks are
-// added to the raw scores first; the bias arrives pre-divided by the softmax scale so that both cases share
-// the rest of the code.
+// (Alg. 2 Part A / Part B), O^T += V^T P^T.  When `general` (wave-uniform) the per-key bias, the lane's `shift` (its
+// query's product with the vector the mean keys are stored short of; 0 for token tiles) and the masks are applied to
+// the raw scores first; bias and shift are in units of the raw score, so that both cases share the rest of the code.
 __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, const uint16_t* __restrict__ vbase,
                                           const bf16x8 (&qf)[8], f32x16 (&oacc)[4], float& m_run, float& l_run,
                                           const int (&koff)[8], const int (&voff)[4], float cscale, int g, bool general,
-                                          int nk, const float* __restrict__ bias, uint32_t mw0, uint32_t mw1) {
+                                          int nk, const float* __restrict__ bias, float shift, uint32_t mw0, uint32_t mw1) {
   f32x16 sacc[2];
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
@@ -220,7 +225,7 @@ __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, co
       for (int e = 0; e < 16; ++e) {
         const int key = 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3);
         const bool off = (key >= nk) || ((mw >> (key & 31)) & 1u);
-        sacc[kb][e] = off ? -INFINITY : sacc[kb][e] + addv[e];
+        sacc[kb][e] = off ? -INFINITY : sacc[kb][e] + (addv[e] + shift);
       }
     }
   }
@@ -307,6 +312,21 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   bf16x8 qf[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+
+  // The gathered mean keys are stored minus the mean key of block 0 (see k_gather_means): q . Kc_0, in fp32, goes back
+  // onto this query's raw scores against mean keys, which share the softmax with the token keys of the exact set.
+  float q_ref = 0.f;
+  {
+    const float* ref = a.kc + bh * T_max * MD + 8 * g;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const float4 r0 = *reinterpret_cast<const float4*>(ref + 16 * s), r1 = *reinterpret_cast<const float4*>(ref + 16 * s + 4);
+      const float rr[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q_ref = fmaf((float)qf[s][e], rr[e], q_ref);
+    }
+    q_ref += __shfl_xor(q_ref, 32, 64);
+  }
 
   f32x16 oacc[4];
 #pragma unroll
@@ -464,6 +484,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   // also wait for the tile loads in flight, which the compiler does not know about).
 #pragma unroll
   for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
+  asm volatile("" : "+v"(q_ref));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int buf = 0;
@@ -475,7 +496,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
     const uint16_t* vbase = ldsV + buf * V_TILE;
     const bool general = cur.bias != nullptr || cur.nk < KT;
     tile_body(kbase, vbase, qf, oacc, m_run, l_run, koff, voff, cscale, g, general, cur.nk,
-              cur.bias != nullptr ? ldsB + buf * 256 : nullptr, cur.mw0, cur.mw1);
+              cur.bias != nullptr ? ldsB + buf * 256 : nullptr, cur.bias != nullptr ? q_ref : 0.f, cur.mw0, cur.mw1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     buf ^= 1;

@@ -627,6 +627,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   MfmaArgs m;
   m.q = (const uint16_t*)a.q; m.k = (const uint16_t*)a.k; m.out = (uint16_t*)a.out;
   m.vt = ws.vt; m.kcn = ws.kcn; m.vcnt = ws.vcnt; m.biasn = ws.biasn; m.tflag = ws.tflag;
+  m.kc = a.kc;
   m.lse_shift = ws.vcnt4 ? 0.f : log2f((float)pr.p.block);
   m.zero_tile = ws.zero_tile;
   m.blk_start = a.blk_start; m.blk_n = a.blk_n;

@@ -136,6 +136,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     ws->olo = (uint16_t*)take(B * H * S * D * 2);
     ws->delta = (float*)take(B * H * S * 4);
     ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
+    ws->kcnb = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * Tn * D * 2) : nullptr;
     ws->dkc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->dvc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->ftab = (int4*)take(B * H * T * 16);
@@ -158,7 +159,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     }
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
-    ws->vcn = ws->olo = nullptr;
+    ws->vcn = ws->olo = ws->kcnb = nullptr;
     ws->ftab = ws->ltab = nullptr;
     ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
     ws->mask_t = nullptr;

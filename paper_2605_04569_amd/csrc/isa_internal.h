@@ -53,7 +53,8 @@ struct Workspace {
   uint32_t* exact_mask;  // [B,H,T_max,mask_words], only when exact_frac > 0
   // operand copies of the MFMA path (bf16, D = 128, block = 128)
   uint16_t* vt;          // [B,H,T_max][D][128]: V of each block, transposed and key-permuted
-  uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order
+  uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order, minus the mean key of block 0
+  uint16_t* kcnb;        // [B,H,Tn_pad][D]: the same without the subtraction (only with exact sets: the backward's mean keys)
   uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
   float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key (without exact sets: ln(n_j / block) sqrt(D)), -inf for padding
   int* tflag;            // [B,H,Tn_pad/64]: 1 if a tile of mean keys needs its bias or masks (padding, a short block, exact sets)

@@ -34,6 +34,7 @@ CASES = [SMALL, RAGGED,
          SMALL.with_(name="key_offset_3", key_offset=3.0),
          SMALL.with_(name="key_offset_3_exact_sets", key_offset=3.0, exact_frac=0.25),
          SMALL.with_(name="key_offset_8_all_taylor", key_offset=8.0, full_frac=0.0),
+         SMALL.with_(name="exact_frac_too_small_for_a_set", exact_frac=0.05, key_offset=3.0),
          SMALL.with_(name="uncentred", centred=False, gamma=0.5),
          SMALL.with_(name="plain_mean_tile", H=2, src_grid=(4, 32, 65), ctx_grids=(((2, 10, 33),),), keep_ratio=1.0, seed=81)]
 

@@ -389,6 +389,8 @@ OFFSET_CASES = [
     SMALL_BF16.with_(name="key_offset_3", key_offset=3.0),
     SMALL_BF16.with_(name="key_offset_3_exact_sets", key_offset=3.0, exact_frac=0.25),
     SMALL_BF16.with_(name="key_offset_8", key_offset=8.0),
+    SMALL_BF16.with_(name="key_offset_8_exact_sets", key_offset=8.0, exact_frac=0.25),
+    SMALL_BF16.with_(name="key_offset_8_exact_frac_too_small_for_a_set", key_offset=8.0, exact_frac=0.05),
     SMALL_BF16.with_(name="key_offset_minus_5_residual", key_offset=-5.0, gamma=0.5),
     SMALL_BF16.with_(name="uncentred", centred=False),
     SMALL_BF16.with_(name="uncentred_tiny_grid", centred=False, src_grid=(1, 3, 5), ctx_grids=(((1, 3, 5),),), keep_ratio=1.0, full_frac=0.5),
