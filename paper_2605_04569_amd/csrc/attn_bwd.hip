@@ -68,6 +68,8 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 struct BwdStream {
   const uint16_t* y1; const uint16_t* y2;     // row-major rows for the scores / for dP; the accumulation product reads
                                               // the transpose of y1 (launches that need dS) or of y2 (the others: dO)
+  const uint16_t* y3;                         // EX == 2, mean tiles: rows whose transpose the accumulation product reads instead of
+                                              // y1's (the mean keys without the subtraction of Kc_0); null otherwise
   const int4* tab;                            // token tiles: [bh][T_max] {token offset, tokens, block id} per list entry; null: mean tiles
   const float2* ybd;                          // per tile of 64 streamed positions: 64 additive exponent terms (-inf: masked), then 64 minus-deltas
   int kind;                                   // token tiles: list entries = 0 kept blocks, 1 full-attention blocks, 2 Taylor blocks
@@ -81,6 +83,9 @@ struct BwdArgs {
   const uint16_t* x1; const uint16_t* x2;
   const int* stat_list;                       // [bh][T_max] block ids; unused for mean rows
   const float* bx; const float* dx;           // per stationary row: additive exponent term / delta ([bh][S_max] or [bh][Tn_pad]); null = 0
+  // EX == 2 only (stationary Taylor queries; the streamed gathered mean keys are stored minus the mean key of block 0):
+  // rx [bh][S_max] = q . Kc_0 of every stationary row in raw score units, added to its scores against mean tiles
+  const float* rx;
   BwdStream s[2];
   int n_phases;
   // exact sets: bit matrix [bh][T_max][mask_words] whose row is a stationary entry (token blocks) or a stationary mean row,
@@ -112,7 +117,8 @@ struct BwdArgs {
 // way round.
 template <bool SM, bool T2, int EX, bool YD>
 __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * STAGE + 2 * SIDE_BYTES / 2];
+  constexpr int STG = EX == 2 ? STAGE + K_TILE : STAGE;      // EX == 2: a third tile per stage (see BwdStream::y3)
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * STG + 2 * SIDE_BYTES / 2];
   // Workgroup ids go round-robin over the 8 XCDs: XCD x gets every 8th (batch, head) and works through its items one
   // head after the other, so that the workgroups that run together on an XCD (and share its L2) stream the same rows.
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
@@ -178,7 +184,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   int rowq[2];
   bool row_ok[2];
   bf16x8 x1f[2][4], x2f[2][4];
-  float bxv[2], dxv[2];
+  float bxv[2], dxv[2], rxv[2] = {0.f, 0.f};
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     rowq[qt] = wq * 32 + 16 * qt + r16;
@@ -191,6 +197,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     }
     bxv[qt] = (a.bx && row_ok[qt]) ? a.bx[bx_base + rowq[qt]] : 0.f;
     dxv[qt] = (a.dx && row_ok[qt]) ? a.dx[bx_base + rowq[qt]] : 0.f;
+    if (EX == 2) rxv[qt] = (a.rx && row_ok[qt]) ? a.rx[bx_base + rowq[qt]] : 0.f;
   }
   // Exact-set bits of the stationary token blocks: lane L holds word L of the row of this wave's own entry and of the
   // pair's other entry (zeros for an entry that does not exist); handed out with readlane.
@@ -216,6 +223,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
       if (T2) asm volatile("" : "+v"(x2f[qt][ks]));
     }
     asm volatile("" : "+v"(bxv[qt]), "+v"(dxv[qt]));
+    if (EX == 2) asm volatile("" : "+v"(rxv[qt]));
   }
   if (EX) asm volatile("" : "+v"(bits_own), "+v"(bits_other), "+v"(bits_own_hi), "+v"(bits_other_hi));
 
@@ -246,6 +254,7 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
   const int ph_masked0 = a.s[0].masked, ph_masked1 = a.s[1].masked;
   const uint16_t* const ph_y1_0 = a.s[0].y1; const uint16_t* const ph_y1_1 = a.s[1].y1;
   const uint16_t* const ph_y2_0 = a.s[0].y2; const uint16_t* const ph_y2_1 = a.s[1].y2;
+  const uint16_t* const ph_y3_0 = a.s[0].y3; const uint16_t* const ph_y3_1 = a.s[1].y3;
   const float2* const ph_ybd_0 = a.s[0].ybd; const float2* const ph_ybd_1 = a.s[1].ybd;
 #define PH(p, x0, x1) ((p) == 0 ? (x0) : (x1))
   auto tiles_of = [&](int p) __attribute__((always_inline)) -> int { return PH(p, ph_tiles0, ph_tiles1); };
@@ -314,15 +323,21 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     const char* const y1_tile = uniform_ptr(y1_head + y_off);
     const char* const y2_tile = uniform_ptr(y2_head + y_off);
     const char* const ybd_tile = uniform_ptr(ybd_head + bd_off);
-    uint16_t* sb = lds + stage * STAGE;
+    uint16_t* sb = lds + stage * STG;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const uint32_t ro = (uint32_t)min(nrow_l[i], nk - 1) * ystride_b + nchunk_b[i];     // rows past the end re-read the last one
       dma16(y1_tile, ro, lds_addr(sb + (wave * 2 + i) * 512));
       dma16(y2_tile, ro, lds_addr(sb + K_TILE + (wave * 2 + i) * 512));
     }
+    if (EX == 2 && means) {                                // the mean keys as they are, for the transposed read
+      const char* const y3_tile = uniform_ptr(reinterpret_cast<const char*>(PH(c.p, ph_y3_0, ph_y3_1) + bh * a.Tn_pad * MD) + y_off);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        dma16(y3_tile, (uint32_t)nrow_l[i] * ystride_b + nchunk_b[i], lds_addr(sb + 2 * K_TILE + (wave * 2 + i) * 512));
+    }
     if (wave == 0)                                         // {bias, delta} of the 64 rows: 512 B, lanes 32..63 repeat lanes 0..31
-      dma16(ybd_tile, (uint32_t)(lane & 31) * 16u, lds_addr(lds + 2 * STAGE + stage * (SIDE_BYTES / 2)));
+      dma16(ybd_tile, (uint32_t)(lane & 31) * 16u, lds_addr(lds + 2 * STG + stage * (SIDE_BYTES / 2)));
   };
 
   // per-lane fragment offsets (bf16 elements), as in the forward kernel
@@ -368,15 +383,16 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     // reading the other stage (the previous tile), which the loads of the next tile now overwrite
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    const uint16_t* sb = lds + (it & 1) * STAGE;
-    const float* side = reinterpret_cast<const float*>(lds + 2 * STAGE + (it & 1) * (SIDE_BYTES / 2));   // 64 terms, 64 minus-deltas
+    const uint16_t* sb = lds + (it & 1) * STG;
+    const float* side = reinterpret_cast<const float*>(lds + 2 * STG + (it & 1) * (SIDE_BYTES / 2));   // 64 terms, 64 minus-deltas
+    const bool mean_tile = EX == 2 && PH(cur.p, ph_tab0, ph_tab1) == nullptr;     // wave-uniform
     f32x4 nd[2];                              // YD: minus delta of the streamed rows of the sub-tile whose T steps are next
     auto load_delta = [&](int hh, int kt) {
       if (T2 && YD) nd[kt] = *reinterpret_cast<const f32x4*>(side + 64 + 32 * hh + 16 * kt + 4 * q);
     };
     // LDS fragments are requested PF steps before the MFMAs that read them (a step is 64 or 32 cycles of matrix pipe,
     // an LDS read takes longer than one of them), in PF + 1 rotating register sets
-    constexpr int PF = 2, NB = PF + 1;
+    constexpr int PF = EX == 2 ? 1 : 2, NB = PF + 1;        // (EX == 2: one step ahead, its registers are all spoken for)
     bf16x8 fa[NB], fb[NB];                    // Y1 / Y2 fragments of T steps n .. n + PF
     bf16x8 fc[NB];                            // Yt fragments of C steps
     auto t_load = [&](int n) {                // fragments of T step n (sub-tile n / 4, k-slice n % 4)
@@ -386,7 +402,8 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
       if (T2) fb[n % NB] = *reinterpret_cast<const bf16x8*>(rowp + K_TILE);
     };
     auto c_load = [&](int n) {                // fragment of C step n (half n / 8, channel tile n % 8)
-      const uint16_t* src = sb + (T2 ? 0 : K_TILE) + (n >> 3) * 32 * MD + tr_pos[n & 7];      // the tile whose transpose is Yt
+      // the tile whose transpose is Yt
+      const uint16_t* src = sb + (T2 ? ((EX == 2 && mean_tile) ? 2 * K_TILE : 0) : K_TILE) + (n >> 3) * 32 * MD + tr_pos[n & 7];
       const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(src + tr_base[0]));
       const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(src + tr_base[1]));
       fc[n % NB] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -438,6 +455,10 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt)
       c1[qt] = EX ? t1_init[qt] + f32x4{gm_tile[qt], gm_tile[qt], gm_tile[qt], gm_tile[qt]} : t1_init[qt];
+    if (EX == 2 && mean_tile) {               // the gathered mean keys are stored minus Kc_0: q . Kc_0 goes back onto the scores
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) c1[qt] += f32x4{rxv[qt], rxv[qt], rxv[qt], rxv[qt]};
+    }
     f32x4 bt[2];                              // exponent terms of the sub-tile whose weights are in progress, [kt]
     auto load_side = [&](int hh, int kt) {
       const uint32_t pos_w = hh ? pos_w1 : pos_w0;
@@ -569,16 +590,19 @@ __global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ 
 // Per list entry: the table row of its block and the {exponent term, minus delta} pair of each of its 128 row positions
 // (masked positions: -inf, 0), stored per tile of 64 positions as 64 terms followed by 64 minus-deltas.  kind 0: kept blocks as streamed keys (term 0), plus the per-mean arrays of the Taylor
 // branch (log2 n_j per gathered mean, -inf for the padding); kinds 1, 2: full-attention / Taylor blocks as streamed
-// queries (term = minus the row's log-sum-exp in the log2 domain, delta of the row).
+// queries (term = minus the row's log-sum-exp in the log2 domain, delta of the row); with `rq` (Taylor blocks under exact
+// sets, for scores against the gathered means, which are stored minus Kc_0) the row's q . Kc_0, scaled to the log2
+// domain, is added to the term.
 __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, int kind, const int4* __restrict__ btab,
-                                                  const float* __restrict__ nlse, const float* __restrict__ delta,
+                                                  const float* __restrict__ nlse, const float* __restrict__ rq, float rq_scale,
+                                                  const float* __restrict__ delta,
                                                   int4* __restrict__ tab, float2* __restrict__ ybd,
                                                   float2* __restrict__ ybd_mean, float* __restrict__ bx_mean, Counts cnt,
                                                   int H, int Tn_pad, int S_max) {
   const int e = blockIdx.x, h = blockIdx.y, b = blockIdx.z, r = threadIdx.x;
   const int T_max = cnt.T_max;
   const long long bh = (long long)b * H + h;
-  const int n_list = kind == 0 ? cnt.b[b].T_new : kind == 1 ? cnt.b[b].n_full : cnt.b[b].n_flat;
+  const int n_list = kind == 0 ? cnt.b[b].T_new : kind == 1 ? cnt.b[b].n_full : cnt.b[b].n_flat;      // kinds 2, 3: Taylor blocks
   if (kind == 0 && e < Tn_pad && r == 0) {
     float l2 = -INFINITY;
     if (e < n_list) l2 = log2f((float)btab[b * T_max + block_in_range(list[bh * T_max + e], cnt.b[b].T)].y);
@@ -594,7 +618,8 @@ __global__ __launch_bounds__(128) void k_bwd_rows(const int* __restrict__ list, 
   float2 v = make_float2(-INFINITY, 0.f);
   if (r < ent.y) {
     if (kind == 0) v = make_float2(0.f, 0.f);
-    else v = make_float2(nlse[bh * S_max + ent.x + r], -delta[bh * S_max + ent.x + r]);
+    else v = make_float2(nlse[bh * S_max + ent.x + r] + (rq ? rq_scale * rq[bh * S_max + ent.x + r] : 0.f),
+                         -delta[bh * S_max + ent.x + r]);
   }
   const long long pos = (bh * T_max + e) * 128 + r;
   float* yf = reinterpret_cast<float*>(ybd);
@@ -865,8 +890,12 @@ static hipError_t launch_one(BwdArgs a, int ex, int B, int H, hipStream_t st, bo
   a.tail_items = 0; a.tail_parts = 1;
   if (!SM && split_tail && a.n_phases == 1 && ex == 0 && a.tail_scratch) {
     // the last round of an XCD's 32 compute units: if at most half of them would have an item, cut those items
-    const int t = a.items_xcd % 32;
-    if (t > 0 && t <= 16) { a.tail_items = t; a.tail_parts = 32 / t > 8 ? 8 : 32 / t; }
+    const int cus = cus_per_xcd(), t = a.items_xcd % cus;
+    if (t > 0 && t <= cus / 2) {
+      int parts = cus / t > 8 ? 8 : cus / t;
+      while (parts > 1 && N_XCD * t * parts > SPLIT_MAX_SUB) --parts;       // the partial-result area holds SPLIT_MAX_SUB sub-items
+      if (parts > 1) { a.tail_items = t; a.tail_parts = parts; }
+    }
   }
   const dim3 grid((unsigned)(SM ? a.items * a.parts * hpx * 8 : (a.items_xcd - a.tail_items + a.tail_items * a.tail_parts) * 8));
   if (ex == 2) {                                // position bits only occur with token rows as stationary rows and dS
@@ -897,7 +926,10 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     sk = c.T_new > sk ? c.T_new : sk;
     kx = c.k_exact > kx ? c.k_exact : kx;
   }
-  const bool ex = kx > 0 && sl > 0 && exact_mask != nullptr;      // some Taylor block has a non-empty exact set
+  // The forward ran its 4-wave kernel (exact sets, possibly empty ones when exact_frac is too small for the list): token
+  // keys and mean keys in one softmax, the mean keys stored minus Kc_0 and q . Kc_0 kept per Taylor row (ws.rq).
+  const bool ex = pr.p.exact_frac > 0.0 && sl > 0 && exact_mask != nullptr;
+  (void)kx;
 #define ISA_BWD_CHECK()                           \
   do {                                            \
     hipError_t e__ = hipGetLastError();           \
@@ -925,12 +957,17 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
                      pr.geo, pr.cnt);
   ISA_BWD_CHECK();
   const int gx = T_max > pr.Tn_pad ? T_max : pr.Tn_pad;
-  hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, kv_list, 0, ws.btab, ws.nlse, ws.delta, ws.ktab,
+  const float* no_rq = nullptr;
+  const float cs = 1.4426950408889634f / sqrtf((float)MD);      // raw score -> log2 domain
+  hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, kv_list, 0, ws.btab, ws.nlse, no_rq, 0.f, ws.delta, ws.ktab,
                      ws.ybd_kv, ws.ybd_mean, ws.bx_mean, pr.cnt, H, pr.Tn_pad, S_max);
-  hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, full_list, 1, ws.btab, ws.nlse, ws.delta, ws.ftab,
+  hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, full_list, 1, ws.btab, ws.nlse, no_rq, 0.f, ws.delta, ws.ftab,
                      ws.ybd_full, ws.ybd_mean, ws.bx_mean, pr.cnt, H, pr.Tn_pad, S_max);
-  hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, flat_list, 2, ws.btab, ws.nlse, ws.delta, ws.ltab,
+  hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, flat_list, 2, ws.btab, ws.nlse, no_rq, 0.f, ws.delta, ws.ltab,
                      ws.ybd_flat, ws.ybd_mean, ws.bx_mean, pr.cnt, H, pr.Tn_pad, S_max);
+  if (ex)             // the same rows with q . Kc_0 in their exponent terms, for the launches that score them against gathered means
+    hipLaunchKernelGGL(k_bwd_rows, dim3(gx, H, B), dim3(128), 0, st, flat_list, 2, ws.btab, ws.nlse, (const float*)ws.rq, cs, ws.delta,
+                       ws.ltab, ws.ybd_flatm, ws.ybd_mean, ws.bx_mean, pr.cnt, H, pr.Tn_pad, S_max);
   ISA_BWD_CHECK();
   if (ex) {
     hipLaunchKernelGGL(k_bwd_tmask, dim3(T_max, H, B), dim3(128), 0, st, exact_mask, ws.mask_t, pr.cnt, H);
@@ -945,17 +982,15 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   a.items_xcd = 0; a.tail_items = 0; a.tail_parts = 1; a.tail_scratch = ws.split_o;   // the forward's partial-result area: 256 x 256 x 128 floats
   const float scale = 1.0f / sqrtf((float)MD);
   const uint16_t *Q = (const uint16_t*)q, *K = (const uint16_t*)k, *V = (const uint16_t*)v, *DO = (const uint16_t*)d_out;
-  const BwdStream none = {nullptr, nullptr, nullptr, nullptr, 0, 0};
+  const BwdStream none = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
   hipError_t e;
 
   // ---- dQ: exact branch over the kept tokens; Taylor branch over the tokens of each block's exact
   // set and the means of the other kept blocks
-  const BwdStream kept_tokens = {K, V, ws.ktab, ws.ybd_kv, 0, 0};
-  // mean keys: minus the mean key of block 0 where they are a Taylor row's only keys (the forward's log-sum-exp refers to
-  // those), the unshifted copy where exact sets put them in one softmax with token keys
-  const uint16_t* mean_keys = pr.p.exact_frac > 0.0 ? ws.kcnb : ws.kcn;      // as the forward chose its Taylor kernel
-  const BwdStream kept_means = {mean_keys, ws.vcn, nullptr, ws.ybd_mean, 0, 0};
-  a.x1 = Q; a.x2 = DO; a.bx = ws.nlse; a.dx = ws.delta;
+  const BwdStream kept_tokens = {K, V, nullptr, ws.ktab, ws.ybd_kv, 0, 0};
+  const uint16_t* mean_keys = ws.kcn;             // stored minus the mean key of block 0
+  const BwdStream kept_means = {mean_keys, ws.vcn, ex ? ws.kcnb : nullptr, nullptr, ws.ybd_mean, 0, 0};
+  a.x1 = Q; a.x2 = DO; a.bx = ws.nlse; a.dx = ws.delta; a.rx = nullptr;
   a.out_bf = (uint16_t*)dq; a.out_f32 = nullptr; a.oscale = scale;
   a.add_rows = resid ? ws.cdq : nullptr; a.add_by_block = 1;       // every query block's share of dQc
   a.stat_list = full_list; a.stat_kind = 0; a.items = (sf + 1) / 2;
@@ -966,6 +1001,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.s[0] = kept_tokens; a.s[0].masked = 1;
     a.s[1] = kept_means; a.s[1].masked = 2;
     a.n_phases = 2; a.bits = exact_mask;
+    a.rx = ws.rq;
   } else {
     a.s[0] = kept_means; a.n_phases = 1;
   }
@@ -980,19 +1016,21 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     const long long wgs = (long long)n_mean_pairs * B * H;
     double best = 1e30;
     for (int p = 1; p <= BWD_MEAN_PARTS; ++p) {
-      const double rounds = (double)((wgs * p + 255) / 256) / p;
+      const long long chip = (long long)cus_per_xcd() * N_XCD;
+      const double rounds = (double)((wgs * p + chip - 1) / chip) / p;
       if (rounds < best - 1e-9) { best = rounds; mean_parts = p; }
     }
   }
-  const BwdStream full_q = {Q, DO, ws.ftab, ws.ybd_full, 1, 0};
-  const BwdStream flat_q = {Q, DO, ws.ltab, ws.ybd_flat, 2, 0};
-  a.dx = nullptr;
+  const BwdStream full_q = {Q, DO, nullptr, ws.ftab, ws.ybd_full, 1, 0};
+  const BwdStream flat_q = {Q, DO, nullptr, ws.ltab, ws.ybd_flat, 2, 0};
+  const BwdStream flat_q_means = {Q, DO, nullptr, ws.ltab, ex ? ws.ybd_flatm : ws.ybd_flat, 2, 0};     // scored against gathered means
+  a.dx = nullptr; a.rx = nullptr;
   for (int pass = 0; pass < 2; ++pass) {          // pass 0: dKc, dK (W = dS, read Q transposed); pass 1: dVc, dV (W = P, dO transposed)
     float* mean_grad = pass == 0 ? ws.dkc : ws.dvc;
     const float osc = pass == 0 ? scale : 1.0f;
     if (sl > 0) {                                 // gradients of the gathered means: every Taylor block, minus its exact set
       a.x1 = mean_keys; a.x2 = pass == 0 ? ws.vcn : nullptr; a.stat_list = nullptr; a.stat_kind = 2; a.bx = ws.bx_mean;
-      a.s[0] = flat_q; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
+      a.s[0] = flat_q_means; a.s[0].masked = ex ? 3 : 0; a.s[1] = none; a.n_phases = 1; a.bits = ws.mask_t;
       a.out_bf = nullptr; a.out_f32 = mean_grad; a.add_rows = nullptr; a.add_by_block = 0; a.oscale = osc; a.items = n_mean_pairs;
       a.parts = mean_parts; a.part_stride = (long long)B * H * pr.Tn_pad * MD;
       e = pass == 0 ? launch_one<true, true, true>(a, ex ? 1 : 0, B, H, st) : launch_one<true, false, false>(a, ex ? 1 : 0, B, H, st);

@@ -65,6 +65,7 @@ struct MfmaArgs {
   int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges
   float* split_o; float* split_ml;          // their partial results: unnormalised outputs [sub-item][2][128][128], {max, sum} [sub-item][2][128][2]
   float* nlse; int S_max;                   // minus the log-sum-exp (log2 domain) of every query row, [bh][S_max]; may be null
+  float* rq;                                // [bh][S_max], may be null: q . Kc_0 (raw score units) of every Taylor row with exact sets
   uint16_t* olo;                            // [bh][S_max][128] bf16, may be null: what the rounding of `out` to bf16 cut off
                                             // (out + olo is the fp32 result to about 2^-17), for the backward's delta
   int taylor_here;                          // k_attn_sp: 1 = also process the Taylor slots (no exact sets), 0 = exact branch only

@@ -128,10 +128,10 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
       // A vector common to all keys of a softmax changes nothing, so the mean key of block 0 (a source block, always
       // kept) is subtracted before the rounding to bf16: a component common to all keys (an offset of many standard
       // deviations costs 2^-9 of itself per channel otherwise) then does not eat the precision of what distinguishes
-      // them.  Without exact sets the mean keys are the only keys of a Taylor row and nothing else is needed (the
-      // forward's log-sum-exp and the backward's recomputed scores refer to the same shifted keys).  With exact sets
-      // they share a softmax with token keys: the 4-wave kernel adds each query's product with the subtracted vector
-      // back onto its mean-key scores, and the backward pass streams the unshifted copy kcnb.
+      // them.  Without exact sets the mean keys are the only keys of a Taylor row and nothing else is needed.  With exact
+      // sets they share a softmax with token keys: the 4-wave kernel and the backward kernels add each query's product
+      // with the subtracted vector (q . Kc_0, kept per query row) back onto its mean-key scores; kcnb is the copy without
+      // the subtraction, which the backward's dQ multiplies dS with.
       const float kraw = kc[(bh * T_max + j) * MD + d];
       kval = kraw - kc[bh * T_max * MD + d];
       if (kcnb) kcnb[(bh * Tn_pad + t0 + r) * MD + d] = f2bf(kraw);
@@ -326,6 +326,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
       for (int e = 0; e < 8; ++e) q_ref = fmaf((float)qf[s][e], rr[e], q_ref);
     }
     q_ref += __shfl_xor(q_ref, 32, 64);
+    if (a.rq && row_ok && g == 0) a.rq[bh * a.S_max + q_start + row] = q_ref;      // the backward pass adds it back the same way
   }
 
   f32x16 oacc[4];

@@ -639,6 +639,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
   m.Tn_pad = pr.Tn_pad;
   m.nlse = a.dense ? nullptr : ws.nlse; m.S_max = pr.S_max;
   m.olo = a.dense ? nullptr : ws.olo;
+  m.rq = a.dense ? nullptr : ws.rq;
   const bool exact_sets = !a.dense && pr.p.exact_frac > 0.0 && a.exact_mask != nullptr;
   m.taylor_here = exact_sets ? 0 : 1;
   // pair slots per (batch, head): the largest counts over the batch
@@ -662,7 +663,7 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
     // most half full, its items are cut into as many key ranges as fill it (each at least 8 key blocks long).
     m.n_split = 0; m.parts = 1;
     m.split_o = ws.split_o; m.split_ml = ws.split_ml;
-    const int cus = 32, rem = m.n_long % cus;
+    const int cus = cus_per_xcd(), rem = m.n_long % cus;
     if (rem > 0 && rem <= cus / 2 && rem <= sf && ws.split_o) {
       int min_list = 1 << 30;
       for (int b = 0; b < pr.p.B; ++b) {
@@ -671,7 +672,8 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
       }
       int parts = cus / rem;
       if (parts > min_list / 8) parts = min_list / 8;
-      if (parts >= 2 && 8 * rem * parts <= SPLIT_MAX_SUB) { m.n_split = rem; m.parts = parts; }
+      while (parts >= 2 && N_XCD * rem * parts > SPLIT_MAX_SUB) --parts;      // the partial-result area holds SPLIT_MAX_SUB sub-items
+      if (parts >= 2) { m.n_split = rem; m.parts = parts; }
     }
     const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts + (long long)m.hpx * ss;
     m.slots = 0; m.total = 0;

@@ -16,6 +16,16 @@ hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 int g_prof_on = 0, g_prof_recorded = 0;
 static std::atomic<int> g_use_mfma{1};
 
+int cus_per_xcd() {
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 32;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 32;
+    return (n >= N_XCD && n % N_XCD == 0) ? n / N_XCD : 32;
+  }();
+  return cus;
+}
+
 static inline bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }   // false for NaN
 // token tensors are read and written 16 bytes at a time
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -136,7 +146,9 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     ws->olo = (uint16_t*)take(B * H * S * D * 2);
     ws->delta = (float*)take(B * H * S * 4);
     ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
+    ws->rq = pr.p.exact_frac > 0.0 ? (float*)take(B * H * S * 4) : nullptr;
     ws->kcnb = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * Tn * D * 2) : nullptr;
+    ws->ybd_flatm = pr.p.exact_frac > 0.0 ? (float2*)take(B * H * T * 128 * 8) : nullptr;
     ws->dkc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->dvc = (float*)take(BWD_MEAN_PARTS * B * H * Tn * D * 4);
     ws->ftab = (int4*)take(B * H * T * 16);
@@ -159,7 +171,10 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     }
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
-    ws->vcn = ws->olo = ws->kcnb = nullptr;
+    ws->vcn = ws->olo = nullptr;
+    ws->rq = nullptr;
+    ws->kcnb = nullptr;
+    ws->ybd_flatm = nullptr;
     ws->ftab = ws->ltab = nullptr;
     ws->ybd_kv = ws->ybd_full = ws->ybd_flat = ws->ybd_mean = nullptr;
     ws->mask_t = nullptr;

@@ -54,7 +54,6 @@ struct Workspace {
   // operand copies of the MFMA path (bf16, D = 128, block = 128)
   uint16_t* vt;          // [B,H,T_max][D][128]: V of each block, transposed and key-permuted
   uint16_t* kcn;         // [B,H,Tn_pad][D]: mean keys gathered in kv_list order, minus the mean key of block 0
-  uint16_t* kcnb;        // [B,H,Tn_pad][D]: the same without the subtraction (only with exact sets: the backward's mean keys)
   uint16_t* vcnt;        // [B,H,Tn_pad/128][D][128]: mean values gathered, transposed, key-permuted
   float* biasn;          // [B,H,Tn_pad]: ln(n_j) sqrt(D) per gathered mean key (without exact sets: ln(n_j / block) sqrt(D)), -inf for padding
   int* tflag;            // [B,H,Tn_pad/64]: 1 if a tile of mean keys needs its bias or masks (padding, a short block, exact sets)
@@ -73,6 +72,11 @@ struct Workspace {
   int4* ftab; int4* ltab;             // [B,H,T_max] table rows of the full-attention / Taylor blocks, in list order
   float2* ybd_kv; float2* ybd_full; float2* ybd_flat;   // [B,H,T_max*128 pairs] per tile of 64 row positions of the list entries: 64 exponent terms, then 64 minus-deltas
   float2* ybd_mean;      // [B,H,Tn_pad] the same per gathered mean key
+  uint16_t* kcnb;        // [B,H,Tn_pad][D]: the gathered mean keys without the subtraction of Kc_0 (only with exact sets: what the
+                         // backward's dQ of a Taylor row multiplies dS with)
+  float2* ybd_flatm;     // as ybd_flat, the exponent terms with the rows' q . Kc_0 added (only with exact sets: for scores against
+                         // the gathered mean keys, which are stored minus Kc_0)
+  float* rq;             // [B,H,S_max] q . Kc_0 in raw score units, written by the forward's 4-wave kernel (only with exact sets)
   float* bx_mean;        // [B,H,Tn_pad] log2(n_j) per gathered mean key
   uint32_t* mask_t;      // [B,H,T_max,mask_words] exact_mask transposed (only when exact_frac > 0)
   float* doc; float* cdq; float* cdk; float* cdv;   // [B,H,T_max,D] coarse residual: gamma * block sums of dO, gradients of the means (only when gamma != 0)
@@ -95,6 +99,12 @@ __device__ __forceinline__ int block_in_range(int j, int T) { return j < 0 ? 0 :
 
 extern hipEvent_t g_prof_start, g_prof_stop;   // events recorded around the MFMA attention kernel when g_prof_on
 extern int g_prof_on, g_prof_recorded;
+
+// Compute units per XCD of the current device (the launch heuristics that cut the items of a last, half-empty round into
+// parts count rounds over them): a device's compute units / 8, as the workgroup ids of a launch go round-robin over the 8
+// XCDs of an MI355X; 32 there, and 32 if the device cannot be asked.  Only work distribution depends on it, no result.
+int cus_per_xcd();
+constexpr int N_XCD = 8;
 
 int validate(const isa_problem* p, Problem* out);
 // forward_only: without the arrays that the forward pass leaves for, and that are scratch of, the backward pass

@@ -36,6 +36,10 @@ CASES = [SMALL, RAGGED,
          SMALL.with_(name="key_offset_8_all_taylor", key_offset=8.0, full_frac=0.0),
          SMALL.with_(name="exact_frac_too_small_for_a_set", exact_frac=0.05, key_offset=3.0),
          SMALL.with_(name="uncentred", centred=False, gamma=0.5),
+         # case 23 of seed 20 of the random stream below: a two-token tail block among two kept blocks, exact_frac too small
+         # for any exact set (the 4-wave forward kernel still runs), the coarse residual
+         SMALL.with_(name="two_token_tail_block", H=3, src_grid=(1, 10, 13), ctx_grids=(((3, 2, 21),),), keep_ratio=0.0,
+                     full_frac=0.2, exact_frac=0.0625, gamma=0.5, seed=1023),
          SMALL.with_(name="plain_mean_tile", H=2, src_grid=(4, 32, 65), ctx_grids=(((2, 10, 33),),), keep_ratio=1.0, seed=81)]
 
 # Gradients are compared relative to their own scale: the kernel rounds the weights P and dS to bf16 before the second
