@@ -24,13 +24,41 @@ def value_scale(Vh):
     return max(1.0, float(np.abs(Vh).max()) / 6.0)
 
 
-def mean_key_scale(Kc):
-    """Same for the Taylor branch and its keys: a block enters through its mean key rounded to bf16 (after the mean key
-    of block 0 has been taken off), so a logit is off by up to 2^-9 |q| |Kc_j - Kc_0| / sqrt(D).  The named workloads
-    have |Kc_j - Kc_0| < 3 per channel; where block means differ by much more than that (un-centred fields on tiny
-    grids: 40) the error of a Taylor block's weights grows in proportion, and the output error is that times the spread
-    of the values: the bounds of a Taylor block are multiplied by both scales; 1 for every named workload."""
-    return max(1.0, float(np.abs(Kc - Kc[0]).max()) / 4.0)
+def taylor_rounding_allowance(q, plan, kv_list, exact_blocks):
+    """First-order size of what rounding the mean keys (minus the mean key of block 0) and the mean values to bf16 does
+    to the outputs of the Taylor query rows `q`: per row, sum_j p_j (dz_j |Vc_j - o| + 2^-9 |Vc_j|), where dz_j is four
+    standard deviations of the logit error of mean key j (each channel off by up to 2^-9 of itself, uniformly) and p_j the
+    softmax weights over the mean keys.  Computed from the inputs alone."""
+    D = q.shape[1]
+    taken = set(int(j) for j in exact_blocks)
+    mean_blocks = [int(j) for j in kv_list if int(j) not in taken]
+    if not mean_blocks:
+        return 0.0
+    Kc, Vc, counts = plan["Kc"], plan["Vc"], plan["counts"]
+    Kp = Kc[mean_blocks] - Kc[0]
+    dz = 4.0 * (2.0 ** -9 / math.sqrt(3.0)) * np.sqrt((q ** 2) @ (Kp ** 2).T) / math.sqrt(D)
+    z = q @ Kc[mean_blocks].T / math.sqrt(D) + np.log(counts[mean_blocks])[None, :]
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    o = p @ Vc[mean_blocks]
+    spread = np.abs(Vc[mean_blocks][None, :, :] - o[:, None, :]).max(axis=2)
+    dv = 2.0 ** -9 * np.abs(Vc[mean_blocks]).max(axis=1)[None, :]
+    return float((p * (dz * spread + dv)).sum(axis=1).max())
+
+
+# the allowance above on the blocks of the named workloads (cfg1: 0.0128, the small bf16 case: 0.0117)
+NAMED_TAYLOR_ALLOWANCE = 0.013
+
+
+def taylor_scale(q, plan, kv_list, exact_blocks):
+    """The benchmark spec's bounds are stated for the named workloads, whose Taylor blocks see hundreds of mean keys that are
+    averages over 128 tokens.  A Taylor block enters through mean keys and values rounded to bf16, so its error grows with
+    what that rounding can do on its inputs: where a kept list has a handful of entries one of which is a tail block of one
+    to three tokens (a "mean" as large as a raw token, carrying most of the weight) the allowance is three times that of
+    the named workloads, on un-centred tiny grids a hundred times.  The bounds of a Taylor block are multiplied by that
+    ratio; 1 for every named workload."""
+    return max(1.0, taylor_rounding_allowance(q, plan, kv_list, exact_blocks) / NAMED_TAYLOR_ALLOWANCE)
+
 
 CFG0 = W.CONFIGS["cfg0"]
 # bf16, D=128, block=128: 5 full source blocks + a 20-token tail; two context references with tails
@@ -333,7 +361,10 @@ def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, 
                 got = f64(out[b, h, s0:s0 + cnt])
                 assert np.isfinite(got).all()
                 emax, emean = err_stats(got, want)
-                vs = value_scale(Vh) * (1.0 if in_full else mean_key_scale(plan["Kc"]))
+                vs = value_scale(Vh)
+                if not in_full:
+                    ex_used = ex if ex is not None else []
+                    vs *= taylor_scale(Qh[s0:s0 + cnt], plan, kv, ex_used)
                 assert emax <= tol_max * vs and emean <= tol_mean * vs, (wl.name, b, h, int(i), in_full, emax, emean, vs)
     return agree_kv / total, agree_grp / total
 
@@ -379,6 +410,24 @@ def test_staged_entry_points_reproduce_the_whole_calls_intermediates(I, wl):
             assert torch.equal(I.workspace_array(ws, lay[name], shape + tail, torch.float32)[b, :, :rows], buf[name][b, :, :rows]), name
         torch.testing.assert_close(I.workspace_array(ws, lay["vc"], shape + (wl.D,), torch.float32)[b, :, :T], buf["vc"][b, :, :T],
                                    rtol=2e-6, atol=2e-6)
+
+
+# Kept lists of four or five entries with a tail block of one to three tokens among them, found by wider runs of the random
+# sweep below (seeds 31 and 37): the Taylor blocks' max-abs errors were 0.0223 and 0.0208; rounding that one mean key to
+# bf16 accounts for 0.017 of it (CPU emulation), and the input-derived allowance is three times the named workloads'.
+TINY_TAIL_CASES = [
+    W.CONFIGS["cfg1"].with_(name="three_token_tail_block_among_four_keys", H=8, src_grid=(1, 7, 37),
+                            ctx_grids=(((2, 12, 33), (3, 6, 22), (2, 8, 16)),), keep_ratio=0.125, full_frac=0.5, seed=3012),
+    W.CONFIGS["cfg1"].with_(name="one_token_tail_block_among_five_keys", H=5, src_grid=(3, 9, 19),
+                            ctx_grids=(((2, 2, 38), (3, 4, 8), (2, 4, 23)),), keep_ratio=0.125, full_frac=0.2, exact_frac=0.3,
+                            gamma=0.5, seed=3016),
+]
+
+
+@pytest.mark.parametrize("wl", TINY_TAIL_CASES, ids=[c.name for c in TINY_TAIL_CASES])
+def test_tiny_tail_blocks_as_mean_keys(I, wl):
+    Q, K, V, q, k, v = gen(wl)
+    check_end_to_end(I, wl, Q, K, V, q, k, v)
 
 
 # Keys with a large common component.  A vector added to every key cancels in every softmax of the operator (the oracle's
