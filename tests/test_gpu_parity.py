@@ -25,10 +25,10 @@ def value_scale(Vh):
 
 
 def taylor_rounding_allowance(q, plan, kv_list, exact_blocks):
-    """First-order size of what rounding the mean keys (minus the mean key of block 0) and the mean values to bf16 does
-    to the outputs of the Taylor query rows `q`: per row, sum_j p_j (dz_j |Vc_j - o| + 2^-9 |Vc_j|), where dz_j is four
-    standard deviations of the logit error of mean key j (each channel off by up to 2^-9 of itself, uniformly) and p_j the
-    softmax weights over the mean keys.  Computed from the inputs alone."""
+    """First-order size of what bf16 storage does to the outputs of the Taylor query rows `q`, from the inputs alone: per
+    row, sum_j p_j (dz_j |Vc_j - o| + 2^-8 |Vc_j|) + 2^-8 |o|, where p_j are the softmax weights over the mean keys, dz_j is
+    four standard deviations of the logit error of mean key j (stored minus the mean key of block 0, each channel off by up
+    to 2^-9 of itself, uniformly), 2^-8 |Vc_j| the largest rounding error of a mean value and 2^-8 |o| that of the output."""
     D = q.shape[1]
     taken = set(int(j) for j in exact_blocks)
     mean_blocks = [int(j) for j in kv_list if int(j) not in taken]
@@ -42,21 +42,22 @@ def taylor_rounding_allowance(q, plan, kv_list, exact_blocks):
     p /= p.sum(axis=1, keepdims=True)
     o = p @ Vc[mean_blocks]
     spread = np.abs(Vc[mean_blocks][None, :, :] - o[:, None, :]).max(axis=2)
-    dv = 2.0 ** -9 * np.abs(Vc[mean_blocks]).max(axis=1)[None, :]
-    return float((p * (dz * spread + dv)).sum(axis=1).max())
+    dv = 2.0 ** -8 * np.abs(Vc[mean_blocks]).max(axis=1)[None, :]
+    return float(((p * (dz * spread + dv)).sum(axis=1) + 2.0 ** -8 * np.abs(o).max(axis=1)).max())
 
 
-# the allowance above on the blocks of the named workloads (cfg1: 0.0128, the small bf16 case: 0.0117)
-NAMED_TAYLOR_ALLOWANCE = 0.013
+# the allowance above on the Taylor blocks of the named workloads (cfg1: 0.0174, the small bf16 case and the key-offset
+# cases: 0.0180 - 0.0182): the size of the benchmark spec's bound itself
+NAMED_TAYLOR_ALLOWANCE = 0.0185
 
 
 def taylor_scale(q, plan, kv_list, exact_blocks):
     """The benchmark spec's bounds are stated for the named workloads, whose Taylor blocks see hundreds of mean keys that are
     averages over 128 tokens.  A Taylor block enters through mean keys and values rounded to bf16, so its error grows with
     what that rounding can do on its inputs: where a kept list has a handful of entries one of which is a tail block of one
-    to three tokens (a "mean" as large as a raw token, carrying most of the weight) the allowance is three times that of
-    the named workloads, on un-centred tiny grids a hundred times.  The bounds of a Taylor block are multiplied by that
-    ratio; 1 for every named workload."""
+    to three tokens (a "mean" as large as a raw token, carrying most of the weight) the allowance is two to two and a half
+    times that of the named workloads, on un-centred tiny grids a hundred times.  The bounds of a Taylor block are
+    multiplied by that ratio; 1 for every named workload."""
     return max(1.0, taylor_rounding_allowance(q, plan, kv_list, exact_blocks) / NAMED_TAYLOR_ALLOWANCE)
 
 
@@ -361,10 +362,9 @@ def check_end_to_end(I, wl, Q, K, V, q, k, v, heads=None, blocks_per_head=None, 
                 got = f64(out[b, h, s0:s0 + cnt])
                 assert np.isfinite(got).all()
                 emax, emean = err_stats(got, want)
-                vs = value_scale(Vh)
-                if not in_full:
-                    ex_used = ex if ex is not None else []
-                    vs *= taylor_scale(Qh[s0:s0 + cnt], plan, kv, ex_used)
+                # exact-branch blocks: the bounds grow with the values; Taylor blocks: with the rounding allowance of their
+                # mean keys, mean values and outputs (both 1 for the named workloads)
+                vs = value_scale(Vh) if in_full else taylor_scale(Qh[s0:s0 + cnt], plan, kv, ex if ex is not None else [])
                 assert emax <= tol_max * vs and emean <= tol_mean * vs, (wl.name, b, h, int(i), in_full, emax, emean, vs)
     return agree_kv / total, agree_grp / total
 
@@ -413,14 +413,17 @@ def test_staged_entry_points_reproduce_the_whole_calls_intermediates(I, wl):
 
 
 # Kept lists of four or five entries with a tail block of one to three tokens among them, found by wider runs of the random
-# sweep below (seeds 31 and 37): the Taylor blocks' max-abs errors were 0.0223 and 0.0208; rounding that one mean key to
-# bf16 accounts for 0.017 of it (CPU emulation), and the input-derived allowance is three times the named workloads'.
+# sweep below (seeds 31, 37 and 42): the Taylor blocks' max-abs errors were 0.0223, 0.0208 and 0.0285; rounding that one mean
+# key (or its mean value, |Vc| = 4.4) to bf16 accounts for 0.015 - 0.017 of it (CPU emulation), the output's own rounding for
+# 0.008 - 0.011, and the input-derived allowance is 2.0 to 2.4 times the named workloads'.
 TINY_TAIL_CASES = [
     W.CONFIGS["cfg1"].with_(name="three_token_tail_block_among_four_keys", H=8, src_grid=(1, 7, 37),
                             ctx_grids=(((2, 12, 33), (3, 6, 22), (2, 8, 16)),), keep_ratio=0.125, full_frac=0.5, seed=3012),
     W.CONFIGS["cfg1"].with_(name="one_token_tail_block_among_five_keys", H=5, src_grid=(3, 9, 19),
                             ctx_grids=(((2, 2, 38), (3, 4, 8), (2, 4, 23)),), keep_ratio=0.125, full_frac=0.2, exact_frac=0.3,
                             gamma=0.5, seed=3016),
+    W.CONFIGS["cfg1"].with_(name="two_token_tail_block_with_large_values", B=2, H=9, src_grid=(1, 5, 26),
+                            ctx_grids=(((1, 9, 37), (3, 6, 36)), ()), keep_ratio=0.8, full_frac=0.2, seed=3018),
 ]
 
 
