@@ -159,93 +159,142 @@ hipError_t launch_block_means(const Problem& pr, const Workspace& ws, const void
 }
 
 // ------------------------------------------------------------------------------------------
-// Pooled attention: rows of S_coarse = softmax_j(qc_i . kc_j / sqrt(D)).
+// Pooled attention: rows of S_coarse = softmax_j(qc_i . kc_j / sqrt(D)) (Alg. 1 Stage 1).
 // One workgroup computes ROWS rows; it writes the context columns of the source rows to pctx (for
-// the column means of Eq. 1) and the sharpness of every row.
+// the column means of Eq. 1) and the sharpness of every row (Alg. 1 Stage 3).
+//
+// Logits: fp32 matrix instructions (v_mfma_f32_16x16x4_f32), transposed: the 16 rows of the A operand are 16 mean
+// keys, the 16 columns of the B operand the workgroup's mean queries, so that a lane ends up with four consecutive
+// columns of one row of S_coarse (one 16-byte LDS store).  With l = lane % 16 and g = lane / 16, lane (l, g) feeds
+// channel 16 t + 4 g + i of key / query l into step (t, i): one 16-byte load per lane covers four steps.  The mean
+// queries stay in registers for the whole workgroup; the four waves take pairs of 16-column tiles in turn.
+// Workgroup ids go round-robin over the XCDs, so XCD x sees ids x, x + 8, ...; each XCD owns every 8th
+// (batch, head) and works through its heads one after the other: the workgroups that run together read the same
+// head's mean keys out of that XCD's L2.
 // ------------------------------------------------------------------------------------------
-constexpr int CROWS = 8;
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-template <int D>
+template <int D, int ROWS>
 __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ qc, const float* __restrict__ kc,
                                                 float* __restrict__ pctx, float* __restrict__ sharp,
                                                 float* __restrict__ z_out, const float* __restrict__ vc,
-                                                float* __restrict__ ocoarse, Counts cnt, int H, int Tsrc_max, int Tctx_max) {
-  extern __shared__ float sm[];
-  float* qs = sm;                       // [CROWS][D]
-  float* zs = sm + CROWS * D;           // [CROWS][T_max]
-  const int b = blockIdx.z, h = blockIdx.y, i0 = blockIdx.x * CROWS;
+                                                float* __restrict__ ocoarse, Counts cnt, int B, int H, int Tsrc_max,
+                                                int Tctx_max, int zs_stride, int row_tiles) {
+  static_assert(ROWS == 8 || ROWS == 16, "a row tile is half or all of the matrix instruction's 16 columns");
+  extern __shared__ __attribute__((aligned(16))) float zs[];      // [ROWS][zs_stride]
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int bhid = (slot / row_tiles) * 8 + xcd;
+  if (bhid >= B * H) return;
+  const int b = bhid / H, i0 = (slot % row_tiles) * ROWS;
   const int T = cnt.b[b].T, T_src = cnt.b[b].T_src, T_max = cnt.T_max;
   if (i0 >= T) return;
-  const long long bh = (long long)b * H + h;
-  const float* qrow = qc + (bh * T_max + i0) * D;
-  for (int x = threadIdx.x; x < CROWS * D; x += 256) qs[x] = (i0 + x / D < T) ? qrow[x] : 0.f;
-  __syncthreads();
+  const long long bh = bhid;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int l16 = lane & 15, g = lane >> 4;
   const float scale = 1.0f / sqrtf((float)D);
-  for (int j = threadIdx.x; j < T; j += 256) {
-    const float4* kr = reinterpret_cast<const float4*>(kc + (bh * T_max + j) * D);
-    float acc[CROWS];
+  constexpr int NT = D / 16;                                       // 16-byte loads per lane and row
+  __shared__ float rowmax[4][16];
+  {
+    // mean queries: rows past the batch item's last block repeat it (their logits are never read)
+    float4 bq[NT];
+    const float* qrow = qc + (bh * T_max + min(i0 + l16, T - 1)) * D + 4 * g;
 #pragma unroll
-    for (int r = 0; r < CROWS; ++r) acc[r] = 0.f;
-#pragma unroll 4
-    for (int d4 = 0; d4 < D / 4; ++d4) {
-      const float4 kv = kr[d4];
+    for (int t = 0; t < NT; ++t)
+      bq[t] = (ROWS == 16 || l16 < ROWS) ? *reinterpret_cast<const float4*>(qrow + 16 * t) : make_float4(0.f, 0.f, 0.f, 0.f);
+    const int n_ct = (T + 15) / 16;
+    // mean keys of the column tiles jt, jt + 1; columns past the last block repeat it, so they change no maximum
+    auto load_pair = [&](int jt, float4 (&ak)[2][NT]) {
 #pragma unroll
-      for (int r = 0; r < CROWS; ++r) {
-        const float* qq = qs + r * D + d4 * 4;
-        acc[r] = fmaf(qq[0], kv.x, acc[r]);
-        acc[r] = fmaf(qq[1], kv.y, acc[r]);
-        acc[r] = fmaf(qq[2], kv.z, acc[r]);
-        acc[r] = fmaf(qq[3], kv.w, acc[r]);
+      for (int u = 0; u < 2; ++u) {
+        const float* krow = kc + (bh * T_max + min((jt + u) * 16 + l16, T - 1)) * D + 4 * g;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) ak[u][t] = *reinterpret_cast<const float4*>(krow + 16 * t);
       }
-    }
+    };
+    float rmax = -INFINITY;                                         // over this lane's columns of row l16
+    float4 ak[2][NT], ak_next[2][NT];
+    load_pair(2 * wave, ak);
+    for (int jt = 2 * wave; jt < n_ct; jt += 8) {
+      load_pair(jt + 8, ak_next);                                   // the next pair's loads fly under this pair's products
+      f32x4_t acc[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int r = 0; r < CROWS; ++r) zs[r * T_max + j] = acc[r] * scale;
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(ak[u][t].x, bq[t].x, acc[u], 0, 0, 0);
+          acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(ak[u][t].y, bq[t].y, acc[u], 0, 0, 0);
+          acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(ak[u][t].z, bq[t].z, acc[u], 0, 0, 0);
+          acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(ak[u][t].w, bq[t].w, acc[u], 0, 0, 0);
+        }
+      // lane (l16, g) holds columns 16 jt + 4 g .. + 3 of row l16; zs_stride covers whole column tiles
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float4 zv = make_float4(acc[u][0] * scale, acc[u][1] * scale, acc[u][2] * scale, acc[u][3] * scale);
+        rmax = fmaxf(fmaxf(rmax, fmaxf(zv.x, zv.y)), fmaxf(zv.z, zv.w));
+        if ((ROWS == 16 || l16 < ROWS) && jt + u < n_ct) *reinterpret_cast<float4*>(zs + l16 * zs_stride + (jt + u) * 16 + 4 * g) = zv;
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) ak[u][t] = ak_next[u][t];
+    }
+    rmax = fmaxf(rmax, __shfl_xor(rmax, 16, 64));
+    rmax = fmaxf(rmax, __shfl_xor(rmax, 32, 64));
+    if (g == 0) rowmax[wave][l16] = rmax;
   }
   __syncthreads();
-  // softmax, context columns and sharpness of a row: one wave per row (waves take rows wave, wave + 4), a lane owns the
-  // columns lane, lane + 64, ... from here on, so that nothing has to be synchronised between the passes over a row
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int r = wave; r < CROWS; r += 4) {
+  // softmax, context columns and sharpness of a row: one wave per row (waves take rows wave, wave + 4, ...), a lane
+  // owns the columns lane, lane + 64, ... from here on, so that nothing has to be synchronised between the passes
+  // over a row.  Sums in double precision: the variance of a softmax row over hundreds of columns cancels badly in
+  // single precision.
+  for (int r = wave; r < ROWS; r += 4) {
     const int i = i0 + r;
     if (i >= T) break;                                  // uniform over the wave
-    float* zr = zs + r * T_max;
+    float* zr = zs + r * zs_stride;
     if (z_out)
       for (int j = lane; j < T; j += 64) z_out[(bh * T_max + i) * T_max + j] = zr[j];
-    float m = -INFINITY;
-    for (int j = lane; j < T; j += 64) m = fmaxf(m, zr[j]);
-    m = wave_max(m);
-    double l = 0.0;
+    const float m = fmaxf(fmaxf(rowmax[0][r], rowmax[1][r]), fmaxf(rowmax[2][r], rowmax[3][r]));
+    // one pass: e = exp(z - m) with the sums of e over all columns, and of e and e^2 over the source columns
+    double l = 0.0, l_src = 0.0, q_src = 0.0;
+#pragma unroll 4
     for (int j = lane; j < T; j += 64) {
       const float e = expf(zr[j] - m);
       zr[j] = e;
-      l += (double)e;
+      const double ed = (double)e;
+      l += ed;
+      if (j < T_src) {
+        l_src += ed;
+        q_src = fma(ed, ed, q_src);
+      }
     }
     l = wave_sum(l);
+    l_src = wave_sum(l_src);
+    q_src = wave_sum(q_src);
+    // sharpness: variance of the row's softmax weights p = e / l over the source columns, E[p^2] - E[p]^2
+    const double mu = l_src / l / (double)T_src;
+    const double var = q_src / (l * l) / (double)T_src - mu * mu;
+    if (lane == 0) sharp[bh * T_max + i] = (float)fmax(var, 0.0);
     const float inv = (float)(1.0 / l);
-    double mu = 0.0;
-    for (int j = lane; j < T; j += 64) {
-      const float p = zr[j] * inv;
-      zr[j] = p;
-      if (j < T_src) mu += (double)p;
-      else if (i < T_src) pctx[(bh * Tsrc_max + i) * Tctx_max + (j - T_src)] = p;
+    // the weights themselves: the context columns of a source row go to pctx (Eq. 1); all of them stay in LDS for
+    // the coarse output
+    const int j_lo = ocoarse ? 0 : T_src;
+    if (ocoarse || i < T_src) {
+#pragma unroll 4
+      for (int j = j_lo + lane; j < T; j += 64) {
+        const float pw = zr[j] * inv;
+        zr[j] = pw;
+        if (j >= T_src && i < T_src) pctx[(bh * Tsrc_max + i) * Tctx_max + (j - T_src)] = pw;
+      }
     }
-    mu = wave_sum(mu) / (double)T_src;
-    double var = 0.0;
-    for (int j = lane; j < T_src; j += 64) {
-      const double d = (double)zr[j] - mu;
-      var += d * d;
-    }
-    var = wave_sum(var) / (double)T_src;
-    if (lane == 0) sharp[bh * T_max + i] = (float)var;
   }
   // O_coarse = S_coarse V^c (Alg. 1 Stage 1), only when the caller wants the coarse residual: the rows of
   // S_coarse of this workgroup's query blocks are in LDS; one thread per (row, channel), channels fastest
   if (ocoarse) {
     __syncthreads();
-    for (int x = threadIdx.x; x < CROWS * D; x += 256) {
+    for (int x = threadIdx.x; x < ROWS * D; x += 256) {
       const int r = x / D, ch = x % D;
       if (i0 + r >= T) continue;
-      const float* pr = zs + r * T_max;
+      const float* pr = zs + r * zs_stride;
       const float* vcol = vc + bh * T_max * D + ch;
       double acc = 0.0;
       for (int j = 0; j < T; ++j) acc += (double)pr[j] * (double)vcol[(long long)j * D];
@@ -273,24 +322,35 @@ __global__ __launch_bounds__(256) void k_colmean(const float* __restrict__ pctx,
     s_ctx[bh * cnt.T_max + j] = (float)((((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) / (double)T_src);
 }
 
-hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc, const float* kc, float* s_ctx,
-                         float* sharp, float* z, const float* vc, float* ocoarse, hipStream_t st) {
+template <int D, int ROWS>
+static hipError_t launch_coarse_rows(const Problem& pr, const Workspace& ws, const float* qc, const float* kc, float* sharp,
+                                     float* z, const float* vc, float* ocoarse, hipStream_t st) {
   const int T_max = pr.cnt.T_max;
-  const dim3 grid((T_max + CROWS - 1) / CROWS, pr.p.H, pr.p.B);
-  const size_t lds = (size_t)CROWS * (pr.p.D + T_max) * sizeof(float);
-  if (lds > 64 * 1024) {                                // beyond the default limit of dynamic LDS (about 1900 blocks): ask for it
-    hipError_t ea = pr.p.D == 128
-        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&k_coarse<128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-        : hipFuncSetAttribute(reinterpret_cast<const void*>(&k_coarse<64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  const int zs_stride = ((T_max + 15) / 16) * 16 + 4;          // whole column tiles; + 4 spreads the rows over the banks
+  const int row_tiles = (T_max + ROWS - 1) / ROWS;
+  const size_t lds = (size_t)ROWS * zs_stride * sizeof(float);
+  if (lds > 64 * 1024) {                                        // beyond the default limit of dynamic LDS: ask for it
+    hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_coarse<D, ROWS>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (ea != hipSuccess) return ea;
   }
-  if (pr.p.D == 128)
-    hipLaunchKernelGGL((k_coarse<128>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, vc, ocoarse, pr.cnt, pr.p.H, pr.Tsrc_max,
-                       pr.Tctx_max);
-  else
-    hipLaunchKernelGGL((k_coarse<64>), grid, dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, vc, ocoarse, pr.cnt, pr.p.H, pr.Tsrc_max,
-                       pr.Tctx_max);
-  hipError_t e = hipGetLastError();
+  const int bh = pr.p.B * pr.p.H;
+  const unsigned grid = (unsigned)(N_XCD * ((bh + N_XCD - 1) / N_XCD) * row_tiles);
+  hipLaunchKernelGGL((k_coarse<D, ROWS>), dim3(grid), dim3(256), lds, st, qc, kc, ws.pctx, sharp, z, vc, ocoarse, pr.cnt,
+                     pr.p.B, pr.p.H, pr.Tsrc_max, pr.Tctx_max, zs_stride, row_tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc, const float* kc, float* s_ctx,
+                         float* sharp, float* z, const float* vc, float* ocoarse, hipStream_t st) {
+  // 16 rows per workgroup (every column of the matrix instruction's B operand in use) while two such workgroups fit
+  // a compute unit's LDS; 8 rows for longer rows (up to ISA_MAX_BLOCKS columns: 131 KB)
+  const bool wide = (size_t)16 * (((pr.cnt.T_max + 15) / 16) * 16 + 4) * sizeof(float) <= 80 * 1024;
+  hipError_t e;
+  if (pr.p.D == 128) e = wide ? launch_coarse_rows<128, 16>(pr, ws, qc, kc, sharp, z, vc, ocoarse, st)
+                              : launch_coarse_rows<128, 8>(pr, ws, qc, kc, sharp, z, vc, ocoarse, st);
+  else e = wide ? launch_coarse_rows<64, 16>(pr, ws, qc, kc, sharp, z, vc, ocoarse, st)
+                : launch_coarse_rows<64, 8>(pr, ws, qc, kc, sharp, z, vc, ocoarse, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_colmean, dim3((pr.Tctx_max + 63) / 64, pr.p.H, pr.p.B), dim3(256), 0, st, ws.pctx, s_ctx, pr.cnt,
                      pr.p.H, pr.Tsrc_max, pr.Tctx_max);
@@ -298,27 +358,54 @@ hipError_t launch_coarse(const Problem& pr, const Workspace& ws, const float* qc
 }
 
 // ------------------------------------------------------------------------------------------
-// Selection.  One workgroup per (head, batch).  Rank of an entry = number of entries that beat it
-// (larger score, or equal score and lower index); entries of rank < k are chosen.  Chosen and
-// unchosen indices are compacted in ascending order with a block-wide scan.
+// Selection.  One workgroup of 1024 threads per (head, batch, list kind): the kept context blocks (Eq. 2), or the
+// split of the query blocks by sharpness (Alg. 1 Stage 3).  Rank of an entry = number of entries that beat it
+// (larger score, or equal score and lower index); entries of rank < k are chosen.  Chosen and unchosen indices are
+// compacted in ascending order with a block-wide scan.
 // ------------------------------------------------------------------------------------------
 __device__ inline bool beats(float sa, int ia, float sb, int ib) { return sa > sb || (sa == sb && ia < ib); }
 
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_PARTS = 16;        // lanes that share the count of one entry's rank (each counts 1/16 of the peers)
+
+// flags[j] = 1 for the entries of sc[0..n) that fewer than k others beat.  Integer counts: the result does not depend
+// on how the peers are divided among the lanes.
+__device__ void rank_flags(const float* sc, int n, int k, int* flags) {
+  const int part = threadIdx.x % SEL_PARTS;
+  const int per = (n + SEL_PARTS - 1) / SEL_PARTS, lo = min(n, part * per), hi = min(n, lo + per);
+  for (int j0 = 0; j0 < n; j0 += SEL_THREADS / SEL_PARTS) {          // the same trip count for every thread
+    const int j = j0 + threadIdx.x / SEL_PARTS;
+    int rank = 0;
+    if (j < n) {
+      const float s = sc[j];
+      for (int x = lo; x < hi; ++x) rank += beats(sc[x], x, s, j) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = SEL_PARTS / 2; o > 0; o >>= 1) rank += __shfl_xor(rank, o, 64);
+    if (j < n && part == 0) flags[j] = rank < k ? 1 : 0;
+  }
+}
+
 // flags[0..n) -> ascending indices of flagged entries to out_yes (offset add), of the others to out_no.
-__device__ void compact(const int* flags, int n, int add, int* out_yes, int* out_no, int* cnts /* [257] LDS */) {
-  const int chunk = (n + 255) / 256;
+__device__ void compact(const int* flags, int n, int add, int* out_yes, int* out_no, int* wsum /* [SEL_THREADS / 64] LDS */) {
+  const int chunk = (n + SEL_THREADS - 1) / SEL_THREADS;
   const int lo = min(n, (int)threadIdx.x * chunk), hi = min(n, lo + chunk);
   int c = 0;
   for (int x = lo; x < hi; ++x) c += flags[x];
-  __syncthreads();
-  cnts[threadIdx.x + 1] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    cnts[0] = 0;
-    for (int t = 1; t <= 256; ++t) cnts[t] += cnts[t - 1];
+  // exclusive scan of c over the workgroup: inside a wave with shuffles, then the sums of the waves before this one
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = c;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
   }
   __syncthreads();
-  int yes = cnts[threadIdx.x], no = lo - yes;
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int yes = inc - c;
+  for (int w = 0; w < wave; ++w) yes += wsum[w];
+  int no = lo - yes;
   for (int x = lo; x < hi; ++x) {
     if (flags[x]) out_yes[yes++] = x + add;
     else if (out_no) out_no[no++] = x + add;
@@ -326,45 +413,35 @@ __device__ void compact(const int* flags, int n, int add, int* out_yes, int* out
   __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_select(const float* __restrict__ s_ctx, const float* __restrict__ sharp,
-                                                int* __restrict__ kv_list, int* __restrict__ full_list,
-                                                int* __restrict__ flat_list, Counts cnt, int H) {
+__global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict__ s_ctx, const float* __restrict__ sharp,
+                                                        int* __restrict__ kv_list, int* __restrict__ full_list,
+                                                        int* __restrict__ flat_list, Counts cnt, int H) {
   extern __shared__ float sm[];
   float* sc = sm;                                   // [T_max]
   int* flags = reinterpret_cast<int*>(sm + cnt.T_max);   // [T_max]
-  __shared__ int cnts[257];
+  __shared__ int wsum[SEL_THREADS / 64];
   const int h = blockIdx.x, b = blockIdx.y;
   const BatchCounts c = cnt.b[b];
   const long long off = ((long long)b * H + h) * cnt.T_max;
 
-  // context blocks by saliency
-  for (int j = threadIdx.x; j < c.T_ctx; j += 256) sc[j] = s_ctx[off + j];
-  __syncthreads();
-  for (int j = threadIdx.x; j < c.T_ctx; j += 256) {
-    const float s = sc[j];
-    int rank = 0;
-    for (int x = 0; x < c.T_ctx; ++x) rank += beats(sc[x], x, s, j) ? 1 : 0;
-    flags[j] = rank < c.k_keep ? 1 : 0;
+  if (blockIdx.z == 0) {       // context blocks by saliency: kv_list = all source blocks, then the kept context blocks
+    for (int j = threadIdx.x; j < c.T_ctx; j += SEL_THREADS) sc[j] = s_ctx[off + j];
+    for (int j = threadIdx.x; j < cnt.T_max; j += SEL_THREADS) kv_list[off + j] = j < c.T_src ? j : -1;
+    __syncthreads();
+    rank_flags(sc, c.T_ctx, c.k_keep, flags);
+    __syncthreads();
+    compact(flags, c.T_ctx, c.T_src, kv_list + off + c.T_src, nullptr, wsum);
+  } else {                     // query blocks by sharpness
+    for (int i = threadIdx.x; i < c.T; i += SEL_THREADS) sc[i] = sharp[off + i];
+    for (int i = threadIdx.x; i < cnt.T_max; i += SEL_THREADS) {
+      full_list[off + i] = -1;
+      flat_list[off + i] = -1;
+    }
+    __syncthreads();
+    rank_flags(sc, c.T, c.n_full, flags);
+    __syncthreads();
+    compact(flags, c.T, 0, full_list + off, flat_list + off, wsum);
   }
-  for (int j = threadIdx.x; j < cnt.T_max; j += 256) kv_list[off + j] = j < c.T_src ? j : -1;
-  __syncthreads();
-  compact(flags, c.T_ctx, c.T_src, kv_list + off + c.T_src, nullptr, cnts);
-
-  // query blocks by sharpness
-  for (int i = threadIdx.x; i < c.T; i += 256) sc[i] = sharp[off + i];
-  for (int i = threadIdx.x; i < cnt.T_max; i += 256) {
-    full_list[off + i] = -1;
-    flat_list[off + i] = -1;
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < c.T; i += 256) {
-    const float s = sc[i];
-    int rank = 0;
-    for (int x = 0; x < c.T; ++x) rank += beats(sc[x], x, s, i) ? 1 : 0;
-    flags[i] = rank < c.n_full ? 1 : 0;
-  }
-  __syncthreads();
-  compact(flags, c.T, 0, full_list + off, flat_list + off, cnts);
 }
 
 // Alg. 2 Stage 2: for the Taylor query block at position r of flat_list, mark the k_exact positions of
@@ -403,8 +480,8 @@ __global__ __launch_bounds__(256) void k_exact_sets(const float* __restrict__ z,
 hipError_t launch_select(const Problem& pr, const Workspace& ws, const float* s_ctx, const float* sharp, const float* z,
                          int* kv_list, int* full_list, int* flat_list, uint32_t* exact_mask, hipStream_t st) {
   const size_t lds = (size_t)pr.cnt.T_max * 8;
-  hipLaunchKernelGGL(k_select, dim3(pr.p.H, pr.p.B), dim3(256), lds, st, s_ctx, sharp, kv_list, full_list, flat_list,
-                     pr.cnt, pr.p.H);
+  hipLaunchKernelGGL(k_select, dim3(pr.p.H, pr.p.B, 2), dim3(SEL_THREADS), lds, st, s_ctx, sharp, kv_list, full_list,
+                     flat_list, pr.cnt, pr.p.H);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !(pr.p.exact_frac > 0.0)) return e;
   int nflat_max = 0;
