@@ -269,6 +269,15 @@ __device__ __forceinline__ void tile_body(const uint16_t* __restrict__ kbase, co
   }
 }
 
+// `a`, `b`: the 8-byte pieces a lane holds of two neighbouring 8-channel groups of its row (lane g = lane / 32 of the row:
+// channels 4 g .. + 3 of each group).  The upper half of `a` changes places with the lower half of `b`; afterwards lane g
+// holds the 16 bytes of group g.
+__device__ __forceinline__ uint4 halves_of_two_groups(uint2 a, uint2 b) {
+  const auto x = __builtin_amdgcn_permlane32_swap(a.x, b.x, false, false);
+  const auto y = __builtin_amdgcn_permlane32_swap(a.y, b.y, false, false);
+  return make_uint4(x[0], y[0], x[1], y[1]);
+}
+
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * K_TILE + 2 * V_TILE + 2 * 512];
   uint16_t* ldsK = lds;                     // [2][K_TILE]
@@ -512,25 +521,32 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(MfmaArgs a) {
   if (row_ok) {
     const float inv = 1.0f / l_tot;
     if (a.nlse && g == 0) a.nlse[bh * a.S_max + q_start + row] = -m_run - __log2f(l_tot);
-    uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * g;
     // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
     const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * g : nullptr;
-    uint16_t* lp = a.olo ? a.olo + (bh * a.S_max + q_start + row) * MD + 4 * g : nullptr;
+    // The two lanes of a row (g = 0, 1) hold channels 4 g .. + 3 of every group of 8: 8 bytes of bf16 each.  Two groups
+    // at a time they exchange halves (the upper half of the wave with the lower half, one swap instruction per
+    // register), after which lane g holds all 8 channels of group e4 + g: one 16-byte store per lane, 32 contiguous
+    // bytes per row and instruction, half the store instructions.
+    uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 8 * g;
+    uint16_t* lp = a.olo ? a.olo + (bh * a.S_max + q_start + row) * MD + 8 * g : nullptr;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        float4 r = make_float4(oacc[db][4 * e4] * inv, oacc[db][4 * e4 + 1] * inv, oacc[db][4 * e4 + 2] * inv,
-                               oacc[db][4 * e4 + 3] * inv);
-        if (oc) {
-          const float4 c4 = *reinterpret_cast<const float4*>(oc + 32 * db + 8 * e4);
-          r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
-          r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
+      for (int e4 = 0; e4 < 4; e4 += 2) {
+        uint2 o[2], cut[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int e = e4 + u;
+          float4 r = make_float4(oacc[db][4 * e] * inv, oacc[db][4 * e + 1] * inv, oacc[db][4 * e + 2] * inv, oacc[db][4 * e + 3] * inv);
+          if (oc) {
+            const float4 c4 = *reinterpret_cast<const float4*>(oc + 32 * db + 8 * e);
+            r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
+            r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
+          }
+          split_bf16x4(r, o[u], cut[u]);
         }
-        uint2 o, cut;
-        split_bf16x4(r, o, cut);
-        *reinterpret_cast<uint2*>(op + 32 * db + 8 * e4) = o;
-        if (lp) *reinterpret_cast<uint2*>(lp + 32 * db + 8 * e4) = cut;
+        *reinterpret_cast<uint4*>(op + 32 * db + 8 * e4) = halves_of_two_groups(o[0], o[1]);
+        if (lp) *reinterpret_cast<uint4*>(lp + 32 * db + 8 * e4) = halves_of_two_groups(cut[0], cut[1]);
       }
   }
 }

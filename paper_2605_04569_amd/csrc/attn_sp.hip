@@ -92,6 +92,15 @@ __device__ __forceinline__ float max_over_q(float x) {
   return max_raw(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
 }
 
+// `a` and `b` are the 8-byte pieces a lane holds of two neighbouring 16-channel tiles of its row (lane (r, q): channels
+// 4 q .. 4 q + 3 of each).  Rows 1, 3 of `a` change places with rows 0, 2 of `b`; afterwards lane q holds, as 16
+// consecutive bytes, channels 8 (q / 2) .. + 7 of tile q % 2.
+__device__ __forceinline__ uint4 pair_halves(uint2 a, uint2 b) {
+  const auto x = __builtin_amdgcn_permlane16_swap(a.x, b.x, false, false);
+  const auto y = __builtin_amdgcn_permlane16_swap(a.y, b.y, false, false);
+  return make_uint4(x[0], y[0], x[1], y[1]);
+}
+
 // One half step g: sixteen steps of two MFMAs each.  Three halves are in flight:
 //   score MFMAs (steps 0..7) produce the raw scores of half g in `sout` from the 8 K fragments in `kf` (fragment f =
 //   key tile f % 2, channels 32 (f / 2) .., fetched from LDS during the previous half step);
@@ -237,7 +246,11 @@ __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[
 template <bool taylor>
 __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
+#ifdef ISA_ITEM_TIMING
+  unsigned long long tm0 = __builtin_amdgcn_s_memrealtime(), tm1 = 0, tm2 = 0, tm3 = 0;
+#endif
   uint16_t* ldsV = lds + NBUF * K_TILE;     // V^T tile T lives in buffer T % NBUF
+  uint16_t* ldsQ = lds + NBUF * K_TILE + NBUF * V_TILE;       // 2 x 128 query rows of a Taylor group's next pair
 
   // ---- which work item.  Workgroup ids go round-robin over the 8 XCDs, so XCD x sees ids x, x + 8, ... in
   // order.  Each XCD owns every 8th (batch, head) (`hpx` of them: batch items of different lengths are spread
@@ -253,8 +266,10 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   const bool split = !taylor && j >= n_whole;
   const int item = taylor ? j - n_whole - n_sub : split ? n_whole + (j - n_whole) / a.parts : j;
   const int part = split ? (j - n_whole) % a.parts : 0;
-  const int hl = taylor ? item / a.slots_second : item / a.slots_first;
-  const int slot = taylor ? item % a.slots_second : item % a.slots_first;           // pair index inside its branch
+  // A Taylor work item is a group of up to `tgroup` consecutive pairs of one head, handled one after the other (all of
+  // them read the same sequence of mean tiles); an exact-branch item is one pair.
+  const int hl = taylor ? item / a.groups_second : item / a.slots_first;
+  int slot = taylor ? (item % a.groups_second) * a.tgroup : item % a.slots_first;   // (first) pair index inside its branch
   const int bhid = hl * 8 + xcd;
   if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
@@ -283,9 +298,21 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   // an odd list
   const int entry = 2 * slot + grp;
   const bool active = entry < (taylor ? n_second_blocks : n_first_blocks);
-  const int qi = !active ? 0 : a.dense ? entry : block_in_range(taylor ? a.flat_list[bh * T_max + entry] : a.full_list[bh * T_max + entry], c.T);
-  const int n_q = active ? bn[qi] : 0;
-  const int q_start = bs[qi];
+  int qi = !active ? 0 : a.dense ? entry : block_in_range(taylor ? a.flat_list[bh * T_max + entry] : a.full_list[bh * T_max + entry], c.T);
+  int n_q = active ? bn[qi] : 0;
+  int q_start = bs[qi];
+  // Taylor group: the pairs that follow the first one, and what lane L knows about list entry 2 (slot + 1) + L (block
+  // index, rows, first row), handed out with readlane when the group moves on
+  const int n_here = taylor ? min(a.tgroup, ((n_second_blocks + 1) >> 1) - slot) : 1;
+  int nx_qi = 0, nx_n = 0, nx_start = 0;
+  if constexpr (taylor) {
+    const int e = 2 * (slot + 1) + lane;
+    if (lane < 2 * (n_here - 1) && e < n_second_blocks) {
+      nx_qi = block_in_range(a.flat_list[bh * T_max + e], c.T);
+      nx_n = bn[nx_qi];
+    }
+    nx_start = bs[nx_qi];
+  }
 
   // Tile idx of the sequence.  Token tiles come from the table row {token offset, real tokens, block index} of their
   // list entry; idx >= t_end (past the end) gives a fully masked tile over valid memory.
@@ -397,6 +424,28 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     lds_dma16(sw, vlane_b, lds_addr_of(ldsV + buf * V_TILE + (wave * 2 + i) * 512));
   };
   auto load_v = [&](const uint16_t* vt, int buf) { load_v1(vt, buf, 0); load_v1(vt, buf, 1); };
+  int pair_in_group = 0;                    // Taylor group: which of its pairs is being worked on
+  // Query rows of the group's next pair, global -> LDS: wave w fetches rows 32 w .. 32 w + 31 of the pair's 256 (its own
+  // rows; waves 0-3 hold the first block), four rows per instruction, chunk c of row r stored at chunk c ^ (r & 15) like
+  // the K tiles.  Rows past the block's end repeat its first row, as in the direct loads above.  `i0`: first of the four
+  // instructions issued by this call (eight per wave and pair).
+  auto stage_q_rows = [&](int i0) {
+    if constexpr (taylor) {
+      const int nn = __builtin_amdgcn_readlane(nx_n, 2 * pair_in_group + grp);
+      const int ns = __builtin_amdgcn_readlane(nx_start, 2 * pair_in_group + grp);
+      const char* src = reinterpret_cast<const char*>(a.q + tbase + (long long)ns * a.geo.stride_t);
+      // the per-lane address arithmetic is redone at every call: hoisted out of the loop, its results would have to live
+      // in registers the loop does not have (the opaque copy of the lane id is what keeps it here)
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+#pragma unroll
+      for (int i = i0; i < i0 + 4; ++i) {
+        const int r = wq * 32 + 4 * i + (ln >> 4);                     // row of the block; its LDS row has the same low bits
+        lds_dma16(src, (uint32_t)(r < nn ? r : 0) * (uint32_t)(a.geo.stride_t * 2) + (uint32_t)(((ln & 15) ^ (r & 15)) * 16),
+                  lds_addr_of(ldsQ + (wave * 32 + 4 * i) * MD));
+      }
+    }
+  };
 
   // per-lane fragment offsets (bf16 elements): K row r of a 16-key tile, chunk (4 ks + q) ^ r; V^T unit row r of a
   // 16-channel tile, chunk q ^ ((r >> 1) & 3)
@@ -451,6 +500,7 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[qt][ks]));
+  if constexpr (taylor) asm volatile("" : "+v"(nx_qi), "+v"(nx_n), "+v"(nx_start));      // likewise
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   const unsigned long long gen_mask = taylor ? __ballot(tile_flag != 0) : 0ull;
   auto needs_general = [&](const STile& t) -> bool {
@@ -470,9 +520,13 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   unsigned long long raise0 = 0ull, raise1 = 0ull;     // ballots that go with mx0 / mx1
   // One iteration; `bcur` = (T - t_begin) % NBUF is the buffer of K tile T, either a compile-time constant (the loop
   // is then unrolled three times and every LDS address is a per-lane constant plus an immediate) or a run-time value.
-  auto iteration = [&](const int T, const auto bcur_c) {
+  // `pending`: what this wave still has in flight that the iteration needs -- 0 nothing, 1 tile loads (wait for
+  // everything), 2 tile loads followed by the eight loads that stage the next pair's query rows (loads complete in the
+  // order of their issue, so "all but the last eight" is enough: the staged rows are not needed before the pair ends).
+  auto iteration = [&](const int T, const auto bcur_c, const int pending, const bool stage_q) {
     const int bcur = bcur_c;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (pending == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (pending == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int bnext = bcur == 2 ? 0 : bcur + 1;                     // buffer of tiles T + 1
     const int bnn = bcur == 0 ? 2 : bcur - 1;                       // buffer of tiles T + 2 and T - 1
@@ -484,13 +538,24 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       const bool raised = prepare_half(s1, mx1, raise1, general, nkh, taylor ? bias_of(tprev) + 32 : nullptr, q, cscale, neg_m, thr, alpha);
       half_step<0>(kbase + 32 * MD, vbase, qf, kf, s1, s0, oacc, neg_m, thr, l_run, mx0, raise0, pa, pb, koff, voff, cscale, [&](int f) {
         if (f == 0) {
-          if (__builtin_expect(min(T + 2, t_end - 1) >= cbase + 64, 0)) refill(cbase + 64);
-          make_tile(T + 2, tnn);
+          if constexpr (taylor) {
+            // the pairs of a group follow each other without a gap: behind a pair's last tile and its drain tile come
+            // the first tiles of the next pair, which are the same mean tiles again
+            make_tile(T + 2 > t_end ? T + 1 - t_end : T + 2, tnn);
+          } else {
+            if (__builtin_expect(min(T + 2, t_end - 1) >= cbase + 64, 0)) refill(cbase + 64);
+            make_tile(T + 2, tnn);
+          }
         }
         if (f == 2) load_k1(tnn, bnn, 0);
         if (f == 3) load_k1(tnn, bnn, 1);
         if (f == 4) load_v1(vt_of(tnext), bnext, 0);
         if (f == 5) load_v1(vt_of(tnext), bnext, 1);
+        if constexpr (taylor) {
+          if (f >= 6 && stage_q) {
+            stage_q_rows(4 * (f - 6));
+          }
+        }
       }
       );
       if (__builtin_expect(raised, 0)) rescale(alpha, l_run, oacc);
@@ -507,69 +572,141 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     tcur = tnext;
     tnext = tnn;
   };
-  if constexpr (taylor) {                   // a handful of iterations per item: not worth three copies of the loop
+  // ---- normalise and store: element i of oacc[ct][qt] is channel 16 ct + 4 q + i of query 16 qt + r
+  auto store_rows = [&]() {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      float l_tot = l_run[qt][0];
+      l_tot += __shfl_xor(l_tot, 16, 64);
+      l_tot += __shfl_xor(l_tot, 32, 64);
+      if (!row_ok[qt]) continue;
+      const int row = rowq[qt];
+      if (split) {
+        // partial result of a sub-item: unnormalised fp32 outputs and the {maximum, sum} they refer to
+        const long long sid = (((long long)xcd * a.n_split + (item - n_whole)) * a.parts + part) * 2 + grp;
+        float* op = a.split_o + (sid * 128 + row) * MD + 4 * q;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          *reinterpret_cast<float4*>(op + 16 * c) = make_float4(oacc[c][qt][0], oacc[c][qt][1], oacc[c][qt][2], oacc[c][qt][3]);
+        if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(-neg_m[qt], l_tot);
+      } else {
+        const float inv = 1.0f / l_tot;
+        // the mean keys' biases may be stored short of a common term (see k_gather_means): the log-sum-exp gets it back
+        if (a.nlse && q == 0) a.nlse[bh * a.S_max + q_start + row] = neg_m[qt] - __log2f(l_tot) - (taylor ? a.lse_shift : 0.f);
+        // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
+        const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * q : nullptr;
+        // A lane holds channels 16 c + 4 q .. + 3 of its row: 8 bytes of bf16.  Two channel tiles at a time, the lanes
+        // q = 0, 1 and q = 2, 3 of a row exchange halves (one row-swap instruction per register), after which lane q
+        // holds 8 consecutive channels, 16 (c + q % 2) + 8 (q / 2) .. + 7: one 16-byte store per lane, 64 contiguous
+        // bytes per row and instruction, half the store instructions.
+        const int ch = 16 * (q & 1) + 8 * (q >> 1);
+        uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + ch;
+        uint16_t* lp = a.olo ? a.olo + (bh * a.S_max + q_start + row) * MD + ch : nullptr;
+#pragma unroll
+        for (int c = 0; c < 8; c += 2) {
+          uint2 o[2], cut[2];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            float4 r = make_float4(oacc[c + u][qt][0] * inv, oacc[c + u][qt][1] * inv, oacc[c + u][qt][2] * inv, oacc[c + u][qt][3] * inv);
+            if (oc) {
+              const float4 c4 = *reinterpret_cast<const float4*>(oc + 16 * (c + u));
+              r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
+              r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
+            }
+            split_bf16x4(r, o[u], cut[u]);
+          }
+          *reinterpret_cast<uint4*>(op + 16 * c) = pair_halves(o[0], o[1]);
+          if (lp) *reinterpret_cast<uint4*>(lp + 16 * c) = pair_halves(cut[0], cut[1]);
+        }
+      }
+    }
+  };
+
+  if constexpr (taylor) {
+    // A handful of iterations per pair: not worth three copies of the loop.  The pairs of the group run through one
+    // continuous tile pipeline: pair p takes positions p (t_end + 1) .. p (t_end + 1) + t_end of it, its mean tiles and
+    // one drain position whose (masked) tile is consumed while the last real tile's value product is added.  In the drain
+    // position the pipeline already holds the next pair's first tiles, so only the accumulators, the running maxima
+    // and the Q fragments change between pairs: the next pair's 2 x 128 query rows are fetched into LDS during the
+    // current pair's first iteration (each wave fetches, and later reads, exactly its own 32 rows).
     int bcur = 0;
-    for (int T = t_begin; T <= t_end; ++T) {
-      iteration(T, bcur);
-      bcur = bcur == 2 ? 0 : bcur + 1;
+    int pending = 1;
+    for (int p = 0;; ++p) {
+      const bool more = p + 1 < n_here;
+      pair_in_group = p;
+#ifdef ISA_ITEM_TIMING
+      tm1 = __builtin_amdgcn_s_memrealtime();
+#endif
+      for (int T = 0; T <= t_end; ++T) {
+        iteration(T, bcur, pending, more && T == 0);
+        pending = (more && T == 0) ? 2 : 1;
+        bcur = bcur == 2 ? 0 : bcur + 1;
+      }
+      // the tile loads of the drain iteration have had that iteration to land: after this wait nothing but the stores
+      // below is in flight, and the next iteration does not wait for them
+#ifdef ISA_ITEM_TIMING
+      tm2 = __builtin_amdgcn_s_memrealtime();
+#endif
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#ifdef ISA_ITEM_TIMING
+      tm3 = __builtin_amdgcn_s_memrealtime();
+#endif
+      store_rows();
+#ifdef ISA_ITEM_TIMING
+      if (tid == 0 && active) {
+        const unsigned long long tm4 = __builtin_amdgcn_s_memrealtime();
+        unsigned long long* tp = reinterpret_cast<unsigned long long*>(a.out + tbase + (long long)q_start * a.geo.stride_t);
+        tp[0] = tm0; tp[1] = tm1; tp[2] = tm2; tp[3] = tm3; tp[4] = tm4; tp[5] = blockIdx.x; tp[6] = p;
+        tm0 = tm4;
+      }
+#endif
+      if (!more) break;
+      // ---- the next pair of the group
+      qi = __builtin_amdgcn_readlane(nx_qi, 2 * p + grp);
+      n_q = __builtin_amdgcn_readlane(nx_n, 2 * p + grp);
+      q_start = __builtin_amdgcn_readlane(nx_start, 2 * p + grp);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        row_ok[qt] = rowq[qt] < n_q;
+        const uint16_t* qrow = ldsQ + (wave * 32 + 16 * qt + r16) * MD;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          qf[qt][ks] = *reinterpret_cast<const bf16x8*>(qrow + (((4 * ks + q) ^ r16) * 8));
+          asm volatile("" : "+v"(qf[qt][ks]));
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) oacc[c][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        l_run[qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        neg_m[qt] = -M_INIT;
+        thr[qt] = M_INIT + RESCALE_TAU;
+        alpha[qt] = 1.f;
+      }
+      pending = 0;
     }
   } else {
     for (int T = t_begin;;) {
-      iteration(T, std::integral_constant<int, 0>{});
+      iteration(T, std::integral_constant<int, 0>{}, 1, false);
       if (++T > t_end) break;
-      iteration(T, std::integral_constant<int, 1>{});
+      iteration(T, std::integral_constant<int, 1>{}, 1, false);
       if (++T > t_end) break;
-      iteration(T, std::integral_constant<int, 2>{});
+      iteration(T, std::integral_constant<int, 2>{}, 1, false);
       if (++T > t_end) break;
     }
-  }
-  // the loads of the two tiles past the end still target this workgroup's LDS: let them land before the waves end
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-
-  // ---- normalise and store: element i of oacc[ct][qt] is channel 16 ct + 4 q + i of query 16 qt + r
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    float l_tot = l_run[qt][0];
-    l_tot += __shfl_xor(l_tot, 16, 64);
-    l_tot += __shfl_xor(l_tot, 32, 64);
-    if (!row_ok[qt]) continue;
-    const int row = rowq[qt];
-    if (split) {
-      // partial result of a sub-item: unnormalised fp32 outputs and the {maximum, sum} they refer to
-      const long long sid = (((long long)xcd * a.n_split + (item - n_whole)) * a.parts + part) * 2 + grp;
-      float* op = a.split_o + (sid * 128 + row) * MD + 4 * q;
-#pragma unroll
-      for (int c = 0; c < 8; ++c)
-        *reinterpret_cast<float4*>(op + 16 * c) = make_float4(oacc[c][qt][0], oacc[c][qt][1], oacc[c][qt][2], oacc[c][qt][3]);
-      if (q == 0) *reinterpret_cast<float2*>(a.split_ml + (sid * 128 + row) * 2) = make_float2(-neg_m[qt], l_tot);
-    } else {
-      const float inv = 1.0f / l_tot;
-      // the mean keys' biases may be stored short of a common term (see k_gather_means): the log-sum-exp gets it back
-      if (a.nlse && q == 0) a.nlse[bh * a.S_max + q_start + row] = neg_m[qt] - __log2f(l_tot) - (taylor ? a.lse_shift : 0.f);
-      uint16_t* op = a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + 4 * q;
-      // coarse residual (Alg. 1 Stage 5): the block's row of O_coarse, the same for all of its tokens
-      const float* oc = a.ocoarse ? a.ocoarse + (bh * T_max + qi) * MD + 4 * q : nullptr;
-      uint16_t* lp = a.olo ? a.olo + (bh * a.S_max + q_start + row) * MD + 4 * q : nullptr;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        float4 r = make_float4(oacc[c][qt][0] * inv, oacc[c][qt][1] * inv, oacc[c][qt][2] * inv, oacc[c][qt][3] * inv);
-        if (oc) {
-          const float4 c4 = *reinterpret_cast<const float4*>(oc + 16 * c);
-          r.x = fmaf(a.gamma, c4.x, r.x); r.y = fmaf(a.gamma, c4.y, r.y);
-          r.z = fmaf(a.gamma, c4.z, r.z); r.w = fmaf(a.gamma, c4.w, r.w);
-        }
-        uint2 o, cut;
-        split_bf16x4(r, o, cut);
-        *reinterpret_cast<uint2*>(op + 16 * c) = o;
-        if (lp) *reinterpret_cast<uint2*>(lp + 16 * c) = cut;
-      }
-    }
+    // the loads of the two tiles past the end still target this workgroup's LDS: let them land before the waves end
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    store_rows();
   }
 }
 
 __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t lds[NBUF * K_TILE + NBUF * V_TILE];
-  // the Taylor pairs of an XCD come after all of its exact-branch items (whole and split)
+  // three K tiles, three V^T tiles, and the staged query rows of a Taylor group's next pair: all 160 KB of a compute unit
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[NBUF * K_TILE + NBUF * V_TILE + 256 * MD];
+  // the Taylor groups of an XCD come after all of its exact-branch items (whole and split)
   if ((int)(blockIdx.x >> 3) >= a.n_long - a.n_split + a.n_split * a.parts) attn_sp_item<true>(a, lds);
   else attn_sp_item<false>(a, lds);
 }
@@ -620,6 +757,12 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
   *reinterpret_cast<uint2*>(a.out + tbase + (long long)(q_start + row) * a.geo.stride_t + ch) = o;
   if (a.olo) *reinterpret_cast<uint2*>(a.olo + ((long long)bhid * a.S_max + q_start + row) * MD + ch) = cut;
 }
+
+// Pairs of Taylor query blocks per workgroup.  A pair costs its mean tiles plus one drain iteration; the set-up of a
+// workgroup (list entry -> block table -> query rows -> first tiles, three dependent memory latencies), its last stores
+// and the hand-over of the compute unit to the next workgroup, about as long as the six mean tiles of a 480p pair together,
+// are paid once per group.  Four keeps the groups short enough to fill the tail of the launch evenly.
+constexpr int TAYLOR_GROUP = 4;
 
 // Launches the attention kernels of the MFMA path: the software-pipelined kernel for dense attention, the
 // exact branch and the Taylor branch without exact sets; the 4-wave kernel for Taylor blocks with exact sets.
@@ -675,7 +818,11 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
       while (parts >= 2 && N_XCD * rem * parts > SPLIT_MAX_SUB) --parts;      // the partial-result area holds SPLIT_MAX_SUB sub-items
       if (parts >= 2) { m.n_split = rem; m.parts = parts; }
     }
-    const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts + (long long)m.hpx * ss;
+    // Taylor pairs go in groups of up to TAYLOR_GROUP consecutive pairs of a head per workgroup
+    m.tgroup = TAYLOR_GROUP;
+    m.groups_second = ss > 0 ? (ss + TAYLOR_GROUP - 1) / TAYLOR_GROUP : 1;
+    const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts +
+                              (ss > 0 ? (long long)m.hpx * m.groups_second : 0);
     m.slots = 0; m.total = 0;
     hipLaunchKernelGGL(k_attn_sp, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, m);
     e = hipGetLastError();
