@@ -246,9 +246,6 @@ __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[
 template <bool taylor>
 __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
-#ifdef ISA_ITEM_TIMING
-  unsigned long long tm0 = __builtin_amdgcn_s_memrealtime(), tm1 = 0, tm2 = 0, tm3 = 0;
-#endif
   uint16_t* ldsV = lds + NBUF * K_TILE;     // V^T tile T lives in buffer T % NBUF
   uint16_t* ldsQ = lds + NBUF * K_TILE + NBUF * V_TILE;       // 2 x 128 query rows of a Taylor group's next pair
 
@@ -634,9 +631,6 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
     for (int p = 0;; ++p) {
       const bool more = p + 1 < n_here;
       pair_in_group = p;
-#ifdef ISA_ITEM_TIMING
-      tm1 = __builtin_amdgcn_s_memrealtime();
-#endif
       for (int T = 0; T <= t_end; ++T) {
         iteration(T, bcur, pending, more && T == 0);
         pending = (more && T == 0) ? 2 : 1;
@@ -644,22 +638,8 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
       }
       // the tile loads of the drain iteration have had that iteration to land: after this wait nothing but the stores
       // below is in flight, and the next iteration does not wait for them
-#ifdef ISA_ITEM_TIMING
-      tm2 = __builtin_amdgcn_s_memrealtime();
-#endif
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#ifdef ISA_ITEM_TIMING
-      tm3 = __builtin_amdgcn_s_memrealtime();
-#endif
       store_rows();
-#ifdef ISA_ITEM_TIMING
-      if (tid == 0 && active) {
-        const unsigned long long tm4 = __builtin_amdgcn_s_memrealtime();
-        unsigned long long* tp = reinterpret_cast<unsigned long long*>(a.out + tbase + (long long)q_start * a.geo.stride_t);
-        tp[0] = tm0; tp[1] = tm1; tp[2] = tm2; tp[3] = tm3; tp[4] = tm4; tp[5] = blockIdx.x; tp[6] = p;
-        tm0 = tm4;
-      }
-#endif
       if (!more) break;
       // ---- the next pair of the group
       qi = __builtin_amdgcn_readlane(nx_qi, 2 * p + grp);
