@@ -61,7 +61,9 @@ struct MfmaArgs {
   int slots;                                // work slots per (batch, head) = T_max
   int total;                                // B * H * slots
   int slots_first, slots_second;            // k_attn_sp: exact / Taylor pair slots per (batch, head), each at least 1
-  int tgroup, groups_second;                // k_attn_sp: Taylor pairs per workgroup; such groups per (batch, head), at least 1
+  int tgroup, groups_second;                // k_attn_sp: Taylor pairs per group; such groups per (batch, head), at least 1
+  int n_taylor_wg;                          // k_attn_sp: workgroups per XCD that work through the Taylor groups
+  int* taylor_ctr;                          // k_attn_sp: the next Taylor group to be taken (device memory, 0 when the launch starts)
   int hpx, n_long;                          // k_attn_sp: (batch, head)s per XCD; exact-branch items per XCD (0 if none)
   int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges
   float* split_o; float* split_ml;          // their partial results: unnormalised outputs [sub-item][2][128][128], {max, sum} [sub-item][2][128][2]

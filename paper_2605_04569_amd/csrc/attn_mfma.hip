@@ -95,11 +95,14 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
                                                       uint16_t* __restrict__ kcnb, uint16_t* __restrict__ vcn, uint16_t* __restrict__ vcnt,
                                                       uint16_t* __restrict__ vcnt4,
                                                       float* __restrict__ biasn, int* __restrict__ tflag,
-                                                      int4* __restrict__ ktab, Counts cnt, int H, int Tn_pad, int block) {
+                                                      int4* __restrict__ ktab, int* __restrict__ taylor_ctr, Counts cnt, int H,
+                                                      int Tn_pad, int block) {
   __shared__ uint16_t vtile[KT][MD + 2];
   __shared__ int ids[KT];
   __shared__ int plain;                       // every mean key of the tile exists and stands for a full block
   if (threadIdx.x == 0) plain = 1;
+  // the attention launch that follows hands out its Taylor groups by counting this up from zero
+  if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) *taylor_ctr = 0;
   __syncthreads();
   const int tile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int T_new = cnt.b[b].T_new, T_max = cnt.T_max;
@@ -155,8 +158,8 @@ __global__ __launch_bounds__(256) void k_gather_means(const float* __restrict__ 
 hipError_t launch_gather_means(const Problem& pr, const Workspace& ws, const float* kc, const float* vc,
                                const int* kv_list, hipStream_t st) {
   hipLaunchKernelGGL(k_gather_means, dim3(pr.Tn_pad / KT, pr.p.H, pr.p.B), dim3(256), 0, st, kc, vc, kv_list, ws.blk_n,
-                     ws.btab, ws.kcn, ws.kcnb, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.tflag, ws.ktab, pr.cnt, pr.p.H, pr.Tn_pad,
-                     pr.p.block);
+                     ws.btab, ws.kcn, ws.kcnb, ws.vcn, ws.vcnt, ws.vcnt4, ws.biasn, ws.tflag, ws.ktab, ws.taylor_ctr, pr.cnt, pr.p.H,
+                     pr.Tn_pad, pr.p.block);
   return hipGetLastError();
 }
 

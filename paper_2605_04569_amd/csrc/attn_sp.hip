@@ -244,31 +244,32 @@ __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[
 // One work item.  `taylor` is a template parameter so that the tile set-up inside the loop carries no selects or
 // branches between the two kinds of key sequence (token tiles of kept blocks / tiles of gathered block means).
 template <bool taylor>
-__device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
+__device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds, const int taylor_group) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
   uint16_t* ldsV = lds + NBUF * K_TILE;     // V^T tile T lives in buffer T % NBUF
   uint16_t* ldsQ = lds + NBUF * K_TILE + NBUF * V_TILE;       // 2 x 128 query rows of a Taylor group's next pair
 
   // ---- which work item.  Workgroup ids go round-robin over the 8 XCDs, so XCD x sees ids x, x + 8, ... in
   // order.  Each XCD owns every 8th (batch, head) (`hpx` of them: batch items of different lengths are spread
-  // evenly over the XCDs), and works through them one after the other, so that the workgroups that run together
-  // on it (and share its L2) read the same head's keys and values; it is handed all their exact-branch pairs first
-  // (the long items) and then all their Taylor pairs (short items, which fill the compute units that the last,
-  // incomplete round of long items leaves idle).
+  // evenly over the XCDs), and works through their exact-branch pairs (the long items) one head after the other, so
+  // that the workgroups that run together on it (and share its L2) read the same head's keys and values.  The Taylor
+  // groups (short items) belong to no XCD: the workgroups that come after an XCD's long items take them from one
+  // counter (`taylor_group`), so they fill the compute units that the last, incomplete round of long items leaves
+  // idle, and the XCDs that get through their long items sooner take more of them.
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   // The last n_split long items of the XCD (those of its last, incomplete round) run as `parts` sub-items, each over
   // 1/parts of the key sequence, so that the round fills all compute units; a merge kernel combines their partial
   // results afterwards.
   const int n_whole = a.n_long - a.n_split, n_sub = a.n_split * a.parts;
   const bool split = !taylor && j >= n_whole;
-  const int item = taylor ? j - n_whole - n_sub : split ? n_whole + (j - n_whole) / a.parts : j;
+  const int item = taylor ? taylor_group : split ? n_whole + (j - n_whole) / a.parts : j;
   const int part = split ? (j - n_whole) % a.parts : 0;
   // A Taylor work item is a group of up to `tgroup` consecutive pairs of one head, handled one after the other (all of
   // them read the same sequence of mean tiles); an exact-branch item is one pair.
   const int hl = taylor ? item / a.groups_second : item / a.slots_first;
   int slot = taylor ? (item % a.groups_second) * a.tgroup : item % a.slots_first;   // (first) pair index inside its branch
-  const int bhid = hl * 8 + xcd;
-  if (hl >= a.hpx || bhid >= a.geo.B * a.geo.H) return;
+  const int bhid = taylor ? hl : hl * 8 + xcd;                 // Taylor groups are numbered over all (batch, head)s
+  if ((!taylor && hl >= a.hpx) || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const BatchCounts c = a.cnt.b[b];
   const int T_max = a.geo.T_max;
@@ -686,9 +687,25 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds) {
 __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
   // three K tiles, three V^T tiles, and the staged query rows of a Taylor group's next pair: all 160 KB of a compute unit
   __shared__ __attribute__((aligned(1024))) uint16_t lds[NBUF * K_TILE + NBUF * V_TILE + 256 * MD];
-  // the Taylor groups of an XCD come after all of its exact-branch items (whole and split)
-  if ((int)(blockIdx.x >> 3) >= a.n_long - a.n_split + a.n_split * a.parts) attn_sp_item<true>(a, lds);
-  else attn_sp_item<false>(a, lds);
+  // the workgroups that take the Taylor groups come after all exact-branch items (whole and split) of their XCD
+  if ((int)(blockIdx.x >> 3) >= a.n_long - a.n_split + a.n_split * a.parts) {
+    // Each of them takes the next group from the counter until none is left: the counter only grows, so every
+    // workgroup gets there.  The taken number reaches the other waves through LDS (the staging area of the query rows,
+    // which is idle between groups); the second barrier keeps it from being overwritten before everyone has read it,
+    // and both together keep the first tile loads of a group behind the last LDS reads of the group before it.
+    int* taken = reinterpret_cast<int*>(lds + NBUF * K_TILE + NBUF * V_TILE);
+    const int n_groups = a.geo.B * a.geo.H * a.groups_second;
+    for (;;) {
+      if (threadIdx.x == 0) *taken = atomicAdd(a.taylor_ctr, 1);
+      __syncthreads();
+      const int g = __builtin_amdgcn_readfirstlane(*taken);
+      __syncthreads();
+      if (g >= n_groups) break;
+      attn_sp_item<true>(a, lds, g);
+    }
+  } else {
+    attn_sp_item<false>(a, lds, 0);
+  }
 }
 
 // Combines the partial results of the split work items: out = sum_p O_p 2^(m_p - m) / sum_p l_p 2^(m_p - m) with
@@ -801,8 +818,11 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
     // Taylor pairs go in groups of up to TAYLOR_GROUP consecutive pairs of a head per workgroup
     m.tgroup = TAYLOR_GROUP;
     m.groups_second = ss > 0 ? (ss + TAYLOR_GROUP - 1) / TAYLOR_GROUP : 1;
-    const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts +
-                              (ss > 0 ? (long long)m.hpx * m.groups_second : 0);
+    // one such workgroup per compute unit (they stay until the groups run out), fewer if there are fewer groups
+    const long long n_groups = ss > 0 ? (long long)pr.p.B * pr.p.H * m.groups_second : 0;
+    m.n_taylor_wg = (int)((n_groups + N_XCD - 1) / N_XCD < cus_per_xcd() ? (n_groups + N_XCD - 1) / N_XCD : cus_per_xcd());
+    m.taylor_ctr = ws.taylor_ctr;
+    const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts + m.n_taylor_wg;
     m.slots = 0; m.total = 0;
     hipLaunchKernelGGL(k_attn_sp, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, m);
     e = hipGetLastError();

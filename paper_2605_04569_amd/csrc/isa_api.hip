@@ -136,6 +136,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     ws->vt4 = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * T * D * 128 * 2) : nullptr;
     ws->vcnt4 = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * (size_t)pr.Tn_pad * D * 2) : nullptr;
     ws->zero_tile = (uint16_t*)take(128 * 64 * 2);
+    ws->taylor_ctr = (int*)take(256);
     ws->ktab = (int4*)take(B * H * T * 16);
     ws->split_o = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 128 * 4);
     ws->split_ml = (float*)take((size_t)SPLIT_MAX_SUB * 2 * 128 * 2 * 4);
@@ -186,6 +187,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     ws->biasn = nullptr;
     ws->tflag = nullptr;
     ws->zero_tile = nullptr;
+    ws->taylor_ctr = nullptr;
     ws->ktab = nullptr;
     ws->split_o = ws->split_ml = nullptr;
   }
