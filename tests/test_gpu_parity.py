@@ -509,6 +509,36 @@ def test_isa_attention_random_sweep(I, wl):
     check_end_to_end(I, wl, Q, K, V, q, k, v)
 
 
+def _taylor_group_cases():
+    """Taylor query blocks run in groups of four pairs per workgroup, the groups handed out from one counter.  Every query
+    block Taylor (full_frac = 0), with the number of blocks stepping over the group boundaries: 1 - 3 blocks (one
+    incomplete group, the last pair with one block), 8 and 9 (exactly one group; one pair into the second), 16, 17, 23; one
+    case with a single mean tile and one with three, many heads (more groups than compute units of an XCD take part) and a
+    batch of two items of different block counts (groups past the shorter item's pairs are taken and dropped)."""
+    cases = []
+    for n_src, n_ctx in ((1, 0), (1, 1), (2, 1), (4, 4), (5, 4), (8, 8), (9, 8), (12, 11)):
+        ctx = (((1, 1, 128 * n_ctx - 9),),) if n_ctx else ((),)
+        cases.append(W.CONFIGS["cfg1"].with_(name="taylor_groups_%d_blocks" % (n_src + n_ctx), H=3, src_grid=(1, 1, 128 * n_src - 5),
+                                             ctx_grids=ctx, keep_ratio=1.0, full_frac=0.0, seed=4100 + n_src))
+    cases.append(W.CONFIGS["cfg1"].with_(name="taylor_groups_three_mean_tiles", H=1, src_grid=(5, 30, 52), ctx_grids=(((10, 30, 52),),),
+                                         keep_ratio=1.0, full_frac=0.0, seed=4120))
+    cases.append(W.CONFIGS["cfg1"].with_(name="taylor_groups_many_heads", H=40, src_grid=(2, 16, 33), ctx_grids=(((4, 16, 33),),),
+                                         keep_ratio=0.5, full_frac=0.1, seed=4121))
+    cases.append(W.CONFIGS["cfg1"].with_(name="taylor_groups_ragged_batch", B=2, H=5, src_grid=(1, 16, 80),
+                                         ctx_grids=(((1, 16, 40), (1, 3, 7)), ()), keep_ratio=0.5, full_frac=0.0, seed=4122))
+    return cases
+
+
+TAYLOR_GROUP_CASES = _taylor_group_cases()
+
+
+@pytest.mark.parametrize("wl", TAYLOR_GROUP_CASES, ids=[c.name for c in TAYLOR_GROUP_CASES])
+def test_taylor_groups(I, wl):
+    Q, K, V, q, k, v = gen(wl)
+    heads = None if wl.H <= 8 else [0, 7, 19, 39]
+    check_end_to_end(I, wl, Q, K, V, q, k, v, heads=heads)
+
+
 def test_all_exact_equals_dense(I):
     """full_frac = 1 and keep_ratio = 1: ISA must reproduce dense attention (GPU vs GPU, and vs the oracle)."""
     wl = SMALL_BF16.with_(keep_ratio=1.0, full_frac=1.0)
