@@ -755,10 +755,10 @@ __global__ __launch_bounds__(256) void k_split_merge(MfmaArgs a) {
   if (a.olo) *reinterpret_cast<uint2*>(a.olo + ((long long)bhid * a.S_max + q_start + row) * MD + ch) = cut;
 }
 
-// Pairs of Taylor query blocks per workgroup.  A pair costs its mean tiles plus one drain iteration; the set-up of a
-// workgroup (list entry -> block table -> query rows -> first tiles, three dependent memory latencies), its last stores
-// and the hand-over of the compute unit to the next workgroup, about as long as the six mean tiles of a 480p pair together,
-// are paid once per group.  Four keeps the groups short enough to fill the tail of the launch evenly.
+// Pairs of Taylor query blocks per group, the unit a workgroup takes from the counter.  A pair costs its mean tiles plus
+// one drain iteration; the set-up of a group (taking its number; list entry -> block table -> query rows -> first tiles,
+// three dependent memory latencies), about as long as half the mean tiles of a 480p pair together, is paid once per group.
+// Four keeps the groups short enough for the workgroups to run out of them at about the same time.
 constexpr int TAYLOR_GROUP = 4;
 
 // Launches the attention kernels of the MFMA path: the software-pipelined kernel for dense attention, the
