@@ -109,6 +109,10 @@ struct BwdArgs {
   // unscaled fp32 sums in tail_scratch [XCD][tail item][part][256 rows][128] and k_bwd_tail_merge writes the rows
   int items_xcd, tail_items, tail_parts;
   float* tail_scratch;
+  // token rows: null, or a counter (0 when the launch starts) from which every workgroup takes the number of its item,
+  // numbered over all (batch, head)s: the launch then has more workgroups than items, and an XCD that gets through its
+  // workgroups sooner takes more of the items (the XCDs of a chip are not equally fast)
+  int* dyn_ctr;
 };
 
 // SM: stationary rows are block means; T2: W = P * (T2 - delta), else W = P; EX: exact-set bits are in play (1: whole
@@ -130,17 +134,27 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
     item = item_all / parts;
     part = item_all - item * parts;
   } else {
-    const int n_reg = a.items_xcd - a.tail_items;         // items_xcd = items x heads of an XCD; no tail: jj itself
-    int idx = jj;
-    if (jj >= n_reg) {
-      const int u = jj - n_reg;
-      tail_slot = u / a.tail_parts;
-      part = u - tail_slot * a.tail_parts;
-      parts = a.tail_parts;
-      idx = n_reg + tail_slot;
+    if (a.dyn_ctr) {
+      __shared__ int taken;
+      if (threadIdx.x == 0) taken = atomicAdd(a.dyn_ctr, 1);
+      __syncthreads();
+      const int idx = __builtin_amdgcn_readfirstlane(taken);
+      if (idx >= a.items * a.geo.B * a.geo.H) return;     // the launch has more workgroups than items
+      item = idx % a.items;
+      bhid = idx / a.items;
+    } else {
+      const int n_reg = a.items_xcd - a.tail_items;       // items_xcd = items x heads of an XCD; no tail: jj itself
+      int idx = jj;
+      if (jj >= n_reg) {
+        const int u = jj - n_reg;
+        tail_slot = u / a.tail_parts;
+        part = u - tail_slot * a.tail_parts;
+        parts = a.tail_parts;
+        idx = n_reg + tail_slot;
+      }
+      item = idx % a.items;
+      bhid = (idx / a.items) * 8 + xcd;
     }
-    item = idx % a.items;
-    bhid = (idx / a.items) * 8 + xcd;
   }
   if (bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
@@ -565,9 +579,11 @@ __global__ __launch_bounds__(512, 1) void k_attn_bwd(BwdArgs a) {
 // alone, delta carries that rounding (2^-9 |dO||O|) into dS = P (dP - delta), which for a query that attends almost
 // one-hot is a difference of nearly equal numbers.
 __global__ __launch_bounds__(256) void k_bwd_delta(const uint16_t* __restrict__ o, const uint16_t* __restrict__ olo,
-                                                   const uint16_t* __restrict__ d_o, float* __restrict__ delta, Geometry g,
-                                                   Counts cnt, int S_max) {
+                                                   const uint16_t* __restrict__ d_o, float* __restrict__ delta, int* __restrict__ ctr,
+                                                   Geometry g, Counts cnt, int S_max) {
   const int h = blockIdx.y, b = blockIdx.z;
+  // the item counters of the launches that follow start at zero (ordinary stores: the call can be captured in a graph)
+  if (blockIdx.x == 0 && h == 0 && b == 0 && threadIdx.x < 8) ctr[threadIdx.x] = 0;
   const int t = blockIdx.x * 16 + (threadIdx.x >> 4), c16 = threadIdx.x & 15;
   const bool ok = t < cnt.b[b].S;
   float s = 0.f;
@@ -882,13 +898,14 @@ __global__ __launch_bounds__(256) void k_bwd_tail_merge(BwdArgs a) {
 // YD (the streamed rows are queries, which carry deltas; the stationary rows then must not: a.dx == nullptr) is implied
 // by what the launch streams.
 template <bool SM, bool T2, bool YD>
-static hipError_t launch_one(BwdArgs a, int ex, int B, int H, hipStream_t st, bool split_tail = false) {
+static hipError_t launch_one(BwdArgs a, int ex, int B, int H, hipStream_t st, bool split_tail = false, int* dyn_ctr = nullptr) {
   if (a.items <= 0) return hipSuccess;
   if (YD && a.dx != nullptr) return hipErrorInvalidValue;
   const int hpx = (B * H + 7) / 8;                // (batch, head)s per XCD
   a.items_xcd = a.items * hpx;
   a.tail_items = 0; a.tail_parts = 1;
-  if (!SM && split_tail && a.n_phases == 1 && ex == 0 && a.tail_scratch) {
+  a.dyn_ctr = SM ? nullptr : dyn_ctr;
+  if (!SM && !a.dyn_ctr && split_tail && a.n_phases == 1 && ex == 0 && a.tail_scratch) {
     // the last round of an XCD's 32 compute units: if at most half of them would have an item, cut those items
     const int cus = cus_per_xcd(), t = a.items_xcd % cus;
     if (t > 0 && t <= cus / 2) {
@@ -897,7 +914,12 @@ static hipError_t launch_one(BwdArgs a, int ex, int B, int H, hipStream_t st, bo
       if (parts > 1) { a.tail_items = t; a.tail_parts = parts; }
     }
   }
-  const dim3 grid((unsigned)(SM ? a.items * a.parts * hpx * 8 : (a.items_xcd - a.tail_items + a.tail_items * a.tail_parts) * 8));
+  // dynamic items: an eighth more workgroups than items and one round of the chip, so that the faster XCDs do not run out
+  // of workgroups before the items run out
+  const long long n_dyn = (long long)a.items * B * H;
+  const long long dyn_wgs = ((n_dyn + n_dyn / 8) / N_XCD + cus_per_xcd() + 1) * N_XCD;
+  const dim3 grid((unsigned)(SM ? a.items * a.parts * hpx * 8
+                                : a.dyn_ctr ? dyn_wgs : (a.items_xcd - a.tail_items + a.tail_items * a.tail_parts) * 8));
   if (ex == 2) {                                // position bits only occur with token rows as stationary rows and dS
     if (SM || !T2 || YD) return hipErrorInvalidValue;
     hipLaunchKernelGGL((k_attn_bwd<false, true, 2, false>), grid, dim3(512), 0, st, a);
@@ -937,7 +959,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   } while (0)
   // delta, zero fill, per-list tables and row terms
   hipLaunchKernelGGL(k_bwd_delta, dim3((S_max + 15) / 16, H, B), dim3(256), 0, st, (const uint16_t*)out,
-                     ws.olo, (const uint16_t*)d_out, ws.delta, pr.geo, pr.cnt, S_max);
+                     ws.olo, (const uint16_t*)d_out, ws.delta, ws.bwd_ctr, pr.geo, pr.cnt, S_max);
   ISA_BWD_CHECK();
   if (resid) {
     // gradient of the coarse residual with respect to the block means (all blocks, by block id), and delta without
@@ -1005,7 +1027,7 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
   } else {
     a.s[0] = kept_means; a.n_phases = 1;
   }
-  if ((e = launch_one<false, true, false>(a, ex ? 2 : 0, B, H, st)) != hipSuccess) return e;
+  if ((e = launch_one<false, true, false>(a, ex ? 2 : 0, B, H, st, false, ws.bwd_ctr + 0)) != hipSuccess) return e;
 
   // ---- dKc and dK (streamed Q, dO)
   const int n_mean_pairs = ((sk + 127) / 128 + 1) / 2;
@@ -1055,8 +1077,8 @@ hipError_t launch_attn_bwd(const Problem& pr, const Workspace& ws, const void* q
     a.out_bf = (uint16_t*)(pass == 0 ? dk : dv); a.out_f32 = nullptr;
     a.add_rows = (sl > 0 || resid) ? mean_grad : nullptr; a.add_by_block = 0;
     a.oscale = osc; a.items = (sk + 1) / 2;
-    e = pass == 0 ? launch_one<false, true, true>(a, ex ? 1 : 0, B, H, st, true)
-                  : launch_one<false, false, false>(a, ex ? 1 : 0, B, H, st, true);
+    e = pass == 0 ? launch_one<false, true, true>(a, ex ? 1 : 0, B, H, st, true, ws.bwd_ctr + 1)
+                  : launch_one<false, false, false>(a, ex ? 1 : 0, B, H, st, true, ws.bwd_ctr + 2);
     if (e != hipSuccess) return e;
   }
 #undef ISA_BWD_CHECK

@@ -146,6 +146,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
     ws->nlse = (float*)take(B * H * S * 4);
     ws->olo = (uint16_t*)take(B * H * S * D * 2);
     ws->delta = (float*)take(B * H * S * 4);
+    ws->bwd_ctr = (int*)take(256);
     ws->vcn = (uint16_t*)take(B * H * Tn * D * 2);
     ws->rq = pr.p.exact_frac > 0.0 ? (float*)take(B * H * S * 4) : nullptr;
     ws->kcnb = pr.p.exact_frac > 0.0 ? (uint16_t*)take(B * H * Tn * D * 2) : nullptr;
@@ -173,6 +174,7 @@ void carve(const Problem& pr, void* base, Workspace* ws, bool forward_only) {
   } else {
     ws->nlse = ws->delta = ws->dkc = ws->dvc = ws->bx_mean = nullptr;
     ws->vcn = ws->olo = nullptr;
+    ws->bwd_ctr = nullptr;
     ws->rq = nullptr;
     ws->kcnb = nullptr;
     ws->ybd_flatm = nullptr;

@@ -60,6 +60,7 @@ struct Workspace {
   uint16_t* vt4; uint16_t* vcnt4;   // the same two arrays in the key order of the 4-wave kernel (only with exact sets)
   uint16_t* zero_tile;   // 16 KB of zeros, written by the V^T pack kernel
   int* taylor_ctr;       // the next Taylor group of the attention launch (zeroed by the mean gather, counted up by the launch)
+  int* bwd_ctr;          // backward: the next work item of each launch that hands its items out dynamically (8 counters, zeroed by k_bwd_delta)
   int4* ktab;            // [B,H,T_max] the btab rows of the blocks of kv_list, in list order
   float* ocoarse;        // [B,H,T_max,D] pooled attention output (only carved when gamma != 0)
   float* split_o;        // partial outputs of work items split along the key sequence (at most 256 sub-items)
