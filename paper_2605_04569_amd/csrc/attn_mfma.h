@@ -64,6 +64,7 @@ struct MfmaArgs {
   int tgroup, groups_second;                // k_attn_sp: Taylor pairs per group; such groups per (batch, head), at least 1
   int n_taylor_wg;                          // k_attn_sp: workgroups per XCD that work through the Taylor groups
   int* taylor_ctr;                          // k_attn_sp: the next Taylor group to be taken (device memory, 0 when the launch starts)
+  int* long_ctr; int n_long_all;            // k_attn_sp: null, or the next long item to be taken, numbered over all (batch, head)s, and their number
   int hpx, n_long;                          // k_attn_sp: (batch, head)s per XCD; exact-branch items per XCD (0 if none)
   int n_split, parts;                       // k_attn_sp: the last n_split exact-branch items of an XCD run as `parts` sub-items over key ranges
   float* split_o; float* split_ml;          // their partial results: unnormalised outputs [sub-item][2][128][128], {max, sum} [sub-item][2][128][2]

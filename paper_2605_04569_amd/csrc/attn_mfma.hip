@@ -31,12 +31,14 @@ namespace isa {
 __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
                                                  uint16_t* __restrict__ vt4, const int* __restrict__ blk_start,
                                                  const int* __restrict__ blk_n, uint16_t* __restrict__ zero_tile,
-                                                 float* __restrict__ vc, Geometry g) {
+                                                 float* __restrict__ vc, int* __restrict__ long_ctr, Geometry g) {
   __shared__ uint16_t tile[128][MD + 2];
   __shared__ float colsum[MD];
   const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (j == 0 && h == 0 && b == 0)                                 // the all-zero V^T tile the attention kernel pads with
+  if (j == 0 && h == 0 && b == 0) {                               // the all-zero V^T tile the attention kernel pads with
     for (int x = threadIdx.x; x < MD * KT / 8; x += 256) reinterpret_cast<uint4*>(zero_tile)[x] = make_uint4(0, 0, 0, 0);
+    if (threadIdx.x == 0) *long_ctr = 0;                          // the counter a dense launch may take its items from
+  }
   const int n = blk_n[b * g.T_max + j];
   if (n == 0) return;
   const int start = blk_start[b * g.T_max + j];
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void k_pack_vt(const uint16_t* __restrict__ v,
 
 hipError_t launch_pack_vt(const Problem& pr, const Workspace& ws, const void* v, float* vc, hipStream_t st) {
   hipLaunchKernelGGL(k_pack_vt, dim3(pr.cnt.T_max, pr.p.H, pr.p.B), dim3(256), 0, st, (const uint16_t*)v, ws.vt,
-                     ws.vt4, ws.blk_start, ws.blk_n, ws.zero_tile, vc, pr.geo);
+                     ws.vt4, ws.blk_start, ws.blk_n, ws.zero_tile, vc, ws.taylor_ctr + 1, pr.geo);
   return hipGetLastError();
 }
 

@@ -244,7 +244,7 @@ __device__ __forceinline__ void rescale(const float (&alpha)[2], f32x4 (&l_run)[
 // One work item.  `taylor` is a template parameter so that the tile set-up inside the loop carries no selects or
 // branches between the two kinds of key sequence (token tiles of kept blocks / tiles of gathered block means).
 template <bool taylor>
-__device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds, const int taylor_group) {
+__device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds, const int taken) {
   uint16_t* ldsK = lds;                     // K tile T lives in buffer T % NBUF
   uint16_t* ldsV = lds + NBUF * K_TILE;     // V^T tile T lives in buffer T % NBUF
   uint16_t* ldsQ = lds + NBUF * K_TILE + NBUF * V_TILE;       // 2 x 128 query rows of a Taylor group's next pair
@@ -254,22 +254,26 @@ __device__ __forceinline__ void attn_sp_item(const MfmaArgs& a, uint16_t* lds, c
   // evenly over the XCDs), and works through their exact-branch pairs (the long items) one head after the other, so
   // that the workgroups that run together on it (and share its L2) read the same head's keys and values.  The Taylor
   // groups (short items) belong to no XCD: the workgroups that come after an XCD's long items take them from one
-  // counter (`taylor_group`), so they fill the compute units that the last, incomplete round of long items leaves
-  // idle, and the XCDs that get through their long items sooner take more of them.
+  // counter (`taken`), so they fill the compute units that the last, incomplete round of long items leaves
+  // idle, and the XCDs that get through their long items sooner take more of them.  A launch of nothing but very many
+  // long items (dense attention over a long sequence) hands those out from a counter as well (`taken` >= 0, numbered
+  // over all (batch, head)s, head after head: the whole chip then works on one head at a time and every XCD streams that
+  // head's tiles through its L2 once per round of its workgroups, as before).
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   // The last n_split long items of the XCD (those of its last, incomplete round) run as `parts` sub-items, each over
   // 1/parts of the key sequence, so that the round fills all compute units; a merge kernel combines their partial
   // results afterwards.
-  const int n_whole = a.n_long - a.n_split, n_sub = a.n_split * a.parts;
-  const bool split = !taylor && j >= n_whole;
-  const int item = taylor ? taylor_group : split ? n_whole + (j - n_whole) / a.parts : j;
+  const int n_whole = a.n_long - a.n_split;
+  const bool counted = taylor || taken >= 0;                    // the item's number comes from a counter
+  const bool split = !counted && j >= n_whole;
+  const int item = counted ? taken : split ? n_whole + (j - n_whole) / a.parts : j;
   const int part = split ? (j - n_whole) % a.parts : 0;
   // A Taylor work item is a group of up to `tgroup` consecutive pairs of one head, handled one after the other (all of
   // them read the same sequence of mean tiles); an exact-branch item is one pair.
   const int hl = taylor ? item / a.groups_second : item / a.slots_first;
   int slot = taylor ? (item % a.groups_second) * a.tgroup : item % a.slots_first;   // (first) pair index inside its branch
-  const int bhid = taylor ? hl : hl * 8 + xcd;                 // Taylor groups are numbered over all (batch, head)s
-  if ((!taylor && hl >= a.hpx) || bhid >= a.geo.B * a.geo.H) return;
+  const int bhid = counted ? hl : hl * 8 + xcd;                // counted items are numbered over all (batch, head)s
+  if ((!counted && hl >= a.hpx) || bhid >= a.geo.B * a.geo.H) return;
   const int h = bhid % a.geo.H, b = bhid / a.geo.H;
   const BatchCounts c = a.cnt.b[b];
   const int T_max = a.geo.T_max;
@@ -703,8 +707,16 @@ __global__ __launch_bounds__(512, 1) void k_attn_sp(MfmaArgs a) {
       if (g >= n_groups) break;
       attn_sp_item<true>(a, lds, g);
     }
+  } else if (a.long_ctr) {
+    // long items from a counter: one per workgroup; the launch has more workgroups than items, the surplus leaves here
+    int* slot = reinterpret_cast<int*>(lds + NBUF * K_TILE + NBUF * V_TILE);
+    if (threadIdx.x == 0) *slot = atomicAdd(a.long_ctr, 1);
+    __syncthreads();
+    const int g = __builtin_amdgcn_readfirstlane(*slot);
+    if (g >= a.n_long_all) return;
+    attn_sp_item<false>(a, lds, g);
   } else {
-    attn_sp_item<false>(a, lds, 0);
+    attn_sp_item<false>(a, lds, -1);
   }
 }
 
@@ -822,6 +834,19 @@ hipError_t launch_attn_mfma(const Problem& pr, const Workspace& ws, const AttnAr
     const long long n_groups = ss > 0 ? (long long)pr.p.B * pr.p.H * m.groups_second : 0;
     m.n_taylor_wg = (int)((n_groups + N_XCD - 1) / N_XCD < cus_per_xcd() ? (n_groups + N_XCD - 1) / N_XCD : cus_per_xcd());
     m.taylor_ctr = ws.taylor_ctr;
+    // Dense attention over a long sequence: nothing but long items, 64 rounds of them or more.  The XCDs of a chip differ
+    // in speed by several per cent, and with equal shares the launch ends with the slowest; there are no short items to
+    // level with, so the long items themselves are taken from a counter (zeroed by the V^T pack, which precedes every
+    // such launch), one per workgroup, with an eighth more workgroups than items and one round of the chip to spare.  With
+    // fewer rounds the last, ragged round of such a launch would cost what the levelling gains.
+    m.long_ctr = nullptr; m.n_long_all = 0;
+    if (a.dense && ss == 0 && m.n_long >= 64 * cus) {
+      const long long all = (long long)pr.p.B * pr.p.H * sf;
+      m.long_ctr = ws.taylor_ctr + 1;
+      m.n_long_all = (int)all;
+      m.n_split = 0; m.parts = 1;
+      m.n_long = (int)((all + all / 8) / N_XCD + cus + 1);      // workgroups per XCD
+    }
     const long long per_xcd = (long long)m.n_long - m.n_split + (long long)m.n_split * m.parts + m.n_taylor_wg;
     m.slots = 0; m.total = 0;
     hipLaunchKernelGGL(k_attn_sp, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, m);
